@@ -1,0 +1,232 @@
+/*
+ * D-CHAG forward oracle: plain fp64 CPU definition.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the yardstick the GPU library is checked against.  It shares no
+ * code with that library and must never be linked into, called from, or used as
+ * a fallback by the product path.  It is slow on purpose: every quantity is
+ * computed exactly as the definition states it, one patch at a time, with no
+ * blocking, fusion, folding of weights or reordering.
+ *
+ * What it computes (paper Section 2.1, "The Channel Aggregation Module";
+ * Section 3.2, "Hierarchical Cross-Channel Aggregation"; Section 3.3, D-CHAG):
+ *
+ *   - tokenization: every p x p patch of every channel is embedded on its own by
+ *     that channel's own linear map (a 2-D convolution whose kernel and stride
+ *     are the patch size), plus that channel's ID embedding (Section 2.1);
+ *   - channel aggregation: a cross-attention layer reduces the tokens of a set
+ *     of channels at one spatial patch to one token (Section 2.1).  The paper
+ *     gives no formula; the reading taken is standard multi-head scaled
+ *     dot-product attention with one learned query per layer, projections
+ *     W_q, W_k, W_v, W_o with optional biases, scale 1/sqrt(D/heads), no norm,
+ *     no residual;
+ *   - hierarchy: the channels are split in contiguous groups of at most g
+ *     ("up to" g, Section 3.2), each group has its own layer, the outputs of a
+ *     level are the inputs of the next, and the last level is one
+ *     cross-attention layer over everything that is left (Section 3.3).
+ *
+ * Inputs are float (exactly representable bf16 or fp32 values); all arithmetic
+ * and all outputs are double.  Rows are summed left to right.
+ *
+ * Pins: the tests under tests/ (not marked gpu) check this file against a
+ * library grouped conv2d, a library multi-head attention with a length-1
+ * query, a pure-Python brute force in another loop order, and the invariants
+ * the definition fixes.  The paper prints no worked numerical example, so
+ * there is no pin to values of the paper itself.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+  int32_t group_size;                  /* nominal g; the last group may be shorter            */
+  int32_t reserved;
+  const float *query;                  /* [G, D]                                               */
+  const float *Wq, *Wk, *Wv, *Wo;      /* [G, D, D], row-major (out, in): y = W x              */
+  const float *bq, *bk, *bv, *bo;      /* [G, D] or NULL (= 0)                                 */
+} oracle_level;
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void oracle_set_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
+static int groups_of(int c_in, int g) { return (c_in + g - 1) / g; }
+
+/* y = W x + b   with W [rows, cols] float row-major, x double, b float or NULL */
+static void affine(const float *W, const float *b, const double *x, int rows, int cols, double *y) {
+  for (int i = 0; i < rows; ++i) {
+    double acc = 0.0;
+    const float *w = W + (size_t)i * cols;
+    for (int j = 0; j < cols; ++j) acc += (double)w[j] * x[j];
+    y[i] = acc + (b ? (double)b[i] : 0.0);
+  }
+}
+
+/*
+ * Tokens of one patch (Section 2.1): for channel c,
+ *   t[c] = W_e[c] . vec(patch) + b_e[c] + e[c],
+ * vec() taking the p x p pixels row by row; patch n = (i, j) counts row by row
+ * over the (H/p) x (W/p) grid.  W_e[c] is [D, p*p] (a conv2d weight [D,1,p,p]).
+ */
+static void tokens_of_patch(int C, int H, int W, int p, int D, const float *x_b /* [C,H,W] */,
+                            const float *We, const float *be, const float *ce, int n,
+                            double *t /* [C, D] */) {
+  const int pw = W / p;
+  const int pi = n / pw, pj = n % pw;
+  const int pp = p * p;
+  double *u = (double *)malloc(sizeof(double) * (size_t)pp);
+  for (int c = 0; c < C; ++c) {
+    const float *img = x_b + (size_t)c * H * W;
+    for (int r = 0; r < p; ++r)
+      for (int s = 0; s < p; ++s) u[r * p + s] = (double)img[(size_t)(pi * p + r) * W + (pj * p + s)];
+    double *tc = t + (size_t)c * D;
+    affine(We + (size_t)c * D * pp, be ? be + (size_t)c * D : NULL, u, D, pp, tc);
+    if (ce)
+      for (int d = 0; d < D; ++d) tc[d] += (double)ce[(size_t)c * D + d];
+  }
+  free(u);
+}
+
+/*
+ * One aggregation level at one patch (Sections 2.1, 3.2): group k holds the
+ * inputs k*g .. min((k+1)*g, c_in)-1.  Per group: project the learned query,
+ * project every member to a key and a value, per head take the scaled dot
+ * products, a softmax over the members, the weighted sum of the values, then
+ * the output projection of the concatenated heads.
+ * alpha (optional) receives the softmax weights [c_in, heads]; pre (optional)
+ * the concatenated heads before W_o, [G, D].
+ */
+static void level_of_patch(int c_in, int D, int heads, const oracle_level *lv, const double *z /* [c_in, D] */,
+                           double *y /* [G, D] */, double *alpha, double *pre) {
+  const int g = lv->group_size;
+  const int G = groups_of(c_in, g);
+  const int dh = D / heads;
+  const double scale = 1.0 / sqrt((double)dh);
+  double *Q = (double *)malloc(sizeof(double) * (size_t)D);
+  double *K = (double *)malloc(sizeof(double) * (size_t)g * D);
+  double *V = (double *)malloc(sizeof(double) * (size_t)g * D);
+  double *s = (double *)malloc(sizeof(double) * (size_t)g);
+  double *o = (double *)malloc(sizeof(double) * (size_t)D);
+  double *qv = (double *)malloc(sizeof(double) * (size_t)D);
+  for (int k = 0; k < G; ++k) {
+    const int c0 = k * g;
+    const int c1 = (c0 + g < c_in) ? c0 + g : c_in;
+    const int m = c1 - c0;
+    const size_t wo = (size_t)k * D * D, bo = (size_t)k * D;
+    for (int d = 0; d < D; ++d) qv[d] = (double)lv->query[bo + d];
+    affine(lv->Wq + wo, lv->bq ? lv->bq + bo : NULL, qv, D, D, Q);
+    for (int c = 0; c < m; ++c) {
+      affine(lv->Wk + wo, lv->bk ? lv->bk + bo : NULL, z + (size_t)(c0 + c) * D, D, D, K + (size_t)c * D);
+      affine(lv->Wv + wo, lv->bv ? lv->bv + bo : NULL, z + (size_t)(c0 + c) * D, D, D, V + (size_t)c * D);
+    }
+    for (int a = 0; a < heads; ++a) {
+      const int r0 = a * dh;
+      double smax = -INFINITY;
+      for (int c = 0; c < m; ++c) {
+        double acc = 0.0;
+        for (int i = 0; i < dh; ++i) acc += Q[r0 + i] * K[(size_t)c * D + r0 + i];
+        s[c] = acc * scale;
+        if (s[c] > smax) smax = s[c];
+      }
+      double den = 0.0;
+      for (int c = 0; c < m; ++c) {
+        s[c] = exp(s[c] - smax);
+        den += s[c];
+      }
+      for (int c = 0; c < m; ++c) {
+        s[c] /= den;
+        if (alpha) alpha[(size_t)(c0 + c) * heads + a] = s[c];
+      }
+      for (int i = 0; i < dh; ++i) {
+        double acc = 0.0;
+        for (int c = 0; c < m; ++c) acc += s[c] * V[(size_t)c * D + r0 + i];
+        o[r0 + i] = acc;
+      }
+    }
+    if (pre) memcpy(pre + (size_t)k * D, o, sizeof(double) * (size_t)D);
+    affine(lv->Wo + wo, lv->bo ? lv->bo + bo : NULL, o, D, D, y + (size_t)k * D);
+  }
+  free(Q); free(K); free(V); free(s); free(o); free(qv);
+}
+
+/*
+ * Tokens of S sampled patches (sample_b[i], sample_n[i]); tokens is [S, C, D].
+ */
+int oracle_tokenize(int B, int C, int H, int W, int p, int D, const float *x, const float *We,
+                    const float *be, const float *ce, int S, const int32_t *sample_b,
+                    const int32_t *sample_n, double *tokens) {
+  if (p <= 0 || H % p || W % p) return -2;
+  const int N = (H / p) * (W / p);
+  for (int i = 0; i < S; ++i)
+    if (sample_b[i] < 0 || sample_b[i] >= B || sample_n[i] < 0 || sample_n[i] >= N) return -2;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int i = 0; i < S; ++i)
+    tokens_of_patch(C, H, W, p, D, x + (size_t)sample_b[i] * C * H * W, We, be, ce, sample_n[i],
+                    tokens + (size_t)i * C * D);
+  return 0;
+}
+
+/*
+ * One level on S independent patches: z is [S, c_in, D], y is [S, G, D];
+ * alpha [S, c_in, heads] and pre [S, G, D] are optional (NULL to skip).
+ */
+int oracle_aggregate_level(int S, int c_in, int D, int heads, const oracle_level *lv, const double *z,
+                           double *y, double *alpha, double *pre) {
+  if (heads <= 0 || D % heads || lv->group_size < 1 || c_in < 1) return -2;
+  const int G = groups_of(c_in, lv->group_size);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int i = 0; i < S; ++i)
+    level_of_patch(c_in, D, heads, lv, z + (size_t)i * c_in * D, y + (size_t)i * G * D,
+                   alpha ? alpha + (size_t)i * c_in * heads : NULL, pre ? pre + (size_t)i * G * D : NULL);
+  return 0;
+}
+
+/*
+ * The whole path on S sampled patches: tokenize, then every level in turn; the
+ * last level must leave one token.  out is [S, D].
+ */
+int oracle_forward(int B, int C, int H, int W, int p, int D, int heads, const float *x, const float *We,
+                   const float *be, const float *ce, int n_levels, const oracle_level *levels, int S,
+                   const int32_t *sample_b, const int32_t *sample_n, double *out) {
+  if (p <= 0 || H % p || W % p || heads <= 0 || D % heads || n_levels < 1) return -2;
+  const int N = (H / p) * (W / p);
+  int c_in = C, c_max = C;
+  for (int l = 0; l < n_levels; ++l) {
+    if (levels[l].group_size < 1) return -2;
+    c_in = groups_of(c_in, levels[l].group_size);
+    if (c_in > c_max) c_max = c_in;
+  }
+  if (c_in != 1) return -2;
+  for (int i = 0; i < S; ++i)
+    if (sample_b[i] < 0 || sample_b[i] >= B || sample_n[i] < 0 || sample_n[i] >= N) return -2;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int i = 0; i < S; ++i) {
+    double *za = (double *)malloc(sizeof(double) * (size_t)c_max * D);
+    double *zb = (double *)malloc(sizeof(double) * (size_t)c_max * D);
+    tokens_of_patch(C, H, W, p, D, x + (size_t)sample_b[i] * C * H * W, We, be, ce, sample_n[i], za);
+    int c = C;
+    for (int l = 0; l < n_levels; ++l) {
+      level_of_patch(c, D, heads, &levels[l], za, zb, NULL, NULL);
+      c = groups_of(c, levels[l].group_size);
+      double *t = za; za = zb; zb = t;
+    }
+    memcpy(out + (size_t)i * D, za, sizeof(double) * (size_t)D);
+    free(za); free(zb);
+  }
+  return 0;
+}

@@ -1,0 +1,240 @@
+"""Seeded synthetic workloads for the D-CHAG tokenize + hierarchical-aggregate path.
+
+This module only draws random numbers and shapes them: it holds none of the
+method's arithmetic.  Both the CPU oracle and the HIP path read the arrays it
+returns; neither of them is imported here.
+
+Shapes follow the paper's two application domains (Section 5): weather
+reanalysis with about 80 variables on a lat-lon grid, and plant hyperspectral
+images with about 500 contiguous bands.  The data themselves are not
+available, so only their channel counts and rough statistics are borrowed.
+
+Every array is float32.  For a bf16 run every value is first rounded once to
+bf16 (round-to-nearest-even) and stored back as float32, so that the oracle
+(which widens to fp64) and the GPU path (which narrows to bf16, exactly) read
+the same numbers.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+__all__ = [
+    "ShapeCfg", "Level", "Problem", "CONFIGS", "get_config", "n_groups",
+    "level_inputs", "round_to_bf16", "make_problem", "make_tokens", "sample_patches",
+]
+
+
+@dataclass(frozen=True)
+class ShapeCfg:
+    name: str
+    dtype: str                     # "f32" | "bf16"
+    B: int
+    C: int
+    H: int
+    W: int
+    p: int
+    D: int
+    heads: int
+    group_sizes: Sequence[int]     # nominal group size per level, last level must give one group
+    x_kind: str = "gauss"          # "gauss_mu_sigma" | "weather" | "ar1" | "gauss"
+    seed: int = 0
+
+    @property
+    def N(self) -> int:
+        return (self.H // self.p) * (self.W // self.p)
+
+    @property
+    def tokens(self) -> int:
+        return self.B * self.C * self.N
+
+
+def n_groups(c_in: int, g: int) -> int:
+    """Number of contiguous groups of nominal size g covering c_in members (last may be short)."""
+    return (c_in + g - 1) // g
+
+
+def level_inputs(C: int, group_sizes: Sequence[int]) -> List[int]:
+    """Number of input tokens per patch at each level (C, G_1, G_2, ...)."""
+    out = [C]
+    for g in group_sizes:
+        out.append(n_groups(out[-1], g))
+    return out[:-1]
+
+
+CONFIGS = {
+    "tiny": ShapeCfg("tiny", "f32", 1, 8, 32, 64, 4, 128, 4, (4, 2), "gauss_mu_sigma", 0),
+    "weather": ShapeCfg("weather", "bf16", 2, 80, 128, 256, 4, 1024, 16, (8, 10), "weather", 1),
+    "hyperspectral": ShapeCfg("hyperspectral", "bf16", 4, 512, 128, 128, 8, 1024, 16, (32, 16), "ar1", 2),
+    "wide": ShapeCfg("wide", "bf16", 1, 256, 256, 512, 8, 4096, 32, (32, 8), "gauss", 3),
+    "deep": ShapeCfg("deep", "bf16", 2, 1024, 128, 128, 8, 2048, 16, (16, 8, 8), "ar1", 4),
+    "deep1000": ShapeCfg("deep1000", "bf16", 2, 1000, 128, 128, 8, 2048, 16, (16, 8, 8), "ar1", 4),
+}
+
+
+def get_config(name: str) -> ShapeCfg:
+    return CONFIGS[name]
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bf16 (ties to even); result stays float32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+@dataclass
+class Level:
+    group_size: int
+    query: np.ndarray              # [G, D]
+    Wq: np.ndarray                 # [G, D, D]  (out, in)
+    Wk: np.ndarray
+    Wv: np.ndarray
+    Wo: np.ndarray
+    bq: Optional[np.ndarray]       # [G, D] or None
+    bk: Optional[np.ndarray]
+    bv: Optional[np.ndarray]
+    bo: Optional[np.ndarray]
+
+    @property
+    def G(self) -> int:
+        return self.query.shape[0]
+
+
+@dataclass
+class Problem:
+    cfg: ShapeCfg
+    x: np.ndarray                  # [B, C, H, W]
+    We: np.ndarray                 # [C, D, p*p]
+    be: Optional[np.ndarray]       # [C, D]
+    ce: Optional[np.ndarray]       # [C, D]
+    levels: List[Level] = field(default_factory=list)
+
+
+def _normal(rng: np.random.Generator, shape, std: float = 1.0) -> np.ndarray:
+    a = rng.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    return a
+
+
+def _box5(f: np.ndarray) -> np.ndarray:
+    """5x5 box mean over the last two axes with wrap-around (periodic in longitude is fine here)."""
+    acc = np.zeros_like(f)
+    for dy in range(-2, 3):
+        for dx in range(-2, 3):
+            acc += np.roll(np.roll(f, dy, axis=-2), dx, axis=-1)
+    return acc / 25.0
+
+
+def _make_x(cfg: ShapeCfg, rng: np.random.Generator) -> np.ndarray:
+    B, C, H, W = cfg.B, cfg.C, cfg.H, cfg.W
+    if cfg.x_kind == "gauss_mu_sigma":
+        mu = rng.uniform(-1.0, 1.0, size=C).astype(np.float32)
+        sg = rng.uniform(0.5, 2.0, size=C).astype(np.float32)
+        x = _normal(rng, (B, C, H, W)) * sg[None, :, None, None] + mu[None, :, None, None]
+    elif cfg.x_kind == "weather":
+        x = _box5(_normal(rng, (B, C, H, W)))
+        x -= x.mean(axis=(0, 2, 3), keepdims=True)
+        x /= x.std(axis=(0, 2, 3), keepdims=True)
+        sc = rng.uniform(0.5, 2.0, size=C).astype(np.float32)
+        x *= sc[None, :, None, None]
+    elif cfg.x_kind == "ar1":
+        rho = np.float32(0.95)
+        inn = np.float32(np.sqrt(1.0 - 0.95 ** 2))
+        x = np.empty((B, C, H, W), dtype=np.float32)
+        prev = _normal(rng, (B, H, W))
+        x[:, 0] = prev
+        for c in range(1, C):
+            prev = rho * prev + inn * _normal(rng, (B, H, W))
+            x[:, c] = prev
+        x += _normal(rng, (B, C, H, W), 0.1)
+    elif cfg.x_kind == "gauss":
+        x = _normal(rng, (B, C, H, W))
+    else:
+        raise ValueError(f"unknown x_kind {cfg.x_kind!r}")
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+def make_level(rng: np.random.Generator, G: int, g: int, D: int, dtype: str,
+               biases: bool = True, query_scale: float = 1.0) -> Level:
+    fin = 1.0 / np.sqrt(D)
+
+    def fin_arr(shape):
+        return _normal(rng, shape, fin)
+
+    lv = Level(
+        group_size=g,
+        query=_normal(rng, (G, D), query_scale),
+        Wq=fin_arr((G, D, D)), Wk=fin_arr((G, D, D)), Wv=fin_arr((G, D, D)), Wo=fin_arr((G, D, D)),
+        bq=fin_arr((G, D)) if biases else None,
+        bk=fin_arr((G, D)) if biases else None,
+        bv=fin_arr((G, D)) if biases else None,
+        bo=fin_arr((G, D)) if biases else None,
+    )
+    if dtype == "bf16":
+        for k in ("query", "Wq", "Wk", "Wv", "Wo", "bq", "bk", "bv", "bo"):
+            v = getattr(lv, k)
+            if v is not None:
+                setattr(lv, k, round_to_bf16(v))
+    return lv
+
+
+def make_problem(cfg: ShapeCfg, seed: Optional[int] = None, biases: bool = True,
+                 query_scale: float = 1.0, with_x: bool = True) -> Problem:
+    """All inputs and weights of one forward pass, drawn from PCG64(seed).
+
+    Weight matrices are N(0, 1/fan_in) (fan_in = p*p for the tokenizer, D for the
+    attention projections); queries and channel embeddings are N(0, 1); biases,
+    when present, are N(0, 1/fan_in).
+    """
+    seed = cfg.seed if seed is None else seed
+    rng = np.random.Generator(np.random.PCG64(seed))
+    pp = cfg.p * cfg.p
+    x = _make_x(cfg, rng) if with_x else np.zeros((cfg.B, cfg.C, cfg.H, cfg.W), np.float32)
+    We = _normal(rng, (cfg.C, cfg.D, pp), 1.0 / np.sqrt(pp))
+    be = _normal(rng, (cfg.C, cfg.D), 1.0 / np.sqrt(pp)) if biases else None
+    ce = _normal(rng, (cfg.C, cfg.D))
+    if cfg.dtype == "bf16":
+        x, We, ce = round_to_bf16(x), round_to_bf16(We), round_to_bf16(ce)
+        be = round_to_bf16(be) if be is not None else None
+    prob = Problem(cfg, x, We, be, ce)
+    c_in = cfg.C
+    for g in cfg.group_sizes:
+        G = n_groups(c_in, g)
+        prob.levels.append(make_level(rng, G, g, cfg.D, cfg.dtype, biases, query_scale))
+        c_in = G
+    if c_in != 1:
+        raise ValueError("last level must reduce to one group")
+    return prob
+
+
+def make_tokens(B: int, Cin: int, N: int, D: int, dtype: str, seed: int) -> np.ndarray:
+    """A [B, Cin, N, D] token tensor with N(0, 2) entries (the spread level-1 tokens have)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    z = _normal(rng, (B, Cin, N, D), np.sqrt(2.0))
+    return round_to_bf16(z) if dtype == "bf16" else z
+
+
+def sample_patches(B: int, N: int, per_batch: int, seed: int):
+    """A seeded sample of patches: per_batch distinct patch indices for every batch item.
+
+    Returns two int32 arrays (b, n) of length B*per_batch.  The first and the
+    last patch of every batch item are always included when per_batch >= 2.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    bs, ns = [], []
+    for b in range(B):
+        k = min(per_batch, N)
+        pick = set()
+        if k >= 2:
+            pick.update((0, N - 1))
+        while len(pick) < k:
+            pick.add(int(rng.integers(0, N)))
+        for n in sorted(pick):
+            bs.append(b)
+            ns.append(n)
+    return np.asarray(bs, dtype=np.int32), np.asarray(ns, dtype=np.int32)
