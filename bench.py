@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the D-CHAG forward hot path on one MI355X.
+
+One "step" is one dchag_forward call (tokenize + every aggregation level) over one batch of
+seeded synthetic input that is already resident in HBM.  The metric is aggregated
+channel-patch tokens per second, B*C*N / time.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload hyperspectral|weather|...]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_tflops": 157.3}
+
+
+def stage_model(cfg, levels_in, stage, level):
+    """Algorithmic work of one launch of a stage: (bound, amount, unit) with amount in flops or bytes."""
+    es = 4 if cfg.dtype == "f32" else 2
+    B, N, D, h = cfg.B, cfg.N, cfg.D, cfg.heads
+    if stage == "tokenize":
+        by = B * cfg.C * cfg.H * cfg.W * es + cfg.C * D * cfg.p * cfg.p * es + B * cfg.C * N * D * es
+        return "hbm", by
+    cin = levels_in[level - 1]
+    g = cfg.group_sizes[level - 1]
+    G = (cin + g - 1) // g
+    tok = B * cin * N
+    if stage == "vproj":
+        return "mfma", 2.0 * tok * D * D
+    if stage == "oproj":
+        return "mfma", 2.0 * B * G * N * D * D
+    if stage == "fused_vagg":
+        return "mfma", 2.0 * tok * D * (D + h)
+    if stage == "scores":
+        return "hbm", tok * D * es + tok * h * 4
+    if stage == "softmax_agg":
+        return "hbm", tok * D * es + tok * h * 4 + B * G * N * D * es
+    if stage in ("query", "fold"):
+        return "hbm", G * D * D * es
+    return "hbm", 0.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="hyperspectral")
+    ap.add_argument("--cpu-patches", type=int, default=64, help="patches the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-other", action="store_true", help="skip the short weather-like side measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the hierarchy is run locally; no collectives). "
+              "Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2506_21411_amd as dchag
+    from workloads import get_config, level_inputs, make_problem, sample_patches
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    dchag.load_library()
+
+    def prepare(cfg):
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        pr = make_problem(cfg)
+
+        def dev(a):
+            return None if a is None else torch.from_numpy(a).to("cuda").to(tdt).contiguous()
+
+        levels = [dchag.LevelWeights(lv.group_size, dev(lv.query), dev(lv.Wq), dev(lv.Wk), dev(lv.Wv), dev(lv.Wo),
+                                     dev(lv.bq), dev(lv.bk), dev(lv.bv), dev(lv.bo)) for lv in pr.levels]
+        dt = dchag.DCHAG_F32 if cfg.dtype == "f32" else dchag.DCHAG_BF16
+        wsb = dchag.dchag_workspace_bytes(dt, cfg.B, cfg.C, cfg.H, cfg.W, cfg.p, cfg.D, cfg.heads,
+                                          list(cfg.group_sizes), 1)
+        ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        out = torch.empty((cfg.B, cfg.N, cfg.D), dtype=tdt, device="cuda")
+        t = (dev(pr.x), dev(pr.We), dev(pr.be), dev(pr.ce), levels, ws, out)
+        return pr, t
+
+    def step(cfg, t):
+        x, We, be, ce, levels, ws, out = t
+        dchag.dchag_forward(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
+
+    def timed(cfg, t, warmup, steps, profile):
+        for _ in range(warmup):
+            step(cfg, t)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if profile:
+            dchag.dchag_profile_begin()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            step(cfg, t)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        recs = dchag.dchag_profile_end() if profile else []
+        return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps, recs
+
+    cfg = get_config(args.workload)
+    pr, t = prepare(cfg)
+    # untimed-stage pass first (value), then the same steps again with per-launch events (roofline)
+    ms_plain, wall_plain, _ = timed(cfg, t, args.warmup, args.steps, profile=False)
+    ms_prof, _, recs = timed(cfg, t, 1, args.steps, profile=True)
+    ms = ms_plain
+    tokens = cfg.tokens
+    value = tokens / (ms * 1e-3)
+
+    # per-stage averages over the profiled region
+    lv_in = level_inputs(cfg.C, cfg.group_sizes)
+    agg = {}
+    for name, level, dur in recs:
+        a = agg.setdefault((name, level), [0.0, 0])
+        a[0] += dur
+        a[1] += 1
+    stages = []
+    for (name, level), (tot, cnt) in agg.items():
+        bound, amount = stage_model(cfg, lv_in, name, level)
+        avg = tot / cnt
+        if bound == "mfma":
+            ach, peak, unit = amount / (avg * 1e-3) / 1e12, PEAK["mfma_bf16_tflops"] if cfg.dtype == "bf16" else PEAK["fp32_tflops"], "TFLOP/s"
+        else:
+            ach, peak, unit = amount / (avg * 1e-3) / 1e9, PEAK["hbm_gbs"], "GB/s"
+        stages.append({"stage": name, "level": level, "avg_ms": round(avg, 5), "launches": cnt, "bound": bound,
+                       "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
+    stages.sort(key=lambda s: -s["avg_ms"])
+    dom = stages[0] if stages else None
+    roofline = None
+    if dom:
+        roofline = {"kernel": f"{dom['stage']}@level{dom['level']}", "bound": dom["bound"], "achieved": dom["achieved"],
+                    "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": None,
+                    "avg_ms": dom["avg_ms"]}
+
+    # the CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
+    cpu = None
+    if args.cpu_patches > 0:
+        import oracle
+        per_b = max(1, args.cpu_patches // cfg.B)
+        bs, ns = sample_patches(cfg.B, cfg.N, per_b, seed=23)
+        t0 = time.perf_counter()
+        want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns))
+        dt_cpu = time.perf_counter() - t0
+        got = t[6][torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()].to(torch.float64).cpu().numpy()
+        err = float(np.abs(got - want).max() / np.abs(want).max())
+        cpu = {"value": bs.size * cfg.C / dt_cpu, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{bs.size} of {cfg.B * cfg.N} patches ({bs.size * cfg.C} channel-patch tokens), fp64, "
+                         f"{dt_cpu:.1f} s; GPU-vs-oracle max|err|/max|ref| on them = {err:.2e}"}
+
+    other = []
+    if not args.no_other and args.workload == "hyperspectral":
+        del t
+        torch.cuda.empty_cache()
+        c2 = get_config("weather")
+        _, t2 = prepare(c2)
+        ms2, _, _ = timed(c2, t2, 3, 10, profile=False)
+        other.append({"workload": "weather", "tokens": c2.tokens, "ms_per_step": round(ms2, 4),
+                      "value": c2.tokens / (ms2 * 1e-3), "unit": "tokens/s"})
+
+    line = {
+        "metric": "aggregated channel-patch tokens/sec (B*C*N) through tokenize + hierarchical aggregation, forward",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "patch": cfg.p, "N": cfg.N,
+                   "D": cfg.D, "heads": cfg.heads, "group_sizes": list(cfg.group_sizes), "tokens_per_step": tokens},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "stages": stages,
+        "ms_per_step_with_stage_events": ms_prof,
+        "wall_ms_per_step": wall_plain,
+        "other_workloads": other,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

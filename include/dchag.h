@@ -1,0 +1,166 @@
+/*
+ * dchag.h -- C ABI of the MI355X (gfx950) D-CHAG forward library.
+ *
+ * D-CHAG = Distributed Cross-Channel Hierarchical Aggregation.  The library
+ * computes the forward pass of per-channel patch tokenization followed by
+ * hierarchical learned-query cross-channel cross-attention, on ONE GPU:
+ *
+ *   x[B,C,H,W] --tokenize--> t[B,C,N,D] --level 1--> [B,G1,N,D] --...--> out[B,N,D]
+ *
+ * with N = (H/p)*(W/p) patches per image, numbered row by row over the patch
+ * grid; the pixels of a patch are flattened row by row.
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers on the current HIP device, dense,
+ *     row-major, last index fastest, 16-byte aligned.  Element type of every
+ *     tensor is given by `dt` (DCHAG_F32: float, DCHAG_BF16: bfloat16);
+ *     accumulation is always fp32.  The `dchag_level` structs themselves live
+ *     in HOST memory and hold device pointers.
+ *   - The caller owns every buffer (inputs, weights, outputs, workspace).  The
+ *     library allocates no device memory and keeps no state between calls.
+ *     Inputs and weights are only read; outputs are fully overwritten; the
+ *     workspace contents are undefined afterwards.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls are asynchronous on that stream: no device synchronisation happens
+ *     inside.  Calls that share a workspace must be ordered by the caller.
+ *   - Return value: DCHAG_OK (0) or a negative dchag_status.  Arguments are
+ *     validated on the host BEFORE anything is launched; on a validation error
+ *     nothing has been launched and no output has been touched.
+ */
+#ifndef DCHAG_H_
+#define DCHAG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DCHAG_F32 = 0, DCHAG_BF16 = 1 } dchag_dtype;
+
+typedef enum {
+  DCHAG_OK = 0,
+  DCHAG_ERR_NULL = -1,      /* a required pointer is NULL                                   */
+  DCHAG_ERR_SHAPE = -2,     /* sizes that do not fit together (see each call)               */
+  DCHAG_ERR_DTYPE = -3,     /* unknown dtype                                                */
+  DCHAG_ERR_WORKSPACE = -4, /* workspace NULL, misaligned or smaller than required          */
+  DCHAG_ERR_LAUNCH = -5,    /* the HIP runtime refused a launch                             */
+  DCHAG_ERR_ALIGN = -6      /* a tensor pointer is not 16-byte aligned                      */
+} dchag_status;
+
+/*
+ * One aggregation level (paper Section 3.2: "multiple cross-attention layers",
+ * each handling "up to" g channels; Section 3.3: partial-channel aggregation
+ * modules followed by a final cross-attention layer).  A level with Cin inputs
+ * per patch has G = ceil(Cin / group_size) groups; group k holds inputs
+ * k*g .. min((k+1)*g, Cin)-1 and owns slice k of every array below.
+ */
+typedef struct {
+  int32_t group_size;               /* nominal g >= 1; the last group may be shorter              */
+  int32_t reserved;                 /* must be 0                                                  */
+  const void *query;                /* [G, D]    learned query of each group                      */
+  const void *Wq, *Wk, *Wv, *Wo;    /* [G, D, D] row-major (out, in): y = W x                     */
+  const void *bq, *bk, *bv, *bo;    /* [G, D]    each may be NULL (= 0)                           */
+} dchag_level;
+
+/*
+ * Per-channel patch tokenization (paper Section 2.1: every 2-D patch of every
+ * channel is tokenized independently by a convolution with kernel = stride =
+ * patch size; each channel is assigned an ID embedding):
+ *
+ *   tokens[b,c,n,:] = We[c] . vec(patch n of x[b,c]) + be[c] + ce[c]
+ *
+ *   x      [B,C,H,W]   in     We  [C,D,p*p]  in  (the conv weight [D,1,p,p] of channel c)
+ *   be     [C,D] or NULL      ce  [C,D] or NULL  (channel-ID embedding, added)
+ *   tokens [B,C,N,D]   out
+ * Errors: NULL x/We/tokens; B,C,D,p < 1; H % p or W % p != 0; D % 8 != 0.
+ */
+int dchag_tokenize(dchag_dtype dt, int B, int C, int H, int W, int p, int D,
+                   const void *x, const void *We, const void *be, const void *ce,
+                   void *tokens, void *stream);
+
+/*
+ * One level of cross-channel aggregation (paper Section 2.1: a cross-attention
+ * layer reduces the channels to one representation; Section 3.2: one such layer
+ * per group of at most g channels).  For every batch item b, patch n and
+ * group k, with S_k the members of the group, Q = Wq[k] query[k] + bq[k],
+ * d_h = D / heads and per head a (rows a*d_h .. (a+1)*d_h-1):
+ *
+ *   s[c]   = < Q_a , (Wk[k] z[b,c,n] + bk[k])_a > / sqrt(d_h)      c in S_k
+ *   alpha  = softmax over c in S_k of s
+ *   o_a    = sum over c in S_k of alpha[c] (Wv[k] z[b,c,n] + bv[k])_a
+ *   tokens_out[b,k,n,:] = Wo[k] concat_a(o_a) + bo[k]
+ *
+ *   tokens_in  [B,Cin,N,D] in      tokens_out [B,G,N,D] out
+ *   workspace: at least dchag_workspace_bytes(..., which = 0) bytes, 256-byte aligned.
+ * Errors: NULL tokens/lvl/required weight; Cin,N,D,heads < 1; D % heads != 0;
+ * D % 8 != 0; group_size < 1; workspace too small.
+ */
+int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads,
+                          const dchag_level *lvl, const void *tokens_in, void *tokens_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The whole path (paper Section 3.3, run on one GPU: tokenize every channel,
+ * aggregate groups level by level, finish with one cross-attention layer over
+ * what is left):  out[b,n,:] = level_L( ... level_1( tokenize(x) ) ... ).
+ * levels[l] takes the G_{l-1} outputs of the level before it as its inputs
+ * (C for the first); the last level must have exactly one group.
+ *
+ *   out [B,N,D]; workspace: at least dchag_workspace_bytes(..., which = 1) bytes.
+ * Errors: as the two calls above; n_levels < 1; last level leaves more than one group.
+ */
+int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
+                  const void *x, const void *We, const void *be, const void *ce,
+                  int n_levels, const dchag_level *levels, void *out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Workspace size in bytes (0 on invalid arguments).
+ *   which = 0: one dchag_aggregate_level call with Cin = C inputs, N = (H/p)*(W/p)
+ *              (pass H = N, W = 1, p = 1 when only N is known), group size group_sizes[0];
+ *   which = 1: one dchag_forward call with the n_levels nominal group sizes.
+ */
+size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
+                             int n_levels, const int32_t *group_sizes, int which);
+
+/*
+ * Stage timing, a diagnostic for benchmarks (not part of the paper's method).  Between
+ * dchag_profile_begin and dchag_profile_end every kernel the library launches is bracketed
+ * by a pair of HIP events recorded on the call's own stream; dchag_profile_end waits for the
+ * recorded events, writes up to `cap` records in launch order and returns how many there
+ * were in total (or a negative status).  This is the only process-wide state of the
+ * library; it is not thread-safe and it creates HIP events, so it must not be used under
+ * stream capture.  `records` is HOST memory.
+ */
+typedef enum {
+  DCHAG_STAGE_TOKENIZE = 0,        /* per-channel patch embedding                              */
+  DCHAG_STAGE_QUERY = 1,           /* Q = Wq q + bq (weight-only)                              */
+  DCHAG_STAGE_FOLD = 2,            /* query folded into the key weights (weight-only)          */
+  DCHAG_STAGE_SCORES = 3,          /* scores of every token against the folded keys            */
+  DCHAG_STAGE_VPROJ = 4,           /* value projection                                         */
+  DCHAG_STAGE_SOFTMAX_AGG = 5,     /* softmax over the group and weighted sum of the values    */
+  DCHAG_STAGE_OPROJ = 6,           /* output projection                                        */
+  DCHAG_STAGE_FUSED_VAGG = 7       /* value projection + scores + online softmax + sum, fused  */
+} dchag_stage;
+
+typedef struct {
+  int32_t stage;                   /* dchag_stage                                              */
+  int32_t level;                   /* 0 for the tokenizer, 1.. for the aggregation levels      */
+  float ms;                        /* elapsed time between the two events                      */
+} dchag_stage_time;
+
+int dchag_profile_begin(void);
+int dchag_profile_end(dchag_stage_time *records, int cap);
+
+/* Static, never-NULL description of a status code. */
+const char *dchag_strerror(int status);
+
+/* Library version, "major.minor". */
+const char *dchag_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCHAG_H_ */

@@ -1,0 +1,208 @@
+"""ctypes binding of include/dchag.h.  Argument marshalling only.
+
+Tensors are torch tensors on the current ROCm device (torch is used for device memory and
+streams, nothing else); they must be contiguous and of dtype float32 (DCHAG_F32) or
+bfloat16 (DCHAG_BF16).  Each function has the name and the meaning of the C entry point.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+DCHAG_F32 = 0
+DCHAG_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdchag.so")
+_lib = None
+
+
+class DchagError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"dchag status {status}: {message}")
+        self.status = status
+
+
+class _CLevel(ctypes.Structure):
+    _fields_ = [("group_size", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("query", ctypes.c_void_p),
+                ("Wq", ctypes.c_void_p), ("Wk", ctypes.c_void_p), ("Wv", ctypes.c_void_p), ("Wo", ctypes.c_void_p),
+                ("bq", ctypes.c_void_p), ("bk", ctypes.c_void_p), ("bv", ctypes.c_void_p), ("bo", ctypes.c_void_p)]
+
+
+class _CStageTime(ctypes.Structure):
+    _fields_ = [("stage", ctypes.c_int32), ("level", ctypes.c_int32), ("ms", ctypes.c_float)]
+
+
+STAGE_NAMES = {0: "tokenize", 1: "query", 2: "fold", 3: "scores", 4: "vproj", 5: "softmax_agg", 6: "oproj",
+               7: "fused_vagg"}
+
+
+@dataclass
+class LevelWeights:
+    """Device tensors of one aggregation level: query [G,D]; Wq..Wo [G,D,D]; biases [G,D] or None."""
+    group_size: int
+    query: torch.Tensor
+    Wq: torch.Tensor
+    Wk: torch.Tensor
+    Wv: torch.Tensor
+    Wo: torch.Tensor
+    bq: Optional[torch.Tensor] = None
+    bk: Optional[torch.Tensor] = None
+    bv: Optional[torch.Tensor] = None
+    bo: Optional[torch.Tensor] = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libdchag.so (built by `python -m paper_2506_21411_amd.build`); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2506_21411_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i, vp, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    lib.dchag_tokenize.restype = i
+    lib.dchag_tokenize.argtypes = [i] * 7 + [vp] * 6
+    lib.dchag_aggregate_level.restype = i
+    lib.dchag_aggregate_level.argtypes = [i] * 6 + [ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
+    lib.dchag_forward.restype = i
+    lib.dchag_forward.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, sz, vp]
+    lib.dchag_workspace_bytes.restype = sz
+    lib.dchag_workspace_bytes.argtypes = [i] * 9 + [ctypes.POINTER(ctypes.c_int32), i]
+    lib.dchag_strerror.restype = ctypes.c_char_p
+    lib.dchag_strerror.argtypes = [i]
+    lib.dchag_version.restype = ctypes.c_char_p
+    lib.dchag_profile_begin.restype = i
+    lib.dchag_profile_end.restype = i
+    lib.dchag_profile_end.argtypes = [ctypes.POINTER(_CStageTime), i]
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise DchagError(status, load_library().dchag_strerror(status).decode())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DCHAG_F32
+    if t.dtype == torch.bfloat16:
+        return DCHAG_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor], like: Optional[torch.Tensor] = None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    if like is not None and t.dtype != like.dtype:
+        raise TypeError("all tensors of a call must share one dtype")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _clevel(lv: LevelWeights, like: torch.Tensor) -> _CLevel:
+    c = _CLevel()
+    c.group_size = int(lv.group_size)
+    c.reserved = 0
+    for name in ("query", "Wq", "Wk", "Wv", "Wo", "bq", "bk", "bv", "bo"):
+        setattr(c, name, _ptr(getattr(lv, name), like))
+    return c
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def dchag_workspace_bytes(dt: int, B: int, C: int, H: int, W: int, p: int, D: int, heads: int,
+                          group_sizes: Sequence[int], which: int) -> int:
+    arr = (ctypes.c_int32 * len(group_sizes))(*[int(g) for g in group_sizes])
+    return int(load_library().dchag_workspace_bytes(dt, B, C, H, W, p, D, heads, len(group_sizes), arr, which))
+
+
+def dchag_tokenize(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                   p: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """tokens[B,C,N,D] of x[B,C,H,W] with We[C,D,p*p], be/ce [C,D] or None."""
+    B, C, H, W = x.shape
+    D = We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    N = (H // p) * (W // p) if p > 0 else 0
+    if out is None:
+        out = torch.empty((B, C, N, D), dtype=x.dtype, device=x.device)
+    _check(load_library().dchag_tokenize(_dt(x), B, C, H, W, p, D, _ptr(x), _ptr(We, x), _ptr(be, x), _ptr(ce, x),
+                                         _ptr(out, x), _stream(stream)))
+    return out
+
+
+def dchag_aggregate_level(tokens_in: torch.Tensor, level: LevelWeights, heads: int,
+                          out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                          stream=None) -> torch.Tensor:
+    """tokens_out[B,G,N,D] of tokens_in[B,Cin,N,D] for one level."""
+    B, Cin, N, D = tokens_in.shape
+    g = int(level.group_size)
+    G = (Cin + g - 1) // g if g > 0 else 0
+    dt = _dt(tokens_in)
+    if workspace is None:
+        workspace = _workspace(dchag_workspace_bytes(dt, B, Cin, N, 1, 1, D, heads, [g], 0), tokens_in.device)
+    if out is None:
+        out = torch.empty((B, G, N, D), dtype=tokens_in.dtype, device=tokens_in.device)
+    cl = _clevel(level, tokens_in)
+    _check(load_library().dchag_aggregate_level(dt, B, Cin, N, D, heads, ctypes.byref(cl), _ptr(tokens_in),
+                                                _ptr(out, tokens_in), ctypes.c_void_p(workspace.data_ptr()),
+                                                workspace.numel(), _stream(stream)))
+    return out
+
+
+def dchag_forward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                  levels: List[LevelWeights], p: int, heads: int, out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """out[B,N,D]: tokenize, then every level in turn (the last must leave one group)."""
+    B, C, H, W = x.shape
+    D = We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    N = (H // p) * (W // p) if p > 0 else 0
+    dt = _dt(x)
+    if workspace is None:
+        workspace = _workspace(dchag_workspace_bytes(dt, B, C, H, W, p, D, heads, [lv.group_size for lv in levels], 1),
+                               x.device)
+    if out is None:
+        out = torch.empty((B, N, D), dtype=x.dtype, device=x.device)
+    arr = (_CLevel * len(levels))(*[_clevel(lv, x) for lv in levels])
+    _check(load_library().dchag_forward(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x), _ptr(ce, x),
+                                        len(levels), arr, _ptr(out, x), ctypes.c_void_p(workspace.data_ptr()),
+                                        workspace.numel(), _stream(stream)))
+    return out
+
+
+def dchag_profile_begin() -> None:
+    """Start bracketing every kernel launch of the library with HIP events (benchmark diagnostic)."""
+    _check(load_library().dchag_profile_begin())
+
+
+def dchag_profile_end(cap: int = 1 << 16):
+    """Stop stage timing; returns [(stage name, level, ms)] in launch order."""
+    buf = (_CStageTime * cap)()
+    n = load_library().dchag_profile_end(buf, cap)
+    if n < 0:
+        _check(n)
+    return [(STAGE_NAMES.get(buf[j].stage, str(buf[j].stage)), int(buf[j].level), float(buf[j].ms))
+            for j in range(min(n, cap))]

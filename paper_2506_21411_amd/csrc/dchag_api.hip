@@ -1,0 +1,413 @@
+// C ABI of the D-CHAG forward library: argument validation, workspace layout, the host-side
+// level scheduler, and kernel launches.  Every step of the path runs in the HIP kernels of
+// this directory; there is no CPU fallback.
+#include "../../include/dchag.h"
+
+#include <hip/hip_runtime.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "dchag_dev.h"
+#include "k_generic.h"
+#include "k_mfma.h"
+
+using namespace dchag;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline size_t elem_size(dchag_dtype dt) { return dt == DCHAG_F32 ? 4 : 2; }
+inline bool misaligned(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u); }
+inline int groups_of(int c_in, int g) { return (c_in + g - 1) / g; }
+
+// Workspace of one aggregation level, carved in this order (every piece 256-byte aligned).
+struct LevelWs {
+  size_t qp, mf, mb, s, v, o, total;
+};
+
+LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g) {
+  const int G = groups_of(Cin, g);
+  const size_t es = elem_size(dt);
+  LevelWs w;
+  size_t off = 0;
+  w.qp = off; off += align_up((size_t)G * D * 4);
+  w.mf = off; off += align_up((size_t)G * heads * D * 4);
+  w.mb = off; off += align_up((size_t)G * heads * D * 2);
+  w.s = off;  off += align_up((size_t)B * Cin * N * heads * 4);
+  w.v = off;  off += align_up((size_t)B * Cin * N * D * es);
+  w.o = off;  off += align_up((size_t)B * G * N * D * es);
+  w.total = off;
+  return w;
+}
+
+struct ForwardWs {
+  size_t tokens, ping, pong, level, total;
+};
+
+// group_sizes has n_levels entries; returns total = 0 when the chain does not end in one group.
+ForwardWs forward_ws(dchag_dtype dt, int B, int C, int N, int D, int heads, int n_levels,
+                     const int32_t* group_sizes) {
+  ForwardWs w{};
+  const size_t es = elem_size(dt);
+  size_t off = 0;
+  w.tokens = off; off += align_up((size_t)B * C * N * D * es);
+  int c_in = C;
+  size_t lvl_max = 0, inter_max = 0;
+  for (int l = 0; l < n_levels; ++l) {
+    const int g = group_sizes[l];
+    if (g < 1) return ForwardWs{};
+    const size_t t = level_ws(dt, B, c_in, N, D, heads, g).total;
+    if (t > lvl_max) lvl_max = t;
+    c_in = groups_of(c_in, g);
+    if (l + 1 < n_levels) {
+      const size_t it = align_up((size_t)B * c_in * N * D * es);
+      if (it > inter_max) inter_max = it;
+    }
+  }
+  if (c_in != 1) return ForwardWs{};
+  w.ping = off; off += inter_max;
+  w.pong = off; off += inter_max;
+  w.level = off; off += lvl_max;
+  w.total = off;
+  return w;
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? DCHAG_OK : DCHAG_ERR_LAUNCH; }
+
+// Optional stage timing (dchag_profile_begin / dchag_profile_end): an event pair per launch.
+struct StageRecord {
+  hipEvent_t start, stop;
+  int stage, level;
+};
+bool g_profiling = false;
+int g_level = 0;
+std::vector<StageRecord> g_records;
+
+struct StageTimer {
+  hipStream_t st;
+  bool on;
+  StageRecord rec;
+  StageTimer(int stage, hipStream_t s) : st(s), on(g_profiling) {
+    if (!on) return;
+    rec.stage = stage;
+    rec.level = g_level;
+    if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(rec.start, st);
+  }
+  ~StageTimer() {
+    if (!on) return;
+    (void)hipEventRecord(rec.stop, st);
+    g_records.push_back(rec);
+  }
+};
+
+bool force_generic() {
+  // DCHAG_GEMM=generic routes the bf16 projections through the fp32-FMA tile kernel (debug aid).
+  const char* e = getenv("DCHAG_GEMM");
+  return e && strcmp(e, "generic") == 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// launches
+// ------------------------------------------------------------------------------------------
+template <typename T>
+int launch_tokenize(int B, int C, int H, int W, int p, int D, const T* x, const T* We, const T* be,
+                    const T* ce, T* tokens, hipStream_t st) {
+  constexpr int TP = 16;
+  const int N = (H / p) * (W / p);
+  dim3 grid((N + TP - 1) / TP, C, B);
+  const size_t lds = (size_t)TP * p * p * sizeof(float);
+  StageTimer tm(DCHAG_STAGE_TOKENIZE, st);
+  k_tokenize_generic<T, TP><<<grid, 256, lds, st>>>(C, H, W, p, D, x, We, be, ce, tokens);
+  return launch_status();
+}
+
+template <typename T>
+int launch_linear_generic(int B, int D, RowBlocks rb, const T* A, const T* Wt, const T* bias, T* Y,
+                          hipStream_t st) {
+  dim3 grid((D + 63) / 64, (rb.rows_per_group + 63) / 64, B * rb.G);
+  k_linear_generic<T><<<grid, 256, 0, st>>>(D, rb, A, Wt, bias, Y);
+  return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, int SH>
+int launch_linear_mfma_cfg(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, const bf16* bias,
+                           bf16* Y, hipStream_t st) {
+  TileWork tw;
+  tw.n_tiles = D / BN;
+  tw.m_tiles = (rb.rows_per_group + BM - 1) / BM;
+  tw.nb = B;
+  tw.total = tw.n_tiles * tw.m_tiles * B * rb.G;
+  const int per = (tw.total + kXcds - 1) / kXcds;
+  const size_t lds = (size_t)2 * (BM + BN) * 128;
+  auto kern = k_linear_mfma<BM, BN, WM, WN, SH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    attr_set = true;
+  }
+  kern<<<dim3(per * kXcds), dim3(WM * WN * 64), lds, st>>>(D, rb, tw, A, Wt, bias, Y);
+  return launch_status();
+}
+
+int mfma_variant() {
+  // DCHAG_MFMA_TILE selects the block tiling of the bf16 projection kernel (tuning aid).
+  const char* e = getenv("DCHAG_MFMA_TILE");
+  return e ? atoi(e) : 0;
+}
+
+template <typename T>
+int launch_linear(int B, int D, RowBlocks rb, const T* A, const T* Wt, const T* bias, T* Y, hipStream_t st);
+
+template <>
+int launch_linear<float>(int B, int D, RowBlocks rb, const float* A, const float* Wt, const float* bias,
+                         float* Y, hipStream_t st) {
+  return launch_linear_generic<float>(B, D, rb, A, Wt, bias, Y, st);
+}
+
+template <>
+int launch_linear<bf16>(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, const bf16* bias, bf16* Y,
+                        hipStream_t st) {
+  if (D % 256 == 0 && !force_generic()) {
+    switch (mfma_variant()) {
+      case 1: return launch_linear_mfma_cfg<256, 256, 2, 4, 0>(B, D, rb, A, Wt, bias, Y, st);
+      case 2: return launch_linear_mfma_cfg<256, 128, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st);
+      case 3: return launch_linear_mfma_cfg<128, 128, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st);
+      case 4: return launch_linear_mfma_cfg<256, 256, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st);
+      default: return launch_linear_mfma_cfg<256, 256, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st);
+    }
+  }
+  return launch_linear_generic<bf16>(B, D, rb, A, Wt, bias, Y, st);
+}
+
+// One aggregation level: weight-only prep, scores, value projection, softmax-weighted sum,
+// output projection.
+template <typename T>
+int run_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dchag_level* lv, const T* zin,
+              T* zout, unsigned char* ws, hipStream_t st) {
+  const int g = lv->group_size;
+  const int G = groups_of(Cin, g);
+  const LevelWs w = level_ws(dt, B, Cin, N, D, heads, g);
+  float* Qp = reinterpret_cast<float*>(ws + w.qp);
+  float* Mf = reinterpret_cast<float*>(ws + w.mf);
+  float* S = reinterpret_cast<float*>(ws + w.s);
+  T* V = reinterpret_cast<T*>(ws + w.v);
+  T* O = reinterpret_cast<T*>(ws + w.o);
+  int rc;
+
+  {
+    StageTimer tm(DCHAG_STAGE_QUERY, st);
+    k_project_query<T><<<dim3((D + 3) / 4, G), 256, 0, st>>>(
+        D, static_cast<const T*>(lv->query), static_cast<const T*>(lv->Wq), static_cast<const T*>(lv->bq), Qp);
+    if ((rc = launch_status())) return rc;
+  }
+  {
+    StageTimer tm(DCHAG_STAGE_FOLD, st);
+    k_fold_query_into_key<T><<<dim3((D + 255) / 256, heads, G), 256, 0, st>>>(
+        D, heads, static_cast<const T*>(lv->Wk), Qp, Mf, nullptr);
+    if ((rc = launch_status())) return rc;
+  }
+  {
+    StageTimer tm(DCHAG_STAGE_SCORES, st);
+    const long T_total = (long)B * Cin * N;
+    k_scores_generic<T, 8><<<dim3((unsigned)((T_total + 3) / 4)), 256, 0, st>>>(T_total, Cin, N, D, heads, g, zin,
+                                                                               Mf, S);
+    if ((rc = launch_status())) return rc;
+  }
+  {
+    StageTimer tm(DCHAG_STAGE_VPROJ, st);
+    RowBlocks rbv{G, Cin * N, g * N};
+    if ((rc = launch_linear<T>(B, D, rbv, zin, static_cast<const T*>(lv->Wv), static_cast<const T*>(lv->bv), V, st)))
+      return rc;
+  }
+  {
+    StageTimer tm(DCHAG_STAGE_SOFTMAX_AGG, st);
+    k_softmax_aggregate_generic<T><<<dim3(N, G, B), 256, 0, st>>>(Cin, N, D, heads, g, S, V, O);
+    if ((rc = launch_status())) return rc;
+  }
+  StageTimer tm(DCHAG_STAGE_OPROJ, st);
+  RowBlocks rbo{G, G * N, N};
+  return launch_linear<T>(B, D, rbo, O, static_cast<const T*>(lv->Wo), static_cast<const T*>(lv->bo), zout, st);
+}
+
+int check_level(const dchag_level* lv) {
+  if (!lv) return DCHAG_ERR_NULL;
+  if (lv->group_size < 1 || lv->reserved != 0) return DCHAG_ERR_SHAPE;
+  if (!lv->query || !lv->Wq || !lv->Wk || !lv->Wv || !lv->Wo) return DCHAG_ERR_NULL;
+  const void* ps[] = {lv->query, lv->Wq, lv->Wk, lv->Wv, lv->Wo, lv->bq, lv->bk, lv->bv, lv->bo};
+  for (const void* p : ps)
+    if (misaligned(p)) return DCHAG_ERR_ALIGN;
+  return DCHAG_OK;
+}
+
+int check_tokenize_shape(int B, int C, int H, int W, int p, int D) {
+  if (B < 1 || C < 1 || H < 1 || W < 1 || p < 1 || D < 1) return DCHAG_ERR_SHAPE;
+  if (H % p || W % p || D % 8) return DCHAG_ERR_SHAPE;
+  if (p > 32 || C > 65535 || B > 65535) return DCHAG_ERR_SHAPE;
+  if ((size_t)B * C * (size_t)(H / p) * (W / p) * D >= ((size_t)1 << 40)) return DCHAG_ERR_SHAPE;
+  return DCHAG_OK;
+}
+
+int check_level_shape(int B, int Cin, int N, int D, int heads, int g) {
+  if (B < 1 || Cin < 1 || N < 1 || D < 1 || heads < 1 || g < 1) return DCHAG_ERR_SHAPE;
+  if (D % heads || D % 8) return DCHAG_ERR_SHAPE;
+  const int G = groups_of(Cin, g);
+  if ((long)B * G > 65535 || B > 65535 || G > 65535 || heads > 65535) return DCHAG_ERR_SHAPE;
+  if ((long)g * N > (1L << 30) || (long)Cin * N > (1L << 30)) return DCHAG_ERR_SHAPE;
+  return DCHAG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dchag_version(void) { return "0.1"; }
+
+int dchag_profile_begin(void) {
+  for (StageRecord& r : g_records) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_records.clear();
+  g_profiling = true;
+  return DCHAG_OK;
+}
+
+int dchag_profile_end(dchag_stage_time* records, int cap) {
+  g_profiling = false;
+  int n = 0, rc = DCHAG_OK;
+  for (StageRecord& r : g_records) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+      rc = DCHAG_ERR_LAUNCH;
+    if (records && n < cap) {
+      records[n].stage = r.stage;
+      records[n].level = r.level;
+      records[n].ms = ms;
+    }
+    ++n;
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_records.clear();
+  return rc ? rc : n;
+}
+
+const char* dchag_strerror(int status) {
+  switch (status) {
+    case DCHAG_OK: return "ok";
+    case DCHAG_ERR_NULL: return "a required pointer is NULL";
+    case DCHAG_ERR_SHAPE: return "sizes do not fit together";
+    case DCHAG_ERR_DTYPE: return "unknown dtype";
+    case DCHAG_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DCHAG_ERR_LAUNCH: return "kernel launch failed";
+    case DCHAG_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+    default: return "unknown status";
+  }
+}
+
+size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, int n_levels,
+                             const int32_t* group_sizes, int which) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return 0;
+  if (!group_sizes || n_levels < 1 || p < 1 || H < 1 || W < 1 || H % p || W % p) return 0;
+  const int N = (H / p) * (W / p);
+  if (check_level_shape(B, C, N, D, heads, group_sizes[0]) != DCHAG_OK) return 0;
+  if (which == 0) return level_ws(dt, B, C, N, D, heads, group_sizes[0]).total;
+  if (which == 1) return forward_ws(dt, B, C, N, D, heads, n_levels, group_sizes).total;
+  return 0;
+}
+
+int dchag_tokenize(dchag_dtype dt, int B, int C, int H, int W, int p, int D, const void* x, const void* We,
+                   const void* be, const void* ce, void* tokens, void* stream) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
+  if (!x || !We || !tokens) return DCHAG_ERR_NULL;
+  int rc = check_tokenize_shape(B, C, H, W, p, D);
+  if (rc) return rc;
+  if (misaligned(x) || misaligned(We) || misaligned(be) || misaligned(ce) || misaligned(tokens)) return DCHAG_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (dt == DCHAG_F32)
+    return launch_tokenize<float>(B, C, H, W, p, D, static_cast<const float*>(x), static_cast<const float*>(We),
+                                  static_cast<const float*>(be), static_cast<const float*>(ce),
+                                  static_cast<float*>(tokens), st);
+  return launch_tokenize<bf16>(B, C, H, W, p, D, static_cast<const bf16*>(x), static_cast<const bf16*>(We),
+                               static_cast<const bf16*>(be), static_cast<const bf16*>(ce),
+                               static_cast<bf16*>(tokens), st);
+}
+
+int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dchag_level* lvl,
+                          const void* tokens_in, void* tokens_out, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
+  if (!tokens_in || !tokens_out) return DCHAG_ERR_NULL;
+  int rc = check_level(lvl);
+  if (rc) return rc;
+  if ((rc = check_level_shape(B, Cin, N, D, heads, lvl->group_size))) return rc;
+  if (misaligned(tokens_in) || misaligned(tokens_out)) return DCHAG_ERR_ALIGN;
+  const size_t need = level_ws(dt, B, Cin, N, D, heads, lvl->group_size).total;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < need)
+    return DCHAG_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  g_level = 1;
+  if (dt == DCHAG_F32)
+    return run_level<float>(dt, B, Cin, N, D, heads, lvl, static_cast<const float*>(tokens_in),
+                            static_cast<float*>(tokens_out), ws, st);
+  return run_level<bf16>(dt, B, Cin, N, D, heads, lvl, static_cast<const bf16*>(tokens_in),
+                         static_cast<bf16*>(tokens_out), ws, st);
+}
+
+int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                  const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                  void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
+  if (!x || !We || !out || !levels) return DCHAG_ERR_NULL;
+  if (n_levels < 1 || n_levels > 16) return DCHAG_ERR_SHAPE;
+  int rc = check_tokenize_shape(B, C, H, W, p, D);
+  if (rc) return rc;
+  const int N = (H / p) * (W / p);
+  int32_t gs[16];
+  int c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    if ((rc = check_level(&levels[l]))) return rc;
+    if ((rc = check_level_shape(B, c_in, N, D, heads, levels[l].group_size))) return rc;
+    gs[l] = levels[l].group_size;
+    c_in = groups_of(c_in, gs[l]);
+  }
+  if (c_in != 1) return DCHAG_ERR_SHAPE;
+  if (misaligned(x) || misaligned(We) || misaligned(be) || misaligned(ce) || misaligned(out)) return DCHAG_ERR_ALIGN;
+  const ForwardWs w = forward_ws(dt, B, C, N, D, heads, n_levels, gs);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
+      workspace_bytes < w.total)
+    return DCHAG_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+
+  g_level = 0;
+  if ((rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, stream))) return rc;
+  const void* zin = ws + w.tokens;
+  c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    g_level = l + 1;
+    void* zout = (l + 1 == n_levels) ? out : static_cast<void*>(ws + ((l & 1) ? w.pong : w.ping));
+    if (dt == DCHAG_F32)
+      rc = run_level<float>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const float*>(zin),
+                            static_cast<float*>(zout), ws + w.level, st);
+    else
+      rc = run_level<bf16>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
+                           static_cast<bf16*>(zout), ws + w.level, st);
+    if (rc) return rc;
+    zin = zout;
+    c_in = groups_of(c_in, gs[l]);
+  }
+  return DCHAG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+include/dchag.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2506_21411_amd as dchag
+from paper_2506_21411_amd.binding import _CLevel
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # never dereferenced: every call below fails validation first
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dchag.library_path()):
+        from paper_2506_21411_amd.build import build
+        build(verbose=False)
+    return dchag.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dchag.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dchag_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"dchag_tokenize", "dchag_aggregate_level", "dchag_forward", "dchag_workspace_bytes",
+            "dchag_strerror", "dchag_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in dchag.h but not exported"
+
+
+def test_strerror_and_version(lib):
+    assert lib.dchag_version().decode().count(".") == 1
+    for s in range(-6, 1):
+        assert lib.dchag_strerror(s)
+    assert lib.dchag_strerror(-99) == b"unknown status"
+
+
+def level(g=4, **over):
+    c = _CLevel()
+    c.group_size, c.reserved = g, 0
+    for n in ("query", "Wq", "Wk", "Wv", "Wo"):
+        setattr(c, n, FAKE)
+    for k, v in over.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_tokenize_validation(lib):
+    t = lib.dchag_tokenize
+    assert t(0, 1, 8, 32, 64, 4, 128, None, FAKE, None, None, FAKE, None) == -1
+    assert t(0, 1, 8, 32, 64, 4, 128, FAKE, FAKE, None, None, None, None) == -1
+    assert t(0, 1, 8, 30, 64, 4, 128, FAKE, FAKE, None, None, FAKE, None) == -2      # H % p
+    assert t(0, 1, 8, 32, 62, 4, 128, FAKE, FAKE, None, None, FAKE, None) == -2      # W % p
+    assert t(0, 1, 8, 32, 64, 4, 124, FAKE, FAKE, None, None, FAKE, None) == -2      # D % 8
+    assert t(0, 0, 8, 32, 64, 4, 128, FAKE, FAKE, None, None, FAKE, None) == -2      # B < 1
+    assert t(7, 1, 8, 32, 64, 4, 128, FAKE, FAKE, None, None, FAKE, None) == -3      # dtype
+    assert t(0, 1, 8, 32, 64, 4, 128, FAKE + 4, FAKE, None, None, FAKE, None) == -6  # alignment
+
+
+def test_aggregate_level_validation(lib):
+    a = lib.dchag_aggregate_level
+    lv = level(4)
+    assert a(0, 1, 8, 128, 128, 4, None, FAKE, FAKE, FAKE, 1 << 30, None) == -1
+    assert a(0, 1, 8, 128, 128, 4, ctypes.byref(lv), None, FAKE, FAKE, 1 << 30, None) == -1
+    assert a(0, 1, 8, 128, 128, 3, ctypes.byref(lv), FAKE, FAKE, FAKE, 1 << 30, None) == -2   # D % heads
+    assert a(0, 1, 8, 128, 128, 4, ctypes.byref(level(0)), FAKE, FAKE, FAKE, 1 << 30, None) == -2
+    assert a(0, 1, 8, 128, 128, 4, ctypes.byref(level(4, Wv=None)), FAKE, FAKE, FAKE, 1 << 30, None) == -1
+    assert a(0, 1, 8, 128, 128, 4, ctypes.byref(lv), FAKE, FAKE, None, 1 << 30, None) == -4
+    assert a(0, 1, 8, 128, 128, 4, ctypes.byref(lv), FAKE, FAKE, FAKE, 16, None) == -4          # too small
+    assert a(0, 1, 8, 128, 128, 4, ctypes.byref(lv), FAKE, FAKE, FAKE + 16, 1 << 30, None) == -4  # misaligned
+
+
+def test_forward_validation(lib):
+    f = lib.dchag_forward
+    two = (_CLevel * 2)(level(4), level(2))
+    bad_chain = (_CLevel * 2)(level(4), level(1))        # leaves two groups
+    args = lambda lv, n, ws=FAKE, wsb=1 << 40: (0, 1, 8, 32, 64, 4, 128, 4, FAKE, FAKE, None, None, n, lv,
+                                                 FAKE, ws, wsb, None)
+    assert f(*args(two, 0)) == -2
+    assert f(*args(bad_chain, 2)) == -2
+    assert f(*args(two, 2, wsb=1024)) == -4
+    assert f(*args(two, 2, ws=None)) == -4
+    assert f(*args(None, 2)) == -1
+
+
+def test_workspace_bytes(lib):
+    w0 = dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 128, 1, 1, 128, 4, [4], 0)
+    w1 = dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 32, 64, 4, 128, 4, [4, 2], 1)
+    assert w0 > 0 and w1 > w0 and w0 % 256 == 0 and w1 % 256 == 0
+    assert dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 32, 64, 4, 128, 4, [4, 1], 1) == 0   # bad chain
+    assert dchag.dchag_workspace_bytes(5, 1, 8, 32, 64, 4, 128, 4, [4, 2], 1) == 0
+    # bf16 tensors are half the size of fp32 ones
+    b = dchag.dchag_workspace_bytes(dchag.DCHAG_BF16, 4, 512, 128, 128, 8, 1024, 16, [32, 16], 1)
+    assert b >= 4 * 512 * 256 * 1024 * 2

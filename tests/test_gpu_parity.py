@@ -1,0 +1,197 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.
+
+Error measure (the target gives only a number): for an output tensor y and the oracle's y^,
+    err = max_i |y_i - y^_i| / max_i |y^_i|
+must stay below 2e-2 for bf16 (bf16 storage, fp32 accumulation) and 1e-4 for fp32.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_21411_amd as dchag
+from workloads import ShapeCfg, get_config, make_problem, make_tokens, n_groups, sample_patches
+from workloads import make_level
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a, dtype):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to("cuda").to(TDT[dtype]).contiguous()
+
+
+def dev_level(lv, dtype):
+    return dchag.LevelWeights(lv.group_size, dev(lv.query, dtype), dev(lv.Wq, dtype), dev(lv.Wk, dtype),
+                              dev(lv.Wv, dtype), dev(lv.Wo, dtype), dev(lv.bq, dtype), dev(lv.bk, dtype),
+                              dev(lv.bv, dtype), dev(lv.bo, dtype))
+
+
+def rel_err(got, want):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape
+    assert np.isfinite(got).all()
+    return float(np.abs(got - want).max() / np.abs(want).max())
+
+
+def host(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def run_forward(pr):
+    cfg = pr.cfg
+    d = cfg.dtype
+    out = dchag.dchag_forward(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
+                              [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    return out
+
+
+def cfg_of(**kw):
+    base = dict(name="t", dtype="f32", B=2, C=6, H=8, W=12, p=2, D=32, heads=4, group_sizes=(3, 2),
+                x_kind="gauss_mu_sigma", seed=3)
+    base.update(kw)
+    return ShapeCfg(**base)
+
+
+# ------------------------------------------------------------------------------------------
+# tokenizer
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kw", [
+    dict(B=2, C=5, H=8, W=12, p=2, D=40),                # N = 24: one full 16-patch tile and a ragged tail
+    dict(B=1, C=3, H=20, W=28, p=4, D=256),              # N = 35
+    dict(B=1, C=2, H=8, W=8, p=8, D=64),                 # N = 1
+    dict(B=3, C=1, H=3, W=5, p=1, D=8),                  # 1x1 patches, one channel
+])
+def test_tokenize_matches_oracle(dtype, kw):
+    cfg = cfg_of(dtype=dtype, heads=1, group_sizes=(kw["C"],), **kw)
+    say(f"tokenize {dtype} {kw}")
+    pr = make_problem(cfg)
+    t = dchag.dchag_tokenize(dev(pr.x, dtype), dev(pr.We, dtype), dev(pr.be, dtype), dev(pr.ce, dtype), cfg.p)
+    torch.cuda.synchronize()
+    want = oracle.tokenize(pr.x, pr.We, pr.be, pr.ce, cfg.p).reshape(cfg.B, cfg.N, cfg.C, cfg.D).transpose(0, 2, 1, 3)
+    assert rel_err(host(t), want) < TOL[dtype]
+
+
+def test_tokenize_without_bias_and_embedding():
+    cfg = cfg_of(B=1, C=3, H=8, W=8, p=4, D=16, heads=1, group_sizes=(3,))
+    pr = make_problem(cfg)
+    t = dchag.dchag_tokenize(dev(pr.x, "f32"), dev(pr.We, "f32"), None, None, cfg.p)
+    want = oracle.tokenize(pr.x, pr.We, None, None, cfg.p).reshape(cfg.B, cfg.N, cfg.C, cfg.D).transpose(0, 2, 1, 3)
+    assert rel_err(host(t), want) < 1e-5
+
+
+# ------------------------------------------------------------------------------------------
+# one aggregation level
+# ------------------------------------------------------------------------------------------
+LEVEL_CASES = [
+    # dtype, B, Cin, N, D, heads, g
+    ("f32", 2, 6, 10, 32, 4, 3),
+    ("f32", 1, 7, 5, 24, 3, 3),          # uneven last group (3,3,1), D not a multiple of 64
+    ("f32", 1, 4, 3, 16, 2, 1),          # groups of one
+    ("f32", 1, 5, 1, 8, 1, 9),           # one short group, one patch, one head
+    ("bf16", 2, 8, 24, 64, 4, 4),        # bf16 on the generic projection kernel (D % 256 != 0)
+    ("bf16", 2, 12, 40, 256, 4, 8),      # MFMA projection: rows 320 and 160 per block -> ragged tiles
+    ("bf16", 1, 33, 19, 512, 8, 16),     # MFMA, uneven last group of 1, rows 304 / 19
+    ("bf16", 1, 70, 9, 256, 2, 70),      # one flat group of 70, head dim 128
+]
+
+
+@pytest.mark.parametrize("dtype,B,Cin,N,D,heads,g", LEVEL_CASES)
+@pytest.mark.parametrize("biases", [True, False])
+def test_aggregate_level_matches_oracle(dtype, B, Cin, N, D, heads, g, biases):
+    say(f"aggregate_level {dtype} B={B} Cin={Cin} N={N} D={D} h={heads} g={g} biases={biases}")
+    rng = np.random.Generator(np.random.PCG64(100 + Cin))
+    lv = make_level(rng, n_groups(Cin, g), g, D, dtype, biases)
+    z = make_tokens(B, Cin, N, D, dtype, seed=7)
+    y = dchag.dchag_aggregate_level(dev(z, dtype), dev_level(lv, dtype), heads)
+    torch.cuda.synchronize()
+    zo = z.transpose(0, 2, 1, 3).reshape(B * N, Cin, D)
+    want = oracle.aggregate_level(zo, lv, heads).reshape(B, N, -1, D).transpose(0, 2, 1, 3)
+    err = rel_err(host(y), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[dtype]
+
+
+# ------------------------------------------------------------------------------------------
+# whole path
+# ------------------------------------------------------------------------------------------
+def test_forward_tiny_config_fp32_full():
+    cfg = get_config("tiny")
+    pr = make_problem(cfg)
+    out = run_forward(pr)
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"tiny fp32 err={err:.3e}")
+    assert err < TOL["f32"]
+
+
+def test_forward_tiny_sharp_softmax_fp32():
+    """Queries scaled by 30: near one-hot softmax weights and large scores."""
+    cfg = get_config("tiny")
+    pr = make_problem(cfg, query_scale=30.0)
+    out = run_forward(pr)
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"tiny sharp fp32 err={err:.3e}")
+    assert err < TOL["f32"]
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", B=2, C=7, H=8, W=12, p=2, D=32, heads=4, group_sizes=(3, 2, 2)),      # 7 -> 3 -> 2 -> 1
+    dict(dtype="f32", B=1, C=5, H=4, W=4, p=2, D=16, heads=2, group_sizes=(5,)),            # flat single layer
+    dict(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3)),     # groups 8, 8, 4
+    dict(dtype="bf16", B=1, C=9, H=24, W=40, p=8, D=512, heads=8, group_sizes=(4, 3)),      # groups 4, 4, 1
+    dict(dtype="bf16", B=1, C=6, H=8, W=8, p=2, D=64, heads=2, group_sizes=(2, 2, 2)),      # generic bf16 path
+])
+def test_forward_matches_oracle_small(kw):
+    cfg = cfg_of(**kw)
+    say(f"forward small {kw}")
+    pr = make_problem(cfg)
+    out = run_forward(pr)
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[cfg.dtype]
+
+
+def test_forward_is_deterministic():
+    cfg = cfg_of(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3))
+    pr = make_problem(cfg)
+    a = run_forward(pr)
+    b = run_forward(pr)
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name,per_batch", [("weather", 8), ("hyperspectral", 6), ("wide", 3), ("deep", 2),
+                                            ("deep1000", 2)])
+def test_forward_full_size_on_sampled_patches(name, per_batch):
+    """The configurations of the benchmark at full size, in the launch configuration the benchmark
+    times; the oracle computes a seeded sample of patches (every weight takes part in every patch)."""
+    cfg = get_config(name)
+    say(f"full-size {name}: generating inputs")
+    pr = make_problem(cfg)
+    say(f"full-size {name}: running the GPU path")
+    out = run_forward(pr)
+    bs, ns = sample_patches(cfg.B, cfg.N, per_batch, seed=17)
+    say(f"full-size {name}: oracle on {bs.size} patches")
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns))
+    got = host(out[torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()])
+    err = rel_err(got, want)
+    say(f"full-size {name}: err={err:.3e}")
+    assert err < TOL[cfg.dtype]
+    # property that holds at any size: every output row is finite and no row was left untouched
+    assert torch.isfinite(out.float()).all()
+    assert (out.float().abs().amax(dim=-1) > 0).all()
