@@ -12,6 +12,7 @@
 #include "dchag_dev.h"
 #include "k_generic.h"
 #include "k_mfma.h"
+#include "k_fused.h"
 
 using namespace dchag;
 
@@ -23,21 +24,37 @@ inline size_t elem_size(dchag_dtype dt) { return dt == DCHAG_F32 ? 4 : 2; }
 inline bool misaligned(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u); }
 inline int groups_of(int c_in, int g) { return (c_in + g - 1) / g; }
 
+// The bf16 MFMA path of a level needs 256-wide column slices that hold whole heads or lie inside one.
+bool fast_level(dchag_dtype dt, int D, int heads) {
+  if (dt != DCHAG_BF16 || D % 256 || heads > 64) return false;
+  const int dh = D / heads;
+  return dh % 32 == 0 && (256 % dh == 0 || dh % 256 == 0);
+}
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
 // Workspace of one aggregation level, carved in this order (every piece 256-byte aligned).
+// Fast path: alpha holds scores, then softmax weights, as [B][G][gpad][heads][Np] floats.
+// Generic path: s holds scores [B,Cin,N,heads], v the projected values [B,Cin,N,D].
 struct LevelWs {
-  size_t qp, mf, mb, s, v, o, total;
+  size_t qp, mf, mb, alpha, s, v, o, total;
 };
 
 LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g) {
   const int G = groups_of(Cin, g);
   const size_t es = elem_size(dt);
-  LevelWs w;
+  const bool fast = fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL");
+  LevelWs w{};
   size_t off = 0;
   w.qp = off; off += align_up((size_t)G * D * 4);
   w.mf = off; off += align_up((size_t)G * heads * D * 4);
   w.mb = off; off += align_up((size_t)G * heads * D * 2);
-  w.s = off;  off += align_up((size_t)B * Cin * N * heads * 4);
-  w.v = off;  off += align_up((size_t)B * Cin * N * D * es);
+  if (fast) {
+    w.alpha = off; off += align_up((size_t)B * G * round_up(g, 8) * heads * round_up(N, 32) * 4);
+  } else {
+    w.s = off;  off += align_up((size_t)B * Cin * N * heads * 4);
+    w.v = off;  off += align_up((size_t)B * Cin * N * D * es);
+  }
   w.o = off;  off += align_up((size_t)B * G * N * D * es);
   w.total = off;
   return w;
@@ -238,6 +255,92 @@ int run_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dch
   return launch_linear<T>(B, D, rbo, O, static_cast<const T*>(lv->Wo), static_cast<const T*>(lv->bo), zout, st);
 }
 
+int launch_linear_dl(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, const bf16* bias, bf16* Y,
+                     hipStream_t st) {
+  TileWork tw;
+  tw.n_tiles = D / kGemmBN;
+  tw.m_tiles = (rb.rows_per_group + kGemmBM - 1) / kGemmBM;
+  tw.nb = B;
+  tw.total = tw.n_tiles * tw.m_tiles * B * rb.G;
+  const int per = (tw.total + kXcds - 1) / kXcds;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_linear_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kGemmRingBytes) != hipSuccess)
+    return DCHAG_ERR_LAUNCH;
+  k_linear_dl<<<dim3(per * kXcds), dim3(512), kGemmRingBytes, st>>>(D, rb, tw, A, Wt, bias, Y);
+  return launch_status();
+}
+
+// One aggregation level on the bf16 MFMA path: weight-only prep, scores (MFMA), softmax over the
+// group, value projection fused with the weighted sum over the group, output projection.
+int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, bf16* zout,
+                   unsigned char* ws, hipStream_t st) {
+  const int g = lv->group_size;
+  const int G = groups_of(Cin, g);
+  const int gpad = round_up(g, 8), Np = round_up(N, 32);
+  const LevelWs w = level_ws(DCHAG_BF16, B, Cin, N, D, heads, g);
+  float* Qp = reinterpret_cast<float*>(ws + w.qp);
+  float* Mf = reinterpret_cast<float*>(ws + w.mf);
+  bf16* Mb = reinterpret_cast<bf16*>(ws + w.mb);
+  float* alpha = reinterpret_cast<float*>(ws + w.alpha);
+  bf16* O = reinterpret_cast<bf16*>(ws + w.o);
+  int rc;
+  {
+    StageTimer tm(DCHAG_STAGE_QUERY, st);
+    k_project_query<bf16><<<dim3((D + 3) / 4, G), 256, 0, st>>>(
+        D, static_cast<const bf16*>(lv->query), static_cast<const bf16*>(lv->Wq), static_cast<const bf16*>(lv->bq), Qp);
+    if ((rc = launch_status())) return rc;
+  }
+  {
+    StageTimer tm(DCHAG_STAGE_FOLD, st);
+    k_fold_query_into_key<bf16><<<dim3((D + 255) / 256, heads, G), 256, 0, st>>>(
+        D, heads, static_cast<const bf16*>(lv->Wk), Qp, Mf, Mb);
+    if ((rc = launch_status())) return rc;
+  }
+  {
+    StageTimer tm(DCHAG_STAGE_SCORES, st);
+    const int KB = (D % 512 == 0) ? 512 : 256;
+    const int NB = (heads + 15) / 16;
+    const int cch = (g + 31) / 32;
+    const dim3 grid((N + 15) / 16, G * cch, B);
+    const size_t lds = (size_t)(NB <= 1 ? 16 : (NB == 2 ? 32 : 64)) * (KB * 2 + 16);
+    if (NB <= 1)
+      k_scores_mfma<1><<<grid, 256, lds, st>>>(Cin, N, D, heads, g, gpad, Np, KB, zin, Mb, alpha);
+    else if (NB == 2)
+      k_scores_mfma<2><<<grid, 256, lds, st>>>(Cin, N, D, heads, g, gpad, Np, KB, zin, Mb, alpha);
+    else {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_mfma<4>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return DCHAG_ERR_LAUNCH;
+      k_scores_mfma<4><<<grid, 256, lds, st>>>(Cin, N, D, heads, g, gpad, Np, KB, zin, Mb, alpha);
+    }
+    if ((rc = launch_status())) return rc;
+    k_softmax_alpha<<<dim3((Np + 255) / 256, heads, B * G), 256, 0, st>>>(Cin, N, heads, g, gpad, G, Np, alpha);
+    if ((rc = launch_status())) return rc;
+  }
+  {
+    StageTimer tm(DCHAG_STAGE_FUSED_VAGG, st);
+    TileWork tw;
+    tw.n_tiles = D / kGemmBN;
+    tw.m_tiles = (N + 31) / 32;
+    tw.nb = B;
+    tw.total = tw.n_tiles * tw.m_tiles * B * G;
+    const int per = (tw.total + kXcds - 1) / kXcds;
+    const int dh = D / heads;
+    const int NHS = dh >= kGemmBN ? 1 : kGemmBN / dh;
+    const int lds = kGemmRingBytes + 3 * 8 * NHS * 32 * 4;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_vagg_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            lds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    k_vagg_mfma<<<dim3(per * kXcds), dim3(512), lds, st>>>(Cin, N, D, heads, g, gpad, G, Np, tw, zin,
+                                                          static_cast<const bf16*>(lv->Wv),
+                                                          static_cast<const bf16*>(lv->bv), alpha, O);
+    if ((rc = launch_status())) return rc;
+  }
+  StageTimer tm(DCHAG_STAGE_OPROJ, st);
+  RowBlocks rbo{G, G * N, N};
+  return launch_linear_dl(B, D, rbo, O, static_cast<const bf16*>(lv->Wo), static_cast<const bf16*>(lv->bo), zout, st);
+}
+
 int check_level(const dchag_level* lv) {
   if (!lv) return DCHAG_ERR_NULL;
   if (lv->group_size < 1 || lv->reserved != 0) return DCHAG_ERR_SHAPE;
@@ -360,6 +463,9 @@ int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int head
   if (dt == DCHAG_F32)
     return run_level<float>(dt, B, Cin, N, D, heads, lvl, static_cast<const float*>(tokens_in),
                             static_cast<float*>(tokens_out), ws, st);
+  if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL"))
+    return run_level_fast(B, Cin, N, D, heads, lvl, static_cast<const bf16*>(tokens_in),
+                          static_cast<bf16*>(tokens_out), ws, st);
   return run_level<bf16>(dt, B, Cin, N, D, heads, lvl, static_cast<const bf16*>(tokens_in),
                          static_cast<bf16*>(tokens_out), ws, st);
 }
@@ -400,6 +506,9 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     if (dt == DCHAG_F32)
       rc = run_level<float>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const float*>(zin),
                             static_cast<float*>(zout), ws + w.level, st);
+    else if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL"))
+      rc = run_level_fast(B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
+                          static_cast<bf16*>(zout), ws + w.level, st);
     else
       rc = run_level<bf16>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
                            static_cast<bf16*>(zout), ws + w.level, st);

@@ -1,0 +1,445 @@
+// bf16 fast path of one aggregation level on gfx950 (paper Section 2.1: a cross-attention layer
+// reduces the channel tokens of a patch to one token; Section 3.2: one layer per channel group).
+//
+//   k_scores_mfma     raw scores of every token against the query-folded key weights (MFMA)
+//   k_softmax_alpha   softmax of the scores over the members of each group
+//   k_vagg_mfma       value projection GEMM whose epilogue takes the softmax-weighted sum over
+//                     the channels of the group, so that the projected values never leave the CU
+//   k_linear_dl       plain per-group projection GEMM (output projection)
+//
+// The two GEMM kernels share one core: 256x256 block tile, 8 wavefronts (2 x 4), 32x32x16 bf16
+// MFMA, K staged in 32-element slices through a ring of LDS stages that is filled by
+// direct-to-LDS global loads (no register staging) and read with conflict-free swizzled
+// ds_read_b128.
+//
+// Softmax weights are exchanged between the kernels in the layout
+//   alpha[b][k][cl][head][n]   (n fastest, pitch Np = N rounded up to 32; cl < gpad = g rounded up to 8)
+// with zeros for the padding members cl >= size of group k.
+#pragma once
+#include "dchag_dev.h"
+#include "k_mfma.h"
+
+namespace dchag {
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Wait until at most N vector-memory operations of this wavefront are outstanding
+// (gfx9 s_waitcnt immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Each lane's 16 bytes of a wave-wide direct-to-LDS load land at lds_base + 16 * lane.
+__device__ __forceinline__ void load16_to_lds(const void* src, void* lds_base) {
+  __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)lds_base, 16, 0, 0);
+}
+
+// LDS stages hold rows of 32 bf16 (64 bytes = 4 chunks of 16 bytes).  Chunk c of row r sits at
+// chunk position c ^ ((r >> 2) & 3): 16 consecutive rows then cover all 64 banks exactly once.
+__device__ __forceinline__ int swz_chunk(int row) { return (row >> 2) & 3; }
+
+constexpr int kGemmBM = 256, kGemmBN = 256, kGemmWM = 2, kGemmWN = 4, kGemmStages = 4;
+constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * 64;                      // 32 KiB
+constexpr int kGemmRingBytes = kGemmStages * kGemmStageBytes;                  // 128 KiB
+
+// ---------------------------------------------------------------------------------------------
+// Scores.  S[b][k][cl][head][n] = z[b, c, n, :] . Mb[k][head][:]   (c = k*g + cl)
+// grid (ceil(N/16), G * ceil(g/32), B), block 256: a block takes 16 patches x up to 32 channels of one
+// group; each wavefront takes 8 channels as two quads of 4 row blocks (16 patches each) that
+// share the key fragments.  The folded keys are staged in LDS in K blocks of KB elements with
+// rows padded by 16 bytes (conflict-free for the 16 heads a fragment read touches).
+// ---------------------------------------------------------------------------------------------
+template <int NB>   // head blocks of 16 (heads padded to 16 * NB)
+__global__ __launch_bounds__(256) void k_scores_mfma(int Cin, int N, int D, int heads, int g, int gpad, int Np,
+                                                     int KB, const bf16* __restrict__ z,
+                                                     const bf16* __restrict__ Mb, float* __restrict__ S) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int cch = (g + 31) / 32;                       // channel chunks of 32 per group
+  const int k = blockIdx.y / cch, cc = blockIdx.y % cch;
+  const int G = gridDim.y / cch;
+  const int b = blockIdx.z, n0 = blockIdx.x * 16;
+  const int c0 = k * g;
+  const int gk = min(g, Cin - c0);                     // members of this group
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int HP = NB * 16;
+  const int pitch = KB * 2 + 16;                       // bytes per staged key row
+
+  f32x4 acc[2][4][NB];
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[q][i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // row pointers of the 8 channels this wavefront takes (clamped into the group)
+  const bf16* zrow[2][4];
+  const int n = min(n0 + l16, N - 1);
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cl = min(cc * 32 + wave * 8 + q * 4 + i, gk - 1);
+      zrow[q][i] = z + (((size_t)b * Cin + c0 + cl) * N + n) * D + lq * 8;
+    }
+
+  for (int kb = 0; kb < D; kb += KB) {
+    __syncthreads();
+    // stage Mb[k][0..HP)[kb .. kb+KB) (rows >= heads are zero)
+    for (int idx = tid; idx < HP * (KB / 8); idx += 256) {
+      const int hrow = idx / (KB / 8), ch = idx % (KB / 8);
+      bf16x8 v = {};
+      if (hrow < heads) v = *reinterpret_cast<const bf16x8*>(Mb + ((size_t)k * heads + hrow) * D + kb + ch * 8);
+      *reinterpret_cast<bf16x8*>(smem + hrow * pitch + ch * 16) = v;
+    }
+    __syncthreads();
+    for (int ks = 0; ks < KB; ks += 32) {
+      bf16x8 bfr[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        bfr[nb] = *reinterpret_cast<const bf16x8*>(smem + (nb * 16 + l16) * pitch + (ks + lq * 8) * 2);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        bf16x8 af[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(zrow[q][i] + kb + ks);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[q][i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[nb], acc[q][i][nb], 0, 0, 0);
+      }
+    }
+  }
+  // 16x16 accumulator block: lane holds head (lane % 16), patches 4 * (lane / 16) + 0..3
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cl = cc * 32 + wave * 8 + q * 4 + i;
+      if (cl >= gk) continue;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int head = nb * 16 + l16;
+        if (head < heads) {
+          float* dst = S + ((((size_t)b * G + k) * gpad + cl) * heads + head) * Np + n0 + lq * 4;
+          *reinterpret_cast<f32x4*>(dst) = acc[q][i][nb];
+        }
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// In-place softmax over the members of a group: S[b][k][0..gk)[head][n] -> alpha, zeros for cl >= gk.
+// grid (ceil(Np/256), heads, B*G), block 256; one thread per (b, k, head, n).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_softmax_alpha(int Cin, int N, int heads, int g, int gpad, int G, int Np,
+                                                       float* __restrict__ S) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= Np) return;
+  const int head = blockIdx.y;
+  const int k = blockIdx.z % G;
+  const int gk = min(g, Cin - k * g);
+  const size_t stride = (size_t)heads * Np;
+  float* p = S + ((size_t)blockIdx.z * gpad * heads + head) * Np + n;
+  if (n >= N) {                                          // pitch padding: never scored, weight zero
+    for (int cl = 0; cl < gpad; ++cl) p[cl * stride] = 0.f;
+    return;
+  }
+  float mx = -INFINITY;
+  for (int cl = 0; cl < gk; ++cl) mx = fmaxf(mx, p[cl * stride]);
+  float den = 0.f;
+  for (int cl = 0; cl < gk; ++cl) den += __expf(p[cl * stride] - mx);
+  const float inv = 1.f / den;
+  for (int cl = 0; cl < gk; ++cl) p[cl * stride] = __expf(p[cl * stride] - mx) * inv;
+  for (int cl = gk; cl < gpad; ++cl) p[cl * stride] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// GEMM core pieces shared by k_vagg_mfma and k_linear_dl.
+//   Block tile 256 x 256, wavefront (wm, wn) of 2 x 4 owns rows [128 wm, +128) x cols [64 wn, +64):
+//   TM = 4 by TN = 2 MFMA blocks of 32 x 32.  One stage = A rows 0..255 then B rows 0..255, 64 bytes each.
+// ---------------------------------------------------------------------------------------------
+struct GemmLane {
+  int lane, wave, wm, wn, l32, lhi;
+  int a_off[4][2], b_off[2][2];   // fragment byte offsets inside a stage, per k-step of 16
+  __device__ __forceinline__ void init() {
+    lane = threadIdx.x & 63;
+    wave = threadIdx.x >> 6;
+    wm = wave / kGemmWN;
+    wn = wave % kGemmWN;
+    l32 = lane & 31;
+    lhi = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const int row = wm * 128 + i * 32 + l32;
+        a_off[i][kk] = row * 64 + (((kk * 2 + lhi) ^ swz_chunk(row)) * 16);
+      }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const int row = wn * 64 + j * 32 + l32;
+        b_off[j][kk] = kGemmBM * 64 + row * 64 + (((kk * 2 + lhi) ^ swz_chunk(row)) * 16);
+      }
+  }
+  // the two wave-wide loads of this wavefront per operand cover tile rows (wave*2 + i) * 16 + lane / 4
+  __device__ __forceinline__ int load_row(int i) const { return (wave * 2 + i) * 16 + (lane >> 2); }
+  __device__ __forceinline__ int load_chunk(int row) const { return (lane & 3) ^ swz_chunk(row); }
+};
+
+struct Frags {
+  bf16x8 a[4], b[2];
+};
+
+__device__ __forceinline__ void read_frags(Frags& f, const unsigned char* stage, const GemmLane& L, int kk) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(stage + L.a_off[i][kk]);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(stage + L.b_off[j][kk]);
+}
+
+__device__ __forceinline__ void mfma_step(f32x16 (&acc)[4][2], const Frags& f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Value projection with the channel aggregation in its epilogue:
+//   O[b,k,n,o] = sum_{cl < gk} alpha[b][k][cl][head(o)][n] * (z[b, k*g + cl, n, :] . Wv[k][o][:]) + bv[k][o]
+// Work item (linear id decoded by TileWork with m = patch tile): group k, batch b, 32 patches, 256 columns.
+// The block walks the group in chunks of 8 channels: tile row r = (channel r / 32 of the chunk, patch r % 32).
+// Requires D % 256 == 0, dh = D / heads a multiple of 32, and 256 % dh == 0 or dh % 256 == 0.
+// Dynamic LDS: ring (128 KiB) + 3 alpha tiles of 8 * NHS * 32 floats (a tile is refilled two chunks
+// after its last reader, so no wavefront can still be reading it).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int heads, int g, int gpad, int G, int Np,
+                                                   TileWork tw, const bf16* __restrict__ z,
+                                                   const bf16* __restrict__ Wv, const bf16* __restrict__ bv,
+                                                   const float* __restrict__ alpha, bf16* __restrict__ O) {
+  constexpr int NS = kGemmStages, LPT = 4;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  int k, b, pt, nt;
+  if (!tw.decode(blockIdx.x, k, b, pt, nt)) return;
+  const int n0 = pt * 32, o0 = nt * kGemmBN;
+  const int c0 = k * g;
+  const int gk = min(g, Cin - c0);
+  const int NCH = (gk + 7) / 8;
+  const int KT = D / 32;
+  const int dh = D / heads;
+  const int NHS = dh >= kGemmBN ? 1 : kGemmBN / dh;      // heads inside this column slice
+  const int h0 = o0 / dh;
+  unsigned char* alds = smem + kGemmRingBytes;           // 3 tiles of [8][NHS][32] floats
+  const int atile = 8 * NHS * 32 * 4;
+
+  GemmLane L;
+  L.init();
+  const bf16* zb = z + (size_t)b * Cin * N * D;
+  const bf16* Wb = Wv + (size_t)k * D * D;
+
+  // per-lane constants of the A loads: channel inside the chunk, patch row, chunk column
+  int a_cl[2];
+  size_t a_rowoff[2];
+  const bf16* b_src[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = L.load_row(i);
+    a_cl[i] = row >> 5;
+    a_rowoff[i] = (size_t)min(n0 + (row & 31), N - 1) * D + L.load_chunk(row) * 8;
+    b_src[i] = Wb + (size_t)(o0 + row) * D + L.load_chunk(row) * 8;
+  }
+  int ci = 0, ki = 0;                                    // issue cursor (chunk, k-slice)
+  int si = 0;                                            // stage the next issue fills
+  auto issue = [&]() {
+    unsigned char* st = smem + si * kGemmStageBytes;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = c0 + min(ci * 8 + a_cl[i], gk - 1);
+      load16_to_lds(zb + (size_t)c * N * D + a_rowoff[i] + ki * 32, st + (L.wave * 2 + i) * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) load16_to_lds(b_src[i] + ki * 32, st + kGemmBM * 64 + (L.wave * 2 + i) * 1024);
+    si = (si + 1 == NS) ? 0 : si + 1;
+    ++ki;
+    const bool wrap = (ki == KT);
+    ki = wrap ? 0 : ki;
+    ci = (wrap && ci + 1 < NCH) ? ci + 1 : ci;           // past the end: harmless re-loads of the last chunk
+  };
+  auto issue_alpha = [&](int chunk) {
+    if (L.wave < NHS) {
+      const int s = L.wave * 8 + (L.lane >> 3);          // segment = (channel of the chunk, head of the slice)
+      const int cl = chunk * 8 + s / NHS, hd = s % NHS;
+      const float* src = alpha + ((((size_t)b * G + k) * gpad + cl) * heads + h0 + hd) * Np + n0 + (L.lane & 7) * 4;
+      load16_to_lds(src, alds + (chunk % 3) * atile + L.wave * 1024);
+    }
+  };
+
+  f32x16 acc[4][2];
+  f32x16 o[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
+
+  // prologue: alpha of chunk 0, the first NS-2 slices, then one more after the first barrier
+  issue_alpha(0);
+#pragma unroll
+  for (int s = 0; s < NS - 2; ++s) issue();
+  wait_vmcnt<(NS - 3) * LPT>();
+  __builtin_amdgcn_s_barrier();
+  issue();
+  Frags f0, f1;
+  int sc = 0;                                            // stage being computed
+  read_frags(f0, smem, L, 0);
+
+  for (int chunk = 0; chunk < NCH; ++chunk) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    if (chunk + 1 < NCH) issue_alpha(chunk + 1);
+    for (int kt = 0; kt < KT; ++kt) {
+      const unsigned char* st = smem + sc * kGemmStageBytes;
+      read_frags(f1, st, L, 1);
+      mfma_step(acc, f0);
+      wait_vmcnt<(NS - 3) * LPT>();                      // the next slice has landed (one more may be in flight)
+      __builtin_amdgcn_s_barrier();
+      issue();
+      sc = (sc + 1 == NS) ? 0 : sc + 1;
+      read_frags(f0, smem + sc * kGemmStageBytes, L, 0);
+      mfma_step(acc, f1);
+    }
+    // o += alpha * acc for the 4 channels of this wavefront
+    const float* al = reinterpret_cast<const float*>(alds + (chunk % 3) * atile);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int hrel = (o0 + L.wn * 64 + j * 32) / dh - h0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float* ap = al + ((L.wm * 4 + i) * NHS + hrel) * 32 + 4 * L.lhi;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 a4 = *reinterpret_cast<const f32x4*>(ap + 8 * q);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[j][4 * q + e] += a4[e] * acc[i][j][4 * q + e];
+        }
+      }
+    }
+  }
+
+  // all direct-to-LDS loads done and every wavefront past its last stage read: the ring is free
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  float* mg = reinterpret_cast<float*>(smem);            // [wn][32 values][64 lanes]
+  if (L.wm == 1) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mg[((L.wn * 32 + j * 16 + r) * 64) + L.lane] = o[j][r];
+  }
+  __syncthreads();
+  if (L.wm == 0) {
+    bf16* Ob = O + (((size_t)b * G + k) * N) * D;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = o0 + L.wn * 64 + j * 32 + L.l32;
+      const float bias = bv ? (float)bv[(size_t)k * D + col] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int nrow = n0 + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
+        const float v = o[j][r] + mg[((L.wn * 32 + j * 16 + r) * 64) + L.lane] + bias;
+        if (nrow < N) Ob[(size_t)nrow * D + col] = (bf16)v;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plain per-group projection  Y[r][o] = sum_j A[r][j] * Wt[k][o][j] + bias[k][o]  on the same core.
+// Requires D % 256 == 0.  Dynamic LDS: the ring (128 KiB).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork tw, const bf16* __restrict__ A,
+                                                   const bf16* __restrict__ Wt, const bf16* __restrict__ bias,
+                                                   bf16* __restrict__ Y) {
+  constexpr int NS = kGemmStages, LPT = 4;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  int k, b, mt, nt;
+  if (!tw.decode(blockIdx.x, k, b, mt, nt)) return;
+  const int rows = rb.rows_of(k);
+  const int r0 = mt * kGemmBM, o0 = nt * kGemmBN;
+  if (r0 >= rows) return;
+  const int KT = D / 32;
+  GemmLane L;
+  L.init();
+  const bf16* Ab = A + (size_t)rb.first_row(b, k) * D;
+  bf16* Yb = Y + (size_t)rb.first_row(b, k) * D;
+  const bf16* Wb = Wt + (size_t)k * D * D;
+  const bf16* a_src[2];
+  const bf16* b_src[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = L.load_row(i);
+    a_src[i] = Ab + (size_t)min(r0 + row, rows - 1) * D + L.load_chunk(row) * 8;
+    b_src[i] = Wb + (size_t)(o0 + row) * D + L.load_chunk(row) * 8;
+  }
+  int ki = 0, si = 0;
+  auto issue = [&]() {
+    unsigned char* st = smem + si * kGemmStageBytes;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) load16_to_lds(a_src[i] + ki * 32, st + (L.wave * 2 + i) * 1024);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) load16_to_lds(b_src[i] + ki * 32, st + kGemmBM * 64 + (L.wave * 2 + i) * 1024);
+    si = (si + 1 == NS) ? 0 : si + 1;
+    ki = (ki + 1 < KT) ? ki + 1 : ki;                    // past the end: harmless re-loads of the last slice
+  };
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+  for (int s = 0; s < NS - 2; ++s) issue();
+  wait_vmcnt<(NS - 3) * LPT>();
+  __builtin_amdgcn_s_barrier();
+  issue();
+  Frags f0, f1;
+  int sc = 0;
+  read_frags(f0, smem, L, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    const unsigned char* st = smem + sc * kGemmStageBytes;
+    read_frags(f1, st, L, 1);
+    mfma_step(acc, f0);
+    wait_vmcnt<(NS - 3) * LPT>();
+    __builtin_amdgcn_s_barrier();
+    issue();
+    sc = (sc + 1 == NS) ? 0 : sc + 1;
+    read_frags(f0, smem + sc * kGemmStageBytes, L, 0);
+    mfma_step(acc, f1);
+  }
+  wait_vmcnt<0>();                                       // no load may still target LDS when the block retires
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = o0 + L.wn * 64 + j * 32 + L.l32;
+    const float bvv = bias ? (float)bias[(size_t)k * D + col] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = r0 + L.wm * 128 + i * 32 + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
+        if (row < rows) Yb[(size_t)row * D + col] = (bf16)(acc[i][j][r] + bvv);
+      }
+  }
+}
+
+}  // namespace dchag

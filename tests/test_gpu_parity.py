@@ -106,6 +106,10 @@ LEVEL_CASES = [
     ("bf16", 2, 12, 40, 256, 4, 8),      # MFMA projection: rows 320 and 160 per block -> ragged tiles
     ("bf16", 1, 33, 19, 512, 8, 16),     # MFMA, uneven last group of 1, rows 304 / 19
     ("bf16", 1, 70, 9, 256, 2, 70),      # one flat group of 70, head dim 128
+    ("bf16", 1, 10, 50, 256, 8, 5),      # head dim 32: 8 heads per 256-column slice; N = 50 (pitch 64)
+    ("bf16", 2, 6, 33, 512, 2, 3),       # head dim 256: one head per slice
+    ("bf16", 1, 5, 20, 1024, 2, 5),      # head dim 512: a head spans two slices
+    ("bf16", 1, 9, 17, 1024, 32, 9),     # 32 heads (two head blocks in the score kernel), 2 chunks of 8
 ]
 
 
@@ -123,6 +127,20 @@ def test_aggregate_level_matches_oracle(dtype, B, Cin, N, D, heads, g, biases):
     err = rel_err(host(y), want)
     say(f"  err={err:.3e}")
     assert err < TOL[dtype]
+
+
+def test_aggregate_level_generic_bf16_kernels_still_match(monkeypatch):
+    """The shape-generic bf16 kernels (taken for shapes the MFMA path does not tile) on a shape
+    the MFMA path would take, forced through the library's DCHAG_GENERIC_LEVEL switch."""
+    monkeypatch.setenv("DCHAG_GENERIC_LEVEL", "1")
+    dtype, B, Cin, N, D, heads, g = "bf16", 2, 12, 40, 256, 4, 8
+    rng = np.random.Generator(np.random.PCG64(5))
+    lv = make_level(rng, n_groups(Cin, g), g, D, dtype, True)
+    z = make_tokens(B, Cin, N, D, dtype, seed=8)
+    y = dchag.dchag_aggregate_level(dev(z, dtype), dev_level(lv, dtype), heads)
+    torch.cuda.synchronize()
+    want = oracle.aggregate_level(z.transpose(0, 2, 1, 3).reshape(B * N, Cin, D), lv, heads)
+    assert rel_err(host(y), want.reshape(B, N, -1, D).transpose(0, 2, 1, 3)) < TOL[dtype]
 
 
 # ------------------------------------------------------------------------------------------
