@@ -145,6 +145,18 @@ int launch_tokenize(int B, int C, int H, int W, int p, int D, const T* x, const 
   return launch_status();
 }
 
+int launch_tokenize_mfma(int B, int C, int H, int W, int p, int D, const bf16* x, const bf16* We, const bf16* be,
+                         const bf16* ce, bf16* tokens, hipStream_t st) {
+  const int N = (H / p) * (W / p);
+  const size_t lds = (size_t)128 * (p * p * 2 + 16);
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)lds) != hipSuccess)
+    return DCHAG_ERR_LAUNCH;
+  StageTimer tm(DCHAG_STAGE_TOKENIZE, st);
+  k_tokenize_mfma<<<dim3((N + 127) / 128, C, B), 256, lds, st>>>(C, H, W, p, D, x, We, be, ce, tokens);
+  return launch_status();
+}
+
 template <typename T>
 int launch_linear_generic(int B, int D, RowBlocks rb, const T* A, const T* Wt, const T* bias, T* Y,
                           hipStream_t st) {
@@ -440,6 +452,10 @@ int dchag_tokenize(dchag_dtype dt, int B, int C, int H, int W, int p, int D, con
     return launch_tokenize<float>(B, C, H, W, p, D, static_cast<const float*>(x), static_cast<const float*>(We),
                                   static_cast<const float*>(be), static_cast<const float*>(ce),
                                   static_cast<float*>(tokens), st);
+  if ((p * p) % 16 == 0 && p * p <= 256 && D % 64 == 0 && !getenv("DCHAG_GENERIC_TOKENIZE"))
+    return launch_tokenize_mfma(B, C, H, W, p, D, static_cast<const bf16*>(x), static_cast<const bf16*>(We),
+                                static_cast<const bf16*>(be), static_cast<const bf16*>(ce),
+                                static_cast<bf16*>(tokens), st);
   return launch_tokenize<bf16>(B, C, H, W, p, D, static_cast<const bf16*>(x), static_cast<const bf16*>(We),
                                static_cast<const bf16*>(be), static_cast<const bf16*>(ce),
                                static_cast<bf16*>(tokens), st);

@@ -442,4 +442,84 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Tokenizer on MFMA (paper Section 2.1: every patch of every channel is embedded on its own by
+// that channel's convolution, kernel = stride = patch):
+//   tokens[b,c,n,d] = sum_k u[b,c,n][k] * We[c][d][k] + be[c][d] + ce[c][d],   k = p*p pixels of the patch
+// grid (ceil(N/128), C, B), block 256.  The block gathers its 128 patches into LDS (rows of p*p bf16,
+// padded by 16 bytes), then every wavefront sweeps 64-column slices: 4 x 2 MFMA blocks whose two
+// column blocks interleave (block j holds columns 2*lane+j), so that a lane owns two adjacent
+// outputs per row and half a wavefront stores 128 contiguous bytes.
+// Requires p*p % 16 == 0, p*p <= 256, D % 64 == 0.  The kernel is HBM-write bound.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void k_tokenize_mfma(int C, int H, int W, int p, int D, const bf16* __restrict__ x,
+                                                       const bf16* __restrict__ We, const bf16* __restrict__ be,
+                                                       const bf16* __restrict__ ce, bf16* __restrict__ tokens) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int pp = p * p, pw = W / p, N = (H / p) * pw;
+  const int KS = pp / 16;
+  const int rbp = pp * 2 + 16;                           // padded bytes per patch row
+  const int n0 = blockIdx.x * 128, c = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const bf16* img = x + ((size_t)b * C + c) * H * W;
+
+  // gather: 4 pixels (8 bytes) at a time; p % 4 == 0 keeps every piece inside one patch row
+  const int pieces = pp / 4;
+  for (int idx = tid; idx < 128 * pieces; idx += 256) {
+    const int t = idx / pieces, q = idx % pieces;
+    const int r = (q * 4) / p, s0 = (q * 4) % p;
+    const int n = n0 + t;
+    bf16x4 v = {};
+    if (n < N) {
+      const int pi = n / pw, pj = n % pw;
+      v = *reinterpret_cast<const bf16x4*>(img + (size_t)(pi * p + r) * W + pj * p + s0);
+    }
+    *reinterpret_cast<bf16x4*>(smem + t * rbp + q * 8) = v;
+  }
+  __syncthreads();
+
+  const bf16* Wc = We + (size_t)c * D * pp;
+  for (int col0 = wave * 64; col0 < D; col0 += 256) {
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const bf16* wrow = Wc + (size_t)(col0 + 2 * l32) * pp + lhi * 8;
+    for (int kk = 0; kk < KS; ++kk) {
+      bf16x8 bfr[2], af[4];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(smem + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    const int d0 = col0 + 2 * l32;
+    float add0 = 0.f, add1 = 0.f;
+    if (be) { add0 += (float)be[(size_t)c * D + d0]; add1 += (float)be[(size_t)c * D + d0 + 1]; }
+    if (ce) { add0 += (float)ce[(size_t)c * D + d0]; add1 += (float)ce[(size_t)c * D + d0 + 1]; }
+    bf16* trow = tokens + (((size_t)b * C + c) * N) * D + d0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int n = n0 + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+        if (n < N) {
+          typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+          bf16x2 pk;
+          pk[0] = (bf16)(acc[i][0][r] + add0);
+          pk[1] = (bf16)(acc[i][1][r] + add1);
+          *reinterpret_cast<bf16x2*>(trow + (size_t)n * D) = pk;
+        }
+      }
+  }
+}
+
 }  // namespace dchag
