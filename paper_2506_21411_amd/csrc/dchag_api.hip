@@ -61,11 +61,11 @@ LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g)
 }
 
 struct ForwardWs {
-  size_t tokens, ping, pong, level, total;
+  size_t tokens, ping, pong, level, ms, cs, mft, total;
 };
 
 // group_sizes has n_levels entries; returns total = 0 when the chain does not end in one group.
-ForwardWs forward_ws(dchag_dtype dt, int B, int C, int N, int D, int heads, int n_levels,
+ForwardWs forward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int heads, int n_levels,
                      const int32_t* group_sizes) {
   ForwardWs w{};
   const size_t es = elem_size(dt);
@@ -88,6 +88,9 @@ ForwardWs forward_ws(dchag_dtype dt, int B, int C, int N, int D, int heads, int 
   w.ping = off; off += inter_max;
   w.pong = off; off += inter_max;
   w.level = off; off += lvl_max;
+  w.ms = off; off += align_up((size_t)kComposeSlices * C * heads * pp * 4);   // composed level-1 score weights
+  w.cs = off; off += align_up((size_t)kComposeSlices * C * heads * 4);
+  w.mft = off; off += align_up((size_t)groups_of(C, group_sizes[0]) * D * heads * 4);
   w.total = off;
   return w;
 }
@@ -241,7 +244,7 @@ int run_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dch
   {
     StageTimer tm(DCHAG_STAGE_FOLD, st);
     k_fold_query_into_key<T><<<dim3((D + 255) / 256, heads, G), 256, 0, st>>>(
-        D, heads, static_cast<const T*>(lv->Wk), Qp, Mf, nullptr);
+        D, heads, static_cast<const T*>(lv->Wk), Qp, Mf, nullptr, nullptr);
     if ((rc = launch_status())) return rc;
   }
   {
@@ -282,10 +285,19 @@ int launch_linear_dl(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, 
   return launch_status();
 }
 
-// One aggregation level on the bf16 MFMA path: weight-only prep, scores (MFMA), softmax over the
-// group, value projection fused with the weighted sum over the group, output projection.
+// Inputs of the first level's score shortcut: scores computed from the pixels through the
+// tokenizer weights composed with the folded keys.
+struct PixelScores {
+  const bf16 *x, *We, *be, *ce;
+  int H, W, p;
+  float *Ms, *cs, *MfT;
+};
+
+// One aggregation level on the bf16 MFMA path: weight-only prep, scores (MFMA on the tokens, or
+// from the pixels at the first level of a forward call), softmax over the group, value projection
+// fused with the weighted sum over the group, output projection.
 int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, bf16* zout,
-                   unsigned char* ws, hipStream_t st) {
+                   unsigned char* ws, hipStream_t st, const PixelScores* px = nullptr) {
   const int g = lv->group_size;
   const int G = groups_of(Cin, g);
   const int gpad = round_up(g, 8), Np = round_up(N, 32);
@@ -305,10 +317,36 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
   {
     StageTimer tm(DCHAG_STAGE_FOLD, st);
     k_fold_query_into_key<bf16><<<dim3((D + 255) / 256, heads, G), 256, 0, st>>>(
-        D, heads, static_cast<const bf16*>(lv->Wk), Qp, Mf, Mb);
+        D, heads, static_cast<const bf16*>(lv->Wk), Qp, Mf, Mb, px ? px->MfT : nullptr);
     if ((rc = launch_status())) return rc;
   }
-  {
+  if (px) {
+    StageTimer tm(DCHAG_STAGE_SCORES, st);
+    const int pp = px->p * px->p;
+    const int ntiles = (heads / 4) * (pp / 4);
+    if (ntiles <= 64)
+      k_compose_score_weights<1><<<dim3(Cin, kComposeSlices), 256, 0, st>>>(Cin, D, heads, pp, g, px->MfT, px->We, px->be, px->ce, px->Ms, px->cs);
+    else if (ntiles <= 128)
+      k_compose_score_weights<2><<<dim3(Cin, kComposeSlices), 256, 0, st>>>(Cin, D, heads, pp, g, px->MfT, px->We, px->be, px->ce, px->Ms, px->cs);
+    else
+      k_compose_score_weights<4><<<dim3(Cin, kComposeSlices), 256, 0, st>>>(Cin, D, heads, pp, g, px->MfT, px->We, px->be, px->ce, px->Ms, px->cs);
+    if ((rc = launch_status())) return rc;
+    const size_t lds = (size_t)(heads * pp + 32 * (pp + 1)) * 4;
+    const dim3 pgrid((N + 31) / 32, G * ((g + 7) / 8), B);
+    if (pp <= 64 && heads * pp <= 1024) {
+      k_scores_pixels<8, 4><<<pgrid, 256, lds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, Np, px->x, px->Ms,
+                                                    px->cs, alpha);
+    } else {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_pixels<32, 32>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return DCHAG_ERR_LAUNCH;
+      k_scores_pixels<32, 32><<<pgrid, 256, lds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, Np, px->x, px->Ms,
+                                                      px->cs, alpha);
+    }
+    if ((rc = launch_status())) return rc;
+    k_softmax_alpha<<<dim3((Np + 255) / 256, heads, B * G), 256, 0, st>>>(Cin, N, heads, g, gpad, G, Np, alpha);
+    if ((rc = launch_status())) return rc;
+  } else {
     StageTimer tm(DCHAG_STAGE_SCORES, st);
     const int KB = (D % 512 == 0) ? 512 : 256;
     const int NB = (heads + 15) / 16;
@@ -436,7 +474,7 @@ size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, 
   const int N = (H / p) * (W / p);
   if (check_level_shape(B, C, N, D, heads, group_sizes[0]) != DCHAG_OK) return 0;
   if (which == 0) return level_ws(dt, B, C, N, D, heads, group_sizes[0]).total;
-  if (which == 1) return forward_ws(dt, B, C, N, D, heads, n_levels, group_sizes).total;
+  if (which == 1) return forward_ws(dt, B, C, N, p * p, D, heads, n_levels, group_sizes).total;
   return 0;
 }
 
@@ -505,7 +543,7 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
   }
   if (c_in != 1) return DCHAG_ERR_SHAPE;
   if (misaligned(x) || misaligned(We) || misaligned(be) || misaligned(ce) || misaligned(out)) return DCHAG_ERR_ALIGN;
-  const ForwardWs w = forward_ws(dt, B, C, N, D, heads, n_levels, gs);
+  const ForwardWs w = forward_ws(dt, B, C, N, p * p, D, heads, n_levels, gs);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
       workspace_bytes < w.total)
     return DCHAG_ERR_WORKSPACE;
@@ -522,9 +560,16 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     if (dt == DCHAG_F32)
       rc = run_level<float>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const float*>(zin),
                             static_cast<float*>(zout), ws + w.level, st);
-    else if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL"))
+    else if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL")) {
+      PixelScores px{static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+                     static_cast<const bf16*>(ce), H, W, p, reinterpret_cast<float*>(ws + w.ms),
+                     reinterpret_cast<float*>(ws + w.cs), reinterpret_cast<float*>(ws + w.mft)};
+      // the pixel shortcut tiles outputs 4 heads x 4 pixels, at most 4 tiles per lane, and gathers 32 patches
+      const bool use_px = (l == 0) && heads % 4 == 0 && (p * p) % 4 == 0 && (heads / 4) * (p * p / 4) <= 256 &&
+                          p * p <= 256 && D % (16 * kComposeSlices) == 0 && !getenv("DCHAG_TOKEN_SCORES");
       rc = run_level_fast(B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
-                          static_cast<bf16*>(zout), ws + w.level, st);
+                          static_cast<bf16*>(zout), ws + w.level, st, use_px ? &px : nullptr);
+    }
     else
       rc = run_level<bf16>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
                            static_cast<bf16*>(zout), ws + w.level, st);

@@ -443,6 +443,181 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
 }
 
 // ---------------------------------------------------------------------------------------------
+// Level-1 scores straight from the pixels.  The tokenizer is linear, so the score of token
+// t = We[c] u + be[c] + ce[c] against the folded key M[k][a] is
+//   t . M[k][a] = u . (We[c]^T M[k][a]) + (be[c] + ce[c]) . M[k][a]
+// k_compose_score_weights builds the weight-only pieces  Ms[c][a][kk] = sum_d M[k][a][d] We[c][d][kk]
+// and cs[c][a] = sum_d M[k][a][d] (be[c][d] + ce[c][d]) in fp32 (k = c / g);
+// k_scores_pixels then scores every (channel, patch) with a p*p-long dot product per head.
+// ---------------------------------------------------------------------------------------------
+// grid (C, kComposeSlices), block 256.  Outputs are tiled 4 heads x 4 pixels; lane l of every wavefront
+// owns tiles l, l+64, ... (TPL of them).  Block slice y sums d over its share of D, its four
+// wavefronts each a quarter of that, meeting in LDS; the slices' partial results are written side by
+// side (Ms[slice][c][heads][pp], cs[slice][c][heads]) and added up by the reader, so the sum order is
+// fixed.  MfT is the folded key transposed to [G][D][heads]: a lane reads its 4 heads as one 16-byte
+// load.  Requires heads % 4 == 0, pp % 4 == 0, D % (16 * kComposeSlices) == 0.
+constexpr int kComposeSlices = 4;
+template <int TPL>
+__global__ __launch_bounds__(256) void k_compose_score_weights(int C, int D, int heads, int pp, int g,
+                                                               const float* __restrict__ MfT,
+                                                               const bf16* __restrict__ We, const bf16* __restrict__ be,
+                                                               const bf16* __restrict__ ce, float* __restrict__ Ms,
+                                                               float* __restrict__ cs) {
+  __shared__ float part[3][TPL * 64 * 20];               // partial sums of wavefronts 1..3: 16 tile values + 4 constants
+  const int c = blockIdx.x, k = c / g, slice = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kq_n = pp / 4, aq_n = heads / 4, ntiles = kq_n * aq_n;
+  const float* M = MfT + (size_t)k * D * heads;
+  const bf16* Wc = We + (size_t)c * D * pp;
+  float acc[TPL][16], cacc[TPL][4];
+  int kq[TPL], aq[TPL];
+#pragma unroll
+  for (int t = 0; t < TPL; ++t) {
+    const int tile = lane + t * 64;
+    kq[t] = tile < ntiles ? tile % kq_n : -1;
+    aq[t] = tile < ntiles ? tile / kq_n : 0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cacc[t][e] = 0.f;
+  }
+  const int dq = D / (4 * kComposeSlices);
+  const int dbeg = (slice * 4 + wave) * dq;
+#pragma unroll 16
+  for (int d = dbeg; d < dbeg + dq; ++d) {
+    float bsum = 0.f;
+    if (be) bsum += (float)be[(size_t)c * D + d];
+    if (ce) bsum += (float)ce[(size_t)c * D + d];
+#pragma unroll
+    for (int t = 0; t < TPL; ++t) {
+      if (kq[t] < 0) continue;
+      const f32x4 m4 = *reinterpret_cast<const f32x4*>(M + (size_t)d * heads + aq[t] * 4);
+      const bf16x4 w4 = *reinterpret_cast<const bf16x4*>(Wc + (size_t)d * pp + kq[t] * 4);
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[t][a * 4 + q] += m4[a] * (float)w4[q];
+        cacc[t][a] += m4[a] * bsum;
+      }
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int t = 0; t < TPL; ++t) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) part[wave - 1][(t * 20 + e) * 64 + lane] = acc[t][e];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) part[wave - 1][(t * 20 + 16 + e) * 64 + lane] = cacc[t][e];
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    float* Mo = Ms + ((size_t)slice * C + c) * heads * pp;
+    float* co = cs + ((size_t)slice * C + c) * heads;
+#pragma unroll
+    for (int t = 0; t < TPL; ++t) {
+      if (kq[t] < 0) continue;
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int head = aq[t] * 4 + a;
+        f32x4 v4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int e = a * 4 + q;
+          v4[q] = acc[t][e] + part[0][(t * 20 + e) * 64 + lane] + part[1][(t * 20 + e) * 64 + lane] +
+                  part[2][(t * 20 + e) * 64 + lane];
+        }
+        *reinterpret_cast<f32x4*>(Mo + (size_t)head * pp + kq[t] * 4) = v4;
+        if (kq[t] == 0) {
+          const int e = 16 + a;
+          co[head] = cacc[t][a] + part[0][(t * 20 + e) * 64 + lane] + part[1][(t * 20 + e) * 64 + lane] +
+                     part[2][(t * 20 + e) * 64 + lane];
+        }
+      }
+    }
+  }
+}
+
+// grid (ceil(N/32), G * ceil(g/8), B), block 256: 32 patches x up to 8 members of one group, one member
+// at a time, the next member's pixels and weights fetched into registers while the current one is scored.
+// Thread (patch = t % 32, hq = t / 32) scores heads hq, hq + 8, ...  The pixel offsets of a thread's
+// share of the gather do not depend on the channel and are computed once.
+// Dynamic LDS: (heads*pp + 32*(pp+1)) floats.  Requires pp <= 256 and heads*pp <= 256 * 32.
+template <int MAXG, int MAXM>   // register slots per thread for the pixel gather (32*pp/256) and the weights (heads*pp/256)
+__global__ __launch_bounds__(256) void k_scores_pixels(int C, int H, int W, int p, int heads, int g, int gpad, int Np,
+                                                       const bf16* __restrict__ x, const float* __restrict__ Ms,
+                                                       const float* __restrict__ cs, float* __restrict__ S) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int pp = p * p, pw = W / p, N = (H / p) * pw;
+  float* ms = reinterpret_cast<float*>(smem);            // [heads][pp]
+  float* u = ms + heads * pp;                            // [32][pp + 1]
+  const int cch = (g + 7) / 8;
+  const int n0 = blockIdx.x * 32, k = blockIdx.y / cch, cc = blockIdx.y % cch, b = blockIdx.z, G = gridDim.y / cch;
+  const int c0 = k * g, gk = min(g, C - c0);
+  const int cl_beg = cc * 8, cl_end = min(cl_beg + 8, gk);
+  if (cl_beg >= cl_end) return;
+  const int tp = threadIdx.x & 31, hq = threadIdx.x >> 5;
+  const int ng = (32 * pp + 255) / 256, nm = (heads * pp + 255) / 256;
+  int goff[MAXG], gdst[MAXG];
+#pragma unroll
+  for (int s = 0; s < MAXG; ++s) {
+    const int idx = threadIdx.x + s * 256;
+    goff[s] = -1;
+    gdst[s] = 0;
+    if (s < ng && idx < 32 * pp) {
+      const int t = idx / pp, kk = idx % pp;
+      const int n = min(n0 + t, N - 1);
+      const int pi = n / pw, pj = n % pw, r = kk / p, s2 = kk % p;
+      goff[s] = (pi * p + r) * W + pj * p + s2;
+      gdst[s] = t * (pp + 1) + kk;
+    }
+  }
+  float upre[MAXG], mpre[MAXM];
+  auto fetch = [&](int cl) {
+    const int c = c0 + cl;
+    const bf16* img = x + ((size_t)b * C + c) * H * W;
+#pragma unroll
+    for (int s = 0; s < MAXG; ++s)
+      if (s < ng && goff[s] >= 0) upre[s] = (float)img[goff[s]];
+#pragma unroll
+    for (int s = 0; s < MAXM; ++s) {
+      const int idx = threadIdx.x + s * 256;
+      if (s < nm && idx < heads * pp) {
+        float v = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < kComposeSlices; ++sl) v += Ms[((size_t)sl * C + c) * heads * pp + idx];
+        mpre[s] = v;
+      }
+    }
+  };
+  fetch(cl_beg);
+  for (int cl = cl_beg; cl < cl_end; ++cl) {
+    const int c = c0 + cl;
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < MAXG; ++s)
+      if (s < ng && goff[s] >= 0) u[gdst[s]] = upre[s];
+#pragma unroll
+    for (int s = 0; s < MAXM; ++s) {
+      const int idx = threadIdx.x + s * 256;
+      if (s < nm && idx < heads * pp) ms[idx] = mpre[s];
+    }
+    __syncthreads();
+    if (cl + 1 < cl_end) fetch(cl + 1);
+    for (int a = hq; a < heads; a += 8) {
+      float acc = 0.f;
+#pragma unroll
+      for (int sl = 0; sl < kComposeSlices; ++sl) acc += cs[((size_t)sl * C + c) * heads + a];
+      const float* m = ms + a * pp;
+      const float* ur = u + tp * (pp + 1);
+#pragma unroll 8
+      for (int kk = 0; kk < pp; ++kk) acc += ur[kk] * m[kk];
+      S[((((size_t)b * G + k) * gpad + cl) * heads + a) * Np + n0 + tp] = acc;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Tokenizer on MFMA (paper Section 2.1: every patch of every channel is embedded on its own by
 // that channel's convolution, kernel = stride = patch):
 //   tokens[b,c,n,d] = sum_k u[b,c,n][k] * We[c][d][k] + be[c][d] + ce[c][d],   k = p*p pixels of the patch
@@ -505,18 +680,21 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mfma(int C, int H, int W, i
     float add0 = 0.f, add1 = 0.f;
     if (be) { add0 += (float)be[(size_t)c * D + d0]; add1 += (float)be[(size_t)c * D + d0 + 1]; }
     if (ce) { add0 += (float)ce[(size_t)c * D + d0]; add1 += (float)ce[(size_t)c * D + d0 + 1]; }
-    bf16* trow = tokens + (((size_t)b * C + c) * N) * D + d0;
+    // uniform row base + per-lane element offset (the two half-wavefronts sit 4 rows apart)
+    bf16* tbase = tokens + (((size_t)b * C + c) * N + n0) * D;
+    const int lane_off = 4 * lhi * D + d0;
+    const int nlim = N - n0 - 4 * lhi;                   // rows of this lane's half that are inside the image
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int n = n0 + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-        if (n < N) {
+        const int rr = i * 32 + 8 * (r >> 2) + (r & 3);  // uniform row index inside the tile
+        if (rr < nlim) {
           typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
           bf16x2 pk;
           pk[0] = (bf16)(acc[i][0][r] + add0);
           pk[1] = (bf16)(acc[i][1][r] + add1);
-          *reinterpret_cast<bf16x2*>(trow + (size_t)n * D) = pk;
+          *reinterpret_cast<bf16x2*>(tbase + (size_t)rr * D + lane_off) = pk;
         }
       }
   }

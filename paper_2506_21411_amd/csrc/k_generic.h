@@ -31,12 +31,14 @@ __global__ __launch_bounds__(256) void k_project_query(int D, const T* __restric
 // same amount and is dropped):
 //   M[k][a][j] = (1/sqrt(dh)) * sum_{i in head a} Wk[k][i][j] * Q[k][i]
 // so that the score of token z for head a is  z . M[k][a][:].
-// grid (ceil(D/256), heads, G), block 256.  Writes fp32 and, when Mb != nullptr, a bf16 copy.
+// grid (ceil(D/256), heads, G), block 256.  Writes fp32 and, when asked, a bf16 copy and a
+// transposed fp32 copy [G][D][heads].
 // ---------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_fold_query_into_key(int D, int heads, const T* __restrict__ Wk,
                                                              const float* __restrict__ Qp,
-                                                             float* __restrict__ Mf, bf16* __restrict__ Mb) {
+                                                             float* __restrict__ Mf, bf16* __restrict__ Mb,
+                                                             float* __restrict__ MfT) {
   const int k = blockIdx.z, a = blockIdx.y;
   const int j = blockIdx.x * 256 + threadIdx.x;
   if (j >= D) return;
@@ -49,6 +51,7 @@ __global__ __launch_bounds__(256) void k_fold_query_into_key(int D, int heads, c
   const size_t o = ((size_t)k * heads + a) * D + j;
   Mf[o] = acc;
   if (Mb) Mb[o] = (bf16)acc;
+  if (MfT) MfT[((size_t)k * D + j) * heads + a] = acc;   // transposed copy [G][D][heads]
 }
 
 // ---------------------------------------------------------------------------------------
