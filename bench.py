@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--workload", default="hyperspectral")
     ap.add_argument("--cpu-patches", type=int, default=64, help="patches the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-other", action="store_true", help="skip the short weather-like side measurement")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy kernel (reads 1 GiB, writes 1 GiB): the yardstick "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the hierarchy is run locally; no collectives). "
@@ -120,6 +123,13 @@ def main() -> int:
     ms = ms_plain
     tokens = cfg.tokens
     value = tokens / (ms * 1e-3)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)          # elementwise kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
+        del src, dst
 
     # per-stage averages over the profiled region
     lv_in = level_inputs(cfg.C, cfg.group_sizes)

@@ -61,7 +61,7 @@ LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g)
 }
 
 struct ForwardWs {
-  size_t tokens, ping, pong, level, ms, cs, mft, total;
+  size_t tokens, ping, pong, level, ms, msb, cs, mft, total;
 };
 
 // group_sizes has n_levels entries; returns total = 0 when the chain does not end in one group.
@@ -88,8 +88,9 @@ ForwardWs forward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int hea
   w.ping = off; off += inter_max;
   w.pong = off; off += inter_max;
   w.level = off; off += lvl_max;
-  w.ms = off; off += align_up((size_t)kComposeSlices * C * heads * pp * 4);   // composed level-1 score weights
-  w.cs = off; off += align_up((size_t)kComposeSlices * C * heads * 4);
+  w.ms = off; off += align_up((size_t)C * heads * pp * 4);   // composed level-1 score weights, fp32 and bf16
+  w.msb = off; off += align_up((size_t)C * heads * pp * 2);
+  w.cs = off; off += align_up((size_t)C * heads * 4);
   w.mft = off; off += align_up((size_t)groups_of(C, group_sizes[0]) * D * heads * 4);
   w.total = off;
   return w;
@@ -291,6 +292,7 @@ struct PixelScores {
   const bf16 *x, *We, *be, *ce;
   int H, W, p;
   float *Ms, *cs, *MfT;
+  bf16* Msb;
 };
 
 // One aggregation level on the bf16 MFMA path: weight-only prep, scores (MFMA on the tokens, or
@@ -324,25 +326,18 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     StageTimer tm(DCHAG_STAGE_SCORES, st);
     const int pp = px->p * px->p;
     const int ntiles = (heads / 4) * (pp / 4);
-    if (ntiles <= 64)
-      k_compose_score_weights<1><<<dim3(Cin, kComposeSlices), 256, 0, st>>>(Cin, D, heads, pp, g, px->MfT, px->We, px->be, px->ce, px->Ms, px->cs);
-    else if (ntiles <= 128)
-      k_compose_score_weights<2><<<dim3(Cin, kComposeSlices), 256, 0, st>>>(Cin, D, heads, pp, g, px->MfT, px->We, px->be, px->ce, px->Ms, px->cs);
-    else
-      k_compose_score_weights<4><<<dim3(Cin, kComposeSlices), 256, 0, st>>>(Cin, D, heads, pp, g, px->MfT, px->We, px->be, px->ce, px->Ms, px->cs);
+    const int TPL = ntiles <= 64 ? 1 : (ntiles <= 128 ? 2 : 4);
+    int DQ = 16384 / pp;                                 // 32 KiB of tokenizer weights per block of d
+    while (D % DQ) DQ >>= 1;
+    const size_t clds = (size_t)DQ * (pp * 2 + heads * 4 + 4) + (size_t)3 * TPL * 64 * 20 * 4;
+    auto compose = TPL == 1 ? k_compose_score_weights<1> : (TPL == 2 ? k_compose_score_weights<2> : k_compose_score_weights<4>);
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(compose), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)clds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    compose<<<dim3(Cin), 256, clds, st>>>(D, heads, pp, g, DQ, px->MfT, px->We, px->be, px->ce, px->Ms, px->Msb, px->cs);
     if ((rc = launch_status())) return rc;
-    const size_t lds = (size_t)(heads * pp + 32 * (pp + 1)) * 4;
-    const dim3 pgrid((N + 31) / 32, G * ((g + 7) / 8), B);
-    if (pp <= 64 && heads * pp <= 1024) {
-      k_scores_pixels<8, 4><<<pgrid, 256, lds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, Np, px->x, px->Ms,
-                                                    px->cs, alpha);
-    } else {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_pixels<32, 32>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return DCHAG_ERR_LAUNCH;
-      k_scores_pixels<32, 32><<<pgrid, 256, lds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, Np, px->x, px->Ms,
-                                                      px->cs, alpha);
-    }
+    k_scores_pixels<<<dim3((N + 127) / 128, Cin, B), 256, 0, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G, Np, px->x,
+                                                                 px->Msb, px->cs, alpha);
     if ((rc = launch_status())) return rc;
     k_softmax_alpha<<<dim3((Np + 255) / 256, heads, B * G), 256, 0, st>>>(Cin, N, heads, g, gpad, G, Np, alpha);
     if ((rc = launch_status())) return rc;
@@ -563,10 +558,13 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     else if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL")) {
       PixelScores px{static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
                      static_cast<const bf16*>(ce), H, W, p, reinterpret_cast<float*>(ws + w.ms),
-                     reinterpret_cast<float*>(ws + w.cs), reinterpret_cast<float*>(ws + w.mft)};
-      // the pixel shortcut tiles outputs 4 heads x 4 pixels, at most 4 tiles per lane, and gathers 32 patches
-      const bool use_px = (l == 0) && heads % 4 == 0 && (p * p) % 4 == 0 && (heads / 4) * (p * p / 4) <= 256 &&
-                          p * p <= 256 && D % (16 * kComposeSlices) == 0 && !getenv("DCHAG_TOKEN_SCORES");
+                     reinterpret_cast<float*>(ws + w.cs), reinterpret_cast<float*>(ws + w.mft),
+                     reinterpret_cast<bf16*>(ws + w.msb)};
+      // the pixel shortcut: 4 x 4 output tiles (at most 4 per lane) in the compose kernel, one 32-wide MFMA
+      // column block of heads and 8-pixel operand chunks in the score kernel
+      const int pp = p * p;
+      const bool use_px = (l == 0) && heads % 4 == 0 && heads <= 32 && pp % 16 == 0 && (p == 4 || p % 8 == 0) &&
+                          (heads / 4) * (pp / 4) <= 256 && pp <= 256 && !getenv("DCHAG_TOKEN_SCORES");
       rc = run_level_fast(B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
                           static_cast<bf16*>(zout), ws + w.level, st, use_px ? &px : nullptr);
     }

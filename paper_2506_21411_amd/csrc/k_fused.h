@@ -8,9 +8,9 @@
 //   k_linear_dl       plain per-group projection GEMM (output projection)
 //
 // The two GEMM kernels share one core: 256x256 block tile, 8 wavefronts (2 x 4), 32x32x16 bf16
-// MFMA, K staged in 32-element slices through a ring of LDS stages that is filled by
-// direct-to-LDS global loads (no register staging) and read with conflict-free swizzled
-// ds_read_b128.
+// MFMA, K staged in 64-element slices through two LDS stages that are filled by direct-to-LDS
+// global loads of 128-byte row segments (no register staging; L2 delivers 128-byte segments at
+// about twice the rate of 64-byte ones) and read with conflict-free swizzled ds_read_b128.
 //
 // Softmax weights are exchanged between the kernels in the layout
 //   alpha[b][k][cl][head][n]   (n fastest, pitch Np = N rounded up to 32; cl < gpad = g rounded up to 8)
@@ -36,12 +36,13 @@ __device__ __forceinline__ void load16_to_lds(const void* src, void* lds_base) {
   __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)lds_base, 16, 0, 0);
 }
 
-// LDS stages hold rows of 32 bf16 (64 bytes = 4 chunks of 16 bytes).  Chunk c of row r sits at
-// chunk position c ^ ((r >> 2) & 3): 16 consecutive rows then cover all 64 banks exactly once.
-__device__ __forceinline__ int swz_chunk(int row) { return (row >> 2) & 3; }
+// LDS stages hold rows of 64 bf16 (128 bytes = 8 chunks of 16 bytes).  Chunk c of row r sits at chunk
+// position c ^ ((r >> 1) & 7): the 16 consecutive rows a quarter-wavefront reads at one logical chunk
+// then fall into 16 different 16-byte bank groups (64 banks x 4 bytes), so ds_read_b128 is conflict-free.
+__device__ __forceinline__ int swz_chunk(int row) { return (row >> 1) & 7; }
 
-constexpr int kGemmBM = 256, kGemmBN = 256, kGemmWM = 2, kGemmWN = 4, kGemmStages = 4;
-constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * 64;                      // 32 KiB
+constexpr int kGemmBM = 256, kGemmBN = 256, kGemmBK = 64, kGemmWM = 2, kGemmWN = 4, kGemmStages = 2;
+constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * kGemmBK * 2;             // 64 KiB
 constexpr int kGemmRingBytes = kGemmStages * kGemmStageBytes;                  // 128 KiB
 
 // ---------------------------------------------------------------------------------------------
@@ -160,12 +161,17 @@ __global__ __launch_bounds__(256) void k_softmax_alpha(int Cin, int N, int heads
 
 // ---------------------------------------------------------------------------------------------
 // GEMM core pieces shared by k_vagg_mfma and k_linear_dl.
-//   Block tile 256 x 256, wavefront (wm, wn) of 2 x 4 owns rows [128 wm, +128) x cols [64 wn, +64):
-//   TM = 4 by TN = 2 MFMA blocks of 32 x 32.  One stage = A rows 0..255 then B rows 0..255, 64 bytes each.
+//   Block tile 256 x 256 x 64, wavefront (wm, wn) of 2 x 4 owns rows [128 wm, +128) x cols [64 wn, +64):
+//   TM = 4 by TN = 2 MFMA blocks of 32 x 32.  One stage = A rows 0..255 then B rows 0..255, 128 bytes each;
+//   two stages: while one is multiplied the other is filled by direct-to-LDS loads of 128-byte row
+//   segments (8 lanes per row), issued a whole slice ahead.
+//   Global -> LDS: wavefront w issues 4 A loads and 4 B loads per slice; load i covers tile rows
+//   w*32 + i*8 + lane/8, i.e. the A rows of wavefront w are the 32 patches of ONE channel of the chunk.
 // ---------------------------------------------------------------------------------------------
 struct GemmLane {
   int lane, wave, wm, wn, l32, lhi;
-  int a_off[4][2], b_off[2][2];   // fragment byte offsets inside a stage, per k-step of 16
+  int a_base, b_base;             // byte offsets of this lane's first A / B fragment row inside a stage
+  int ck[4];                      // swizzled chunk byte offset of k-step kk
   __device__ __forceinline__ void init() {
     lane = threadIdx.x & 63;
     wave = threadIdx.x >> 6;
@@ -173,24 +179,15 @@ struct GemmLane {
     wn = wave % kGemmWN;
     l32 = lane & 31;
     lhi = lane >> 5;
+    a_base = (wm * 128 + l32) * 128;
+    b_base = kGemmBM * 128 + (wn * 64 + l32) * 128;
+    const int sw = swz_chunk(l32);               // row offsets of the other fragments are multiples of 32
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const int row = wm * 128 + i * 32 + l32;
-        a_off[i][kk] = row * 64 + (((kk * 2 + lhi) ^ swz_chunk(row)) * 16);
-      }
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const int row = wn * 64 + j * 32 + l32;
-        b_off[j][kk] = kGemmBM * 64 + row * 64 + (((kk * 2 + lhi) ^ swz_chunk(row)) * 16);
-      }
+    for (int kk = 0; kk < 4; ++kk) ck[kk] = ((kk * 2 + lhi) ^ sw) * 16;
   }
-  // the two wave-wide loads of this wavefront per operand cover tile rows (wave*2 + i) * 16 + lane / 4
-  __device__ __forceinline__ int load_row(int i) const { return (wave * 2 + i) * 16 + (lane >> 2); }
-  __device__ __forceinline__ int load_chunk(int row) const { return (lane & 3) ^ swz_chunk(row); }
+  // load i of this wavefront covers tile row wave*32 + i*8 + lane/8, logical chunk (lane%8) ^ swz(row)
+  __device__ __forceinline__ int load_row(int i) const { return wave * 32 + i * 8 + (lane >> 3); }
+  __device__ __forceinline__ int load_chunk(int row) const { return (lane & 7) ^ swz_chunk(row); }
 };
 
 struct Frags {
@@ -199,9 +196,9 @@ struct Frags {
 
 __device__ __forceinline__ void read_frags(Frags& f, const unsigned char* stage, const GemmLane& L, int kk) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(stage + L.a_off[i][kk]);
+  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(stage + L.a_base + i * 4096 + L.ck[kk]);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(stage + L.b_off[j][kk]);
+  for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(stage + L.b_base + j * 4096 + L.ck[kk]);
 }
 
 __device__ __forceinline__ void mfma_step(f32x16 (&acc)[4][2], const Frags& f) {
@@ -209,6 +206,19 @@ __device__ __forceinline__ void mfma_step(f32x16 (&acc)[4][2], const Frags& f) {
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+
+// One 64-deep slice: four k-steps with the fragments of step kk+1 read while step kk multiplies.
+__device__ __forceinline__ void mfma_slice(f32x16 (&acc)[4][2], const unsigned char* stage, const GemmLane& L) {
+  Frags f0, f1;
+  read_frags(f0, stage, L, 0);
+  read_frags(f1, stage, L, 1);
+  mfma_step(acc, f0);
+  read_frags(f0, stage, L, 2);
+  mfma_step(acc, f1);
+  read_frags(f1, stage, L, 3);
+  mfma_step(acc, f0);
+  mfma_step(acc, f1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -224,7 +234,6 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
                                                    TileWork tw, const bf16* __restrict__ z,
                                                    const bf16* __restrict__ Wv, const bf16* __restrict__ bv,
                                                    const float* __restrict__ alpha, bf16* __restrict__ O) {
-  constexpr int NS = kGemmStages, LPT = 4;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   int k, b, pt, nt;
   if (!tw.decode(blockIdx.x, k, b, pt, nt)) return;
@@ -232,7 +241,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
   const int c0 = k * g;
   const int gk = min(g, Cin - c0);
   const int NCH = (gk + 7) / 8;
-  const int KT = D / 32;
+  const int KT = D / kGemmBK;
   const int dh = D / heads;
   const int NHS = dh >= kGemmBN ? 1 : kGemmBN / dh;      // heads inside this column slice
   const int h0 = o0 / dh;
@@ -244,14 +253,12 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
   const bf16* zb = z + (size_t)b * Cin * N * D;
   const bf16* Wb = Wv + (size_t)k * D * D;
 
-  // per-lane constants of the A loads: channel inside the chunk, patch row, chunk column
-  int a_cl[2];
-  size_t a_rowoff[2];
-  const bf16* b_src[2];
+  // per-lane constants of the loads: patch row and chunk column (the channel of the A rows is the wavefront id)
+  size_t a_rowoff[4];
+  const bf16* b_src[4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < 4; ++i) {
     const int row = L.load_row(i);
-    a_cl[i] = row >> 5;
     a_rowoff[i] = (size_t)min(n0 + (row & 31), N - 1) * D + L.load_chunk(row) * 8;
     b_src[i] = Wb + (size_t)(o0 + row) * D + L.load_chunk(row) * 8;
   }
@@ -259,14 +266,13 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
   int si = 0;                                            // stage the next issue fills
   auto issue = [&]() {
     unsigned char* st = smem + si * kGemmStageBytes;
+    const bf16* zc = zb + (size_t)(c0 + min(ci * 8 + L.wave, gk - 1)) * N * D + ki * kGemmBK;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = c0 + min(ci * 8 + a_cl[i], gk - 1);
-      load16_to_lds(zb + (size_t)c * N * D + a_rowoff[i] + ki * 32, st + (L.wave * 2 + i) * 1024);
-    }
+    for (int i = 0; i < 4; ++i) load16_to_lds(zc + a_rowoff[i], st + (L.wave * 4 + i) * 1024);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) load16_to_lds(b_src[i] + ki * 32, st + kGemmBM * 64 + (L.wave * 2 + i) * 1024);
-    si = (si + 1 == NS) ? 0 : si + 1;
+    for (int i = 0; i < 4; ++i)
+      load16_to_lds(b_src[i] + ki * kGemmBK, st + kGemmBM * 128 + (L.wave * 4 + i) * 1024);
+    si ^= 1;
     ++ki;
     const bool wrap = (ki == KT);
     ki = wrap ? 0 : ki;
@@ -288,17 +294,9 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
 
-  // prologue: alpha of chunk 0, the first NS-2 slices, then one more after the first barrier
   issue_alpha(0);
-#pragma unroll
-  for (int s = 0; s < NS - 2; ++s) issue();
-  wait_vmcnt<(NS - 3) * LPT>();
-  __builtin_amdgcn_s_barrier();
-  issue();
-  Frags f0, f1;
-  int sc = 0;                                            // stage being computed
-  read_frags(f0, smem, L, 0);
-
+  issue();                                               // slice 0 -> stage 0
+  int sc = 0;                                            // stage being multiplied
   for (int chunk = 0; chunk < NCH; ++chunk) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -308,15 +306,11 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     if (chunk + 1 < NCH) issue_alpha(chunk + 1);
     for (int kt = 0; kt < KT; ++kt) {
-      const unsigned char* st = smem + sc * kGemmStageBytes;
-      read_frags(f1, st, L, 1);
-      mfma_step(acc, f0);
-      wait_vmcnt<(NS - 3) * LPT>();                      // the next slice has landed (one more may be in flight)
-      __builtin_amdgcn_s_barrier();
-      issue();
-      sc = (sc + 1 == NS) ? 0 : sc + 1;
-      read_frags(f0, smem + sc * kGemmStageBytes, L, 0);
-      mfma_step(acc, f1);
+      wait_vmcnt<0>();                                   // this wavefront's share of the current slice has landed
+      __builtin_amdgcn_s_barrier();                      // ... everybody's has, and the other stage is free
+      issue();                                           // next slice -> other stage, a whole slice ahead
+      mfma_slice(acc, smem + sc * kGemmStageBytes, L);
+      sc ^= 1;
     }
     // o += alpha * acc for the 4 channels of this wavefront
     const float* al = reinterpret_cast<const float*>(alds + (chunk % 3) * atile);
@@ -338,7 +332,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
 
   // all direct-to-LDS loads done and every wavefront past its last stage read: the ring is free
   wait_vmcnt<0>();
-  __builtin_amdgcn_s_barrier();
+  __syncthreads();
   float* mg = reinterpret_cast<float*>(smem);            // [wn][32 values][64 lanes]
   if (L.wm == 1) {
 #pragma unroll
@@ -370,23 +364,22 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
 __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork tw, const bf16* __restrict__ A,
                                                    const bf16* __restrict__ Wt, const bf16* __restrict__ bias,
                                                    bf16* __restrict__ Y) {
-  constexpr int NS = kGemmStages, LPT = 4;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   int k, b, mt, nt;
   if (!tw.decode(blockIdx.x, k, b, mt, nt)) return;
   const int rows = rb.rows_of(k);
   const int r0 = mt * kGemmBM, o0 = nt * kGemmBN;
   if (r0 >= rows) return;
-  const int KT = D / 32;
+  const int KT = D / kGemmBK;
   GemmLane L;
   L.init();
   const bf16* Ab = A + (size_t)rb.first_row(b, k) * D;
   bf16* Yb = Y + (size_t)rb.first_row(b, k) * D;
   const bf16* Wb = Wt + (size_t)k * D * D;
-  const bf16* a_src[2];
-  const bf16* b_src[2];
+  const bf16* a_src[4];
+  const bf16* b_src[4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < 4; ++i) {
     const int row = L.load_row(i);
     a_src[i] = Ab + (size_t)min(r0 + row, rows - 1) * D + L.load_chunk(row) * 8;
     b_src[i] = Wb + (size_t)(o0 + row) * D + L.load_chunk(row) * 8;
@@ -395,11 +388,12 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
   auto issue = [&]() {
     unsigned char* st = smem + si * kGemmStageBytes;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) load16_to_lds(a_src[i] + ki * 32, st + (L.wave * 2 + i) * 1024);
+    for (int i = 0; i < 4; ++i) load16_to_lds(a_src[i] + ki * kGemmBK, st + (L.wave * 4 + i) * 1024);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) load16_to_lds(b_src[i] + ki * 32, st + kGemmBM * 64 + (L.wave * 2 + i) * 1024);
-    si = (si + 1 == NS) ? 0 : si + 1;
-    ki = (ki + 1 < KT) ? ki + 1 : ki;                    // past the end: harmless re-loads of the last slice
+    for (int i = 0; i < 4; ++i)
+      load16_to_lds(b_src[i] + ki * kGemmBK, st + kGemmBM * 128 + (L.wave * 4 + i) * 1024);
+    si ^= 1;
+    ki = (ki + 1 < KT) ? ki + 1 : ki;                    // past the end: harmless re-load of the last slice
   };
   f32x16 acc[4][2];
 #pragma unroll
@@ -408,24 +402,14 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-#pragma unroll
-  for (int s = 0; s < NS - 2; ++s) issue();
-  wait_vmcnt<(NS - 3) * LPT>();
-  __builtin_amdgcn_s_barrier();
   issue();
-  Frags f0, f1;
   int sc = 0;
-  read_frags(f0, smem, L, 0);
   for (int kt = 0; kt < KT; ++kt) {
-    const unsigned char* st = smem + sc * kGemmStageBytes;
-    read_frags(f1, st, L, 1);
-    mfma_step(acc, f0);
-    wait_vmcnt<(NS - 3) * LPT>();
+    wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     issue();
-    sc = (sc + 1 == NS) ? 0 : sc + 1;
-    read_frags(f0, smem + sc * kGemmStageBytes, L, 0);
-    mfma_step(acc, f1);
+    mfma_slice(acc, smem + sc * kGemmStageBytes, L);
+    sc ^= 1;
   }
   wait_vmcnt<0>();                                       // no load may still target LDS when the block retires
 #pragma unroll
@@ -450,22 +434,26 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
 // and cs[c][a] = sum_d M[k][a][d] (be[c][d] + ce[c][d]) in fp32 (k = c / g);
 // k_scores_pixels then scores every (channel, patch) with a p*p-long dot product per head.
 // ---------------------------------------------------------------------------------------------
-// grid (C, kComposeSlices), block 256.  Outputs are tiled 4 heads x 4 pixels; lane l of every wavefront
-// owns tiles l, l+64, ... (TPL of them).  Block slice y sums d over its share of D, its four
-// wavefronts each a quarter of that, meeting in LDS; the slices' partial results are written side by
-// side (Ms[slice][c][heads][pp], cs[slice][c][heads]) and added up by the reader, so the sum order is
-// fixed.  MfT is the folded key transposed to [G][D][heads]: a lane reads its 4 heads as one 16-byte
-// load.  Requires heads % 4 == 0, pp % 4 == 0, D % (16 * kComposeSlices) == 0.
-constexpr int kComposeSlices = 4;
+// grid (C), block 256.  The channel's tokenizer weights and the transposed folded key MfT[G][D][heads]
+// stream through LDS in blocks of DQ rows of d (full-width 16-byte loads); outputs are tiled 4 heads x 4
+// pixels, lane l of every wavefront owns tiles l, l+64, ... (TPL of them) and wavefront w sums the
+// rows d = w (mod 4) of a block; the four partial sums meet in LDS in a fixed order.  Writes fp32 Ms,
+// its bf16 copy Msb (the MFMA operand of k_scores_pixels) and cs.
+// Requires heads % 4 == 0, pp % 8 == 0, DQ % 4 == 0, D % DQ == 0.
+// Dynamic LDS: DQ * (pp * 2 + heads * 4 + 4) bytes, then 3 * TPL * 64 * 20 floats.
 template <int TPL>
-__global__ __launch_bounds__(256) void k_compose_score_weights(int C, int D, int heads, int pp, int g,
+__global__ __launch_bounds__(256) void k_compose_score_weights(int D, int heads, int pp, int g, int DQ,
                                                                const float* __restrict__ MfT,
                                                                const bf16* __restrict__ We, const bf16* __restrict__ be,
                                                                const bf16* __restrict__ ce, float* __restrict__ Ms,
-                                                               float* __restrict__ cs) {
-  __shared__ float part[3][TPL * 64 * 20];               // partial sums of wavefronts 1..3: 16 tile values + 4 constants
-  const int c = blockIdx.x, k = c / g, slice = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+                                                               bf16* __restrict__ Msb, float* __restrict__ cs) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* w_s = reinterpret_cast<bf16*>(smem);                                   // [DQ][pp]
+  float* m_s = reinterpret_cast<float*>(smem + (size_t)DQ * pp * 2);           // [DQ][heads]
+  float* b_s = m_s + (size_t)DQ * heads;                                       // [DQ]
+  float* part = b_s + DQ;                                                      // [3][TPL*20][64]
+  const int c = blockIdx.x, k = c / g;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kq_n = pp / 4, aq_n = heads / 4, ntiles = kq_n * aq_n;
   const float* M = MfT + (size_t)k * D * heads;
   const bf16* Wc = We + (size_t)c * D * pp;
@@ -481,23 +469,33 @@ __global__ __launch_bounds__(256) void k_compose_score_weights(int C, int D, int
 #pragma unroll
     for (int e = 0; e < 4; ++e) cacc[t][e] = 0.f;
   }
-  const int dq = D / (4 * kComposeSlices);
-  const int dbeg = (slice * 4 + wave) * dq;
-#pragma unroll 16
-  for (int d = dbeg; d < dbeg + dq; ++d) {
-    float bsum = 0.f;
-    if (be) bsum += (float)be[(size_t)c * D + d];
-    if (ce) bsum += (float)ce[(size_t)c * D + d];
+  for (int d0 = 0; d0 < D; d0 += DQ) {
+    __syncthreads();
+    for (int idx = tid; idx < DQ * pp / 8; idx += 256)
+      reinterpret_cast<bf16x8*>(w_s)[idx] = reinterpret_cast<const bf16x8*>(Wc + (size_t)d0 * pp)[idx];
+    for (int idx = tid; idx < DQ * heads / 4; idx += 256)
+      reinterpret_cast<f32x4*>(m_s)[idx] = reinterpret_cast<const f32x4*>(M + (size_t)d0 * heads)[idx];
+    for (int idx = tid; idx < DQ; idx += 256) {
+      float bsum = 0.f;
+      if (be) bsum += (float)be[(size_t)c * D + d0 + idx];
+      if (ce) bsum += (float)ce[(size_t)c * D + d0 + idx];
+      b_s[idx] = bsum;
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int d = wave; d < DQ; d += 4) {
+      const float bsum = b_s[d];
 #pragma unroll
-    for (int t = 0; t < TPL; ++t) {
-      if (kq[t] < 0) continue;
-      const f32x4 m4 = *reinterpret_cast<const f32x4*>(M + (size_t)d * heads + aq[t] * 4);
-      const bf16x4 w4 = *reinterpret_cast<const bf16x4*>(Wc + (size_t)d * pp + kq[t] * 4);
+      for (int t = 0; t < TPL; ++t) {
+        if (kq[t] < 0) continue;
+        const f32x4 m4 = *reinterpret_cast<const f32x4*>(m_s + (size_t)d * heads + aq[t] * 4);
+        const bf16x4 w4 = *reinterpret_cast<const bf16x4*>(w_s + (size_t)d * pp + kq[t] * 4);
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
+        for (int a = 0; a < 4; ++a) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) acc[t][a * 4 + q] += m4[a] * (float)w4[q];
-        cacc[t][a] += m4[a] * bsum;
+          for (int q = 0; q < 4; ++q) acc[t][a * 4 + q] += m4[a] * (float)w4[q];
+          cacc[t][a] += m4[a] * bsum;
+        }
       }
     }
   }
@@ -505,15 +503,15 @@ __global__ __launch_bounds__(256) void k_compose_score_weights(int C, int D, int
 #pragma unroll
     for (int t = 0; t < TPL; ++t) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) part[wave - 1][(t * 20 + e) * 64 + lane] = acc[t][e];
+      for (int e = 0; e < 16; ++e) part[((wave - 1) * TPL * 20 + t * 20 + e) * 64 + lane] = acc[t][e];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) part[wave - 1][(t * 20 + 16 + e) * 64 + lane] = cacc[t][e];
+      for (int e = 0; e < 4; ++e) part[((wave - 1) * TPL * 20 + t * 20 + 16 + e) * 64 + lane] = cacc[t][e];
     }
   }
   __syncthreads();
   if (wave == 0) {
-    float* Mo = Ms + ((size_t)slice * C + c) * heads * pp;
-    float* co = cs + ((size_t)slice * C + c) * heads;
+    float* Mo = Ms + (size_t)c * heads * pp;
+    bf16* Mbo = Msb + (size_t)c * heads * pp;
 #pragma unroll
     for (int t = 0; t < TPL; ++t) {
       if (kq[t] < 0) continue;
@@ -521,98 +519,71 @@ __global__ __launch_bounds__(256) void k_compose_score_weights(int C, int D, int
       for (int a = 0; a < 4; ++a) {
         const int head = aq[t] * 4 + a;
         f32x4 v4;
+        bf16x4 b4;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int e = a * 4 + q;
-          v4[q] = acc[t][e] + part[0][(t * 20 + e) * 64 + lane] + part[1][(t * 20 + e) * 64 + lane] +
-                  part[2][(t * 20 + e) * 64 + lane];
+          v4[q] = acc[t][e] + part[((0 * TPL + t) * 20 + e) * 64 + lane] + part[((1 * TPL + t) * 20 + e) * 64 + lane] +
+                  part[((2 * TPL + t) * 20 + e) * 64 + lane];
+          b4[q] = (bf16)v4[q];
         }
         *reinterpret_cast<f32x4*>(Mo + (size_t)head * pp + kq[t] * 4) = v4;
+        *reinterpret_cast<bf16x4*>(Mbo + (size_t)head * pp + kq[t] * 4) = b4;
         if (kq[t] == 0) {
           const int e = 16 + a;
-          co[head] = cacc[t][a] + part[0][(t * 20 + e) * 64 + lane] + part[1][(t * 20 + e) * 64 + lane] +
-                     part[2][(t * 20 + e) * 64 + lane];
+          cs[(size_t)c * heads + head] = cacc[t][a] + part[((0 * TPL + t) * 20 + e) * 64 + lane] +
+                                         part[((1 * TPL + t) * 20 + e) * 64 + lane] +
+                                         part[((2 * TPL + t) * 20 + e) * 64 + lane];
         }
       }
     }
   }
 }
 
-// grid (ceil(N/32), G * ceil(g/8), B), block 256: 32 patches x up to 8 members of one group, one member
-// at a time, the next member's pixels and weights fetched into registers while the current one is scored.
-// Thread (patch = t % 32, hq = t / 32) scores heads hq, hq + 8, ...  The pixel offsets of a thread's
-// share of the gather do not depend on the channel and are computed once.
-// Dynamic LDS: (heads*pp + 32*(pp+1)) floats.  Requires pp <= 256 and heads*pp <= 256 * 32.
-template <int MAXG, int MAXM>   // register slots per thread for the pixel gather (32*pp/256) and the weights (heads*pp/256)
-__global__ __launch_bounds__(256) void k_scores_pixels(int C, int H, int W, int p, int heads, int g, int gpad, int Np,
-                                                       const bf16* __restrict__ x, const float* __restrict__ Ms,
-                                                       const float* __restrict__ cs, float* __restrict__ S) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+// Level-1 scores on MFMA: S[b][k][cl][head][n] = u[b,c,n][:] . Msb[c][head][:] + cs[c][head].
+// grid (ceil(N/128), C, B), block 256: wavefront w scores 32 patches of channel c against up to 32 heads
+// with one 32x32x16 MFMA per 16 pixels.  A lane's operand (8 consecutive pixels of a patch) is one
+// 16-byte load when p % 8 == 0, two 8-byte loads when p == 4.  Requires heads <= 32, pp % 16 == 0.
+__global__ __launch_bounds__(256) void k_scores_pixels(int C, int H, int W, int p, int heads, int g, int gpad, int G,
+                                                       int Np, const bf16* __restrict__ x,
+                                                       const bf16* __restrict__ Msb, const float* __restrict__ cs,
+                                                       float* __restrict__ S) {
   const int pp = p * p, pw = W / p, N = (H / p) * pw;
-  float* ms = reinterpret_cast<float*>(smem);            // [heads][pp]
-  float* u = ms + heads * pp;                            // [32][pp + 1]
-  const int cch = (g + 7) / 8;
-  const int n0 = blockIdx.x * 32, k = blockIdx.y / cch, cc = blockIdx.y % cch, b = blockIdx.z, G = gridDim.y / cch;
-  const int c0 = k * g, gk = min(g, C - c0);
-  const int cl_beg = cc * 8, cl_end = min(cl_beg + 8, gk);
-  if (cl_beg >= cl_end) return;
-  const int tp = threadIdx.x & 31, hq = threadIdx.x >> 5;
-  const int ng = (32 * pp + 255) / 256, nm = (heads * pp + 255) / 256;
-  int goff[MAXG], gdst[MAXG];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+  const int c = blockIdx.y, b = blockIdx.z, k = c / g, cl = c % g;
+  const int n0 = blockIdx.x * 128 + wave * 32;
+  if (n0 >= N) return;
+  const int n = min(n0 + l32, N - 1);
+  const int pi = n / pw, pj = n % pw;
+  const bf16* img = x + ((size_t)b * C + c) * H * W + (size_t)(pi * p) * W + pj * p;
+  const bf16* mrow = Msb + ((size_t)c * heads + min(l32, heads - 1)) * pp;
+  f32x16 acc;
 #pragma unroll
-  for (int s = 0; s < MAXG; ++s) {
-    const int idx = threadIdx.x + s * 256;
-    goff[s] = -1;
-    gdst[s] = 0;
-    if (s < ng && idx < 32 * pp) {
-      const int t = idx / pp, kk = idx % pp;
-      const int n = min(n0 + t, N - 1);
-      const int pi = n / pw, pj = n % pw, r = kk / p, s2 = kk % p;
-      goff[s] = (pi * p + r) * W + pj * p + s2;
-      gdst[s] = t * (pp + 1) + kk;
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int kc = lhi; kc < pp / 8; kc += 2) {            // 8-pixel chunk of the patch
+    bf16x8 a;
+    if (p == 4) {
+      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc) * W);
+      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc + 1) * W);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { a[e] = lo[e]; a[4 + e] = hi[e]; }
+    } else {
+      const int r = (kc * 8) / p, s0 = (kc * 8) % p;
+      a = *reinterpret_cast<const bf16x8*>(img + (size_t)r * W + s0);
     }
+    bf16x8 m = *reinterpret_cast<const bf16x8*>(mrow + kc * 8);
+    if (l32 >= heads) m = bf16x8{};
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, m, acc, 0, 0, 0);
   }
-  float upre[MAXG], mpre[MAXM];
-  auto fetch = [&](int cl) {
-    const int c = c0 + cl;
-    const bf16* img = x + ((size_t)b * C + c) * H * W;
+  if (l32 < heads) {
+    const float add = cs[(size_t)c * heads + l32];
+    float* dst = S + ((((size_t)b * G + k) * gpad + cl) * heads + l32) * Np + n0 + 4 * lhi;
 #pragma unroll
-    for (int s = 0; s < MAXG; ++s)
-      if (s < ng && goff[s] >= 0) upre[s] = (float)img[goff[s]];
+    for (int q = 0; q < 4; ++q) {
+      f32x4 v;
 #pragma unroll
-    for (int s = 0; s < MAXM; ++s) {
-      const int idx = threadIdx.x + s * 256;
-      if (s < nm && idx < heads * pp) {
-        float v = 0.f;
-#pragma unroll
-        for (int sl = 0; sl < kComposeSlices; ++sl) v += Ms[((size_t)sl * C + c) * heads * pp + idx];
-        mpre[s] = v;
-      }
-    }
-  };
-  fetch(cl_beg);
-  for (int cl = cl_beg; cl < cl_end; ++cl) {
-    const int c = c0 + cl;
-    __syncthreads();
-#pragma unroll
-    for (int s = 0; s < MAXG; ++s)
-      if (s < ng && goff[s] >= 0) u[gdst[s]] = upre[s];
-#pragma unroll
-    for (int s = 0; s < MAXM; ++s) {
-      const int idx = threadIdx.x + s * 256;
-      if (s < nm && idx < heads * pp) ms[idx] = mpre[s];
-    }
-    __syncthreads();
-    if (cl + 1 < cl_end) fetch(cl + 1);
-    for (int a = hq; a < heads; a += 8) {
-      float acc = 0.f;
-#pragma unroll
-      for (int sl = 0; sl < kComposeSlices; ++sl) acc += cs[((size_t)sl * C + c) * heads + a];
-      const float* m = ms + a * pp;
-      const float* ur = u + tp * (pp + 1);
-#pragma unroll 8
-      for (int kk = 0; kk < pp; ++kk) acc += ur[kk] * m[kk];
-      S[((((size_t)b * G + k) * gpad + cl) * heads + a) * Np + n0 + tp] = acc;
+      for (int e = 0; e < 4; ++e) v[e] = acc[4 * q + e] + add;
+      *reinterpret_cast<f32x4*>(dst + 8 * q) = v;
     }
   }
 }
