@@ -128,6 +128,19 @@ struct StageTimer {
   }
 };
 
+int compute_units() {
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n >= kXcds)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
 bool force_generic() {
   // DCHAG_GEMM=generic routes the bf16 projections through the fp32-FMA tile kernel (debug aid).
   const char* e = getenv("DCHAG_GEMM");
@@ -376,9 +389,11 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_vagg_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
                             lds) != hipSuccess)
       return DCHAG_ERR_LAUNCH;
-    k_vagg_mfma<<<dim3(per * kXcds), dim3(512), lds, st>>>(Cin, N, D, heads, g, gpad, G, Np, tw, zin,
-                                                          static_cast<const bf16*>(lv->Wv),
-                                                          static_cast<const bf16*>(lv->bv), alpha, O);
+    // persistent workgroups: one per compute unit (the LDS ring allows no more), `slots` per XCD
+    const int slots = per < compute_units() / kXcds ? per : compute_units() / kXcds;
+    k_vagg_mfma<<<dim3(slots * kXcds), dim3(512), lds, st>>>(Cin, N, D, heads, g, gpad, G, Np, tw, slots, zin,
+                                                            static_cast<const bf16*>(lv->Wv),
+                                                            static_cast<const bf16*>(lv->bv), alpha, O);
     if ((rc = launch_status())) return rc;
   }
   StageTimer tm(DCHAG_STAGE_OPROJ, st);

@@ -224,137 +224,184 @@ __device__ __forceinline__ void mfma_slice(f32x16 (&acc)[4][2], const unsigned c
 // ---------------------------------------------------------------------------------------------
 // Value projection with the channel aggregation in its epilogue:
 //   O[b,k,n,o] = sum_{cl < gk} alpha[b][k][cl][head(o)][n] * (z[b, k*g + cl, n, :] . Wv[k][o][:]) + bv[k][o]
-// Work item (linear id decoded by TileWork with m = patch tile): group k, batch b, 32 patches, 256 columns.
-// The block walks the group in chunks of 8 channels: tile row r = (channel r / 32 of the chunk, patch r % 32).
+// Work item (decoded by TileWork with m = patch tile): group k, batch b, 32 patches, 256 columns; the group
+// is walked in chunks of 8 channels.  LDS tile row (wm*128 + i*32 + l) holds channel 2i + l/16 of the chunk,
+// patch 16*wm + l%16, so wavefront (wm, wn) sees all 8 channels of ITS 16 patches: the weighted sum over
+// the channels stays inside the wavefront's registers (rows q = 0,1 of an accumulator block belong to
+// channel 2i, rows q = 2,3 to channel 2i+1) and no cross-wavefront merge is needed.
+// The kernel is persistent: workgroup L takes items L/8, L/8 + slots, ... of its XCD's contiguous
+// range, and the two-stage ring keeps prefetching across chunk and item boundaries (one slice ahead).
 // Requires D % 256 == 0, dh = D / heads a multiple of 32, and 256 % dh == 0 or dh % 256 == 0.
-// Dynamic LDS: ring (128 KiB) + 3 alpha tiles of 8 * NHS * 32 floats (a tile is refilled two chunks
-// after its last reader, so no wavefront can still be reading it).
+// Dynamic LDS: ring (128 KiB) + 3 alpha tiles of 8 * NHS * 32 floats, used round-robin by chunk.
 // ---------------------------------------------------------------------------------------------
+struct VaggItem {
+  int k, b, n0, o0, c0, gk, nch, h0;
+};
+
 __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int heads, int g, int gpad, int G, int Np,
-                                                   TileWork tw, const bf16* __restrict__ z,
+                                                   TileWork tw, int slots, const bf16* __restrict__ z,
                                                    const bf16* __restrict__ Wv, const bf16* __restrict__ bv,
                                                    const float* __restrict__ alpha, bf16* __restrict__ O) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  int k, b, pt, nt;
-  if (!tw.decode(blockIdx.x, k, b, pt, nt)) return;
-  const int n0 = pt * 32, o0 = nt * kGemmBN;
-  const int c0 = k * g;
-  const int gk = min(g, Cin - c0);
-  const int NCH = (gk + 7) / 8;
   const int KT = D / kGemmBK;
   const int dh = D / heads;
-  const int NHS = dh >= kGemmBN ? 1 : kGemmBN / dh;      // heads inside this column slice
-  const int h0 = o0 / dh;
+  const int NHS = dh >= kGemmBN ? 1 : kGemmBN / dh;      // heads inside a 256-column slice
   unsigned char* alds = smem + kGemmRingBytes;           // 3 tiles of [8][NHS][32] floats
   const int atile = 8 * NHS * 32 * 4;
 
+  // this workgroup's items: w = xcd * per + t * slots + slot, t = 0, 1, ...
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int per = (tw.total + kXcds - 1) / kXcds;
+  const int xcd_end = min((xcd + 1) * per, tw.total);
+  auto item_of = [&](int t, VaggItem& it) -> bool {
+    const int w = xcd * per + t * slots + slot;
+    if (w >= xcd_end) return false;
+    int pt, nt;
+    tw.decode_linear(w, it.k, it.b, pt, nt);
+    it.n0 = pt * 32;
+    it.o0 = nt * kGemmBN;
+    it.c0 = it.k * g;
+    it.gk = min(g, Cin - it.c0);
+    it.nch = (it.gk + 7) / 8;
+    it.h0 = it.o0 / dh;
+    return true;
+  };
+
   GemmLane L;
   L.init();
-  const bf16* zb = z + (size_t)b * Cin * N * D;
-  const bf16* Wb = Wv + (size_t)k * D * D;
-
-  // per-lane constants of the loads: patch row and chunk column (the channel of the A rows is the wavefront id)
-  size_t a_rowoff[4];
-  const bf16* b_src[4];
+  // A loads of wavefront w fill LDS rows w*32 + i*8 + lane/8: channel 2*(w%4) + (l>>4), patch 16*(w/4) + (l&15)
+  int a_ch[4], a_patch[4], ld_chunk[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int row = L.load_row(i);
-    a_rowoff[i] = (size_t)min(n0 + (row & 31), N - 1) * D + L.load_chunk(row) * 8;
-    b_src[i] = Wb + (size_t)(o0 + row) * D + L.load_chunk(row) * 8;
+    const int l = i * 8 + (L.lane >> 3);
+    a_ch[i] = 2 * (L.wave & 3) + (l >> 4);
+    a_patch[i] = 16 * (L.wave >> 2) + (l & 15);
+    ld_chunk[i] = L.load_chunk(L.load_row(i)) * 8;
   }
-  int ci = 0, ki = 0;                                    // issue cursor (chunk, k-slice)
-  int si = 0;                                            // stage the next issue fills
+
+  // ---- issue side ----
+  VaggItem ii;
+  int ti = 0;
+  bool live = item_of(0, ii);
+  if (!live) return;                                     // uniform: the whole workgroup has nothing to do
+  size_t a_rowoff[4];
+  const bf16* b_src[4];
+  const bf16* zb;
+  auto setup_issue = [&]() {
+    zb = z + (size_t)ii.b * Cin * N * D;
+    const bf16* Wb = Wv + (size_t)ii.k * D * D;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a_rowoff[i] = (size_t)min(ii.n0 + a_patch[i], N - 1) * D + ld_chunk[i];
+      b_src[i] = Wb + (size_t)(ii.o0 + L.load_row(i)) * D + ld_chunk[i];
+    }
+  };
+  setup_issue();
+  int ci = 0, ki = 0, si = 0, gci = 0;                   // chunk, k-slice, stage, running chunk count (alpha buffer)
   auto issue = [&]() {
-    unsigned char* st = smem + si * kGemmStageBytes;
-    const bf16* zc = zb + (size_t)(c0 + min(ci * 8 + L.wave, gk - 1)) * N * D + ki * kGemmBK;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) load16_to_lds(zc + a_rowoff[i], st + (L.wave * 4 + i) * 1024);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      load16_to_lds(b_src[i] + ki * kGemmBK, st + kGemmBM * 128 + (L.wave * 4 + i) * 1024);
-    si ^= 1;
-    ++ki;
-    const bool wrap = (ki == KT);
-    ki = wrap ? 0 : ki;
-    ci = (wrap && ci + 1 < NCH) ? ci + 1 : ci;           // past the end: harmless re-loads of the last chunk
-  };
-  auto issue_alpha = [&](int chunk) {
-    if (L.wave < NHS) {
-      const int s = L.wave * 8 + (L.lane >> 3);          // segment = (channel of the chunk, head of the slice)
-      const int cl = chunk * 8 + s / NHS, hd = s % NHS;
-      const float* src = alpha + ((((size_t)b * G + k) * gpad + cl) * heads + h0 + hd) * Np + n0 + (L.lane & 7) * 4;
-      load16_to_lds(src, alds + (chunk % 3) * atile + L.wave * 1024);
-    }
-  };
-
-  f32x16 acc[4][2];
-  f32x16 o[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
-
-  issue_alpha(0);
-  issue();                                               // slice 0 -> stage 0
-  int sc = 0;                                            // stage being multiplied
-  for (int chunk = 0; chunk < NCH; ++chunk) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    if (chunk + 1 < NCH) issue_alpha(chunk + 1);
-    for (int kt = 0; kt < KT; ++kt) {
-      wait_vmcnt<0>();                                   // this wavefront's share of the current slice has landed
-      __builtin_amdgcn_s_barrier();                      // ... everybody's has, and the other stage is free
-      issue();                                           // next slice -> other stage, a whole slice ahead
-      mfma_slice(acc, smem + sc * kGemmStageBytes, L);
-      sc ^= 1;
-    }
-    // o += alpha * acc for the 4 channels of this wavefront
-    const float* al = reinterpret_cast<const float*>(alds + (chunk % 3) * atile);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int hrel = (o0 + L.wn * 64 + j * 32) / dh - h0;
+    if (live) {
+      if (ki == 0 && L.wave < NHS) {                     // entering a chunk: fetch its softmax weights
+        const int sgm = L.wave * 8 + (L.lane >> 3);      // segment = (channel of the chunk, head of the slice)
+        const int cl = ci * 8 + sgm / NHS, hd = sgm % NHS;
+        const float* src = alpha + ((((size_t)ii.b * G + ii.k) * gpad + cl) * heads + ii.h0 + hd) * Np + ii.n0 +
+                           (L.lane & 7) * 4;
+        load16_to_lds(src, alds + (gci % 3) * atile + L.wave * 1024);
+      }
+      unsigned char* st = smem + si * kGemmStageBytes;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float* ap = al + ((L.wm * 4 + i) * NHS + hrel) * 32 + 4 * L.lhi;
+        const int c = ii.c0 + min(ci * 8 + a_ch[i], ii.gk - 1);
+        load16_to_lds(zb + (size_t)c * N * D + a_rowoff[i] + ki * kGemmBK, st + (L.wave * 4 + i) * 1024);
+      }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 a4 = *reinterpret_cast<const f32x4*>(ap + 8 * q);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[j][4 * q + e] += a4[e] * acc[i][j][4 * q + e];
+      for (int i = 0; i < 4; ++i)
+        load16_to_lds(b_src[i] + ki * kGemmBK, st + kGemmBM * 128 + (L.wave * 4 + i) * 1024);
+      if (++ki == KT) {
+        ki = 0;
+        ++gci;
+        if (++ci == ii.nch) {
+          ci = 0;
+          live = item_of(++ti, ii);
+          if (live) setup_issue();
         }
       }
     }
-  }
+    si ^= 1;
+  };
 
-  // all direct-to-LDS loads done and every wavefront past its last stage read: the ring is free
+  // ---- compute side ----
+  issue();                                               // first slice -> stage 0
+  int sc = 0, gcc = 0;
+  Frags f0, f1;
   wait_vmcnt<0>();
-  __syncthreads();
-  float* mg = reinterpret_cast<float*>(smem);            // [wn][32 values][64 lanes]
-  if (L.wm == 1) {
+  __builtin_amdgcn_s_barrier();
+  issue();                                               // second slice -> stage 1
+  read_frags(f0, smem, L, 0);
+  VaggItem ic;
+  for (int tc = 0; item_of(tc, ic); ++tc) {
+    f32x16 o[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mg[((L.wn * 32 + j * 16 + r) * 64) + L.lane] = o[j][r];
-  }
-  __syncthreads();
-  if (L.wm == 0) {
-    bf16* Ob = O + (((size_t)b * G + k) * N) * D;
+      for (int r = 0; r < 16; ++r) o[j][r] = 0.f;      // only entries 0..7 are used
+    for (int chunk = 0; chunk < ic.nch; ++chunk, ++gcc) {
+      f32x16 acc[4][2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int kt = 0; kt < KT; ++kt) {
+        // k-steps 0..2 of the current slice; the fragments of step 0 were read across the last barrier
+        const unsigned char* st = smem + sc * kGemmStageBytes;
+        read_frags(f1, st, L, 1);
+        mfma_step(acc, f0);
+        read_frags(f0, st, L, 2);
+        mfma_step(acc, f1);
+        read_frags(f1, st, L, 3);
+        mfma_step(acc, f0);
+        // every read of this stage is in registers and the next slice has landed: swap stages
+        __builtin_amdgcn_s_waitcnt(0);                   // vmcnt(0) and lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        issue();                                         // slice after next -> the stage just released
+        sc ^= 1;
+        read_frags(f0, smem + sc * kGemmStageBytes, L, 0);
+        mfma_step(acc, f1);
+      }
+      // o += alpha * acc over the 8 channels of the chunk (channel 2i in rows q = 0,1; 2i+1 in rows q = 2,3)
+      const float* al = reinterpret_cast<const float*>(alds + (gcc % 3) * atile);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int hrel = (ic.o0 + L.wn * 64 + j * 32) / dh - ic.h0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const float* ap = al + ((2 * i + half) * NHS + hrel) * 32 + 16 * L.wm + 4 * L.lhi;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+              const f32x4 a4 = *reinterpret_cast<const f32x4*>(ap + 8 * q);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) o[j][4 * q + e] += a4[e] * acc[i][j][8 * half + 4 * q + e];
+            }
+          }
+        }
+      }
+    }
+    bf16* Ob = O + (((size_t)ic.b * G + ic.k) * N) * D;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int col = o0 + L.wn * 64 + j * 32 + L.l32;
-      const float bias = bv ? (float)bv[(size_t)k * D + col] : 0.f;
+      const int col = ic.o0 + L.wn * 64 + j * 32 + L.l32;
+      const float bias = bv ? (float)bv[(size_t)ic.k * D + col] : 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int nrow = n0 + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
-        const float v = o[j][r] + mg[((L.wn * 32 + j * 16 + r) * 64) + L.lane] + bias;
-        if (nrow < N) Ob[(size_t)nrow * D + col] = (bf16)v;
+      for (int r = 0; r < 8; ++r) {
+        const int nrow = ic.n0 + 16 * L.wm + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
+        if (nrow < N) Ob[(size_t)nrow * D + col] = (bf16)(o[j][r] + bias);
       }
     }
   }
+  wait_vmcnt<0>();                                       // nothing may still target LDS when the block retires
 }
 
 // ---------------------------------------------------------------------------------------------

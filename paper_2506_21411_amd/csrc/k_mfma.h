@@ -20,6 +20,15 @@ __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * 8 + (
 // n-tiles sharing an A tile and the m-tiles/batches sharing a group's weights meet in one L2.
 struct TileWork {
   int total, n_tiles, m_tiles, nb;
+  // position w of the (k, b, m, n) order, n fastest
+  __device__ __forceinline__ void decode_linear(int w, int& k, int& b, int& mt, int& nt) const {
+    nt = w % n_tiles;
+    int rest = w / n_tiles;
+    mt = rest % m_tiles;
+    rest /= m_tiles;
+    b = rest % nb;
+    k = rest / nb;
+  }
   __device__ __forceinline__ bool decode(int L, int& k, int& b, int& mt, int& nt) const {
     const int per = (total + kXcds - 1) / kXcds;
     const int w = (L % kXcds) * per + L / kXcds;
