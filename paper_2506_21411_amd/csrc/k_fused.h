@@ -174,7 +174,7 @@ struct GemmLane {
   int ck[4];                      // swizzled chunk byte offset of k-step kk
   __device__ __forceinline__ void init() {
     lane = threadIdx.x & 63;
-    wave = threadIdx.x >> 6;
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: lives in a scalar register
     wm = wave / kGemmWN;
     wn = wave % kGemmWN;
     l32 = lane & 31;
@@ -206,6 +206,15 @@ __device__ __forceinline__ void mfma_step(f32x16 (&acc)[4][2], const Frags& f) {
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+
+// First k-step of an accumulation: C = 0 is an inline operand of the MFMA, the accumulators need no clearing.
+__device__ __forceinline__ void mfma_step_first(f32x16 (&acc)[4][2], const Frags& f) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], zero, 0, 0, 0);
 }
 
 // One 64-deep slice: four k-steps with the fragments of step kk+1 read while step kk multiplies.
@@ -287,6 +296,17 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
   size_t a_rowoff[4];
   const bf16* b_src[4];
   const bf16* zb;
+  const bf16* a_cur[4];                                  // running source pointers: advance 64 elements per slice
+  const bf16* b_cur[4];
+  int ci = 0, ki = 0, si = 0, gci = 0;                   // chunk, k-slice, stage, running chunk count (alpha buffer)
+  auto setup_chunk = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = ii.c0 + min(ci * 8 + a_ch[i], ii.gk - 1);
+      a_cur[i] = zb + (size_t)c * N * D + a_rowoff[i];
+      b_cur[i] = b_src[i];
+    }
+  };
   auto setup_issue = [&]() {
     zb = z + (size_t)ii.b * Cin * N * D;
     const bf16* Wb = Wv + (size_t)ii.k * D * D;
@@ -297,7 +317,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
     }
   };
   setup_issue();
-  int ci = 0, ki = 0, si = 0, gci = 0;                   // chunk, k-slice, stage, running chunk count (alpha buffer)
+  setup_chunk();
   auto issue = [&]() {
     if (live) {
       if (ki == 0 && L.wave < NHS) {                     // entering a chunk: fetch its softmax weights
@@ -307,15 +327,17 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
                            (L.lane & 7) * 4;
         load16_to_lds(src, alds + (gci % 3) * atile + L.wave * 1024);
       }
-      unsigned char* st = smem + si * kGemmStageBytes;
+      unsigned char* st = smem + si * kGemmStageBytes + L.wave * 4096;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int c = ii.c0 + min(ci * 8 + a_ch[i], ii.gk - 1);
-        load16_to_lds(zb + (size_t)c * N * D + a_rowoff[i] + ki * kGemmBK, st + (L.wave * 4 + i) * 1024);
+        load16_to_lds(a_cur[i], st + i * 1024);
+        a_cur[i] += kGemmBK;
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        load16_to_lds(b_src[i] + ki * kGemmBK, st + kGemmBM * 128 + (L.wave * 4 + i) * 1024);
+      for (int i = 0; i < 4; ++i) {
+        load16_to_lds(b_cur[i], st + kGemmBM * 128 + i * 1024);
+        b_cur[i] += kGemmBK;
+      }
       if (++ki == KT) {
         ki = 0;
         ++gci;
@@ -324,6 +346,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
           live = item_of(++ti, ii);
           if (live) setup_issue();
         }
+        if (live) setup_chunk();
       }
     }
     si ^= 1;
@@ -346,17 +369,12 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
       for (int r = 0; r < 16; ++r) o[j][r] = 0.f;      // only entries 0..7 are used
     for (int chunk = 0; chunk < ic.nch; ++chunk, ++gcc) {
       f32x16 acc[4][2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
       for (int kt = 0; kt < KT; ++kt) {
         // k-steps 0..2 of the current slice; the fragments of step 0 were read across the last barrier
         const unsigned char* st = smem + sc * kGemmStageBytes;
         read_frags(f1, st, L, 1);
-        mfma_step(acc, f0);
+        if (kt == 0) mfma_step_first(acc, f0);           // a chunk starts from C = 0
+        else mfma_step(acc, f0);
         read_frags(f0, st, L, 2);
         mfma_step(acc, f1);
         read_frags(f1, st, L, 3);
