@@ -358,7 +358,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
   Frags f0, f1;
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
-  issue();                                               // second slice -> stage 1
+  if (L.wm == 0) issue();                                // second slice -> stage 1 (wm = 1 issues inside the loop)
   read_frags(f0, smem, L, 0);
   VaggItem ic;
   for (int tc = 0; item_of(tc, ic); ++tc) {
@@ -375,6 +375,9 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
         read_frags(f1, st, L, 1);
         if (kt == 0) mfma_step_first(acc, f0);           // a chunk starts from C = 0
         else mfma_step(acc, f0);
+        // The two wavefronts of a SIMD (wm = 0 and 1) issue their loads at different points of the slice, so
+        // that one's address arithmetic and load issue overlaps the other's MFMAs.
+        if (L.wm == 1) issue();                          // slice after next -> the stage released at the last barrier
         read_frags(f0, st, L, 2);
         mfma_step(acc, f1);
         read_frags(f1, st, L, 3);
@@ -382,7 +385,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
         // every read of this stage is in registers and the next slice has landed: swap stages
         __builtin_amdgcn_s_waitcnt(0);                   // vmcnt(0) and lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        issue();                                         // slice after next -> the stage just released
+        if (L.wm == 0) issue();                          // slice after next -> the stage just released
         sc ^= 1;
         read_frags(f0, smem + sc * kGemmStageBytes, L, 0);
         mfma_step(acc, f1);
