@@ -257,7 +257,7 @@ int run_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dch
   }
   {
     StageTimer tm(DCHAG_STAGE_FOLD, st);
-    k_fold_query_into_key<T><<<dim3((D + 255) / 256, heads, G), 256, 0, st>>>(
+    k_fold_query_into_key<T><<<dim3((D + 63) / 64, heads, G), 256, 0, st>>>(
         D, heads, static_cast<const T*>(lv->Wk), Qp, Mf, nullptr, nullptr);
     if ((rc = launch_status())) return rc;
   }
@@ -291,6 +291,8 @@ int launch_linear_dl(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, 
   tw.m_tiles = (rb.rows_per_group + kGemmBM - 1) / kGemmBM;
   tw.nb = B;
   tw.total = tw.n_tiles * tw.m_tiles * B * rb.G;
+  if (tw.total * 2 < compute_units())                    // too few 256x256 tiles to fill the chip: 128x128 tiles
+    return launch_linear_mfma_cfg<128, 128, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st);
   const int per = (tw.total + kXcds - 1) / kXcds;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_linear_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
                           kGemmRingBytes) != hipSuccess)
@@ -331,7 +333,7 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
   }
   {
     StageTimer tm(DCHAG_STAGE_FOLD, st);
-    k_fold_query_into_key<bf16><<<dim3((D + 255) / 256, heads, G), 256, 0, st>>>(
+    k_fold_query_into_key<bf16><<<dim3((D + 63) / 64, heads, G), 256, 0, st>>>(
         D, heads, static_cast<const bf16*>(lv->Wk), Qp, Mf, Mb, px ? px->MfT : nullptr);
     if ((rc = launch_status())) return rc;
   }
@@ -356,21 +358,14 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     if ((rc = launch_status())) return rc;
   } else {
     StageTimer tm(DCHAG_STAGE_SCORES, st);
-    const int KB = (D % 512 == 0) ? 512 : 256;
     const int NB = (heads + 15) / 16;
-    const int cch = (g + 31) / 32;
-    const dim3 grid((N + 15) / 16, G * cch, B);
-    const size_t lds = (size_t)(NB <= 1 ? 16 : (NB == 2 ? 32 : 64)) * (KB * 2 + 16);
+    const dim3 grid((N + 15) / 16, G * ((g + 3) / 4), B);
     if (NB <= 1)
-      k_scores_mfma<1><<<grid, 256, lds, st>>>(Cin, N, D, heads, g, gpad, Np, KB, zin, Mb, alpha);
+      k_scores_mfma<1><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, gpad, Np, zin, Mb, alpha);
     else if (NB == 2)
-      k_scores_mfma<2><<<grid, 256, lds, st>>>(Cin, N, D, heads, g, gpad, Np, KB, zin, Mb, alpha);
-    else {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_mfma<4>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return DCHAG_ERR_LAUNCH;
-      k_scores_mfma<4><<<grid, 256, lds, st>>>(Cin, N, D, heads, g, gpad, Np, KB, zin, Mb, alpha);
-    }
+      k_scores_mfma<2><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, gpad, Np, zin, Mb, alpha);
+    else
+      k_scores_mfma<4><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, gpad, Np, zin, Mb, alpha);
     if ((rc = launch_status())) return rc;
     k_softmax_alpha<<<dim3((Np + 255) / 256, heads, B * G), 256, 0, st>>>(Cin, N, heads, g, gpad, G, Np, alpha);
     if ((rc = launch_status())) return rc;

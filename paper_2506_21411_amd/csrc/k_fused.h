@@ -47,90 +47,89 @@ constexpr int kGemmRingBytes = kGemmStages * kGemmStageBytes;                  /
 
 // ---------------------------------------------------------------------------------------------
 // Scores.  S[b][k][cl][head][n] = z[b, c, n, :] . Mb[k][head][:]   (c = k*g + cl)
-// grid (ceil(N/16), G * ceil(g/32), B), block 256: a block takes 16 patches x up to 32 channels of one
-// group; each wavefront takes 8 channels as two quads of 4 row blocks (16 patches each) that
-// share the key fragments.  The folded keys are staged in LDS in K blocks of KB elements with
-// rows padded by 16 bytes (conflict-free for the 16 heads a fragment read touches).
+// grid (ceil(N/16), G * ceil(g/4), B), block 256: a block takes 16 patches x 4 channels of one group; its
+// four wavefronts each take a quarter of D (operands straight from global memory: 16 rows x 64 bytes per
+// load for the tokens, the folded keys come from L2), and the partial 16x16 blocks meet in LDS in a
+// fixed order.  The kernel is bound by the HBM read of the tokens (2*D bytes per token).
+// Requires D % 128 == 0.
 // ---------------------------------------------------------------------------------------------
 template <int NB>   // head blocks of 16 (heads padded to 16 * NB)
 __global__ __launch_bounds__(256) void k_scores_mfma(int Cin, int N, int D, int heads, int g, int gpad, int Np,
-                                                     int KB, const bf16* __restrict__ z,
-                                                     const bf16* __restrict__ Mb, float* __restrict__ S) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int cch = (g + 31) / 32;                       // channel chunks of 32 per group
-  const int k = blockIdx.y / cch, cc = blockIdx.y % cch;
-  const int G = gridDim.y / cch;
+                                                     const bf16* __restrict__ z, const bf16* __restrict__ Mb,
+                                                     float* __restrict__ S) {
+  __shared__ float part[3][4 * NB * 4][64];
+  const int qch = (g + 3) / 4;                         // channel quads per group
+  const int k = blockIdx.y / qch, cq = blockIdx.y % qch;
+  const int G = gridDim.y / qch;
   const int b = blockIdx.z, n0 = blockIdx.x * 16;
   const int c0 = k * g;
   const int gk = min(g, Cin - c0);                     // members of this group
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (cq * 4 >= gk) return;                            // uniform: nothing in this quad
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l16 = lane & 15, lq = lane >> 4;
-  const int HP = NB * 16;
-  const int pitch = KB * 2 + 16;                       // bytes per staged key row
+  const int kq = D / 4, kbeg = wave * kq;
+  const int n = min(n0 + l16, N - 1);
 
-  f32x4 acc[2][4][NB];
+  const bf16* zrow[4];
+  const bf16* mrow[NB];
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
+  for (int i = 0; i < 4; ++i)
+    zrow[i] = z + (((size_t)b * Cin + c0 + min(cq * 4 + i, gk - 1)) * N + n) * D + kbeg + lq * 8;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+    mrow[nb] = Mb + ((size_t)k * heads + min(nb * 16 + l16, heads - 1)) * D + kbeg + lq * 8;
+
+  f32x4 acc[4][NB];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int ks = 0; ks < kq; ks += 32) {
+    bf16x8 bfr[NB], af[4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      bfr[nb] = *reinterpret_cast<const bf16x8*>(mrow[nb] + ks);
+      if (nb * 16 + l16 >= heads) bfr[nb] = bf16x8{};
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(zrow[i] + ks);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) acc[q][i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // row pointers of the 8 channels this wavefront takes (clamped into the group)
-  const bf16* zrow[2][4];
-  const int n = min(n0 + l16, N - 1);
+      for (int nb = 0; nb < NB; ++nb)
+        acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[nb], acc[i][nb], 0, 0, 0);
+  }
+  if (wave > 0) {
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int cl = min(cc * 32 + wave * 8 + q * 4 + i, gk - 1);
-      zrow[q][i] = z + (((size_t)b * Cin + c0 + cl) * N + n) * D + lq * 8;
-    }
-
-  for (int kb = 0; kb < D; kb += KB) {
-    __syncthreads();
-    // stage Mb[k][0..HP)[kb .. kb+KB) (rows >= heads are zero)
-    for (int idx = tid; idx < HP * (KB / 8); idx += 256) {
-      const int hrow = idx / (KB / 8), ch = idx % (KB / 8);
-      bf16x8 v = {};
-      if (hrow < heads) v = *reinterpret_cast<const bf16x8*>(Mb + ((size_t)k * heads + hrow) * D + kb + ch * 8);
-      *reinterpret_cast<bf16x8*>(smem + hrow * pitch + ch * 16) = v;
-    }
-    __syncthreads();
-    for (int ks = 0; ks < KB; ks += 32) {
-      bf16x8 bfr[NB];
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
-        bfr[nb] = *reinterpret_cast<const bf16x8*>(smem + (nb * 16 + l16) * pitch + (ks + lq * 8) * 2);
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        bf16x8 af[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(zrow[q][i] + kb + ks);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            acc[q][i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[nb], acc[q][i][nb], 0, 0, 0);
-      }
-    }
+        for (int e = 0; e < 4; ++e) part[wave - 1][(i * NB + nb) * 4 + e][lane] = acc[i][nb][e];
   }
-  // 16x16 accumulator block: lane holds head (lane % 16), patches 4 * (lane / 16) + 0..3
-#pragma unroll
-  for (int q = 0; q < 2; ++q)
+  __syncthreads();
+  if (wave == 0) {
+    // 16x16 accumulator block: lane holds head (lane % 16), patches 4 * (lane / 16) + 0..3
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int cl = cc * 32 + wave * 8 + q * 4 + i;
+      const int cl = cq * 4 + i;
       if (cl >= gk) continue;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         const int head = nb * 16 + l16;
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int slot = (i * NB + nb) * 4 + e;
+          v[e] = acc[i][nb][e] + part[0][slot][lane] + part[1][slot][lane] + part[2][slot][lane];
+        }
         if (head < heads) {
           float* dst = S + ((((size_t)b * G + k) * gpad + cl) * heads + head) * Np + n0 + lq * 4;
-          *reinterpret_cast<f32x4*>(dst) = acc[q][i][nb];
+          *reinterpret_cast<f32x4*>(dst) = v;
         }
       }
     }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------

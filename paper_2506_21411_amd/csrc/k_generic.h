@@ -21,7 +21,18 @@ __global__ __launch_bounds__(256) void k_project_query(int D, const T* __restric
   const T* w = Wq + ((size_t)k * D + i) * D;
   const T* q = query + (size_t)k * D;
   float acc = 0.f;
-  for (int j = lane; j < D; j += kWave) acc += to_f32(w[j]) * to_f32(q[j]);
+  constexpr int V = 16 / sizeof(T);                       // elements per 16-byte load
+  if (D % (kWave * V) == 0) {
+    typedef __attribute__((ext_vector_type(V))) T vec;
+    for (int j = lane * V; j < D; j += kWave * V) {
+      const vec wv = *reinterpret_cast<const vec*>(w + j);
+      const vec qv = *reinterpret_cast<const vec*>(q + j);
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc += to_f32(wv[e]) * to_f32(qv[e]);
+    }
+  } else {
+    for (int j = lane; j < D; j += kWave) acc += to_f32(w[j]) * to_f32(q[j]);
+  }
   acc = wave_sum(acc);
   if (lane == 0) Qp[(size_t)k * D + i] = acc + (bq ? to_f32(bq[(size_t)k * D + i]) : 0.f);
 }
@@ -31,27 +42,37 @@ __global__ __launch_bounds__(256) void k_project_query(int D, const T* __restric
 // same amount and is dropped):
 //   M[k][a][j] = (1/sqrt(dh)) * sum_{i in head a} Wk[k][i][j] * Q[k][i]
 // so that the score of token z for head a is  z . M[k][a][:].
-// grid (ceil(D/256), heads, G), block 256.  Writes fp32 and, when asked, a bf16 copy and a
-// transposed fp32 copy [G][D][heads].
+// grid (ceil(D/64), heads, G), block 256: 64 columns per block, the four wavefronts each sum a
+// quarter of the head's rows and meet in LDS in a fixed order.  Writes fp32 and, when asked, a
+// bf16 copy and a transposed fp32 copy [G][D][heads].
 // ---------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_fold_query_into_key(int D, int heads, const T* __restrict__ Wk,
                                                              const float* __restrict__ Qp,
                                                              float* __restrict__ Mf, bf16* __restrict__ Mb,
                                                              float* __restrict__ MfT) {
+  __shared__ float part[3][64];
   const int k = blockIdx.z, a = blockIdx.y;
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= D) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
   const int dh = D / heads;
-  const T* w = Wk + ((size_t)k * D + (size_t)a * dh) * D + j;
-  const float* q = Qp + (size_t)k * D + (size_t)a * dh;
+  const int i0 = (dh * wave) / 4, i1 = (dh * (wave + 1)) / 4;
   float acc = 0.f;
-  for (int i = 0; i < dh; ++i) acc += to_f32(w[(size_t)i * D]) * q[i];
-  acc *= rsqrtf((float)dh);
-  const size_t o = ((size_t)k * heads + a) * D + j;
-  Mf[o] = acc;
-  if (Mb) Mb[o] = (bf16)acc;
-  if (MfT) MfT[((size_t)k * D + j) * heads + a] = acc;   // transposed copy [G][D][heads]
+  if (j < D) {
+    const T* w = Wk + ((size_t)k * D + (size_t)a * dh) * D + j;
+    const float* q = Qp + (size_t)k * D + (size_t)a * dh;
+#pragma unroll 8
+    for (int i = i0; i < i1; ++i) acc += to_f32(w[(size_t)i * D]) * q[i];
+  }
+  if (wave > 0) part[wave - 1][lane] = acc;
+  __syncthreads();
+  if (wave == 0 && j < D) {
+    acc = (acc + part[0][lane] + part[1][lane] + part[2][lane]) * rsqrtf((float)dh);
+    const size_t o = ((size_t)k * heads + a) * D + j;
+    Mf[o] = acc;
+    if (Mb) Mb[o] = (bf16)acc;
+    if (MfT) MfT[((size_t)k * D + j) * heads + a] = acc;   // transposed copy [G][D][heads]
+  }
 }
 
 // ---------------------------------------------------------------------------------------
