@@ -21,6 +21,11 @@ if ROOT not in sys.path:
 
 PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_tflops": 157.3}
 
+# HBM-side bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs summarised in
+# profiles/hbm_traffic_hyperspectral.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the scales a plain
+# 1 GiB copy kernel gives for the same counters).  Valid for that workload and kernel only.
+MEASURED_TRAFFIC = {("hyperspectral", "fused_vagg", 1): 1677.9e6}
+
 
 def stage_model(cfg, levels_in, stage, level):
     """Algorithmic work of one launch of a stage: (bound, amount, unit) with amount in flops or bytes."""
@@ -40,6 +45,9 @@ def stage_model(cfg, levels_in, stage, level):
     if stage == "fused_vagg":
         return "mfma", 2.0 * tok * D * (D + h)
     if stage == "scores":
+        if level == 1 and cfg.dtype == "bf16":
+            # first level of a forward call: scores come from the pixels through composed weights
+            return "hbm", B * cfg.C * cfg.H * cfg.W * es + cfg.C * D * cfg.p * cfg.p * es + 2 * tok * h * 4
         return "hbm", tok * D * es + tok * h * 4
     if stage == "softmax_agg":
         return "hbm", tok * D * es + tok * h * 4 + B * G * N * D * es
@@ -153,7 +161,8 @@ def main() -> int:
     roofline = None
     if dom:
         roofline = {"kernel": f"{dom['stage']}@level{dom['level']}", "bound": dom["bound"], "achieved": dom["achieved"],
-                    "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": None,
+                    "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
+                    "traffic": MEASURED_TRAFFIC.get((cfg.name, dom["stage"], dom["level"])),
                     "avg_ms": dom["avg_ms"]}
 
     # the CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
