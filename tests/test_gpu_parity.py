@@ -77,6 +77,8 @@ def cfg_of(**kw):
     dict(B=2, C=3, H=48, W=52, p=4, D=320),              # MFMA tokenizer: N = 156 (two 128-patch tiles), 5 slices
     dict(B=1, C=2, H=80, W=136, p=8, D=1024),            # MFMA tokenizer: 8x8 patches, N = 170
     dict(B=1, C=2, H=32, W=48, p=16, D=128),             # 16x16 patches (k = 256), N = 6
+    dict(B=2, C=2, H=48, W=52, p=4, D=512),              # two tiles, eight 64-column slices, N = 156
+    dict(B=1, C=1, H=32, W=32, p=16, D=256),             # 16x16 patches with D = 256
 ])
 def test_tokenize_matches_oracle(dtype, kw):
     cfg = cfg_of(dtype=dtype, heads=1, group_sizes=(kw["C"],), **kw)
