@@ -7,7 +7,9 @@ imports nothing of it.
 All functions take float32 numpy arrays for inputs and weights (bf16 values are
 exactly representable in float32) and return float64 arrays.  A "level" is any
 object with the attributes ``group_size, query, Wq, Wk, Wv, Wo, bq, bk, bv, bo``
-(biases may be None).
+(biases may be None) and optionally ``kind`` ("attention", the default, or "linear":
+then ``Wv`` holds the channel-mixing weights [G, g, D], ``bv`` the bias [G, D], and
+the other arrays are ignored).
 """
 from __future__ import annotations
 
@@ -28,7 +30,7 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 
 
 class _CLevel(ctypes.Structure):
-    _fields_ = [("group_size", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    _fields_ = [("group_size", ctypes.c_int32), ("kind", ctypes.c_int32),
                 ("query", _f32p),
                 ("Wq", _f32p), ("Wk", _f32p), ("Wv", _f32p), ("Wo", _f32p),
                 ("bq", _f32p), ("bk", _f32p), ("bv", _f32p), ("bo", _f32p)]
@@ -105,7 +107,12 @@ def _clevel(lv, c_in: int, D: int, keep: list) -> _CLevel:
     G = (c_in + g - 1) // g
     c = _CLevel()
     c.group_size = g
-    c.reserved = 0
+    if getattr(lv, "kind", "attention") == "linear":
+        c.kind = 1
+        c.Wv = _f32(lv.Wv, (G, g, D), keep)[1]
+        c.bv = _f32(lv.bv, (G, D), keep)[1]
+        return c
+    c.kind = 0
     c.query = _f32(lv.query, (G, D), keep)[1]
     for name in ("Wq", "Wk", "Wv", "Wo"):
         setattr(c, name, _f32(getattr(lv, name), (G, D, D), keep)[1])

@@ -22,7 +22,14 @@
  *   - hierarchy: the channels are split in contiguous groups of at most g
  *     ("up to" g, Section 3.2), each group has its own layer, the outputs of a
  *     level are the inputs of the next, and the last level is one
- *     cross-attention layer over everything that is left (Section 3.3).
+ *     cross-attention layer over everything that is left (Section 3.3);
+ *   - D-CHAG-L (Sections 3.2, 3.3): a partial-aggregation level may be a
+ *     "lightweight linear layer" instead of cross-attention, the last level
+ *     stays cross-attention.  The paper does not define that layer beyond
+ *     saying that it has fewer parameters than a cross-attention layer; the
+ *     reading taken is a learned mixing along the channel axis with one weight
+ *     per member and feature:  y = sum_c w[c] * z[c] + b  (elementwise in the
+ *     feature), g*D + D parameters per group.
  *
  * Inputs are float (exactly representable bf16 or fp32 values); all arithmetic
  * and all outputs are double.  Rows are summed left to right.
@@ -43,7 +50,7 @@
 
 typedef struct {
   int32_t group_size;                  /* nominal g; the last group may be shorter            */
-  int32_t reserved;
+  int32_t kind;                        /* 0: cross-attention; 1: linear mixing (Wv = [G,g,D] weights, bv = bias) */
   const float *query;                  /* [G, D]                                               */
   const float *Wq, *Wk, *Wv, *Wo;      /* [G, D, D], row-major (out, in): y = W x              */
   const float *bq, *bk, *bv, *bo;      /* [G, D] or NULL (= 0)                                 */
@@ -103,6 +110,27 @@ static void tokens_of_patch(int C, int H, int W, int p, int D, const float *x_b 
 }
 
 /*
+ * One linear partial-aggregation level at one patch (D-CHAG-L, Sections 3.2, 3.3, in the
+ * reading stated at the top): group k holds inputs k*g .. min((k+1)*g, c_in)-1 and
+ *   y[k][d] = sum over members c of w[k][c - k*g][d] * z[c][d] + b[k][d],
+ * with w = lv->Wv laid out [G, g, D] and b = lv->bv [G, D] (or NULL).
+ */
+static void linear_level_of_patch(int c_in, int D, const oracle_level *lv, const double *z, double *y) {
+  const int g = lv->group_size;
+  const int G = groups_of(c_in, g);
+  for (int k = 0; k < G; ++k) {
+    const int c0 = k * g;
+    const int c1 = (c0 + g < c_in) ? c0 + g : c_in;
+    for (int d = 0; d < D; ++d) {
+      double acc = 0.0;
+      for (int c = c0; c < c1; ++c)
+        acc += (double)lv->Wv[((size_t)k * g + (c - c0)) * D + d] * z[(size_t)c * D + d];
+      y[(size_t)k * D + d] = acc + (lv->bv ? (double)lv->bv[(size_t)k * D + d] : 0.0);
+    }
+  }
+}
+
+/*
  * One aggregation level at one patch (Sections 2.1, 3.2): group k holds the
  * inputs k*g .. min((k+1)*g, c_in)-1.  Per group: project the learned query,
  * project every member to a key and a value, per head take the scaled dot
@@ -113,6 +141,10 @@ static void tokens_of_patch(int C, int H, int W, int p, int D, const float *x_b 
  */
 static void level_of_patch(int c_in, int D, int heads, const oracle_level *lv, const double *z /* [c_in, D] */,
                            double *y /* [G, D] */, double *alpha, double *pre) {
+  if (lv->kind == 1) {
+    linear_level_of_patch(c_in, D, lv, z, y);
+    return;
+  }
   const int g = lv->group_size;
   const int G = groups_of(c_in, g);
   const int dh = D / heads;
@@ -188,6 +220,8 @@ int oracle_tokenize(int B, int C, int H, int W, int p, int D, const float *x, co
 int oracle_aggregate_level(int S, int c_in, int D, int heads, const oracle_level *lv, const double *z,
                            double *y, double *alpha, double *pre) {
   if (heads <= 0 || D % heads || lv->group_size < 1 || c_in < 1) return -2;
+  if (lv->kind != 0 && lv->kind != 1) return -2;
+  if (lv->kind == 1 && (alpha || pre)) return -2;      /* a linear level has no softmax weights */
   const int G = groups_of(c_in, lv->group_size);
 #pragma omp parallel for schedule(dynamic, 1)
   for (int i = 0; i < S; ++i)
@@ -208,10 +242,12 @@ int oracle_forward(int B, int C, int H, int W, int p, int D, int heads, const fl
   int c_in = C, c_max = C;
   for (int l = 0; l < n_levels; ++l) {
     if (levels[l].group_size < 1) return -2;
+    if (levels[l].kind != 0 && levels[l].kind != 1) return -2;
     c_in = groups_of(c_in, levels[l].group_size);
     if (c_in > c_max) c_max = c_in;
   }
   if (c_in != 1) return -2;
+  if (levels[n_levels - 1].kind != 0) return -2;        /* the final layer is always cross-attention (Section 3.3) */
   for (int i = 0; i < S; ++i)
     if (sample_b[i] < 0 || sample_b[i] >= B || sample_n[i] < 0 || sample_n[i] >= N) return -2;
 #pragma omp parallel for schedule(dynamic, 1)

@@ -22,7 +22,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 __all__ = [
-    "ShapeCfg", "Level", "Problem", "CONFIGS", "get_config", "n_groups",
+    "ShapeCfg", "Level", "Problem", "CONFIGS", "get_config", "n_groups", "make_level", "make_linear_level",
     "level_inputs", "round_to_bf16", "make_problem", "make_tokens", "sample_patches",
 ]
 
@@ -41,6 +41,7 @@ class ShapeCfg:
     group_sizes: Sequence[int]     # nominal group size per level, last level must give one group
     x_kind: str = "gauss"          # "gauss_mu_sigma" | "weather" | "ar1" | "gauss"
     seed: int = 0
+    level_kinds: Optional[Sequence[str]] = None   # per level "attention" (default) or "linear" (D-CHAG-L)
 
     @property
     def N(self) -> int:
@@ -71,6 +72,9 @@ CONFIGS = {
     "wide": ShapeCfg("wide", "bf16", 1, 256, 256, 512, 8, 4096, 32, (32, 8), "gauss", 3),
     "deep": ShapeCfg("deep", "bf16", 2, 1024, 128, 128, 8, 2048, 16, (16, 8, 8), "ar1", 4),
     "deep1000": ShapeCfg("deep1000", "bf16", 2, 1000, 128, 128, 8, 2048, 16, (16, 8, 8), "ar1", 4),
+    # D-CHAG-L (Section 4.5): linear partial-aggregation layers, cross-attention only at the top
+    "hyperspectral_linear": ShapeCfg("hyperspectral_linear", "bf16", 4, 512, 128, 128, 8, 1024, 16, (32, 16), "ar1", 2,
+                                     ("linear", "attention")),
 }
 
 
@@ -89,19 +93,20 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
 @dataclass
 class Level:
     group_size: int
-    query: np.ndarray              # [G, D]
-    Wq: np.ndarray                 # [G, D, D]  (out, in)
-    Wk: np.ndarray
-    Wv: np.ndarray
-    Wo: np.ndarray
+    query: Optional[np.ndarray]    # [G, D]
+    Wq: Optional[np.ndarray]       # [G, D, D]  (out, in)
+    Wk: Optional[np.ndarray]
+    Wv: np.ndarray                 # attention: [G, D, D]; linear: channel-mixing weights [G, g, D]
+    Wo: Optional[np.ndarray]
     bq: Optional[np.ndarray]       # [G, D] or None
     bk: Optional[np.ndarray]
-    bv: Optional[np.ndarray]
+    bv: Optional[np.ndarray]       # attention: value bias; linear: output bias
     bo: Optional[np.ndarray]
+    kind: str = "attention"        # "attention" | "linear"
 
     @property
     def G(self) -> int:
-        return self.query.shape[0]
+        return self.Wv.shape[0]
 
 
 @dataclass
@@ -159,6 +164,16 @@ def _make_x(cfg: ShapeCfg, rng: np.random.Generator) -> np.ndarray:
     return np.ascontiguousarray(x, dtype=np.float32)
 
 
+def make_linear_level(rng: np.random.Generator, G: int, g: int, D: int, dtype: str, biases: bool = True) -> Level:
+    """A linear (D-CHAG-L) level: mixing weights around the plain mean, N(1/g, 1/g^2), bias N(0, 1/g)."""
+    w = _normal(rng, (G, g, D), 1.0 / g) + np.float32(1.0 / g)
+    b = _normal(rng, (G, D), 1.0 / np.sqrt(g)) if biases else None
+    if dtype == "bf16":
+        w = round_to_bf16(w)
+        b = round_to_bf16(b) if b is not None else None
+    return Level(g, None, None, None, w, None, None, None, b, None, "linear")
+
+
 def make_level(rng: np.random.Generator, G: int, g: int, D: int, dtype: str,
                biases: bool = True, query_scale: float = 1.0) -> Level:
     fin = 1.0 / np.sqrt(D)
@@ -203,9 +218,13 @@ def make_problem(cfg: ShapeCfg, seed: Optional[int] = None, biases: bool = True,
         be = round_to_bf16(be) if be is not None else None
     prob = Problem(cfg, x, We, be, ce)
     c_in = cfg.C
-    for g in cfg.group_sizes:
+    for li, g in enumerate(cfg.group_sizes):
         G = n_groups(c_in, g)
-        prob.levels.append(make_level(rng, G, g, cfg.D, cfg.dtype, biases, query_scale))
+        kind = cfg.level_kinds[li] if cfg.level_kinds else "attention"
+        if kind == "linear":
+            prob.levels.append(make_linear_level(rng, G, g, cfg.D, cfg.dtype, biases))
+        else:
+            prob.levels.append(make_level(rng, G, g, cfg.D, cfg.dtype, biases, query_scale))
         c_in = G
     if c_in != 1:
         raise ValueError("last level must reduce to one group")
