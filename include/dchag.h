@@ -49,6 +49,11 @@ typedef enum {
   DCHAG_ERR_ALIGN = -6      /* a tensor pointer is not 16-byte aligned                      */
 } dchag_status;
 
+typedef enum {
+  DCHAG_LEVEL_ATTENTION = 0,        /* learned-query multi-head cross-attention (D-CHAG-C)        */
+  DCHAG_LEVEL_LINEAR = 1            /* linear mixing along the channel axis (D-CHAG-L)            */
+} dchag_level_kind;
+
 /*
  * One aggregation level (paper Section 3.2: "multiple cross-attention layers",
  * each handling "up to" g channels; Section 3.3: partial-channel aggregation
@@ -58,11 +63,23 @@ typedef enum {
  */
 typedef struct {
   int32_t group_size;               /* nominal g >= 1; the last group may be shorter              */
-  int32_t reserved;                 /* must be 0                                                  */
+  int32_t kind;                     /* dchag_level_kind                                           */
   const void *query;                /* [G, D]    learned query of each group                      */
   const void *Wq, *Wk, *Wv, *Wo;    /* [G, D, D] row-major (out, in): y = W x                     */
   const void *bq, *bk, *bv, *bo;    /* [G, D]    each may be NULL (= 0)                           */
 } dchag_level;
+/*
+ * DCHAG_LEVEL_LINEAR (paper Section 3.2: intermediate cross-attention layers may be replaced by
+ * lightweight linear layers; Section 3.3: the D-CHAG-L variant, whose final layer stays
+ * cross-attention).  The paper does not define the layer; the reading built here mixes the members
+ * of a group along the channel axis with one learned weight per member and feature:
+ *
+ *   tokens_out[b,k,n,d] = sum over members c of group k of  w[k][c - k*g][d] * z[b,c,n,d]  +  bias[k][d]
+ *
+ * For such a level `Wv` holds w as [G, g, D] and `bv` the bias [G, D] (or NULL); every other
+ * pointer of the struct is ignored and may be NULL.  The last level of dchag_forward must be
+ * DCHAG_LEVEL_ATTENTION.
+ */
 
 /*
  * Per-channel patch tokenization (paper Section 2.1: every 2-D patch of every
@@ -94,8 +111,10 @@ int dchag_tokenize(dchag_dtype dt, int B, int C, int H, int W, int p, int D,
  *
  *   tokens_in  [B,Cin,N,D] in      tokens_out [B,G,N,D] out
  *   workspace: at least dchag_workspace_bytes(..., which = 0) bytes, 256-byte aligned.
+ * A DCHAG_LEVEL_LINEAR level computes the weighted sum given with dchag_level instead; it uses no
+ * workspace (NULL is accepted) and `heads` only has to pass the shape check (1 will do).
  * Errors: NULL tokens/lvl/required weight; Cin,N,D,heads < 1; D % heads != 0;
- * D % 8 != 0; group_size < 1; workspace too small.
+ * D % 8 != 0; group_size < 1; unknown kind; workspace too small.
  */
 int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads,
                           const dchag_level *lvl, const void *tokens_in, void *tokens_out,
@@ -109,7 +128,8 @@ int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int head
  * (C for the first); the last level must have exactly one group.
  *
  *   out [B,N,D]; workspace: at least dchag_workspace_bytes(..., which = 1) bytes.
- * Errors: as the two calls above; n_levels < 1; last level leaves more than one group.
+ * Errors: as the two calls above; n_levels < 1; last level leaves more than one group or is not
+ * DCHAG_LEVEL_ATTENTION.
  */
 int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
                   const void *x, const void *We, const void *be, const void *ce,
@@ -142,7 +162,9 @@ typedef enum {
   DCHAG_STAGE_VPROJ = 4,           /* value projection                                         */
   DCHAG_STAGE_SOFTMAX_AGG = 5,     /* softmax over the group and weighted sum of the values    */
   DCHAG_STAGE_OPROJ = 6,           /* output projection                                        */
-  DCHAG_STAGE_FUSED_VAGG = 7       /* value projection + scores + online softmax + sum, fused  */
+  DCHAG_STAGE_FUSED_VAGG = 7,      /* value projection + scores + online softmax + sum, fused  */
+  DCHAG_STAGE_CHANNEL_MIX = 8,     /* linear (D-CHAG-L) level: weighted sum over the group      */
+  DCHAG_STAGE_TOKENIZE_MIX = 9     /* tokenizer fused with a linear first level                 */
 } dchag_stage;
 
 typedef struct {

@@ -28,7 +28,7 @@ class DchagError(RuntimeError):
 
 
 class _CLevel(ctypes.Structure):
-    _fields_ = [("group_size", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    _fields_ = [("group_size", ctypes.c_int32), ("kind", ctypes.c_int32),
                 ("query", ctypes.c_void_p),
                 ("Wq", ctypes.c_void_p), ("Wk", ctypes.c_void_p), ("Wv", ctypes.c_void_p), ("Wo", ctypes.c_void_p),
                 ("bq", ctypes.c_void_p), ("bk", ctypes.c_void_p), ("bv", ctypes.c_void_p), ("bo", ctypes.c_void_p)]
@@ -39,22 +39,29 @@ class _CStageTime(ctypes.Structure):
 
 
 STAGE_NAMES = {0: "tokenize", 1: "query", 2: "fold", 3: "scores", 4: "vproj", 5: "softmax_agg", 6: "oproj",
-               7: "fused_vagg"}
+               7: "fused_vagg", 8: "channel_mix", 9: "tokenize_mix"}
+
+LEVEL_ATTENTION, LEVEL_LINEAR = 0, 1
 
 
 @dataclass
 class LevelWeights:
-    """Device tensors of one aggregation level: query [G,D]; Wq..Wo [G,D,D]; biases [G,D] or None."""
+    """Device tensors of one aggregation level.
+
+    Attention level (kind 0): query [G,D]; Wq..Wo [G,D,D]; biases [G,D] or None.
+    Linear level (kind 1, D-CHAG-L): Wv = mixing weights [G,g,D], bv = bias [G,D] or None; the rest None.
+    """
     group_size: int
-    query: torch.Tensor
-    Wq: torch.Tensor
-    Wk: torch.Tensor
+    query: Optional[torch.Tensor]
+    Wq: Optional[torch.Tensor]
+    Wk: Optional[torch.Tensor]
     Wv: torch.Tensor
-    Wo: torch.Tensor
+    Wo: Optional[torch.Tensor]
     bq: Optional[torch.Tensor] = None
     bk: Optional[torch.Tensor] = None
     bv: Optional[torch.Tensor] = None
     bo: Optional[torch.Tensor] = None
+    kind: int = LEVEL_ATTENTION
 
 
 def library_path() -> str:
@@ -121,7 +128,7 @@ def _stream(stream) -> ctypes.c_void_p:
 def _clevel(lv: LevelWeights, like: torch.Tensor) -> _CLevel:
     c = _CLevel()
     c.group_size = int(lv.group_size)
-    c.reserved = 0
+    c.kind = int(lv.kind)
     for name in ("query", "Wq", "Wk", "Wv", "Wo", "bq", "bk", "bv", "bo"):
         setattr(c, name, _ptr(getattr(lv, name), like))
     return c

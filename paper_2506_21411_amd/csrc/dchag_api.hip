@@ -396,9 +396,28 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
   return launch_linear_dl(B, D, rbo, O, static_cast<const bf16*>(lv->Wo), static_cast<const bf16*>(lv->bo), zout, st);
 }
 
+// A linear (D-CHAG-L) level: one memory-bound mixing kernel, no workspace.
+template <typename T>
+int run_level_linear(int B, int Cin, int N, int D, const dchag_level* lv, const T* zin, T* zout, hipStream_t st) {
+  const int g = lv->group_size;
+  const int G = groups_of(Cin, g);
+  constexpr int V = 16 / sizeof(T);
+  const long total = (long)N * (D / V);
+  StageTimer tm(DCHAG_STAGE_CHANNEL_MIX, st);
+  k_channel_mix<T><<<dim3((unsigned)((total + 255) / 256), G, B), 256, 0, st>>>(
+      Cin, N, D, g, zin, static_cast<const T*>(lv->Wv), static_cast<const T*>(lv->bv), zout);
+  return launch_status();
+}
+
 int check_level(const dchag_level* lv) {
   if (!lv) return DCHAG_ERR_NULL;
-  if (lv->group_size < 1 || lv->reserved != 0) return DCHAG_ERR_SHAPE;
+  if (lv->group_size < 1) return DCHAG_ERR_SHAPE;
+  if (lv->kind == DCHAG_LEVEL_LINEAR) {
+    if (!lv->Wv) return DCHAG_ERR_NULL;
+    if (misaligned(lv->Wv) || misaligned(lv->bv)) return DCHAG_ERR_ALIGN;
+    return DCHAG_OK;
+  }
+  if (lv->kind != DCHAG_LEVEL_ATTENTION) return DCHAG_ERR_SHAPE;
   if (!lv->query || !lv->Wq || !lv->Wk || !lv->Wv || !lv->Wo) return DCHAG_ERR_NULL;
   const void* ps[] = {lv->query, lv->Wq, lv->Wk, lv->Wv, lv->Wo, lv->bq, lv->bk, lv->bv, lv->bo};
   for (const void* p : ps)
@@ -513,6 +532,14 @@ int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int head
   if (rc) return rc;
   if ((rc = check_level_shape(B, Cin, N, D, heads, lvl->group_size))) return rc;
   if (misaligned(tokens_in) || misaligned(tokens_out)) return DCHAG_ERR_ALIGN;
+  if (lvl->kind == DCHAG_LEVEL_LINEAR) {  // needs no workspace
+    g_level = 1;
+    if (dt == DCHAG_F32)
+      return run_level_linear<float>(B, Cin, N, D, lvl, static_cast<const float*>(tokens_in),
+                                     static_cast<float*>(tokens_out), static_cast<hipStream_t>(stream));
+    return run_level_linear<bf16>(B, Cin, N, D, lvl, static_cast<const bf16*>(tokens_in),
+                                  static_cast<bf16*>(tokens_out), static_cast<hipStream_t>(stream));
+  }
   const size_t need = level_ws(dt, B, Cin, N, D, heads, lvl->group_size).total;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < need)
     return DCHAG_ERR_WORKSPACE;
@@ -546,7 +573,7 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     gs[l] = levels[l].group_size;
     c_in = groups_of(c_in, gs[l]);
   }
-  if (c_in != 1) return DCHAG_ERR_SHAPE;
+  if (c_in != 1 || levels[n_levels - 1].kind != DCHAG_LEVEL_ATTENTION) return DCHAG_ERR_SHAPE;
   if (misaligned(x) || misaligned(We) || misaligned(be) || misaligned(ce) || misaligned(out)) return DCHAG_ERR_ALIGN;
   const ForwardWs w = forward_ws(dt, B, C, N, p * p, D, heads, n_levels, gs);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
@@ -556,13 +583,42 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
   unsigned char* ws = static_cast<unsigned char*>(workspace);
 
   g_level = 0;
-  if ((rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, stream))) return rc;
   const void* zin = ws + w.tokens;
   c_in = C;
-  for (int l = 0; l < n_levels; ++l) {
+  int first = 0;
+  const int pp0 = p * p;
+  if (dt == DCHAG_BF16 && levels[0].kind == DCHAG_LEVEL_LINEAR && pp0 % 16 == 0 && pp0 <= 256 && D % 256 == 0 &&
+      !getenv("DCHAG_GENERIC_TOKENIZE")) {
+    // tokenizer and linear first level in one kernel: the per-channel tokens never reach HBM
+    g_level = 1;
+    const int g = gs[0], G = groups_of(C, g);
+    bf16* y = reinterpret_cast<bf16*>(ws + w.ping);
+    const size_t lds = (size_t)2 * 64 * (pp0 * 2 + 16);
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_mix_mfma),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    {
+      StageTimer tm(DCHAG_STAGE_TOKENIZE_MIX, st);
+      k_tokenize_mix_mfma<<<dim3((unsigned)(((N + 63) / 64) * (D / 256)), G, B), 256, lds, st>>>(
+          C, H, W, p, D, g, static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+          static_cast<const bf16*>(ce), static_cast<const bf16*>(levels[0].Wv), static_cast<const bf16*>(levels[0].bv),
+          y);
+    }
+    if ((rc = launch_status())) return rc;
+    zin = y;
+    c_in = G;
+    first = 1;
+  } else if ((rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, stream)))
+    return rc;
+  for (int l = first; l < n_levels; ++l) {
     g_level = l + 1;
     void* zout = (l + 1 == n_levels) ? out : static_cast<void*>(ws + ((l & 1) ? w.pong : w.ping));
-    if (dt == DCHAG_F32)
+    if (levels[l].kind == DCHAG_LEVEL_LINEAR)
+      rc = (dt == DCHAG_F32) ? run_level_linear<float>(B, c_in, N, D, &levels[l], static_cast<const float*>(zin),
+                                                       static_cast<float*>(zout), st)
+                             : run_level_linear<bf16>(B, c_in, N, D, &levels[l], static_cast<const bf16*>(zin),
+                                                      static_cast<bf16*>(zout), st);
+    else if (dt == DCHAG_F32)
       rc = run_level<float>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const float*>(zin),
                             static_cast<float*>(zout), ws + w.level, st);
     else if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL")) {

@@ -237,4 +237,45 @@ __global__ __launch_bounds__(256) void k_softmax_aggregate_generic(int Cin, int 
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Linear partial-aggregation level (D-CHAG-L, paper Sections 3.2 and 3.3):
+//   y[b,k,n,d] = sum_{cl < gk} w[k][cl][d] * z[b, k*g + cl, n, d] + bias[k][d]
+// grid (ceil(N * D / V / 256), G, B), block 256; a thread owns V = 16 bytes of adjacent features of
+// one (b, k, n) and walks the members of the group.  Bound by the HBM read of z.  Requires D % V == 0.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_channel_mix(int Cin, int N, int D, int g, const T* __restrict__ z,
+                                                     const T* __restrict__ w, const T* __restrict__ bias,
+                                                     T* __restrict__ y) {
+  constexpr int V = 16 / sizeof(T);
+  typedef __attribute__((ext_vector_type(V))) T vec;
+  const int dv_n = D / V;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)N * dv_n) return;
+  const int n = (int)(idx / dv_n), d0 = (int)(idx % dv_n) * V;
+  const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  float acc[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
+  const T* zp = z + (((size_t)b * Cin + c0) * N + n) * D + d0;
+  const T* wp = w + (size_t)k * g * D + d0;
+#pragma unroll 4
+  for (int cl = 0; cl < gk; ++cl) {
+    const vec zv = *reinterpret_cast<const vec*>(zp + (size_t)cl * N * D);
+    const vec wv = *reinterpret_cast<const vec*>(wp + (size_t)cl * D);
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] += to_f32(wv[e]) * to_f32(zv[e]);
+  }
+  vec out;
+  if (bias) {
+    const vec bv = *reinterpret_cast<const vec*>(bias + (size_t)k * D + d0);
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] += to_f32(bv[e]);
+  }
+#pragma unroll
+  for (int e = 0; e < V; ++e) out[e] = from_f32<T>(acc[e]);
+  *reinterpret_cast<vec*>(y + (((size_t)b * G + k) * N + n) * D + d0) = out;
+}
+
 }  // namespace dchag

@@ -44,7 +44,7 @@ def test_strerror_and_version(lib):
 
 def level(g=4, **over):
     c = _CLevel()
-    c.group_size, c.reserved = g, 0
+    c.group_size, c.kind = g, 0
     for n in ("query", "Wq", "Wk", "Wv", "Wo"):
         setattr(c, n, FAKE)
     for k, v in over.items():

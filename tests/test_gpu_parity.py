@@ -14,7 +14,7 @@ import torch
 import oracle
 import paper_2506_21411_amd as dchag
 from workloads import ShapeCfg, get_config, make_problem, make_tokens, n_groups, sample_patches
-from workloads import make_level
+from workloads import make_level, make_linear_level
 
 pytestmark = pytest.mark.gpu
 
@@ -34,7 +34,7 @@ def dev(a, dtype):
 def dev_level(lv, dtype):
     return dchag.LevelWeights(lv.group_size, dev(lv.query, dtype), dev(lv.Wq, dtype), dev(lv.Wk, dtype),
                               dev(lv.Wv, dtype), dev(lv.Wo, dtype), dev(lv.bq, dtype), dev(lv.bk, dtype),
-                              dev(lv.bv, dtype), dev(lv.bo, dtype))
+                              dev(lv.bv, dtype), dev(lv.bo, dtype), kind=1 if lv.kind == "linear" else 0)
 
 
 def rel_err(got, want):
@@ -149,6 +149,84 @@ def test_aggregate_level_generic_bf16_kernels_still_match(monkeypatch):
 
 
 # ------------------------------------------------------------------------------------------
+# linear partial-aggregation level (D-CHAG-L)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,B,Cin,N,D,g", [
+    ("f32", 2, 6, 10, 32, 3),
+    ("f32", 1, 7, 5, 24, 3),             # uneven last group (3,3,1); D / 4 = 6 vectors per row
+    ("f32", 1, 4, 3, 16, 1),             # groups of one: a per-feature scale and shift
+    ("bf16", 2, 12, 40, 256, 8),         # short last group of 4
+    ("bf16", 1, 33, 19, 72, 16),         # D = 9 vectors of 8; last group of one
+    ("bf16", 1, 70, 300, 1024, 70),      # one flat group; several blocks per (b, k)
+])
+@pytest.mark.parametrize("biases", [True, False])
+def test_linear_level_matches_oracle(dtype, B, Cin, N, D, g, biases):
+    say(f"linear level {dtype} B={B} Cin={Cin} N={N} D={D} g={g} biases={biases}")
+    rng = np.random.Generator(np.random.PCG64(300 + Cin))
+    lv = make_linear_level(rng, n_groups(Cin, g), g, D, dtype, biases)
+    z = make_tokens(B, Cin, N, D, dtype, seed=9)
+    y = dchag.dchag_aggregate_level(dev(z, dtype), dev_level(lv, dtype), heads=1)
+    torch.cuda.synchronize()
+    zo = z.transpose(0, 2, 1, 3).reshape(B * N, Cin, D)
+    want = oracle.aggregate_level(zo, lv, 1).reshape(B, N, -1, D).transpose(0, 2, 1, 3)
+    err = rel_err(host(y), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[dtype]
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", B=2, C=7, H=8, W=12, p=2, D=32, heads=4, group_sizes=(3, 3), level_kinds=("linear", "attention")),
+    dict(dtype="f32", B=1, C=9, H=8, W=8, p=2, D=16, heads=2, group_sizes=(2, 3, 2),
+         level_kinds=("linear", "linear", "attention")),                                    # 9 -> 5 -> 2 -> 1
+    # bf16, D % 256 == 0 and p*p % 16 == 0: tokenizer fused with the linear first level; groups 8, 8, 4;
+    # N = 24 patches (one ragged 64-patch tile)
+    dict(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3),
+         level_kinds=("linear", "attention")),
+    # fused, p = 8, N = 150 (three 64-patch tiles, the last ragged), two 256-column slices, groups 4, 4, 1
+    dict(dtype="bf16", B=1, C=9, H=80, W=120, p=8, D=512, heads=8, group_sizes=(4, 3),
+         level_kinds=("linear", "attention")),
+    # fused first level followed by a second linear level and the attention top
+    dict(dtype="bf16", B=1, C=12, H=16, W=16, p=4, D=256, heads=2, group_sizes=(3, 2, 2),
+         level_kinds=("linear", "linear", "attention")),
+    # bf16 shape the fused kernel does not take (D = 64): tokenizer, then the mixing kernel
+    dict(dtype="bf16", B=1, C=6, H=8, W=8, p=2, D=64, heads=2, group_sizes=(2, 3),
+         level_kinds=("linear", "attention")),
+])
+def test_forward_with_linear_levels_matches_oracle(kw):
+    cfg = cfg_of(**kw)
+    say(f"forward with linear levels {kw}")
+    pr = make_problem(cfg)
+    out = run_forward(pr)
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[cfg.dtype]
+
+
+def test_forward_linear_fused_and_unfused_agree(monkeypatch):
+    """The fused tokenizer + linear level against the two-kernel route on the same inputs: equal up to the
+    bf16 rounding of the per-channel tokens, which only the two-kernel route stores."""
+    cfg = cfg_of(dtype="bf16", B=1, C=20, H=32, W=32, p=4, D=256, heads=4, group_sizes=(8, 3),
+                 level_kinds=("linear", "attention"))
+    pr = make_problem(cfg, biases=False)
+    a = run_forward(pr)
+    monkeypatch.setenv("DCHAG_GENERIC_TOKENIZE", "1")
+    b = run_forward(pr)
+    assert rel_err(host(a), host(b)) < TOL["bf16"]
+
+
+def test_forward_rejects_linear_last_level():
+    cfg = cfg_of(dtype="f32", C=6, group_sizes=(3, 2), level_kinds=("linear", "attention"))
+    pr = make_problem(cfg)
+    lvls = [dev_level(lv, "f32") for lv in pr.levels]
+    lvls[1] = dchag.LevelWeights(2, None, None, None, torch.zeros(1, 2, cfg.D, device="cuda"), None, kind=1)
+    with pytest.raises(dchag.DchagError) as e:
+        dchag.dchag_forward(dev(pr.x, "f32"), dev(pr.We, "f32"), dev(pr.be, "f32"), dev(pr.ce, "f32"), lvls,
+                            cfg.p, cfg.heads)
+    assert e.value.status == -2
+
+
+# ------------------------------------------------------------------------------------------
 # whole path
 # ------------------------------------------------------------------------------------------
 def test_forward_tiny_config_fp32_full():
@@ -199,7 +277,7 @@ def test_forward_is_deterministic():
 
 
 @pytest.mark.parametrize("name,per_batch", [("weather", 8), ("hyperspectral", 6), ("wide", 3), ("deep", 2),
-                                            ("deep1000", 2)])
+                                            ("deep1000", 2), ("hyperspectral_linear", 6)])
 def test_forward_full_size_on_sampled_patches(name, per_batch):
     """The configurations of the benchmark at full size, in the launch configuration the benchmark
     times; the oracle computes a seeded sample of patches (every weight takes part in every patch)."""
