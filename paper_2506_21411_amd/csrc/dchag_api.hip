@@ -360,7 +360,39 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     StageTimer tm(DCHAG_STAGE_SCORES, st);
     const int NB = (heads + 15) / 16;
     const dim3 grid((N + 15) / 16, G * ((g + 3) / 4), B);
-    if (NB <= 1)
+    // group-resident form: folded keys in registers (KI * NB fragments); enough blocks to fill the chip
+    const int KI = D / 128, nq = (g + 3) / 4;
+    const long base_blocks = (long)((N + 15) / 16) * G * B;
+    int qsplit = (int)((8L * compute_units() + base_blocks - 1) / base_blocks);
+    qsplit = qsplit < 1 ? 1 : (qsplit > nq ? nq : qsplit);
+    const int qper = (nq + qsplit - 1) / qsplit;
+    qsplit = (nq + qper - 1) / qper;
+    const dim3 ggrid((N + 15) / 16, G * qsplit, B);
+#define DCHAG_SCORES_GROUP(NB_, KI_)                                                                         \
+  k_scores_group<NB_, KI_><<<ggrid, 256, 0, st>>>(Cin, N, heads, g, gpad, Np, qsplit, qper, zin, Mb, alpha)
+    const bool resident = D % 128 == 0 && !getenv("DCHAG_SCORES_PER_QUAD");
+    // scores + softmax in one kernel: folded keys of the whole row in registers, raw scores in LDS
+    const size_t slds = (size_t)16 * (2 * D + 16) + (size_t)gpad * 2048;
+    // DCHAG_SCORES_ONE_KERNEL = 0 / 1 overrides the size heuristic (never the shape limits)
+    const char* force = getenv("DCHAG_SCORES_ONE_KERNEL");
+    const bool fits = NB <= 1 && D % 256 == 0 && slds <= 150 * 1024;
+    const bool one_kernel = fits && (force ? force[0] == '1' : (long)(Np / 32) * G * B >= compute_units());
+    if (one_kernel) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_softmax),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds) != hipSuccess)
+        return DCHAG_ERR_LAUNCH;
+      k_scores_softmax<<<dim3(Np / 32, G, B), 512, slds, st>>>(Cin, N, D, heads, g, gpad, Np, zin, Mb, alpha);
+      if ((rc = launch_status())) return rc;
+    } else {
+    if (resident && NB <= 1 && KI == 2) DCHAG_SCORES_GROUP(1, 2);
+    else if (resident && NB <= 1 && KI == 4) DCHAG_SCORES_GROUP(1, 4);
+    else if (resident && NB <= 1 && KI == 8) DCHAG_SCORES_GROUP(1, 8);
+    else if (resident && NB <= 1 && KI == 16) DCHAG_SCORES_GROUP(1, 16);
+    else if (resident && NB == 2 && KI == 2) DCHAG_SCORES_GROUP(2, 2);
+    else if (resident && NB == 2 && KI == 4) DCHAG_SCORES_GROUP(2, 4);
+    else if (resident && NB == 2 && KI == 8) DCHAG_SCORES_GROUP(2, 8);
+#undef DCHAG_SCORES_GROUP
+    else if (NB <= 1)
       k_scores_mfma<1><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, gpad, Np, zin, Mb, alpha);
     else if (NB == 2)
       k_scores_mfma<2><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, gpad, Np, zin, Mb, alpha);
@@ -369,6 +401,7 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     if ((rc = launch_status())) return rc;
     k_softmax_alpha<<<dim3((Np + 255) / 256, heads, B * G), 256, 0, st>>>(Cin, N, heads, g, gpad, G, Np, alpha);
     if ((rc = launch_status())) return rc;
+    }
   }
   {
     StageTimer tm(DCHAG_STAGE_FUSED_VAGG, st);

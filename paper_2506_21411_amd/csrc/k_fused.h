@@ -133,6 +133,199 @@ __global__ __launch_bounds__(256) void k_scores_mfma(int Cin, int N, int D, int 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Scores, group-resident form of the kernel above for D = 128 * KI (KI even): a block takes 16 patches and a
+// run of whole channel quads of ONE group, so each wavefront loads its quarter of the folded keys once into
+// registers (KI * NB operand fragments) and then only streams tokens; the token loads of the next 32-feature
+// step are in flight while the current one is multiplied.  The four partial 16x16 blocks of a quad meet in
+// LDS (two buffers, one barrier per quad) and wavefront w adds up and stores channel w of the quad, always in
+// the order of the wavefronts.  grid (ceil(N/16), G * qsplit, B), block 256; part = blockIdx.y % qsplit takes
+// quads [part * qper, (part + 1) * qper) of its group.  Bound by the HBM read of the tokens.
+// ---------------------------------------------------------------------------------------------
+template <int NB, int KI>
+__global__ __launch_bounds__(256) void k_scores_group(int Cin, int N, int heads, int g, int gpad, int Np, int qsplit,
+                                                      int qper, const bf16* __restrict__ z,
+                                                      const bf16* __restrict__ Mb, float* __restrict__ S) {
+  // one step = one 16-byte load per lane = 32 features of one channel; a quad takes 4 * KI steps, channel after
+  // channel, so that a wavefront streams 16 rows x (D / 4) contiguous bytes of one channel before it moves on
+  constexpr int STEPS = 4 * KI;
+  constexpr int NBUF = STEPS < 8 ? STEPS : 8;            // NBUF - 1 loads in flight per lane
+  constexpr int PD = NBUF - 1;
+  static_assert(STEPS % NBUF == 0, "the fragment buffers rotate with the step index");
+  constexpr int D = KI * 128;
+  __shared__ float part[2][4][4][NB * 4][64];           // [buffer][source wavefront][channel of the quad]
+  const int k = blockIdx.y / qsplit, prt = blockIdx.y % qsplit;
+  const int G = gridDim.y / qsplit;
+  const int b = blockIdx.z, n0 = blockIdx.x * 16;
+  const int c0 = k * g;
+  const int gk = min(g, Cin - c0);
+  const int q_end = min((gk + 3) / 4, (prt + 1) * qper);
+  const int q_begin = prt * qper;
+  if (q_begin >= q_end) return;                          // uniform over the block
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int n = min(n0 + l16, N - 1);
+  const int koff = wave * (D / 4) + lq * 16;
+  // features of step ks (same for tokens and keys): the two steps of a pair read the two 16-byte halves of a
+  // lane's 32 bytes, so that the four lanes of a row cover one 128-byte line with two back-to-back loads
+  auto kstep = [](int ks) { return (ks >> 1) * 64 + (ks & 1) * 8; };
+
+  bf16x8 bfr[KI][NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const bf16* mrow = Mb + ((size_t)k * heads + min(nb * 16 + l16, heads - 1)) * D + koff;
+#pragma unroll
+    for (int ks = 0; ks < KI; ++ks) {
+      bfr[ks][nb] = *reinterpret_cast<const bf16x8*>(mrow + kstep(ks));
+      if (nb * 16 + l16 >= heads) bfr[ks][nb] = bf16x8{};
+    }
+  }
+  // tokens of channel cl of this group, this lane's patch and feature offset; members past the end of a
+  // short group re-read the last member (their scores are never stored)
+  const bf16* zb = z + (((size_t)b * Cin + c0) * N + n) * D + koff;
+  const size_t cstride = (size_t)N * D;
+  auto zptr = [&](int cl) { return zb + (size_t)min(cl, gk - 1) * cstride; };
+
+  bf16x8 af[NBUF];
+#pragma unroll
+  for (int t = 0; t < PD; ++t) af[t] = *reinterpret_cast<const bf16x8*>(zptr(q_begin * 4 + t / KI) + kstep(t % KI));
+  for (int q = q_begin; q < q_end; ++q) {
+    const bf16* cur[4];
+    const bf16* nxt[4];
+    const int qn = min(q + 1, q_end - 1);                // past the last quad: re-read it (in bounds, unused)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      cur[i] = zptr(q * 4 + i);
+      nxt[i] = zptr(qn * 4 + i);
+    }
+    f32x4 acc[4][NB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t) {
+      const int tp = t + PD;                             // the step whose load is issued now
+      af[tp % NBUF] = (tp < STEPS) ? *reinterpret_cast<const bf16x8*>(cur[tp / KI] + kstep(tp % KI))
+                                   : *reinterpret_cast<const bf16x8*>(nxt[(tp - STEPS) / KI] + kstep((tp - STEPS) % KI));
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        acc[t / KI][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[t % NBUF], bfr[t % KI][nb], acc[t / KI][nb], 0, 0, 0);
+    }
+    const int pb = (q - q_begin) & 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) part[pb][wave][i][nb * 4 + e][lane] = acc[i][nb][e];
+    __syncthreads();
+    // 16x16 accumulator block: lane holds head (lane % 16), patches 4 * (lane / 16) + 0..3
+    const int cl = q * 4 + wave;
+    if (cl < gk) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int head = nb * 16 + l16;
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          v[e] = ((part[pb][0][wave][nb * 4 + e][lane] + part[pb][1][wave][nb * 4 + e][lane]) +
+                  part[pb][2][wave][nb * 4 + e][lane]) + part[pb][3][wave][nb * 4 + e][lane];
+        if (head < heads) {
+          float* dst = S + ((((size_t)b * G + k) * gpad + cl) * heads + head) * Np + n0 + lq * 4;
+          *reinterpret_cast<f32x4*>(dst) = v;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scores and softmax in one kernel, for heads <= 16 and D % 256 == 0: a block takes 32 patches and ALL members
+// of one group, so the raw scores stay in LDS and only the softmax weights are written (128-byte runs).
+// The folded keys of the group sit in LDS (rows padded by 16 bytes: conflict-free ds_read_b128).  Wavefront w
+// streams whole token rows of members w, w + 8, ...: per step two 16-row fragments (patches 0..15 and 16..31,
+// 64 contiguous bytes per row and load) that share one key fragment, with the loads of the next seven steps in
+// flight; no cross-wavefront reduction is needed.  After one barrier thread (head, patch) takes the softmax
+// over the members and writes alpha, zeros for padding members and padding patches.
+// grid (Np / 32, G, B), block 512, dynamic LDS 16 * (2 D + 16) + gpad * 2048 bytes.
+// Bound by the HBM read of the tokens.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void k_scores_softmax(int Cin, int N, int D, int heads, int g, int gpad, int Np,
+                                                        const bf16* __restrict__ z, const bf16* __restrict__ Mb,
+                                                        float* __restrict__ alpha) {
+  constexpr int NBUF = 8, PD = NBUF - 1;                 // PD steps of loads in flight per lane and fragment
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int krow = D * 2 + 16;                           // bytes of one padded key row
+  float* sc = reinterpret_cast<float*>(smem + 16 * krow);   // [gpad][16 heads][32 patches]
+  const int k = blockIdx.y, G = gridDim.y, b = blockIdx.z, n0 = blockIdx.x * 32;
+  const int c0 = k * g;
+  const int gk = min(g, Cin - c0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int KF = D / 32;
+
+  for (int idx = threadIdx.x; idx < 16 * (D / 8); idx += 512) {
+    const int head = idx / (D / 8), c = idx % (D / 8);
+    bf16x8 v = {};
+    if (head < heads) v = *reinterpret_cast<const bf16x8*>(Mb + ((size_t)k * heads + head) * D + c * 8);
+    *reinterpret_cast<bf16x8*>(smem + head * krow + c * 16) = v;
+  }
+  __syncthreads();
+
+  if (wave < gk) {
+    const bf16* zb0 = z + (((size_t)b * Cin + c0) * N + min(n0 + l16, N - 1)) * D + lq * 8;
+    const bf16* zb1 = z + (((size_t)b * Cin + c0) * N + min(n0 + 16 + l16, N - 1)) * D + lq * 8;
+    const size_t cstride = (size_t)N * D;
+    const unsigned char* kfrag = smem + l16 * krow + lq * 16;
+    const int last = wave + ((gk - 1 - wave) / 8) * 8;     // this wavefront's last member
+    bf16x8 a0[NBUF], a1[NBUF];
+#pragma unroll
+    for (int t = 0; t < PD; ++t) {
+      a0[t] = *reinterpret_cast<const bf16x8*>(zb0 + (size_t)wave * cstride + t * 32);
+      a1[t] = *reinterpret_cast<const bf16x8*>(zb1 + (size_t)wave * cstride + t * 32);
+    }
+    for (int cl = wave; cl < gk; cl += 8) {
+      const size_t co = (size_t)cl * cstride;
+      const size_t no = (size_t)min(cl + 8, last) * cstride - (size_t)KF * 32;   // past the end: re-read (unused)
+      f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+      for (int tb = 0; tb < KF; tb += NBUF) {
+#pragma unroll
+        for (int u = 0; u < NBUF; ++u) {
+          const int t = tb + u, tp = t + PD;               // tp: the step whose loads are issued now
+          const size_t off = (tp < KF ? co : no) + (size_t)tp * 32;
+          a0[(u + PD) % NBUF] = *reinterpret_cast<const bf16x8*>(zb0 + off);
+          a1[(u + PD) % NBUF] = *reinterpret_cast<const bf16x8*>(zb1 + off);
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kfrag + t * 64);
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], kf, acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], kf, acc1, 0, 0, 0);
+        }
+      }
+      // 16x16 accumulator block: lane holds head (lane % 16), patches 4 * (lane / 16) + 0..3
+      *reinterpret_cast<f32x4*>(&sc[(cl * 16 + l16) * 32 + lq * 4]) = acc0;
+      *reinterpret_cast<f32x4*>(&sc[(cl * 16 + l16) * 32 + 16 + lq * 4]) = acc1;
+    }
+  }
+  __syncthreads();
+  const int head = threadIdx.x >> 5, patch = threadIdx.x & 31;
+  if (head >= heads) return;
+  const int n = n0 + patch;
+  const size_t stride = (size_t)heads * Np;
+  float* p = alpha + ((((size_t)b * G + k) * gpad) * heads + head) * Np + n;
+  if (n >= N) {                                            // pitch padding: never scored, weight zero
+    for (int cl = 0; cl < gpad; ++cl) p[cl * stride] = 0.f;
+    return;
+  }
+  const float* s = sc + head * 32 + patch;
+  float mx = -INFINITY;
+  for (int cl = 0; cl < gk; ++cl) mx = fmaxf(mx, s[cl * 512]);
+  float den = 0.f;
+  for (int cl = 0; cl < gk; ++cl) den += __expf(s[cl * 512] - mx);
+  const float inv = 1.f / den;
+  for (int cl = 0; cl < gk; ++cl) p[cl * stride] = __expf(s[cl * 512] - mx) * inv;
+  for (int cl = gk; cl < gpad; ++cl) p[cl * stride] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
 // In-place softmax over the members of a group: S[b][k][0..gk)[head][n] -> alpha, zeros for cl >= gk.
 // grid (ceil(Np/256), heads, B*G), block 256; one thread per (b, k, head, n).
 // ---------------------------------------------------------------------------------------------

@@ -134,6 +134,48 @@ def test_aggregate_level_matches_oracle(dtype, B, Cin, N, D, heads, g, biases):
     assert err < TOL[dtype]
 
 
+@pytest.mark.parametrize("one_kernel", ["0", "1"])
+@pytest.mark.parametrize("B,Cin,N,D,heads,g", [
+    (2, 12, 40, 256, 4, 8),        # N = 40: second 32-patch tile holds 8 patches; short last group of 4
+    (1, 33, 19, 512, 8, 16),       # last group of one member; fewer members than wavefronts in it
+    (1, 70, 9, 256, 2, 70),        # one group of 70: wavefronts take 9 or 8 members each
+    (1, 10, 50, 512, 16, 5),       # 16 heads: every key row of the 16-row fragment is a real head
+    (1, 5, 20, 1024, 2, 5),        # D = 1024: 32 steps per token row
+])
+def test_aggregate_level_score_kernels(monkeypatch, one_kernel, B, Cin, N, D, heads, g):
+    """Both score routes of the bf16 MFMA path on the same small shapes: scores and softmax in one kernel
+    (the library takes it by itself only on large inputs) and the two-kernel route."""
+    monkeypatch.setenv("DCHAG_SCORES_ONE_KERNEL", one_kernel)
+    say(f"score route one_kernel={one_kernel} B={B} Cin={Cin} N={N} D={D} h={heads} g={g}")
+    rng = np.random.Generator(np.random.PCG64(400 + Cin))
+    lv = make_level(rng, n_groups(Cin, g), g, D, "bf16", True)
+    z = make_tokens(B, Cin, N, D, "bf16", seed=11)
+    y = dchag.dchag_aggregate_level(dev(z, "bf16"), dev_level(lv, "bf16"), heads)
+    torch.cuda.synchronize()
+    want = oracle.aggregate_level(z.transpose(0, 2, 1, 3).reshape(B * N, Cin, D), lv, heads)
+    err = rel_err(host(y), want.reshape(B, N, -1, D).transpose(0, 2, 1, 3))
+    say(f"  err={err:.3e}")
+    assert err < TOL["bf16"]
+
+
+def test_aggregate_level_large_enough_for_the_one_kernel_score_route():
+    """A level big enough that the library picks the one-kernel score route by itself (at least one
+    32-patch block per compute unit), ragged in N, checked on sampled patches."""
+    B, Cin, N, D, heads, g = 2, 24, 1500, 256, 4, 8
+    rng = np.random.Generator(np.random.PCG64(77))
+    lv = make_level(rng, n_groups(Cin, g), g, D, "bf16", True)
+    z = make_tokens(B, Cin, N, D, "bf16", seed=12)
+    y = dchag.dchag_aggregate_level(dev(z, "bf16"), dev_level(lv, "bf16"), heads)
+    torch.cuda.synchronize()
+    ns = np.array([0, 1, 31, 32, 700, 1471, 1472, 1498, 1499])
+    zo = z[:, :, ns, :].transpose(0, 2, 1, 3).reshape(B * ns.size, Cin, D)
+    want = oracle.aggregate_level(zo, lv, heads).reshape(B, ns.size, -1, D).transpose(0, 2, 1, 3)
+    err = rel_err(host(y)[:, :, ns, :], want)
+    say(f"one-kernel route at scale: err={err:.3e}")
+    assert err < TOL["bf16"]
+    assert torch.isfinite(y.float()).all()
+
+
 def test_aggregate_level_generic_bf16_kernels_still_match(monkeypatch):
     """The shape-generic bf16 kernels (taken for shapes the MFMA path does not tile) on a shape
     the MFMA path would take, forced through the library's DCHAG_GENERIC_LEVEL switch."""
