@@ -165,12 +165,31 @@ int launch_tokenize(int B, int C, int H, int W, int p, int D, const T* x, const 
 int launch_tokenize_mfma(int B, int C, int H, int W, int p, int D, const bf16* x, const bf16* We, const bf16* be,
                          const bf16* ce, bf16* tokens, hipStream_t st) {
   const int N = (H / p) * (W / p);
+  const int ks = p * p / 16;
+  if ((ks == 1 || ks == 2 || ks == 4) && p * p == 16 * ks && D % 256 == 0 && !getenv("DCHAG_TOKENIZE_PER_TILE")) {
+    // weight-stationary form: enough blocks for about eight per compute unit, each walking `per` tiles
+    const int T = B * ((N + 127) / 128);
+    const long base = (long)(D / 256) * C;
+    int ts = (int)((8L * compute_units() + base - 1) / base);
+    ts = ts < 1 ? 1 : (ts > T ? T : ts);
+    const int per = (T + ts - 1) / ts;
+    ts = (T + per - 1) / per;
+    const size_t wlds = (size_t)2 * 128 * (p * p * 2 + 16);
+    auto wk = ks == 1 ? k_tokenize_ws<1> : ks == 2 ? k_tokenize_ws<2> : k_tokenize_ws<4>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(wk), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)wlds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    StageTimer tm(DCHAG_STAGE_TOKENIZE, st);
+    wk<<<dim3(D / 256, C, ts), 256, wlds, st>>>(B, C, H, W, p, D, per, x, We, be, ce, tokens);
+    return launch_status();
+  }
   const size_t lds = (size_t)128 * (p * p * 2 + 16);
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
+  auto kern = ks == 1 ? k_tokenize_mfma<1> : ks == 2 ? k_tokenize_mfma<2> : ks == 4 ? k_tokenize_mfma<4> : k_tokenize_mfma<0>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)lds) != hipSuccess)
     return DCHAG_ERR_LAUNCH;
   StageTimer tm(DCHAG_STAGE_TOKENIZE, st);
-  k_tokenize_mfma<<<dim3((N + 127) / 128, C, B), 256, lds, st>>>(C, H, W, p, D, x, We, be, ce, tokens);
+  kern<<<dim3((N + 127) / 128, C, B), 256, lds, st>>>(C, H, W, p, D, x, We, be, ce, tokens);
   return launch_status();
 }
 

@@ -858,12 +858,16 @@ __global__ __launch_bounds__(256) void k_scores_pixels(int C, int H, int W, int 
 // outputs per row and half a wavefront stores 128 contiguous bytes.
 // Requires p*p % 16 == 0, p*p <= 256, D % 64 == 0.  The kernel is HBM-write bound.
 // ---------------------------------------------------------------------------------------------
+// KSS = p*p / 16 when that is 1, 2 or 4 (the weight fragments of the next column slice are then fetched while
+// the current slice is multiplied and stored), 0 for any other patch size (fragments fetched step by step).
+template <int KSS>
 __global__ __launch_bounds__(256, 2) void k_tokenize_mfma(int C, int H, int W, int p, int D, const bf16* __restrict__ x,
                                                        const bf16* __restrict__ We, const bf16* __restrict__ be,
                                                        const bf16* __restrict__ ce, bf16* __restrict__ tokens) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   const int pp = p * p, pw = W / p, N = (H / p) * pw;
-  const int KS = pp / 16;
+  const int KS = KSS ? KSS : pp / 16;
   const int rbp = pp * 2 + 16;                           // padded bytes per patch row
   const int n0 = blockIdx.x * 128, c = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -886,6 +890,25 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mfma(int C, int H, int W, i
   __syncthreads();
 
   const bf16* Wc = We + (size_t)c * D * pp;
+  // uniform tile base + per-lane byte offset (the two half-wavefronts sit 4 rows apart); a tile spans at most
+  // 128 rows of 2 D bytes, so 32-bit offsets do
+  typedef __attribute__((address_space(1))) unsigned char gbyte_t;
+  typedef __attribute__((address_space(1))) bf16x2 gbf16x2_t;
+  gbyte_t* tbase = (gbyte_t*)(tokens + (((size_t)b * C + c) * N + n0) * D);
+  const unsigned rowb = (unsigned)D * 2;
+  const int nlim = N - n0 - 4 * lhi;                     // rows of this lane's half that are inside the image
+  const bool full = n0 + 128 <= N;                       // uniform: no row of the tile is outside
+
+  constexpr int NF = KSS ? KSS : 1;
+  bf16x8 bfrag[NF][2];                                   // weight fragments of the slice about to be multiplied
+  if (KSS) {
+    const bf16* wrow = Wc + (size_t)(wave * 64 + 2 * l32) * pp + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < NF; ++kk)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bfrag[kk][j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
+  }
+  const unsigned rowb5 = 5 * rowb;
   for (int col0 = wave * 64; col0 < D; col0 += 256) {
     f32x16 acc[4][2];
 #pragma unroll
@@ -894,40 +917,211 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mfma(int C, int H, int W, i
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    const bf16* wrow = Wc + (size_t)(col0 + 2 * l32) * pp + lhi * 8;
-    for (int kk = 0; kk < KS; ++kk) {
-      bf16x8 bfr[2], af[4];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(smem + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
     const int d0 = col0 + 2 * l32;
+    if (KSS) {
+#pragma unroll
+      for (int kk = 0; kk < NF; ++kk) {
+        bf16x8 af[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          af[i] = *reinterpret_cast<const bf16x8*>(smem + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfrag[kk][j], acc[i][j], 0, 0, 0);
+      }
+      // fetch the slice after this one while this one is stored (the last slice fetches itself again:
+      // in bounds, unused)
+      const int coln = col0 + 256 < D ? col0 + 256 : col0;
+      const bf16* wrow = Wc + (size_t)(coln + 2 * l32) * pp + lhi * 8;
+#pragma unroll
+      for (int kk = 0; kk < NF; ++kk)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bfrag[kk][j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
+    } else {
+      const bf16* wrow = Wc + (size_t)d0 * pp + lhi * 8;
+      for (int kk = 0; kk < KS; ++kk) {
+        bf16x8 bfr[2], af[4];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          af[i] = *reinterpret_cast<const bf16x8*>(smem + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+    }
     float add0 = 0.f, add1 = 0.f;
     if (be) { add0 += (float)be[(size_t)c * D + d0]; add1 += (float)be[(size_t)c * D + d0 + 1]; }
     if (ce) { add0 += (float)ce[(size_t)c * D + d0]; add1 += (float)ce[(size_t)c * D + d0 + 1]; }
-    // uniform row base + per-lane element offset (the two half-wavefronts sit 4 rows apart)
-    bf16* tbase = tokens + (((size_t)b * C + c) * N + n0) * D;
-    const int lane_off = 4 * lhi * D + d0;
-    const int nlim = N - n0 - 4 * lhi;                   // rows of this lane's half that are inside the image
+    // rows of a lane in register order: 0 1 2 3 8 9 10 11 16 ... (steps of 1, 1, 1, 5 rows).  The row pointer
+    // is uniform and walks in scalar registers; the asm keeps the compiler from precomputing all 64 of them
+    // outside the slice loop (which costs more registers than there are).
+    const unsigned lane_off = (unsigned)(4 * lhi * D + d0) * 2;
+    gbyte_t* rowp = tbase;
+    asm volatile("" : "+s"(rowp));
+    if (full) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int rr = i * 32 + 8 * (r >> 2) + (r & 3);  // uniform row index inside the tile
-        if (rr < nlim) {
-          typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        for (int r = 0; r < 16; ++r) {
           bf16x2 pk;
           pk[0] = (bf16)(acc[i][0][r] + add0);
           pk[1] = (bf16)(acc[i][1][r] + add1);
-          *reinterpret_cast<bf16x2*>(tbase + (size_t)rr * D + lane_off) = pk;
+          *(gbf16x2_t*)(rowp + lane_off) = pk;
+          rowp += (r & 3) == 3 ? rowb5 : rowb;
         }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int rr = i * 32 + 8 * (r >> 2) + (r & 3);  // uniform row index inside the tile
+          if (rr < nlim) {
+            bf16x2 pk;
+            pk[0] = (bf16)(acc[i][0][r] + add0);
+            pk[1] = (bf16)(acc[i][1][r] + add1);
+            *(gbf16x2_t*)(rowp + lane_off) = pk;
+          }
+          rowp += (r & 3) == 3 ? rowb5 : rowb;
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tokenizer on MFMA, weight-stationary form for p*p = 16 * KSS, KSS in {1, 2, 4}, D % 256 == 0 (same result
+// as k_tokenize_mfma).  grid (D / 256, C, TS), block 256: wavefront w of block (x, c, z) owns the 64 columns
+// 256 x + 64 w .. + 63 of channel c, loads their weight fragments ONCE and then walks the 128-patch tiles
+// [z * per, (z + 1) * per) of the B * ceil(N / 128) tiles of its channel.  The patches of the next tile are
+// fetched into registers while the current tile is multiplied and stored, and handed over through one of two
+// LDS buffers (one barrier per tile).  Dynamic LDS: 2 * 128 * (p*p*2 + 16) bytes.  HBM-write bound.
+// ---------------------------------------------------------------------------------------------
+template <int KSS>
+__global__ __launch_bounds__(256, 2) void k_tokenize_ws(int B, int C, int H, int W, int p, int D, int per,
+                                                        const bf16* __restrict__ x, const bf16* __restrict__ We,
+                                                        const bf16* __restrict__ be, const bf16* __restrict__ ce,
+                                                        bf16* __restrict__ tokens) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  typedef __attribute__((address_space(1))) unsigned char gbyte_t;
+  typedef __attribute__((address_space(1))) bf16x2 gbf16x2_t;
+  constexpr int pp = 16 * KSS, pieces = pp / 4;          // 8-byte pieces per patch
+  constexpr int rbp = pp * 2 + 16;                       // padded bytes per patch row
+  constexpr int NG = 128 * pieces / 256;                 // pieces a thread gathers per tile
+  const int pw = W / p, N = (H / p) * pw;
+  const int ntile = (N + 127) / 128, T = B * ntile;
+  const int c = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int d0 = blockIdx.x * 256 + wave * 64 + 2 * l32;   // this lane's two adjacent columns
+  const int t_begin = blockIdx.z * per, t_end = min(T, t_begin + per);
+  if (t_begin >= t_end) return;                          // uniform over the block
+
+  bf16x8 bfrag[KSS][2];
+  {
+    const bf16* wrow = We + ((size_t)c * D + d0) * pp + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bfrag[kk][j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
+  }
+  float add0 = 0.f, add1 = 0.f;
+  if (be) { add0 += (float)be[(size_t)c * D + d0]; add1 += (float)be[(size_t)c * D + d0 + 1]; }
+  if (ce) { add0 += (float)ce[(size_t)c * D + d0]; add1 += (float)ce[(size_t)c * D + d0 + 1]; }
+
+  // gather of tile t: piece idx = tid + 256 * i covers patch idx / pieces, pixels 4 * (idx % pieces) .. + 3
+  bf16x4 gv[NG];
+  auto fetch = [&](int t) {
+    const int b = t / ntile, n0 = (t % ntile) * 128;
+    const bf16* img = x + ((size_t)b * C + c) * H * W;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      const int idx = tid + 256 * i;
+      const int tp = idx / pieces, q = idx % pieces;
+      const int r = (q * 4) / p, s0 = (q * 4) % p;
+      const int n = n0 + tp;
+      gv[i] = bf16x4{};
+      if (n < N) {
+        const int pi = n / pw, pj = n % pw;
+        gv[i] = *reinterpret_cast<const bf16x4*>(img + (size_t)(pi * p + r) * W + pj * p + s0);
       }
+    }
+  };
+  auto stash = [&](int buf) {
+    unsigned char* u = smem + buf * 128 * rbp;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      const int idx = tid + 256 * i;
+      *reinterpret_cast<bf16x4*>(u + (idx / pieces) * rbp + (idx % pieces) * 8) = gv[i];
+    }
+  };
+  fetch(t_begin);
+  stash(0);
+  __syncthreads();
+
+  const unsigned rowb = (unsigned)D * 2, rowb5 = 5 * rowb;
+  const unsigned lane_off = (unsigned)(4 * lhi * D + d0) * 2;
+  for (int t = t_begin; t < t_end; ++t) {
+    const int cur = (t - t_begin) & 1;
+    if (t + 1 < t_end) fetch(t + 1);
+    const unsigned char* u = smem + cur * 128 * rbp;
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk) {
+      bf16x8 af[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(u + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfrag[kk][j], acc[i][j], 0, 0, 0);
+    }
+    // rows of a lane in register order: 0 1 2 3 8 9 10 11 16 ... (steps of 1, 1, 1, 5 rows); the row pointer
+    // is uniform and walks in scalar registers (the asm keeps it from being expanded into 64 precomputed ones)
+    const int b = t / ntile, n0 = (t % ntile) * 128;
+    gbyte_t* rowp = (gbyte_t*)(tokens + (((size_t)b * C + c) * N + n0) * D);
+    asm volatile("" : "+s"(rowp));
+    if (n0 + 128 <= N) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          bf16x2 pk;
+          pk[0] = (bf16)(acc[i][0][r] + add0);
+          pk[1] = (bf16)(acc[i][1][r] + add1);
+          *(gbf16x2_t*)(rowp + lane_off) = pk;
+          rowp += (r & 3) == 3 ? rowb5 : rowb;
+        }
+    } else {
+      const int nlim = N - n0 - 4 * lhi;                 // rows of this lane's half that are inside the image
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
+          if (rr < nlim) {
+            bf16x2 pk;
+            pk[0] = (bf16)(acc[i][0][r] + add0);
+            pk[1] = (bf16)(acc[i][1][r] + add1);
+            *(gbf16x2_t*)(rowp + lane_off) = pk;
+          }
+          rowp += (r & 3) == 3 ? rowb5 : rowb;
+        }
+    }
+    if (t + 1 < t_end) stash(cur ^ 1);
+    __syncthreads();
   }
 }
 
