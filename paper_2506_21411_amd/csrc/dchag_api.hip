@@ -639,19 +639,20 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
   c_in = C;
   int first = 0;
   const int pp0 = p * p;
-  if (dt == DCHAG_BF16 && levels[0].kind == DCHAG_LEVEL_LINEAR && pp0 % 16 == 0 && pp0 <= 256 && D % 256 == 0 &&
+  if (dt == DCHAG_BF16 && levels[0].kind == DCHAG_LEVEL_LINEAR && (pp0 == 16 || pp0 == 64) && D % 256 == 0 &&
       !getenv("DCHAG_GENERIC_TOKENIZE")) {
     // tokenizer and linear first level in one kernel: the per-channel tokens never reach HBM
     g_level = 1;
     const int g = gs[0], G = groups_of(C, g);
     bf16* y = reinterpret_cast<bf16*>(ws + w.ping);
     const size_t lds = (size_t)2 * 64 * (pp0 * 2 + 16);
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_mix_mfma),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    auto mixk = pp0 == 16 ? k_tokenize_mix_mfma<1> : k_tokenize_mix_mfma<4>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixk), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
       return DCHAG_ERR_LAUNCH;
     {
       StageTimer tm(DCHAG_STAGE_TOKENIZE_MIX, st);
-      k_tokenize_mix_mfma<<<dim3((unsigned)(((N + 63) / 64) * (D / 256)), G, B), 256, lds, st>>>(
+      mixk<<<dim3((unsigned)(((N + 63) / 64) * (D / 256)), G, B), 256, lds, st>>>(
           C, H, W, p, D, g, static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
           static_cast<const bf16*>(ce), static_cast<const bf16*>(levels[0].Wv), static_cast<const bf16*>(levels[0].bv),
           y);

@@ -1131,19 +1131,23 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_ws(int B, int C, int H, int
 //   y[b,k,n,d] = sum_{cl < gk} w[k][cl][d] * (We[c] u[b,c,n] + be[c] + ce[c])[d] + bias[k][d],   c = k*g + cl.
 // grid (ceil(N/64) * (D/256), G, B), block 256: 64 patches x 256 columns x all members of one group.
 // Wavefront w owns columns 64 w .. 64 w + 63 of the block's slice as 2 x 2 MFMA blocks (the two column
-// blocks interleave as in k_tokenize_mfma); per member the 64 patches are gathered into one of two LDS
-// buffers, multiplied, scaled by the member's weight of the lane's column and added up in registers.
-// Requires p*p % 16 == 0, p*p <= 256, D % 256 == 0.  Dynamic LDS: 2 * 64 * (p*p*2 + 16) bytes.
+// blocks interleave as in k_tokenize_mfma).  Members are pipelined: while member cl is multiplied, scaled by
+// its weight of the lane's column and added up in registers, the 64 patches and the weight fragments of member
+// cl + 1 are already on their way (patches through registers into the other of two LDS buffers, one barrier
+// per member).  p*p = 16 * KSS, KSS in {1, 4}; D % 256 == 0.  Dynamic LDS: 2 * 64 * (p*p*2 + 16) bytes.
 // ---------------------------------------------------------------------------------------------
+template <int KSS>
 __global__ __launch_bounds__(256, 2) void k_tokenize_mix_mfma(int C, int H, int W, int p, int D, int g,
                                                               const bf16* __restrict__ x, const bf16* __restrict__ We,
                                                               const bf16* __restrict__ be, const bf16* __restrict__ ce,
                                                               const bf16* __restrict__ wmix,
                                                               const bf16* __restrict__ bias, bf16* __restrict__ y) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int pp = p * p, pw = W / p, N = (H / p) * pw;
-  const int KS = pp / 16;
-  const int rbp = pp * 2 + 16;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  constexpr int pp = 16 * KSS, pieces = pp / 4;
+  constexpr int rbp = pp * 2 + 16;
+  constexpr int NG = (64 * pieces + 255) / 256;          // 8-byte pieces a thread gathers per member
+  const int pw = W / p, N = (H / p) * pw;
   const int ns_n = D / 256;
   const int n0 = (blockIdx.x / ns_n) * 64, col_base = (blockIdx.x % ns_n) * 256;
   const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
@@ -1151,7 +1155,49 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mix_mfma(int C, int H, int 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lhi = lane >> 5;
   const int d0 = col_base + wave * 64 + 2 * l32;         // this lane's two adjacent columns
-  const int pieces = pp / 4;
+
+  // what member cl needs: its patches (gv), its weight fragments (bfrag) and four per-column scalars
+  bf16x4 gv[NG];
+  bf16x8 bfrag[KSS][2];
+  float w0, w1, a0, a1;
+  // source offsets of this thread's pieces inside a channel image (-1: patch outside the image)
+  int goff[NG];
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    const int idx = tid + 256 * i;
+    const int t = idx / pieces, q = idx % pieces;
+    const int r = (q * 4) / p, s0 = (q * 4) % p;
+    const int n = n0 + t;
+    goff[i] = (idx < 64 * pieces && n < N) ? ((n / pw) * p + r) * W + (n % pw) * p + s0 : -1;
+  }
+  auto fetch = [&](int cl) {
+    const int c = c0 + cl;
+    const bf16* img = x + ((size_t)b * C + c) * H * W;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      gv[i] = bf16x4{};
+      if (goff[i] >= 0) gv[i] = *reinterpret_cast<const bf16x4*>(img + goff[i]);
+    }
+    const bf16* wrow = We + ((size_t)c * D + d0) * pp + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bfrag[kk][j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
+    w0 = (float)wmix[((size_t)k * g + cl) * D + d0];
+    w1 = (float)wmix[((size_t)k * g + cl) * D + d0 + 1];
+    a0 = 0.f;
+    a1 = 0.f;
+    if (be) { a0 += (float)be[(size_t)c * D + d0]; a1 += (float)be[(size_t)c * D + d0 + 1]; }
+    if (ce) { a0 += (float)ce[(size_t)c * D + d0]; a1 += (float)ce[(size_t)c * D + d0 + 1]; }
+  };
+  auto stash = [&](int buf) {
+    unsigned char* u = smem + buf * 64 * rbp;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      const int idx = tid + 256 * i;
+      if (idx < 64 * pieces) *reinterpret_cast<bf16x4*>(u + (idx / pieces) * rbp + (idx % pieces) * 8) = gv[i];
+    }
+  };
 
   f32x16 o[2][2];
 #pragma unroll
@@ -1162,55 +1208,39 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mix_mfma(int C, int H, int 
       for (int r = 0; r < 16; ++r) o[i][j][r] = 0.f;
   float cst0 = 0.f, cst1 = 0.f;                          // patch-independent part: sum_c w * (be + ce) + bias
 
+  fetch(0);
+  stash(0);
+  __syncthreads();
   for (int cl = 0; cl < gk; ++cl) {
-    const int c = c0 + cl;
-    unsigned char* u_s = smem + (cl & 1) * 64 * rbp;
-    const bf16* img = x + ((size_t)b * C + c) * H * W;
-    for (int idx = tid; idx < 64 * pieces; idx += 256) {
-      const int t = idx / pieces, q = idx % pieces;
-      const int r = (q * 4) / p, s0 = (q * 4) % p;
-      const int n = n0 + t;
-      bf16x4 v = {};
-      if (n < N) {
-        const int pi = n / pw, pj = n % pw;
-        v = *reinterpret_cast<const bf16x4*>(img + (size_t)(pi * p + r) * W + pj * p + s0);
+    const unsigned char* u = smem + (cl & 1) * 64 * rbp;
+    // this member's operands move to their own registers; the next member's loads start right away
+    bf16x8 bcur[KSS][2];
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bcur[kk][j] = bfrag[kk][j];
+    const float cw0 = w0, cw1 = w1;
+    cst0 += w0 * a0;
+    cst1 += w1 * a1;
+    if (cl + 1 < gk) fetch(cl + 1);
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      f32x16 acc0 = zero, acc1 = zero;                   // two independent chains: row block i, both column blocks
+#pragma unroll
+      for (int kk = 0; kk < KSS; ++kk) {
+        const bf16x8 af = *reinterpret_cast<const bf16x8*>(u + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bcur[kk][0], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bcur[kk][1], acc1, 0, 0, 0);
       }
-      *reinterpret_cast<bf16x4*>(u_s + t * rbp + q * 8) = v;
-    }
-    __syncthreads();                                     // buffer (cl & 1) is complete; the other one is free again
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    const bf16* wrow = We + ((size_t)c * D + d0) * pp + lhi * 8;
-    for (int kk = 0; kk < KS; ++kk) {
-      bf16x8 bfr[2], af[2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(wrow + (size_t)j * pp + kk * 16);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(u_s + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    const float w0 = (float)wmix[((size_t)k * g + cl) * D + d0], w1 = (float)wmix[((size_t)k * g + cl) * D + d0 + 1];
-    float add0 = 0.f, add1 = 0.f;
-    if (be) { add0 += (float)be[(size_t)c * D + d0]; add1 += (float)be[(size_t)c * D + d0 + 1]; }
-    if (ce) { add0 += (float)ce[(size_t)c * D + d0]; add1 += (float)ce[(size_t)c * D + d0 + 1]; }
-    cst0 += w0 * add0;
-    cst1 += w1 * add1;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        o[i][0][r] += w0 * acc[i][0][r];
-        o[i][1][r] += w1 * acc[i][1][r];
+        o[i][0][r] += cw0 * acc0[r];
+        o[i][1][r] += cw1 * acc1[r];
       }
+    }
+    if (cl + 1 < gk) stash((cl + 1) & 1);
+    __syncthreads();
   }
   if (bias) { cst0 += (float)bias[(size_t)k * D + d0]; cst1 += (float)bias[(size_t)k * D + d0 + 1]; }
   bf16* ybase = y + (((size_t)b * G + k) * N + n0) * D;
@@ -1222,7 +1252,6 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mix_mfma(int C, int H, int 
     for (int r = 0; r < 16; ++r) {
       const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
       if (rr < nlim) {
-        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
         bf16x2 pk;
         pk[0] = (bf16)(o[i][0][r] + cst0);
         pk[1] = (bf16)(o[i][1][r] + cst1);
