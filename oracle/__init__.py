@@ -36,6 +36,12 @@ class _CLevel(ctypes.Structure):
                 ("bq", _f32p), ("bk", _f32p), ("bv", _f32p), ("bo", _f32p)]
 
 
+class _CLevelGrad(ctypes.Structure):
+    _fields_ = [("dquery", _f64p),
+                ("dWq", _f64p), ("dWk", _f64p), ("dWv", _f64p), ("dWo", _f64p),
+                ("dbq", _f64p), ("dbk", _f64p), ("dbv", _f64p), ("dbo", _f64p)]
+
+
 def compile_source(src: str, lib_path: str) -> str:
     """gcc line used for the oracle: OpenMP, -O2, no fast-math (fp64 sums stay in source order)."""
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
@@ -79,6 +85,10 @@ def _load():
         lib.oracle_forward.restype = ctypes.c_int
         lib.oracle_forward.argtypes = ([ctypes.c_int] * 7 + [_f32p] * 4 + [ctypes.c_int, ctypes.POINTER(_CLevel)]
                                        + [ctypes.c_int, _i32p, _i32p, _f64p])
+        lib.oracle_backward.restype = ctypes.c_int
+        lib.oracle_backward.argtypes = ([ctypes.c_int] * 7 + [_f32p] * 4 + [ctypes.c_int, ctypes.POINTER(_CLevel)]
+                                        + [ctypes.c_int, _i32p, _i32p, _f64p, _f64p, _f64p, _f64p,
+                                           ctypes.POINTER(_CLevelGrad)])
         _libs[path] = lib
     return _libs[path]
 
@@ -205,3 +215,59 @@ def forward(x, We, be, ce, levels: Sequence, p: int, heads: int, sample=None) ->
     if rc != 0:
         raise ValueError(f"oracle_forward rejected the shape (rc={rc})")
     return out
+
+
+def backward(x, We, be, ce, levels: Sequence, p: int, heads: int, dout, sample=None, want_dx: bool = True) -> dict:
+    """Gradients of L = sum_i <dout[i], out[i]> over the sampled patches (all B*N patches in (b, n)
+    order if sample is None); dout is [S, D].
+
+    Returns {"dx": [S, C, p*p] or None (pixel gradients of each sampled patch, row by row),
+    "dWe": [C, D, p*p], "dtok_bias": [C, D] (the gradient of be and of ce alike),
+    "levels": [{"dquery", "dWq", "dWk", "dWv", "dWo", "dbq", "dbk", "dbv", "dbo"}, ...]}, all float64;
+    a linear level has only "dWv" [G, g, D] and "dbv".
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    B, C, H, W = x.shape
+    We = np.ascontiguousarray(We, dtype=np.float32)
+    D = We.shape[1]
+    if We.shape != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    N = (H // p) * (W // p)
+    sb, sn = _samples(B, N, sample)
+    dout = np.ascontiguousarray(dout, dtype=np.float64)
+    if dout.shape != (sb.size, D):
+        raise ValueError("dout must be [S, D]")
+    keep: list = []
+    arr = (_CLevel * len(levels))()
+    garr = (_CLevelGrad * len(levels))()
+    res_levels = []
+    c_in = C
+    for i, lv in enumerate(levels):
+        arr[i] = _clevel(lv, c_in, D, keep)
+        g = arr[i].group_size
+        G = (c_in + g - 1) // g
+        d = {}
+        if arr[i].kind == 1:
+            d["dWv"] = np.zeros((G, g, D))
+            d["dbv"] = np.zeros((G, D))
+        else:
+            d["dquery"] = np.zeros((G, D))
+            for name in ("dWq", "dWk", "dWv", "dWo"):
+                d[name] = np.zeros((G, D, D))
+            for name in ("dbq", "dbk", "dbv", "dbo"):
+                d[name] = np.zeros((G, D))
+        for name, a in d.items():
+            setattr(garr[i], name, a.ctypes.data_as(_f64p))
+        res_levels.append(d)
+        c_in = G
+    dx = np.zeros((sb.size, C, p * p)) if want_dx else None
+    dWe = np.zeros((C, D, p * p))
+    dtb = np.zeros((C, D))
+    rc = _load().oracle_backward(B, C, H, W, p, D, heads, x.ctypes.data_as(_f32p), We.ctypes.data_as(_f32p),
+                                 _f32(be, (C, D), keep)[1], _f32(ce, (C, D), keep)[1], len(levels), arr,
+                                 sb.size, sb.ctypes.data_as(_i32p), sn.ctypes.data_as(_i32p),
+                                 dout.ctypes.data_as(_f64p), dx.ctypes.data_as(_f64p) if want_dx else None,
+                                 dWe.ctypes.data_as(_f64p), dtb.ctypes.data_as(_f64p), garr)
+    if rc != 0:
+        raise ValueError(f"oracle_backward rejected the shape (rc={rc})")
+    return {"dx": dx, "dWe": dWe, "dtok_bias": dtb, "levels": res_levels}

@@ -5,6 +5,7 @@ import os
 import pytest
 
 import oracle
+import tests.test_oracle_backward as bwd
 import tests.test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "dchag_oracle.c")
@@ -28,6 +29,46 @@ MUTATIONS = {
     "value_of_wrong_member": ("acc += s[c] * V[(size_t)c * D + r0 + i];", "acc += s[c] * V[(size_t)(m - 1 - c) * D + r0 + i];"),
     "groups_overlap": ("const int c0 = k * g;", "const int c0 = k * g > 0 ? k * g - 1 : 0;"),
 }
+
+
+# planted in the backward half of the source; caught by the backward pins
+BACKWARD_MUTATIONS = {
+    "bwd_softmax_jacobian_without_the_mean": ("(dal[c] - dot);", "(dal[c]);"),
+    "bwd_no_scale_on_the_query_gradient": ("dQ[r0 + i] += scale * ds * K[(size_t)c * D + r0 + i];",
+                                           "dQ[r0 + i] += ds * K[(size_t)c * D + r0 + i];"),
+    "bwd_key_gradient_uses_keys": ("dK[(size_t)c * D + r0 + i] = scale * ds * Q[r0 + i];",
+                                   "dK[(size_t)c * D + r0 + i] = scale * ds * K[(size_t)c * D + r0 + i];"),
+    "bwd_value_gradient_without_alpha": ("dV[(size_t)c * D + r0 + i] = al[(size_t)c * heads + a] * d_o[r0 + i];",
+                                         "dV[(size_t)c * D + r0 + i] = d_o[r0 + i];"),
+    "bwd_outer_product_transposed": ("gr[j] += yi * x[j];", "gr[j] += y[j % rows] * x[i % cols];"),
+    "bwd_input_gradient_misses_the_key_path": (
+        "affine_transposed_add(lv->Wk + wo, dK + (size_t)c * D, D, D, dzc);", ""),
+    "bwd_output_projection_not_transposed": (
+        "affine_transposed_add(lv->Wo + wo, dy, D, D, d_o);", "affine(lv->Wo + wo, NULL, dy, D, D, d_o);"),
+    "bwd_patch_pixels_transposed": ("u[r * p + s] = (double)img[(size_t)(pi * p + r) * W + (pj * p + s)];\n      const double *dt",
+                                    "u[s * p + r] = (double)img[(size_t)(pi * p + r) * W + (pj * p + s)];\n      const double *dt"),
+    "bwd_linear_level_input_gradient_without_weight": ("dz[(size_t)c * D + d] = (double)lv->Wv[wi] * dy[d];",
+                                                       "dz[(size_t)c * D + d] = dy[d];"),
+    "bwd_level_gradients_of_group_zero_only": ("const double *dy = dzs[l + 1] + ((size_t)i * G + k) * D;",
+                                               "const double *dy = dzs[l + 1] + ((size_t)i * G + 0 * k) * D;"),
+}
+
+
+def run_backward_pins():
+    checks = [
+        ("autograd", lambda: bwd.test_backward_matches_library_autograd(bwd.CASES[1])),
+        ("autograd_linear", lambda: bwd.test_backward_matches_library_autograd(bwd.CASES[4])),
+        ("fd", lambda: bwd.test_backward_matches_finite_differences_of_the_forward(bwd.CASES[1])),
+        ("dbk", bwd.test_key_bias_has_zero_gradient_and_token_biases_share_theirs),
+        ("dbv", bwd.test_value_bias_gradient_is_the_output_projection_of_the_output_bias_gradient),
+    ]
+    failed = []
+    for name, fn in checks:
+        try:
+            fn()
+        except AssertionError:
+            failed.append(name)
+    return failed
 
 
 def run_pins():
@@ -57,6 +98,24 @@ def run_pins():
 
 def test_unmutated_source_passes_the_subset():
     assert run_pins() == []
+    assert run_backward_pins() == []
+
+
+@pytest.mark.parametrize("name", sorted(BACKWARD_MUTATIONS))
+def test_planted_backward_mistake_is_caught(name, tmp_path):
+    old, new = BACKWARD_MUTATIONS[name]
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation anchor for {name} not found exactly once in the oracle source"
+    bad_src = tmp_path / "bad_oracle.c"
+    bad_src.write_text(text.replace(old, new))
+    bad_lib = str(tmp_path / f"libbad_{name}.so")
+    oracle.compile_source(str(bad_src), bad_lib)
+    oracle.use_library(bad_lib)
+    try:
+        failed = run_backward_pins()
+    finally:
+        oracle.use_library(None)
+    assert failed, f"no backward pin noticed the planted mistake {name!r}"
 
 
 @pytest.mark.parametrize("name", sorted(MUTATIONS))
