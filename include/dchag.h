@@ -1,5 +1,5 @@
 /*
- * dchag.h -- C ABI of the MI355X (gfx950) D-CHAG forward library.
+ * dchag.h -- C ABI of the MI355X (gfx950) D-CHAG library (forward and backward).
  *
  * D-CHAG = Distributed Cross-Channel Hierarchical Aggregation.  The library
  * computes the forward pass of per-channel patch tokenization followed by
@@ -137,10 +137,67 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The whole path with the value projection moved behind the softmax-weighted sum (an inference
+ * variant; same arguments, same result up to rounding as dchag_forward).  The weights of a softmax
+ * sum to one, so for every head a
+ *
+ *   o_a = sum_c alpha[c,a] (Wv z[c] + bv)_a = Wv_a ( sum_c alpha[c,a] z[c] ) + bv_a :
+ *
+ * the group's tokens are averaged per head first (u_a, one D-vector per head) and Wv is applied once
+ * per (group, patch, head) instead of once per member -- g*D*D multiply-adds per group and patch
+ * become D*D + g*heads*D.  The paper states the layer as plain cross-attention (Section 2.1); this
+ * is the same function evaluated in another order, kept as a call of its own so that the as-defined
+ * path stays measurable.  workspace: dchag_workspace_bytes(..., which = 2).
+ */
+int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
+                         const void *x, const void *We, const void *be, const void *ce,
+                         int n_levels, const dchag_level *levels, void *out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Gradients of one level, shaped like the weights of dchag_level (host struct, device pointers).
+ * Any pointer may be NULL: that gradient is not written.  A DCHAG_LEVEL_LINEAR level uses dWv
+ * ([G, g, D]) and dbv only.
+ */
+typedef struct {
+  void *dquery;                     /* [G, D]                                                     */
+  void *dWq, *dWk, *dWv, *dWo;      /* [G, D, D]                                                  */
+  void *dbq, *dbk, *dbv, *dbo;      /* [G, D]                                                     */
+} dchag_level_grads;
+
+/*
+ * Backward pass of dchag_forward (the paper's module is trained through; Section 3.3 notes that the
+ * backward of the partial aggregation needs no communication, it is the plain reverse of the forward).
+ * Given dout = dL/d(out) for a scalar loss L, writes dL/d(every weight) and, if asked, dL/dx:
+ *
+ *   dout      [B,N,D]    in
+ *   dx        [B,C,H,W]  out, or NULL
+ *   dWe       [C,D,p*p]  out, or NULL
+ *   dtok_bias [C,D]      out, or NULL: dL/d(be) = dL/d(ce) (the two enter a token as a sum)
+ *   grads     n_levels entries (host), grads[l] for levels[l]
+ *
+ * Every gradient tensor has element type `dt` and is overwritten (not accumulated into); sums over
+ * patches and members are fp32 in a fixed order (results are reproducible run to run).  The key bias
+ * shifts all scores of a softmax equally, so dbk is written as zeros.  Nothing is kept from a forward
+ * call: the activations the reverse sweep needs (tokens, softmax weights, per-head token averages,
+ * pre-projection outputs) are recomputed into the workspace first, with the value projection applied
+ * after the weighted sum (see dchag_forward_folded), so a training step is dchag_forward (or nothing,
+ * if `out` is not needed) followed by this call.
+ * workspace: dchag_workspace_bytes(..., which = 3).
+ * Errors: as dchag_forward; NULL dout or grads.
+ */
+int dchag_backward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
+                   const void *x, const void *We, const void *be, const void *ce,
+                   int n_levels, const dchag_level *levels, const void *dout,
+                   void *dx, void *dWe, void *dtok_bias, const dchag_level_grads *grads,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Workspace size in bytes (0 on invalid arguments).
  *   which = 0: one dchag_aggregate_level call with Cin = C inputs, N = (H/p)*(W/p)
  *              (pass H = N, W = 1, p = 1 when only N is known), group size group_sizes[0];
- *   which = 1: one dchag_forward call with the n_levels nominal group sizes.
+ *   which = 1: one dchag_forward call with the n_levels nominal group sizes;
+ *   which = 2: one dchag_forward_folded call;   which = 3: one dchag_backward call.
  */
 size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
                              int n_levels, const int32_t *group_sizes, int which);
@@ -164,7 +221,16 @@ typedef enum {
   DCHAG_STAGE_OPROJ = 6,           /* output projection                                        */
   DCHAG_STAGE_FUSED_VAGG = 7,      /* value projection + scores + online softmax + sum, fused  */
   DCHAG_STAGE_CHANNEL_MIX = 8,     /* linear (D-CHAG-L) level: weighted sum over the group      */
-  DCHAG_STAGE_TOKENIZE_MIX = 9     /* tokenizer fused with a linear first level                 */
+  DCHAG_STAGE_TOKENIZE_MIX = 9,    /* tokenizer fused with a linear first level                 */
+  DCHAG_STAGE_HEAD_SUMS = 10,      /* per-head softmax-weighted token averages u_a              */
+  DCHAG_STAGE_HEAD_VPROJ = 11,     /* value projection applied to u_a, one head at a time       */
+  DCHAG_STAGE_BWD_OPROJ = 12,      /* backward of the output projection (dWo, dbo, d o)         */
+  DCHAG_STAGE_BWD_VALUE = 13,      /* backward of the value path (dWv, dbv, w = Wv_a^T d o_a)   */
+  DCHAG_STAGE_BWD_SOFTMAX = 14,    /* d alpha, softmax Jacobian                                 */
+  DCHAG_STAGE_BWD_TOKENS = 15,     /* gradient at the level's input tokens                      */
+  DCHAG_STAGE_BWD_KEY_QUERY = 16,  /* key / query weight gradients (rank-one per head)          */
+  DCHAG_STAGE_BWD_TOKENIZE = 17,   /* tokenizer backward (dWe, token bias, dx)                  */
+  DCHAG_STAGE_BWD_CHANNEL_MIX = 18 /* backward of a linear level                                */
 } dchag_stage;
 
 typedef struct {

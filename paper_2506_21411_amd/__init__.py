@@ -1,4 +1,4 @@
-"""MI355X-native forward path of D-CHAG: per-channel patch tokenization + hierarchical
+"""MI355X-native forward and backward path of D-CHAG: per-channel patch tokenization + hierarchical
 cross-channel cross-attention aggregation, as hand-written HIP kernels behind a C ABI.
 
 The Python layer only marshals arguments (device pointers, sizes, the current stream) into
@@ -6,6 +6,6 @@ The Python layer only marshals arguments (device pointers, sizes, the current st
 PyTorch fallback: if the library is missing, importing `binding` functions raises.
 """
 from .binding import (  # noqa: F401
-    DCHAG_BF16, DCHAG_F32, DchagError, LevelWeights, dchag_aggregate_level, dchag_forward,
-    dchag_profile_begin, dchag_profile_end, dchag_tokenize, dchag_workspace_bytes, library_path, load_library,
+    DCHAG_BF16, DCHAG_F32, DchagError, LevelGrads, LevelWeights, dchag_aggregate_level, dchag_backward,
+    dchag_forward, dchag_forward_folded, dchag_profile_begin, dchag_profile_end, dchag_tokenize, dchag_workspace_bytes, library_path, load_library,
 )

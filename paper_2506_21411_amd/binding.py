@@ -34,12 +34,20 @@ class _CLevel(ctypes.Structure):
                 ("bq", ctypes.c_void_p), ("bk", ctypes.c_void_p), ("bv", ctypes.c_void_p), ("bo", ctypes.c_void_p)]
 
 
+class _CLevelGrads(ctypes.Structure):
+    _fields_ = [("dquery", ctypes.c_void_p),
+                ("dWq", ctypes.c_void_p), ("dWk", ctypes.c_void_p), ("dWv", ctypes.c_void_p), ("dWo", ctypes.c_void_p),
+                ("dbq", ctypes.c_void_p), ("dbk", ctypes.c_void_p), ("dbv", ctypes.c_void_p), ("dbo", ctypes.c_void_p)]
+
+
 class _CStageTime(ctypes.Structure):
     _fields_ = [("stage", ctypes.c_int32), ("level", ctypes.c_int32), ("ms", ctypes.c_float)]
 
 
 STAGE_NAMES = {0: "tokenize", 1: "query", 2: "fold", 3: "scores", 4: "vproj", 5: "softmax_agg", 6: "oproj",
-               7: "fused_vagg", 8: "channel_mix", 9: "tokenize_mix"}
+               7: "fused_vagg", 8: "channel_mix", 9: "tokenize_mix", 10: "head_sums", 11: "head_vproj",
+               12: "bwd_oproj", 13: "bwd_value", 14: "bwd_softmax", 15: "bwd_tokens", 16: "bwd_key_query",
+               17: "bwd_tokenize", 18: "bwd_channel_mix"}
 
 LEVEL_ATTENTION, LEVEL_LINEAR = 0, 1
 
@@ -64,6 +72,20 @@ class LevelWeights:
     kind: int = LEVEL_ATTENTION
 
 
+@dataclass
+class LevelGrads:
+    """Gradient tensors of one level, shaped like its weights; None = not wanted."""
+    dquery: Optional[torch.Tensor] = None
+    dWq: Optional[torch.Tensor] = None
+    dWk: Optional[torch.Tensor] = None
+    dWv: Optional[torch.Tensor] = None
+    dWo: Optional[torch.Tensor] = None
+    dbq: Optional[torch.Tensor] = None
+    dbk: Optional[torch.Tensor] = None
+    dbv: Optional[torch.Tensor] = None
+    dbo: Optional[torch.Tensor] = None
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -85,6 +107,11 @@ def load_library():
     lib.dchag_aggregate_level.argtypes = [i] * 6 + [ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
     lib.dchag_forward.restype = i
     lib.dchag_forward.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, sz, vp]
+    lib.dchag_forward_folded.restype = i
+    lib.dchag_forward_folded.argtypes = lib.dchag_forward.argtypes
+    lib.dchag_backward.restype = i
+    lib.dchag_backward.argtypes = ([i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, vp, vp,
+                                                        ctypes.POINTER(_CLevelGrads), vp, sz, vp])
     lib.dchag_workspace_bytes.restype = sz
     lib.dchag_workspace_bytes.argtypes = [i] * 9 + [ctypes.POINTER(ctypes.c_int32), i]
     lib.dchag_strerror.restype = ctypes.c_char_p
@@ -198,6 +225,56 @@ def dchag_forward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor],
                                         len(levels), arr, _ptr(out, x), ctypes.c_void_p(workspace.data_ptr()),
                                         workspace.numel(), _stream(stream)))
     return out
+
+
+def dchag_forward_folded(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                         levels: List[LevelWeights], p: int, heads: int, out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """out[B,N,D] as dchag_forward, with the value projection applied after the softmax-weighted sum."""
+    B, C, H, W = x.shape
+    D = We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    N = (H // p) * (W // p) if p > 0 else 0
+    dt = _dt(x)
+    if workspace is None:
+        workspace = _workspace(dchag_workspace_bytes(dt, B, C, H, W, p, D, heads, [lv.group_size for lv in levels], 2),
+                               x.device)
+    if out is None:
+        out = torch.empty((B, N, D), dtype=x.dtype, device=x.device)
+    arr = (_CLevel * len(levels))(*[_clevel(lv, x) for lv in levels])
+    _check(load_library().dchag_forward_folded(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x),
+                                               _ptr(ce, x), len(levels), arr, _ptr(out, x),
+                                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                               _stream(stream)))
+    return out
+
+
+def dchag_backward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                   levels: List[LevelWeights], p: int, heads: int, dout: torch.Tensor,
+                   grads: List[LevelGrads], dx: Optional[torch.Tensor] = None, dWe: Optional[torch.Tensor] = None,
+                   dtok_bias: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                   stream=None) -> None:
+    """Writes the gradients of <dout, dchag_forward(...)> into the given tensors (None = not wanted)."""
+    B, C, H, W = x.shape
+    D = We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    if len(grads) != len(levels):
+        raise ValueError("one LevelGrads per level")
+    dt = _dt(x)
+    if workspace is None:
+        workspace = _workspace(dchag_workspace_bytes(dt, B, C, H, W, p, D, heads, [lv.group_size for lv in levels], 3),
+                               x.device)
+    arr = (_CLevel * len(levels))(*[_clevel(lv, x) for lv in levels])
+    garr = (_CLevelGrads * len(levels))()
+    for j, g in enumerate(grads):
+        for name in ("dquery", "dWq", "dWk", "dWv", "dWo", "dbq", "dbk", "dbv", "dbo"):
+            setattr(garr[j], name, _ptr(getattr(g, name), x))
+    _check(load_library().dchag_backward(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x), _ptr(ce, x),
+                                         len(levels), arr, _ptr(dout, x), _ptr(dx, x), _ptr(dWe, x),
+                                         _ptr(dtok_bias, x), garr, ctypes.c_void_p(workspace.data_ptr()),
+                                         workspace.numel(), _stream(stream)))
 
 
 def dchag_profile_begin() -> None:

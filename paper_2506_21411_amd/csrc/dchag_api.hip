@@ -7,12 +7,14 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "dchag_dev.h"
 #include "k_generic.h"
 #include "k_mfma.h"
 #include "k_fused.h"
+#include "k_train.h"
 
 using namespace dchag;
 
@@ -494,6 +496,8 @@ int check_level_shape(int B, int Cin, int N, int D, int heads, int g) {
   return DCHAG_OK;
 }
 
+#include "host_train.h"
+
 }  // namespace
 
 extern "C" {
@@ -551,6 +555,9 @@ size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, 
   if (check_level_shape(B, C, N, D, heads, group_sizes[0]) != DCHAG_OK) return 0;
   if (which == 0) return level_ws(dt, B, C, N, D, heads, group_sizes[0]).total;
   if (which == 1) return forward_ws(dt, B, C, N, p * p, D, heads, n_levels, group_sizes).total;
+  if (n_levels > 16) return 0;
+  if (which == 2) return folded_ws(dt, B, C, N, D, heads, n_levels, group_sizes).total;
+  if (which == 3) return backward_ws(dt, B, C, N, p * p, D, heads, n_levels, group_sizes, nullptr).total;
   return 0;
 }
 
@@ -695,6 +702,78 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     c_in = groups_of(c_in, gs[l]);
   }
   return DCHAG_OK;
+}
+
+// Shared argument checks of the calls that take the whole chain of levels; fills gs / kinds.
+static int check_chain(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                       const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                       int32_t* gs, int32_t* kinds) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
+  if (!x || !We || !levels) return DCHAG_ERR_NULL;
+  if (n_levels < 1 || n_levels > 16) return DCHAG_ERR_SHAPE;
+  int rc = check_tokenize_shape(B, C, H, W, p, D);
+  if (rc) return rc;
+  const int N = (H / p) * (W / p);
+  int c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    if ((rc = check_level(&levels[l]))) return rc;
+    if ((rc = check_level_shape(B, c_in, N, D, heads, levels[l].group_size))) return rc;
+    gs[l] = levels[l].group_size;
+    kinds[l] = levels[l].kind;
+    c_in = groups_of(c_in, gs[l]);
+  }
+  if (c_in != 1 || levels[n_levels - 1].kind != DCHAG_LEVEL_ATTENTION) return DCHAG_ERR_SHAPE;
+  if (misaligned(x) || misaligned(We) || misaligned(be) || misaligned(ce)) return DCHAG_ERR_ALIGN;
+  return DCHAG_OK;
+}
+
+int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                         const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                         void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t gs[16], kinds[16];
+  int rc = check_chain(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, kinds);
+  if (rc) return rc;
+  if (!out) return DCHAG_ERR_NULL;
+  if (misaligned(out)) return DCHAG_ERR_ALIGN;
+  const int N = (H / p) * (W / p);
+  const FoldedWs w = folded_ws(dt, B, C, N, D, heads, n_levels, gs);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
+      workspace_bytes < w.total)
+    return DCHAG_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  if (dt == DCHAG_F32)
+    return forward_folded_impl<float>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out, ws, w, st);
+  return forward_folded_impl<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out, ws, w, st);
+}
+
+int dchag_backward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                   const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                   const void* dout, void* dx, void* dWe, void* dtok_bias, const dchag_level_grads* grads,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t gs[16], kinds[16];
+  int rc = check_chain(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, kinds);
+  if (rc) return rc;
+  if (!dout || !grads) return DCHAG_ERR_NULL;
+  if (misaligned(dout) || misaligned(dx) || misaligned(dWe) || misaligned(dtok_bias)) return DCHAG_ERR_ALIGN;
+  for (int l = 0; l < n_levels; ++l) {
+    const void* ps[] = {grads[l].dquery, grads[l].dWq, grads[l].dWk, grads[l].dWv, grads[l].dWo,
+                        grads[l].dbq,    grads[l].dbk, grads[l].dbv, grads[l].dbo};
+    for (const void* q : ps)
+      if (misaligned(q)) return DCHAG_ERR_ALIGN;
+  }
+  const int N = (H / p) * (W / p);
+  const BackwardWs w = backward_ws(dt, B, C, N, p * p, D, heads, n_levels, gs, kinds);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
+      workspace_bytes < w.total)
+    return DCHAG_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  if (dt == DCHAG_F32)
+    return backward_impl<float>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, dout, dx, dWe,
+                                dtok_bias, grads, ws, w, st);
+  return backward_impl<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, dout, dx, dWe,
+                             dtok_bias, grads, ws, w, st);
 }
 
 }  // extern "C"

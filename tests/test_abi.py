@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"dchag_tokenize", "dchag_aggregate_level", "dchag_forward", "dchag_workspace_bytes",
-            "dchag_strerror", "dchag_version"} <= set(names)
+            "dchag_strerror", "dchag_version", "dchag_forward_folded", "dchag_backward"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in dchag.h but not exported"
 
@@ -90,12 +90,40 @@ def test_forward_validation(lib):
     assert f(*args(None, 2)) == -1
 
 
+def test_forward_folded_and_backward_validation(lib):
+    from paper_2506_21411_amd.binding import _CLevelGrads
+    two = (_CLevel * 2)(level(4), level(2))
+    bad_chain = (_CLevel * 2)(level(4), level(1))
+    ff = lib.dchag_forward_folded
+    args = lambda lv, n, ws=FAKE, wsb=1 << 40: (0, 1, 8, 32, 64, 4, 128, 4, FAKE, FAKE, None, None, n, lv,
+                                                 FAKE, ws, wsb, None)
+    assert ff(*args(two, 0)) == -2
+    assert ff(*args(bad_chain, 2)) == -2
+    assert ff(*args(two, 2, wsb=1024)) == -4
+    assert ff(*args(None, 2)) == -1
+    bw = lib.dchag_backward
+    gr = (_CLevelGrads * 2)()
+    bargs = lambda lv, n, dout=FAKE, g=gr, ws=FAKE, wsb=1 << 40: (0, 1, 8, 32, 64, 4, 128, 4, FAKE, FAKE, None, None, n,
+                                                                   lv, dout, None, None, None, g, ws, wsb, None)
+    assert bw(*bargs(two, 2, dout=None)) == -1
+    assert bw(*bargs(two, 2, g=None)) == -1
+    assert bw(*bargs(bad_chain, 2)) == -2
+    assert bw(*bargs(two, 2, wsb=4096)) == -4
+    assert bw(*bargs(two, 2, ws=None)) == -4
+    gr[1].dWv = FAKE + 2
+    assert bw(*bargs(two, 2)) == -6                                                     # misaligned gradient
+
+
 def test_workspace_bytes(lib):
     w0 = dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 128, 1, 1, 128, 4, [4], 0)
     w1 = dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 32, 64, 4, 128, 4, [4, 2], 1)
     assert w0 > 0 and w1 > w0 and w0 % 256 == 0 and w1 % 256 == 0
     assert dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 32, 64, 4, 128, 4, [4, 1], 1) == 0   # bad chain
     assert dchag.dchag_workspace_bytes(5, 1, 8, 32, 64, 4, 128, 4, [4, 2], 1) == 0
+    w2 = dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 32, 64, 4, 128, 4, [4, 2], 2)
+    w3 = dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 32, 64, 4, 128, 4, [4, 2], 3)
+    assert w2 > 0 and w3 > w2 and w2 % 256 == 0 and w3 % 256 == 0
+    assert dchag.dchag_workspace_bytes(dchag.DCHAG_F32, 1, 8, 32, 64, 4, 128, 4, [4, 1], 3) == 0
     # bf16 tensors are half the size of fp32 ones
     b = dchag.dchag_workspace_bytes(dchag.DCHAG_BF16, 4, 512, 128, 128, 8, 1024, 16, [32, 16], 1)
     assert b >= 4 * 512 * 256 * 1024 * 2

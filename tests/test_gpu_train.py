@@ -1,0 +1,240 @@
+"""GPU parity of the weight-folded forward call and of the backward call, through the C ABI,
+against the fp64 CPU oracle on the same seeded inputs.
+
+Error measure, per tensor (output or gradient): max_i |y_i - y^_i| / max_i |y^_i|, below 2e-2 for bf16
+(bf16 storage, fp32 accumulation) and 1e-4 for fp32.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_21411_amd as dchag
+from workloads import ShapeCfg, get_config, make_problem, n_groups, sample_patches
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+ATT = ("query", "Wq", "Wk", "Wv", "Wo", "bq", "bk", "bv", "bo")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a, dtype):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to("cuda").to(TDT[dtype]).contiguous()
+
+
+def dev_level(lv, dtype):
+    return dchag.LevelWeights(lv.group_size, dev(lv.query, dtype), dev(lv.Wq, dtype), dev(lv.Wk, dtype),
+                              dev(lv.Wv, dtype), dev(lv.Wo, dtype), dev(lv.bq, dtype), dev(lv.bk, dtype),
+                              dev(lv.bv, dtype), dev(lv.bo, dtype), kind=1 if lv.kind == "linear" else 0)
+
+
+def host(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def rel_err(got, want):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all()
+    return float(np.abs(got - want).max() / np.abs(want).max())
+
+
+def cfg_of(**kw):
+    base = dict(name="t", dtype="f32", B=2, C=6, H=8, W=12, p=2, D=32, heads=4, group_sizes=(3, 2),
+                x_kind="gauss_mu_sigma", seed=3)
+    base.update(kw)
+    return ShapeCfg(**base)
+
+
+SMALL = [
+    dict(dtype="f32", B=2, C=7, H=8, W=12, p=2, D=32, heads=4, group_sizes=(3, 2, 2)),      # 7 -> 3 -> 2 -> 1
+    dict(dtype="f32", B=1, C=5, H=4, W=4, p=2, D=24, heads=3, group_sizes=(5,)),            # flat single layer
+    dict(dtype="f32", B=1, C=70, H=10, W=14, p=2, D=72, heads=2, group_sizes=(40, 2)),      # groups 40 + 30: two 32-member chunks
+    dict(dtype="f32", B=2, C=7, H=8, W=12, p=2, D=32, heads=4, group_sizes=(3, 3), level_kinds=("linear", "attention")),
+    dict(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3)),     # groups 8, 8, 4
+    dict(dtype="bf16", B=1, C=9, H=24, W=40, p=8, D=512, heads=8, group_sizes=(4, 3)),      # groups 4, 4, 1
+    dict(dtype="bf16", B=1, C=6, H=8, W=8, p=2, D=64, heads=2, group_sizes=(2, 2, 2)),      # three levels
+    dict(dtype="bf16", B=1, C=10, H=80, W=72, p=8, D=320, heads=20, group_sizes=(5, 2)),    # 20 heads (two head passes), N = 90
+    dict(dtype="bf16", B=2, C=12, H=16, W=16, p=4, D=256, heads=2, group_sizes=(3, 2, 2),
+         level_kinds=("linear", "linear", "attention")),
+]
+
+
+# ------------------------------------------------------------------------------------------
+# forward with the value projection behind the weighted sum
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("kw", SMALL)
+def test_forward_folded_matches_oracle(kw):
+    cfg = cfg_of(**kw)
+    say(f"forward_folded {kw}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    out = dchag.dchag_forward_folded(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
+                                     [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[d]
+
+
+def test_forward_folded_without_biases_and_sharp_softmax():
+    cfg = get_config("tiny")
+    pr = make_problem(cfg, biases=False, query_scale=30.0)
+    out = dchag.dchag_forward_folded(dev(pr.x, "f32"), dev(pr.We, "f32"), None, dev(pr.ce, "f32"),
+                                     [dev_level(lv, "f32") for lv in pr.levels], cfg.p, cfg.heads)
+    want = oracle.forward(pr.x, pr.We, None, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    assert rel_err(host(out), want) < TOL["f32"]
+
+
+# ------------------------------------------------------------------------------------------
+# backward
+# ------------------------------------------------------------------------------------------
+def run_backward(pr, dout_img, want_dx=True):
+    """dout_img [B, N, D] float; returns (dx, dWe, dtok_bias, [LevelGrads]) as device tensors."""
+    cfg = pr.cfg
+    d = cfg.dtype
+    tdt = TDT[d]
+    lv_dev = [dev_level(lv, d) for lv in pr.levels]
+    grads = []
+    for lv in lv_dev:
+        if lv.kind == 1:
+            grads.append(dchag.LevelGrads(dWv=torch.full_like(lv.Wv, 7.0),
+                                          dbv=None if lv.bv is None else torch.full_like(lv.bv, 7.0)))
+        else:
+            kw = {}
+            for n in ATT:
+                w = getattr(lv, n)
+                kw["d" + n] = torch.full_like(w if w is not None else lv.query, 7.0)     # 7: must be overwritten
+            grads.append(dchag.LevelGrads(**kw))
+    x = dev(pr.x, d)
+    dx = torch.full_like(x, 7.0) if want_dx else None
+    dWe = torch.full((cfg.C, cfg.D, cfg.p * cfg.p), 7.0, dtype=tdt, device="cuda")
+    dtb = torch.full((cfg.C, cfg.D), 7.0, dtype=tdt, device="cuda")
+    dchag.dchag_backward(x, dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d), lv_dev, cfg.p, cfg.heads,
+                         dev(dout_img, d), grads, dx=dx, dWe=dWe, dtok_bias=dtb)
+    torch.cuda.synchronize()
+    return dx, dWe, dtb, grads
+
+
+def image_of_patches(dxp, cfg, bs, ns):
+    """[S, C, p*p] patch gradients of the sampled patches -> [B, C, H, W] image (zero elsewhere)."""
+    p = cfg.p
+    img = np.zeros((cfg.B, cfg.C, cfg.H, cfg.W))
+    pw = cfg.W // p
+    for i, (b, n) in enumerate(zip(bs, ns)):
+        r, c = (n // pw) * p, (n % pw) * p
+        img[b, :, r:r + p, c:c + p] = dxp[i].reshape(cfg.C, p, p)
+    return img
+
+
+def compare_grads(cfg, pr, got, want, tol, bs, ns):
+    dx, dWe, dtb, grads = got
+    errs = {}
+    if dx is not None:
+        errs["dx"] = rel_err(host(dx), image_of_patches(want["dx"], cfg, bs, ns))
+    errs["dWe"] = rel_err(host(dWe), want["dWe"])
+    errs["dtok_bias"] = rel_err(host(dtb), want["dtok_bias"])
+    for li, lv in enumerate(pr.levels):
+        names = ("Wv", "bv") if lv.kind == "linear" else ATT
+        for n in names:
+            have = host(getattr(grads[li], "d" + n))
+            ref = want["levels"][li]["d" + n]
+            if n == "bk":
+                assert np.abs(have).max() == 0.0                     # the key bias cannot matter
+                continue
+            errs[f"l{li}.d{n}"] = rel_err(have, ref)
+    worst = max(errs, key=errs.get)
+    say("  " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+    assert errs[worst] < tol, (worst, errs[worst])
+
+
+@pytest.mark.parametrize("kw", SMALL)
+def test_backward_matches_oracle(kw):
+    cfg = cfg_of(**kw)
+    say(f"backward {kw}")
+    pr = make_problem(cfg)
+    rng = np.random.Generator(np.random.PCG64(41))
+    dout = rng.standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32)
+    if cfg.dtype == "bf16":
+        from workloads import round_to_bf16
+        dout = round_to_bf16(dout)
+    got = run_backward(pr, dout)
+    want = oracle.backward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads,
+                           dout.reshape(cfg.B * cfg.N, cfg.D).astype(np.float64))
+    bs = np.repeat(np.arange(cfg.B), cfg.N)
+    ns = np.tile(np.arange(cfg.N), cfg.B)
+    compare_grads(cfg, pr, got, want, TOL[cfg.dtype], bs, ns)
+
+
+def test_backward_skips_gradients_that_are_not_asked_for():
+    cfg = cfg_of(dtype="f32", B=1, C=6, H=8, W=8, p=2, D=32, heads=4, group_sizes=(3, 2))
+    pr = make_problem(cfg)
+    d = "f32"
+    dout = np.random.Generator(np.random.PCG64(5)).standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32)
+    lv_dev = [dev_level(lv, d) for lv in pr.levels]
+    grads = [dchag.LevelGrads(dWv=torch.zeros_like(lv.Wv)) for lv in lv_dev]
+    dchag.dchag_backward(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d), lv_dev, cfg.p, cfg.heads,
+                         dev(dout, d), grads)
+    torch.cuda.synchronize()
+    want = oracle.backward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads,
+                           dout.reshape(-1, cfg.D).astype(np.float64), want_dx=False)
+    for li in range(2):
+        assert rel_err(host(grads[li].dWv), want["levels"][li]["dWv"]) < TOL[d]
+
+
+def test_backward_is_deterministic():
+    cfg = cfg_of(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3))
+    pr = make_problem(cfg)
+    dout = np.random.Generator(np.random.PCG64(6)).standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32)
+    a = run_backward(pr, dout)
+    b = run_backward(pr, dout)
+    assert torch.equal(a[1], b[1]) and torch.equal(a[0], b[0])
+    assert torch.equal(a[3][0].dWk, b[3][0].dWk) and torch.equal(a[3][1].dWv, b[3][1].dWv)
+
+
+@pytest.mark.parametrize("name,per_batch", [("weather", 4), ("hyperspectral", 3)])
+def test_backward_full_size_with_upstream_gradient_on_sampled_patches(name, per_batch):
+    """Full-size configurations in the launch configuration of the benchmark.  The upstream gradient is
+    non-zero on a seeded sample of patches only; the path is independent per patch, so every other patch
+    contributes exactly nothing and the oracle only has to visit the sample."""
+    cfg = get_config(name)
+    say(f"backward full-size {name}: generating inputs")
+    pr = make_problem(cfg)
+    bs, ns = sample_patches(cfg.B, cfg.N, per_batch, seed=19)
+    rng = np.random.Generator(np.random.PCG64(43))
+    from workloads import round_to_bf16
+    ds = round_to_bf16(rng.standard_normal((bs.size, cfg.D)).astype(np.float32))
+    dout = np.zeros((cfg.B, cfg.N, cfg.D), dtype=np.float32)
+    dout[bs, ns] = ds
+    say(f"backward full-size {name}: GPU")
+    got = run_backward(pr, dout)
+    say(f"backward full-size {name}: oracle on {bs.size} patches")
+    want = oracle.backward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, ds.astype(np.float64),
+                           sample=(bs, ns))
+    compare_grads(cfg, pr, got, want, TOL[cfg.dtype], bs, ns)
+
+
+def test_backward_full_size_output_bias_gradient_is_the_sum_of_the_upstream_gradient():
+    """A property that holds at any size, with a dense upstream gradient: the last level's output-bias
+    gradient is the plain sum of dout over all patches."""
+    cfg = get_config("weather")
+    pr = make_problem(cfg)
+    rng = np.random.Generator(np.random.PCG64(44))
+    dout = rng.standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32)
+    got = run_backward(pr, dout, want_dx=False)
+    from workloads import round_to_bf16
+    want = round_to_bf16(dout).astype(np.float64).sum(axis=(0, 1))
+    assert rel_err(host(got[3][-1].dbo)[0], want) < TOL["bf16"]
+    for g in got[3]:
+        for n in ("dWq", "dWk", "dWv", "dWo", "dquery"):
+            assert torch.isfinite(getattr(g, n).float()).all()
