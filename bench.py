@@ -34,6 +34,9 @@ def stage_model(cfg, levels_in, stage, level):
     if stage == "tokenize":
         by = B * cfg.C * cfg.H * cfg.W * es + cfg.C * D * cfg.p * cfg.p * es + B * cfg.C * N * D * es
         return "hbm", by
+    if stage == "bwd_tokenize":
+        # token gradients read for dWe and again for dx; pixels in, pixel gradients out, weights in and out
+        return "hbm", (2 * B * cfg.C * N * D + 2 * B * cfg.C * cfg.H * cfg.W + 2 * cfg.C * D * cfg.p * cfg.p) * es
     cin = levels_in[level - 1]
     g = cfg.group_sizes[level - 1]
     G = (cin + g - 1) // g
@@ -58,6 +61,22 @@ def stage_model(cfg, levels_in, stage, level):
         return "hbm", tok * D * es + tok * h * 4 + B * G * N * D * es
     if stage in ("query", "fold"):
         return "hbm", G * D * D * es
+    # weight-folded forward and backward: u / w are the per-head tensors [B,G,N,h,D]
+    uw = B * G * N * h * D * es
+    if stage == "head_sums":
+        return "hbm", tok * D * es + tok * h * 4 + uw
+    if stage == "head_vproj":
+        return "mfma", 2.0 * B * G * N * D * D
+    if stage in ("bwd_oproj", "bwd_value"):
+        return "mfma", 4.0 * B * G * N * D * D
+    if stage == "bwd_softmax":
+        return "hbm", tok * D * es + uw + 3 * tok * h * 4
+    if stage == "bwd_tokens":
+        return "hbm", uw + tok * D * es + 2 * tok * h * 4
+    if stage == "bwd_key_query":
+        return "hbm", tok * D * es + tok * h * 4 + 3 * G * D * D * es
+    if stage == "bwd_channel_mix":
+        return "hbm", (2 * tok * D + 2 * B * G * N * D + 2 * G * g * D) * es
     return "hbm", 0.0
 
 
@@ -67,6 +86,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="hyperspectral")
+    ap.add_argument("--mode", default="forward", choices=["forward", "folded", "backward"],
+                    help="what one step is: dchag_forward (the headline), dchag_forward_folded, or dchag_backward")
     ap.add_argument("--cpu-patches", type=int, default=64, help="patches the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-other", action="store_true", help="skip the short weather-like side measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -101,16 +122,44 @@ def main() -> int:
                                      dev(lv.bq), dev(lv.bk), dev(lv.bv), dev(lv.bo),
                                      kind=1 if lv.kind == "linear" else 0) for lv in pr.levels]
         dt = dchag.DCHAG_F32 if cfg.dtype == "f32" else dchag.DCHAG_BF16
-        wsb = dchag.dchag_workspace_bytes(dt, cfg.B, cfg.C, cfg.H, cfg.W, cfg.p, cfg.D, cfg.heads,
-                                          list(cfg.group_sizes), 1)
+        wsb = max(dchag.dchag_workspace_bytes(dt, cfg.B, cfg.C, cfg.H, cfg.W, cfg.p, cfg.D, cfg.heads,
+                                              list(cfg.group_sizes), which) for which in (1, 2))
         ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
         out = torch.empty((cfg.B, cfg.N, cfg.D), dtype=tdt, device="cuda")
         t = (dev(pr.x), dev(pr.We), dev(pr.be), dev(pr.ce), levels, ws, out)
         return pr, t
 
+    def prepare_backward(cfg, t):
+        """Gradient buffers, a seeded upstream gradient and the workspace of dchag_backward."""
+        x, We, be, ce, levels, _, out = t
+        grads = []
+        for lv in levels:
+            if lv.kind == 1:
+                grads.append(dchag.LevelGrads(dWv=torch.empty_like(lv.Wv), dbv=torch.empty_like(lv.bv)))
+            else:
+                grads.append(dchag.LevelGrads(**{"d" + n: torch.empty_like(getattr(lv, n)) for n in
+                                                 ("query", "Wq", "Wk", "Wv", "Wo", "bq", "bk", "bv", "bo")}))
+        g = torch.Generator(device="cuda")
+        g.manual_seed(7)
+        dout = torch.randn(out.shape, generator=g, device="cuda", dtype=torch.float32).to(out.dtype)
+        dt = dchag.DCHAG_F32 if cfg.dtype == "f32" else dchag.DCHAG_BF16
+        wsb = dchag.dchag_workspace_bytes(dt, cfg.B, cfg.C, cfg.H, cfg.W, cfg.p, cfg.D, cfg.heads,
+                                          list(cfg.group_sizes), 3)
+        return {"grads": grads, "dout": dout, "dx": torch.empty_like(x), "dWe": torch.empty_like(We),
+                "dtb": torch.empty_like(ce), "ws": torch.empty(wsb, dtype=torch.uint8, device="cuda")}
+
+    mode = {"name": args.mode, "bwd": None}
+
     def step(cfg, t):
         x, We, be, ce, levels, ws, out = t
-        dchag.dchag_forward(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
+        if mode["name"] == "forward":
+            dchag.dchag_forward(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
+        elif mode["name"] == "folded":
+            dchag.dchag_forward_folded(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
+        else:
+            bw = mode["bwd"]
+            dchag.dchag_backward(x, We, be, ce, levels, cfg.p, cfg.heads, bw["dout"], bw["grads"], dx=bw["dx"],
+                                 dWe=bw["dWe"], dtok_bias=bw["dtb"], workspace=bw["ws"])
 
     def timed(cfg, t, warmup, steps, profile):
         for _ in range(warmup):
@@ -131,6 +180,8 @@ def main() -> int:
 
     cfg = get_config(args.workload)
     pr, t = prepare(cfg)
+    if args.mode == "backward":
+        mode["bwd"] = prepare_backward(cfg, t)
     # untimed-stage pass first (value), then the same steps again with per-launch events (roofline)
     ms_plain, wall_plain, _ = timed(cfg, t, args.warmup, args.steps, profile=False)
     ms_prof, _, recs = timed(cfg, t, 1, args.steps, profile=True)
@@ -155,12 +206,12 @@ def main() -> int:
     stages = []
     for (name, level), (tot, cnt) in agg.items():
         bound, amount = stage_model(cfg, lv_in, name, level)
-        avg = tot / cnt
+        avg = tot / args.steps                       # per step: a stage may take several launches
         if bound == "mfma":
             ach, peak, unit = amount / (avg * 1e-3) / 1e12, PEAK["mfma_bf16_tflops"] if cfg.dtype == "bf16" else PEAK["fp32_tflops"], "TFLOP/s"
         else:
             ach, peak, unit = amount / (avg * 1e-3) / 1e9, PEAK["hbm_gbs"], "GB/s"
-        stages.append({"stage": name, "level": level, "avg_ms": round(avg, 5), "launches": cnt, "bound": bound,
+        stages.append({"stage": name, "level": level, "avg_ms": round(avg, 5), "launches": cnt // args.steps, "bound": bound,
                        "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
     stages.sort(key=lambda s: -s["avg_ms"])
     dom = stages[0] if stages else None
@@ -173,7 +224,7 @@ def main() -> int:
 
     # the CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
     cpu = None
-    if args.cpu_patches > 0:
+    if args.cpu_patches > 0 and args.mode != "backward":
         import oracle
         per_b = max(1, args.cpu_patches // cfg.B)
         bs, ns = sample_patches(cfg.B, cfg.N, per_b, seed=23)
@@ -189,7 +240,7 @@ def main() -> int:
     # the staged entry points on the same workload: dchag_tokenize, then dchag_aggregate_level on level 1
     # with its tokens coming from HBM (its score kernel is the HBM-bound aggregation stage)
     staged = None
-    if not args.no_other and pr.levels[0].kind == "attention":
+    if not args.no_other and pr.levels[0].kind == "attention" and args.mode == "forward":
         x, We, be, ce, levels, ws, out = t
         tok = dchag.dchag_tokenize(x, We, be, ce, cfg.p)
         lvl_out = dchag.dchag_aggregate_level(tok, levels[0], cfg.heads)
@@ -215,7 +266,18 @@ def main() -> int:
         del tok, lvl_out
 
     other = []
-    if not args.no_other and args.workload == "hyperspectral":
+    if not args.no_other and args.workload == "hyperspectral" and args.mode == "forward":
+        # the same workload through the other two calls (their own stage tables come with --mode)
+        mode["name"] = "folded"
+        msf, _, _ = timed(cfg, t, 3, 10, profile=False)
+        other.append({"workload": "hyperspectral", "call": "dchag_forward_folded", "tokens": cfg.tokens,
+                      "ms_per_step": round(msf, 4), "value": cfg.tokens / (msf * 1e-3), "unit": "tokens/s"})
+        mode["name"], mode["bwd"] = "backward", prepare_backward(cfg, t)
+        msb, _, _ = timed(cfg, t, 2, 5, profile=False)
+        other.append({"workload": "hyperspectral", "call": "dchag_backward (recomputes the forward)",
+                      "tokens": cfg.tokens, "ms_per_step": round(msb, 4), "value": cfg.tokens / (msb * 1e-3),
+                      "unit": "tokens/s"})
+        mode["name"], mode["bwd"] = "forward", None
         del t
         torch.cuda.empty_cache()
         c2 = get_config("weather")
@@ -233,11 +295,14 @@ def main() -> int:
                       "value": c3.tokens / (ms3 * 1e-3), "unit": "tokens/s"})
 
     line = {
-        "metric": "aggregated channel-patch tokens/sec (B*C*N) through tokenize + hierarchical aggregation, forward",
+        "metric": "aggregated channel-patch tokens/sec (B*C*N) through tokenize + hierarchical aggregation, "
+                  + {"forward": "forward", "folded": "forward (value projection behind the weighted sum)",
+                     "backward": "backward (with forward recomputation)"}[args.mode],
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "patch": cfg.p, "N": cfg.N,
+        "config": {"workload": cfg.name, "call": {"forward": "dchag_forward", "folded": "dchag_forward_folded",
+                                                  "backward": "dchag_backward"}[args.mode], "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "patch": cfg.p, "N": cfg.N,
                    "D": cfg.D, "heads": cfg.heads, "group_sizes": list(cfg.group_sizes),
                    "level_kinds": list(cfg.level_kinds or ["attention"] * len(cfg.group_sizes)),
                    "tokens_per_step": tokens},

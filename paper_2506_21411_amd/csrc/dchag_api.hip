@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <vector>
 
 #include "dchag_dev.h"
@@ -331,20 +332,21 @@ struct PixelScores {
   bf16* Msb;
 };
 
-// One aggregation level on the bf16 MFMA path: weight-only prep, scores (MFMA on the tokens, or
-// from the pixels at the first level of a forward call), softmax over the group, value projection
-// fused with the weighted sum over the group, output projection.
-int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, bf16* zout,
-                   unsigned char* ws, hipStream_t st, const PixelScores* px = nullptr) {
+// The first level's scores can come from the pixels when the compose kernel (4 x 4 output tiles, at most 4 per
+// lane) and the pixel-score kernel (one 32-wide MFMA column block of heads, 8-pixel operand chunks) tile the shape.
+bool pixel_scores_ok(int p, int heads) {
+  const int pp = p * p;
+  return heads % 4 == 0 && heads <= 32 && pp % 16 == 0 && (p == 4 || p % 8 == 0) && (heads / 4) * (pp / 4) <= 256 &&
+         pp <= 256 && !getenv("DCHAG_TOKEN_SCORES");
+}
+
+// Weight-only prep, scores and softmax of one level on the bf16 MFMA path: leaves the projected query in
+// Qp, the folded keys in Mf / Mb and the softmax weights in alpha, laid out [B][G][gpad][heads][Np].
+int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, float* Qp, float* Mf,
+                bf16* Mb, float* alpha, hipStream_t st, const PixelScores* px) {
   const int g = lv->group_size;
   const int G = groups_of(Cin, g);
   const int gpad = round_up(g, 8), Np = round_up(N, 32);
-  const LevelWs w = level_ws(DCHAG_BF16, B, Cin, N, D, heads, g);
-  float* Qp = reinterpret_cast<float*>(ws + w.qp);
-  float* Mf = reinterpret_cast<float*>(ws + w.mf);
-  bf16* Mb = reinterpret_cast<bf16*>(ws + w.mb);
-  float* alpha = reinterpret_cast<float*>(ws + w.alpha);
-  bf16* O = reinterpret_cast<bf16*>(ws + w.o);
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_QUERY, st);
@@ -424,6 +426,24 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     if ((rc = launch_status())) return rc;
     }
   }
+  return DCHAG_OK;
+}
+
+// One aggregation level on the bf16 MFMA path: weight-only prep, scores (MFMA on the tokens, or
+// from the pixels at the first level of a forward call), softmax over the group, value projection
+// fused with the weighted sum over the group, output projection.
+int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, bf16* zout,
+                   unsigned char* ws, hipStream_t st, const PixelScores* px = nullptr) {
+  const int g = lv->group_size;
+  const int G = groups_of(Cin, g);
+  const int gpad = round_up(g, 8), Np = round_up(N, 32);
+  const LevelWs w = level_ws(DCHAG_BF16, B, Cin, N, D, heads, g);
+  float* alpha = reinterpret_cast<float*>(ws + w.alpha);
+  bf16* O = reinterpret_cast<bf16*>(ws + w.o);
+  int rc;
+  if ((rc = fast_scores(B, Cin, N, D, heads, lv, zin, reinterpret_cast<float*>(ws + w.qp),
+                        reinterpret_cast<float*>(ws + w.mf), reinterpret_cast<bf16*>(ws + w.mb), alpha, st, px)))
+    return rc;
   {
     StageTimer tm(DCHAG_STAGE_FUSED_VAGG, st);
     TileWork tw;
@@ -556,7 +576,7 @@ size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, 
   if (which == 0) return level_ws(dt, B, C, N, D, heads, group_sizes[0]).total;
   if (which == 1) return forward_ws(dt, B, C, N, p * p, D, heads, n_levels, group_sizes).total;
   if (n_levels > 16) return 0;
-  if (which == 2) return folded_ws(dt, B, C, N, D, heads, n_levels, group_sizes).total;
+  if (which == 2) return folded_ws(dt, B, C, N, p * p, D, heads, n_levels, group_sizes).total;
   if (which == 3) return backward_ws(dt, B, C, N, p * p, D, heads, n_levels, group_sizes, nullptr).total;
   return 0;
 }
@@ -686,11 +706,7 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
                      static_cast<const bf16*>(ce), H, W, p, reinterpret_cast<float*>(ws + w.ms),
                      reinterpret_cast<float*>(ws + w.cs), reinterpret_cast<float*>(ws + w.mft),
                      reinterpret_cast<bf16*>(ws + w.msb)};
-      // the pixel shortcut: 4 x 4 output tiles (at most 4 per lane) in the compose kernel, one 32-wide MFMA
-      // column block of heads and 8-pixel operand chunks in the score kernel
-      const int pp = p * p;
-      const bool use_px = (l == 0) && heads % 4 == 0 && heads <= 32 && pp % 16 == 0 && (p == 4 || p % 8 == 0) &&
-                          (heads / 4) * (pp / 4) <= 256 && pp <= 256 && !getenv("DCHAG_TOKEN_SCORES");
+      const bool use_px = (l == 0) && pixel_scores_ok(p, heads);
       rc = run_level_fast(B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
                           static_cast<bf16*>(zout), ws + w.level, st, use_px ? &px : nullptr);
     }
@@ -736,7 +752,7 @@ int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int 
   if (!out) return DCHAG_ERR_NULL;
   if (misaligned(out)) return DCHAG_ERR_ALIGN;
   const int N = (H / p) * (W / p);
-  const FoldedWs w = folded_ws(dt, B, C, N, D, heads, n_levels, gs);
+  const FoldedWs w = folded_ws(dt, B, C, N, p * p, D, heads, n_levels, gs);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
       workspace_bytes < w.total)
     return DCHAG_ERR_WORKSPACE;

@@ -9,8 +9,13 @@
 
 // Per-level pieces that a forward sweep leaves behind for the reverse sweep.
 struct KeptLevel {
-  size_t qp, mf, alpha, u, o, y, total;
+  size_t qp, mf, mb, alpha_f, alpha, u, o, y, total;
 };
+
+// The bf16 kernels of this file keep one fp32 value per head and lane: 16 heads at most.
+inline bool train_fast(dchag_dtype dt, int D, int heads) {
+  return fast_level(dt, D, heads) && heads <= 16 && !getenv("DCHAG_GENERIC_LEVEL");
+}
 
 inline KeptLevel kept_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g, bool linear,
                             bool keep_y) {
@@ -21,6 +26,10 @@ inline KeptLevel kept_level(dchag_dtype dt, int B, int Cin, int N, int D, int he
   if (!linear) {
     w.qp = off; off += align_up((size_t)G * D * 4);
     w.mf = off; off += align_up((size_t)G * heads * D * 4);
+    w.mb = off; off += align_up((size_t)G * heads * D * 2);
+    if (train_fast(dt, D, heads)) {
+      w.alpha_f = off; off += align_up((size_t)B * G * round_up(g, 8) * heads * round_up(N, 32) * 4);
+    }
     w.alpha = off; off += align_up((size_t)B * Cin * N * heads * 4);
     w.u = off; off += align_up((size_t)B * G * N * heads * D * es);
     w.o = off; off += align_up((size_t)B * G * N * D * es);
@@ -32,10 +41,21 @@ inline KeptLevel kept_level(dchag_dtype dt, int B, int Cin, int N, int D, int he
 }
 
 struct FoldedWs {
-  size_t tokens, ping, pong, level, total;
+  size_t tokens, ping, pong, level, ms, msb, cs, mft, total;
 };
 
-inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int D, int heads, int n_levels,
+// Scratch of the first level's pixel-score shortcut (composed score weights, fp32 and bf16; constants;
+// transposed folded keys).
+inline size_t pixel_scratch(size_t off, int C, int pp, int D, int heads, int G0, size_t* ms, size_t* msb, size_t* cs,
+                            size_t* mft) {
+  *ms = off; off += align_up((size_t)C * heads * pp * 4);
+  *msb = off; off += align_up((size_t)C * heads * pp * 2);
+  *cs = off; off += align_up((size_t)C * heads * 4);
+  *mft = off; off += align_up((size_t)G0 * D * heads * 4);
+  return off;
+}
+
+inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int heads, int n_levels,
                           const int32_t* group_sizes) {
   FoldedWs w{};
   const size_t es = elem_size(dt);
@@ -58,12 +78,13 @@ inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int D, int heads,
   w.ping = off; off += inter_max;
   w.pong = off; off += inter_max;
   w.level = off; off += lvl_max;
+  off = pixel_scratch(off, C, pp, D, heads, groups_of(C, group_sizes[0]), &w.ms, &w.msb, &w.cs, &w.mft);
   w.total = off;
   return w;
 }
 
 struct BackwardWs {
-  size_t tokens, patches, kept[16], dz[2], dalpha, w, d_o, r, dq, total;
+  size_t tokens, patches, kept[16], dz[2], dalpha, w, d_o, r, dq, rpart, ms, msb, cs, mft, total;
 };
 
 inline BackwardWs backward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int heads, int n_levels,
@@ -74,7 +95,7 @@ inline BackwardWs backward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D
   w.tokens = off; off += align_up((size_t)B * C * N * D * es);
   w.patches = off; off += align_up((size_t)B * C * N * pp * es);
   int c_in = C;
-  size_t dal = 0, wv = 0, dov = 0, rv = 0, dqv = 0, dz0 = 0, dz1 = 0;
+  size_t dal = 0, wv = 0, dov = 0, rv = 0, dqv = 0, dz0 = 0, dz1 = 0, rp = 0;
   for (int l = 0; l < n_levels; ++l) {
     const int g = group_sizes[l];
     if (g < 1) return BackwardWs{};
@@ -90,6 +111,7 @@ inline BackwardWs backward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D
       dov = std::max(dov, align_up((size_t)B * G * N * D * es));
       rv = std::max(rv, align_up((size_t)G * heads * D * 4));
       dqv = std::max(dqv, align_up((size_t)G * D * 4));
+      rp = std::max(rp, align_up((size_t)B * G * ((N + kDzPatches - 1) / kDzPatches) * heads * D * 4));
     }
     c_in = G;
   }
@@ -101,6 +123,8 @@ inline BackwardWs backward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D
   w.d_o = off; off += dov;
   w.r = off; off += rv;
   w.dq = off; off += dqv;
+  w.rpart = off; off += rp;
+  off = pixel_scratch(off, C, pp, D, heads, groups_of(C, group_sizes[0]), &w.ms, &w.msb, &w.cs, &w.mft);
   w.total = off;
   return w;
 }
@@ -114,40 +138,147 @@ int launch_gemm(const GemmDesc& d, const TA* A, const TB* Bm, const TB* bias, TC
   return launch_status();
 }
 
-// One attention level evaluated as  alpha -> u -> o -> y  (y skipped when zout is NULL).
+// bf16 products go to the MFMA kernel when it tiles them: K a multiple of 64 and not ragged, each operand with
+// one unit stride, every other stride and offset a multiple of 8 elements (16-byte rows).
+inline bool mult8(long v) { return (v & 7) == 0; }
+inline bool gemm_mfma_ok(const GemmDesc& d) {
+  if (d.K % 64 || d.ragged == 2 || getenv("DCHAG_GEMM_GENERIC")) return false;
+  const bool at = d.A.s1 != 1, bt = d.Bm.s0 != 1;
+  if (at && (d.A.s0 != 1 || d.M % 8 || d.M < 8 || d.ragged)) return false;
+  if (bt && (d.Bm.s1 != 1 || d.N % 8 || d.N < 8)) return false;
+  return mult8(d.A.sb) && mult8(d.A.sk) && mult8(d.A.sa) && mult8(at ? d.A.s1 : d.A.s0) && mult8(d.Bm.sb) &&
+         mult8(d.Bm.sk) && mult8(d.Bm.sa) && mult8(bt ? d.Bm.s0 : d.Bm.s1);
+}
+
+template <typename TC>
+int launch_gemm_bf16(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st) {
+  if (!gemm_mfma_ok(d)) return launch_gemm<bf16, bf16, TC>(d, A, Bm, bias, C, st);
+  const long batch = (long)(d.reduce_b ? 1 : d.nb) * d.nk * d.na;
+  const long mt = (d.M + 127) / 128;
+  if (batch > 65535 || mt > 65535 || d.M < 1 || d.N < 1) return DCHAG_ERR_SHAPE;
+  const bool at = d.A.s1 != 1, bt = d.Bm.s0 != 1;
+  auto kern = at ? (bt ? k_gemm_mfma<true, true, TC> : k_gemm_mfma<true, false, TC>)
+                 : (bt ? k_gemm_mfma<false, true, TC> : k_gemm_mfma<false, false, TC>);
+  constexpr int lds = 2 * 256 * 128;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+      hipSuccess)
+    return DCHAG_ERR_LAUNCH;
+  kern<<<dim3((d.N + 127) / 128, (unsigned)mt, (unsigned)batch), 256, lds, st>>>(d, A, Bm, bias, C);
+  return launch_status();
+}
+
+// Same-type products of the level kernels: MFMA for bf16 where it tiles, the fp32-FMA kernel otherwise.
+inline int gemm_tt(const GemmDesc& d, const float* A, const float* Bm, const float* bias, float* C, hipStream_t st) {
+  return launch_gemm<float, float, float>(d, A, Bm, bias, C, st);
+}
+inline int gemm_tt(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, bf16* C, hipStream_t st) {
+  return launch_gemm_bf16<bf16>(d, A, Bm, bias, C, st);
+}
+
+// Buffers of one attention level (see KeptLevel); alpha_f and Mb are used by the bf16 kernels only.
 template <typename T>
-int folded_level_forward(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const T* zin, T* zout,
-                         float* Qp, float* Mf, float* alpha, T* u, T* o, hipStream_t st) {
-  const int g = lv->group_size, G = groups_of(Cin, g), dh = D / heads;
-  const T* Wv = static_cast<const T*>(lv->Wv);
+struct LevelBufs {
+  float *Qp, *Mf;
+  bf16* Mb;
+  float *alpha_f, *alpha;
+  T *u, *o;
+};
+
+template <typename T>
+LevelBufs<T> level_bufs(unsigned char* lw, const KeptLevel& kl) {
+  return LevelBufs<T>{reinterpret_cast<float*>(lw + kl.qp),      reinterpret_cast<float*>(lw + kl.mf),
+                      reinterpret_cast<bf16*>(lw + kl.mb),       reinterpret_cast<float*>(lw + kl.alpha_f),
+                      reinterpret_cast<float*>(lw + kl.alpha),   reinterpret_cast<T*>(lw + kl.u),
+                      reinterpret_cast<T*>(lw + kl.o)};
+}
+
+// alpha of one level, token-major [B,Cin,N,heads], on the shape-generic kernels.
+template <typename T>
+int generic_alpha(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const T* zin, const LevelBufs<T>& lb,
+                  hipStream_t st) {
+  const int g = lv->group_size, G = groups_of(Cin, g);
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_QUERY, st);
     k_project_query<T><<<dim3((D + 3) / 4, G), 256, 0, st>>>(D, static_cast<const T*>(lv->query),
                                                              static_cast<const T*>(lv->Wq),
-                                                             static_cast<const T*>(lv->bq), Qp);
+                                                             static_cast<const T*>(lv->bq), lb.Qp);
     if ((rc = launch_status())) return rc;
   }
   {
     StageTimer tm(DCHAG_STAGE_FOLD, st);
     k_fold_query_into_key<T><<<dim3((D + 63) / 64, heads, G), 256, 0, st>>>(D, heads, static_cast<const T*>(lv->Wk),
-                                                                            Qp, Mf, nullptr, nullptr);
+                                                                            lb.Qp, lb.Mf, lb.Mb, nullptr);
     if ((rc = launch_status())) return rc;
   }
-  {
-    StageTimer tm(DCHAG_STAGE_SCORES, st);
-    const long T_total = (long)B * Cin * N;
-    k_scores_generic<T, 8><<<dim3((unsigned)((T_total + 3) / 4)), 256, 0, st>>>(T_total, Cin, N, D, heads, g, zin,
-                                                                               Mf, alpha);
-    if ((rc = launch_status())) return rc;
-    const long total = (long)B * G * N * heads;
-    k_softmax_group<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(Cin, N, heads, g, G, total, alpha);
-    if ((rc = launch_status())) return rc;
+  StageTimer tm(DCHAG_STAGE_SCORES, st);
+  const long T_total = (long)B * Cin * N;
+  k_scores_generic<T, 8><<<dim3((unsigned)((T_total + 3) / 4)), 256, 0, st>>>(T_total, Cin, N, D, heads, g, zin, lb.Mf,
+                                                                             lb.alpha);
+  if ((rc = launch_status())) return rc;
+  const long total = (long)B * G * N * heads;
+  k_softmax_group<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(Cin, N, heads, g, G, total, lb.alpha);
+  return launch_status();
+}
+
+// alpha of one level through the score kernels of the bf16 forward path, then re-laid token-major.
+inline int fast_alpha(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin,
+                      const LevelBufs<bf16>& lb, hipStream_t st, const PixelScores* px) {
+  const int g = lv->group_size, G = groups_of(Cin, g);
+  int rc = fast_scores(B, Cin, N, D, heads, lv, zin, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, px);
+  if (rc) return rc;
+  StageTimer tm(DCHAG_STAGE_SCORES, st);
+  const long total = (long)B * Cin * N * heads;
+  k_alpha_token_major<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(total, Cin, N, heads, g, round_up(g, 8), G,
+                                                                            round_up(N, 32), lb.alpha_f, lb.alpha);
+  return launch_status();
+}
+
+inline int head_sums(int B, int Cin, int N, int D, int heads, int g, const float* alpha, const float* z, float* u,
+                     hipStream_t st) {
+  k_head_sums<float, 16><<<dim3(N, groups_of(Cin, g), B), 256, 0, st>>>(Cin, N, D, heads, g, alpha, z, u);
+  return launch_status();
+}
+inline int head_sums(int B, int Cin, int N, int D, int heads, int g, const float* alpha, const bf16* z, bf16* u,
+                     hipStream_t st) {
+  const size_t lds = (size_t)std::min(g, Cin) * 16 * 4;
+  if (heads <= 16 && D % 4 == 0 && lds <= 160 * 1024 - 4096 && !getenv("DCHAG_GENERIC_LEVEL")) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_sums_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    k_head_sums_bf16<<<dim3(N, groups_of(Cin, g), B), 256, lds, st>>>(Cin, N, D, heads, g, alpha, z, u);
+  } else {
+    k_head_sums<bf16, 16><<<dim3(N, groups_of(Cin, g), B), 256, 0, st>>>(Cin, N, D, heads, g, alpha, z, u);
   }
+  return launch_status();
+}
+
+inline int oproj(int B, int D, RowBlocks rb, const float* o, const float* Wo, const float* bo, float* y, hipStream_t st) {
+  return launch_linear<float>(B, D, rb, o, Wo, bo, y, st);
+}
+inline int oproj(int B, int D, RowBlocks rb, const bf16* o, const bf16* Wo, const bf16* bo, bf16* y, hipStream_t st) {
+  if (D % 256 == 0 && !force_generic()) return launch_linear_dl(B, D, rb, o, Wo, bo, y, st);
+  return launch_linear<bf16>(B, D, rb, o, Wo, bo, y, st);
+}
+
+// One attention level evaluated as  alpha -> u -> o -> y  (y skipped when zout is NULL).  px: the first
+// level of the bf16 path may take its scores from the pixels.
+template <typename T>
+int folded_level_forward(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dchag_level* lv, const T* zin,
+                         T* zout, const LevelBufs<T>& lb, hipStream_t st, const PixelScores* px) {
+  const int g = lv->group_size, G = groups_of(Cin, g), dh = D / heads;
+  const T* Wv = static_cast<const T*>(lv->Wv);
+  int rc;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (train_fast(dt, D, heads)) rc = fast_alpha(B, Cin, N, D, heads, lv, zin, lb, st, px);
+    else rc = generic_alpha<T>(B, Cin, N, D, heads, lv, zin, lb, st);
+  } else {
+    rc = generic_alpha<T>(B, Cin, N, D, heads, lv, zin, lb, st);
+  }
+  if (rc) return rc;
   {
     StageTimer tm(DCHAG_STAGE_HEAD_SUMS, st);
-    k_head_sums<T, 16><<<dim3(N, G, B), 256, 0, st>>>(Cin, N, D, heads, g, alpha, zin, u);
-    if ((rc = launch_status())) return rc;
+    if ((rc = head_sums(B, Cin, N, D, heads, g, lb.alpha, zin, lb.u, st))) return rc;
   }
   {
     StageTimer tm(DCHAG_STAGE_HEAD_VPROJ, st);
@@ -159,12 +290,21 @@ int folded_level_forward(int B, int Cin, int N, int D, int heads, const dchag_le
     d.C = {(long)G * N * D, (long)N * D, (long)dh, (long)D, 1};
     d.bias_sk = D; d.bias_sa = dh;
     d.scale = 1.f;
-    if ((rc = launch_gemm<T, T, T>(d, u, Wv, static_cast<const T*>(lv->bv), o, st))) return rc;
+    if ((rc = gemm_tt(d, lb.u, Wv, static_cast<const T*>(lv->bv), lb.o, st))) return rc;
   }
   if (!zout) return DCHAG_OK;
   StageTimer tm(DCHAG_STAGE_OPROJ, st);
-  RowBlocks rbo{G, G * N, N};
-  return launch_linear<T>(B, D, rbo, o, static_cast<const T*>(lv->Wo), static_cast<const T*>(lv->bo), zout, st);
+  return oproj(B, D, RowBlocks{G, G * N, N}, lb.o, static_cast<const T*>(lv->Wo), static_cast<const T*>(lv->bo), zout,
+               st);
+}
+
+template <typename T>
+PixelScores pixel_scores_of(const void* x, const void* We, const void* be, const void* ce, int H, int W, int p,
+                            unsigned char* ws, size_t ms, size_t msb, size_t cs, size_t mft) {
+  return PixelScores{static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+                     static_cast<const bf16*>(ce), H, W, p, reinterpret_cast<float*>(ws + ms),
+                     reinterpret_cast<float*>(ws + cs), reinterpret_cast<float*>(ws + mft),
+                     reinterpret_cast<bf16*>(ws + msb)};
 }
 
 template <typename T>
@@ -175,6 +315,8 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   g_level = 0;
   int rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st);
   if (rc) return rc;
+  const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
+  const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
   const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
   int c_in = C;
   for (int l = 0; l < n_levels; ++l) {
@@ -184,10 +326,8 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
       rc = run_level_linear<T>(B, c_in, N, D, &levels[l], zin, zout, st);
     else {
       const KeptLevel kl = kept_level(dt, B, c_in, N, D, heads, gs[l], false, false);
-      unsigned char* lw = ws + w.level;
-      rc = folded_level_forward<T>(B, c_in, N, D, heads, &levels[l], zin, zout, reinterpret_cast<float*>(lw + kl.qp),
-                                   reinterpret_cast<float*>(lw + kl.mf), reinterpret_cast<float*>(lw + kl.alpha),
-                                   reinterpret_cast<T*>(lw + kl.u), reinterpret_cast<T*>(lw + kl.o), st);
+      rc = folded_level_forward<T>(dt, B, c_in, N, D, heads, &levels[l], zin, zout, level_bufs<T>(ws + w.level, kl), st,
+                                   (l == 0 && use_px) ? &px : nullptr);
     }
     if (rc) return rc;
     zin = zout;
@@ -202,13 +342,98 @@ int colsum(int B, int D, RowBlocks rb, const T* X, T* out, hipStream_t st) {
   return launch_status();
 }
 
+// d alpha -> ds (softmax Jacobian), token-major.
+inline int softmax_backward(int B, int Cin, int N, int D, int heads, int g, const float* z, const float* w,
+                            const float* alpha, float* ds, hipStream_t st) {
+  const int G = groups_of(Cin, g);
+  const long T_total = (long)B * Cin * N;
+  k_dalpha<float><<<dim3((unsigned)((T_total + 3) / 4)), 256, 0, st>>>(T_total, Cin, N, D, heads, g, G, z, w, ds);
+  int rc = launch_status();
+  if (rc) return rc;
+  const long total = (long)B * G * N * heads;
+  k_softmax_group_backward<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(Cin, N, heads, g, G, total, alpha, ds);
+  return launch_status();
+}
+inline int softmax_backward(int B, int Cin, int N, int D, int heads, int g, const bf16* z, const bf16* w,
+                            const float* alpha, float* ds, hipStream_t st) {
+  const int G = groups_of(Cin, g);
+  const int mt = (std::min(g, Cin) + 15) / 16;
+  if (D % 32 == 0 && mt <= 4 && !getenv("DCHAG_GENERIC_LEVEL")) {
+    const long items = (long)B * G * N;
+    const dim3 grid((unsigned)((items + 3) / 4));
+    if (mt == 1) k_dalpha_softmax_mfma<1><<<grid, 256, 0, st>>>(items, Cin, N, D, heads, g, G, z, w, alpha, ds);
+    else if (mt == 2) k_dalpha_softmax_mfma<2><<<grid, 256, 0, st>>>(items, Cin, N, D, heads, g, G, z, w, alpha, ds);
+    else k_dalpha_softmax_mfma<4><<<grid, 256, 0, st>>>(items, Cin, N, D, heads, g, G, z, w, alpha, ds);
+    return launch_status();
+  }
+  const long T_total = (long)B * Cin * N;
+  k_dalpha<bf16><<<dim3((unsigned)((T_total + 3) / 4)), 256, 0, st>>>(T_total, Cin, N, D, heads, g, G, z, w, ds);
+  int rc = launch_status();
+  if (rc) return rc;
+  const long total = (long)B * G * N * heads;
+  k_softmax_group_backward<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(Cin, N, heads, g, G, total, alpha, ds);
+  return launch_status();
+}
+
+// dz (value and key path) and r[k][a][:] = sum over the group's tokens of ds[., a] z[., :].
+template <typename T>
+int tokens_backward_generic(int B, int Cin, int N, int D, int heads, int g, const T* zin, const T* w, const float* alpha,
+                            const float* ds, const float* Mf, T* dz, float* r, bool want_r, hipStream_t st) {
+  const int G = groups_of(Cin, g);
+  int rc;
+  {
+    StageTimer tm(DCHAG_STAGE_BWD_TOKENS, st);
+    k_dz_attention<T><<<dim3(Cin, N, B), 256, 0, st>>>(Cin, N, D, heads, g, G, alpha, ds, w, Mf, dz);
+    if ((rc = launch_status())) return rc;
+  }
+  if (!want_r) return DCHAG_OK;
+  StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);
+  GemmDesc d{};
+  d.M = heads; d.N = D; d.K = g * N; d.nb = B; d.nk = G; d.na = 1; d.reduce_b = 1;
+  d.ragged = 2; d.ragged_total = Cin * N; d.ragged_nominal = g * N;
+  d.A = {(long)Cin * N * heads, (long)g * N * heads, 0, 1, (long)heads};
+  d.Bm = {(long)Cin * N * D, (long)g * N * D, 0, (long)D, 1};
+  d.C = {0, (long)heads * D, 0, (long)D, 1};
+  d.scale = 1.f;
+  return launch_gemm<float, T, float>(d, ds, zin, nullptr, r, st);
+}
+
+inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const float* zin, const float* w,
+                           const float* alpha, const float* ds, const float* Mf, const bf16*, float* dz, float* r,
+                           float*, bool want_r, hipStream_t st) {
+  return tokens_backward_generic<float>(B, Cin, N, D, heads, g, zin, w, alpha, ds, Mf, dz, r, want_r, st);
+}
+inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const bf16* zin, const bf16* w,
+                           const float* alpha, const float* ds, const float* Mf, const bf16* Mb, bf16* dz, float* r,
+                           float* rpart, bool want_r, hipStream_t st) {
+  const int G = groups_of(Cin, g);
+  const size_t lds = (size_t)2 * kDzPatches * g * 16 * 4;
+  if (heads > 16 || D % 4 || lds > 128 * 1024 || getenv("DCHAG_GENERIC_LEVEL"))
+    return tokens_backward_generic<bf16>(B, Cin, N, D, heads, g, zin, w, alpha, ds, Mf, dz, r, want_r, st);
+  const int n_tiles = (N + kDzPatches - 1) / kDzPatches;
+  int rc;
+  {
+    StageTimer tm(DCHAG_STAGE_BWD_TOKENS, st);
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dz_rpart_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    k_dz_rpart_bf16<<<dim3((unsigned)(n_tiles * ((D + 1023) / 1024)), G, B), 256, lds, st>>>(
+        Cin, N, D, heads, g, n_tiles, alpha, ds, zin, w, Mb, dz, rpart);
+    if ((rc = launch_status())) return rc;
+  }
+  if (!want_r) return DCHAG_OK;
+  StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);
+  const long per = (long)heads * D;
+  k_sum_partials<<<dim3((unsigned)((per + 255) / 256), G), 256, 0, st>>>(B, G, n_tiles, per, rpart, r);
+  return launch_status();
+}
+
 // Reverse of one attention level.  dy is the gradient at the level's output [B,G,N,D]; dz receives the
 // gradient at its input [B,Cin,N,D].
 template <typename T>
 int attention_level_backward(int B, int Cin, int N, int D, int heads, const dchag_level* lv,
-                             const dchag_level_grads* gr, const T* zin, const T* dy, T* dz, const float* Qp,
-                             const float* Mf, const float* alpha, const T* u, const T* o, float* dalpha, T* w,
-                             T* d_o, float* r, float* dQ, hipStream_t st) {
+                             const dchag_level_grads* gr, const T* zin, const T* dy, T* dz, const LevelBufs<T>& lb,
+                             float* dalpha, T* w, T* d_o, float* r, float* dQ, float* rpart, hipStream_t st) {
   const int g = lv->group_size, G = groups_of(Cin, g), dh = D / heads;
   const T* Wv = static_cast<const T*>(lv->Wv);
   const T* Wo = static_cast<const T*>(lv->Wo);
@@ -226,7 +451,7 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
       d.Bm = {sBG, sG, 0, (long)D, 1};
       d.C = {0, (long)D * D, 0, (long)D, 1};
       d.scale = 1.f;
-      if ((rc = launch_gemm<T, T, T>(d, dy, o, nullptr, static_cast<T*>(gr->dWo), st))) return rc;
+      if ((rc = gemm_tt(d, dy, lb.o, nullptr, static_cast<T*>(gr->dWo), st))) return rc;
     }
     GemmDesc d{};                                               // d_o[.., j] = sum_i dy[.., i] Wo[k][i][j]
     d.M = N; d.N = D; d.K = D; d.nb = B; d.nk = G; d.na = 1;
@@ -234,7 +459,7 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
     d.Bm = {0, (long)D * D, 0, (long)D, 1};
     d.C = {sBG, sG, 0, (long)D, 1};
     d.scale = 1.f;
-    if ((rc = launch_gemm<T, T, T>(d, dy, Wo, nullptr, d_o, st))) return rc;
+    if ((rc = gemm_tt(d, dy, Wo, nullptr, d_o, st))) return rc;
   }
   {
     StageTimer tm(DCHAG_STAGE_BWD_VALUE, st);
@@ -246,7 +471,7 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
       d.Bm = {uB, uG, (long)D, (long)heads * D, 1};
       d.C = {0, (long)D * D, (long)dh * D, (long)D, 1};
       d.scale = 1.f;
-      if ((rc = launch_gemm<T, T, T>(d, d_o, u, nullptr, static_cast<T*>(gr->dWv), st))) return rc;
+      if ((rc = gemm_tt(d, d_o, lb.u, nullptr, static_cast<T*>(gr->dWv), st))) return rc;
     }
     GemmDesc d{};                                               // w[.., a, j] = sum_i d_o[.., a*dh+i] Wv[k][a*dh+i][j]
     d.M = N; d.N = D; d.K = dh; d.nb = B; d.nk = G; d.na = heads;
@@ -254,46 +479,28 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
     d.Bm = {0, (long)D * D, (long)dh * D, (long)D, 1};
     d.C = {uB, uG, (long)D, (long)heads * D, 1};
     d.scale = 1.f;
-    if ((rc = launch_gemm<T, T, T>(d, d_o, Wv, nullptr, w, st))) return rc;
+    if ((rc = gemm_tt(d, d_o, Wv, nullptr, w, st))) return rc;
   }
   {
     StageTimer tm(DCHAG_STAGE_BWD_SOFTMAX, st);
-    const long T_total = (long)B * Cin * N;
-    k_dalpha<T><<<dim3((unsigned)((T_total + 3) / 4)), 256, 0, st>>>(T_total, Cin, N, D, heads, g, G, zin, w, dalpha);
-    if ((rc = launch_status())) return rc;
-    const long total = (long)B * G * N * heads;
-    k_softmax_group_backward<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(Cin, N, heads, g, G, total, alpha,
-                                                                                   dalpha);
-    if ((rc = launch_status())) return rc;
+    if ((rc = softmax_backward(B, Cin, N, D, heads, g, zin, w, lb.alpha, dalpha, st))) return rc;
   }
-  {
-    StageTimer tm(DCHAG_STAGE_BWD_TOKENS, st);
-    k_dz_attention<T><<<dim3(Cin, N, B), 256, 0, st>>>(Cin, N, D, heads, g, G, alpha, dalpha, w, Mf, dz);
-    if ((rc = launch_status())) return rc;
-  }
+  const bool want_q = gr->dWq || gr->dbq || gr->dquery;
+  const bool want_r = gr->dWk || want_q;
+  if ((rc = tokens_backward(B, Cin, N, D, heads, g, zin, w, lb.alpha, dalpha, lb.Mf, lb.Mb, dz, r, rpart, want_r, st)))
+    return rc;
   StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);
   if (gr->dbk) {
     const long n = (long)G * D;
     k_fill_zero<T><<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(n, static_cast<T*>(gr->dbk));
     if ((rc = launch_status())) return rc;
   }
-  if (!gr->dWk && !gr->dWq && !gr->dbq && !gr->dquery) return DCHAG_OK;
-  {
-    GemmDesc d{};                                               // r[k][a][j] = sum over the group's tokens of ds[., a] z[., j]
-    d.M = heads; d.N = D; d.K = g * N; d.nb = B; d.nk = G; d.na = 1; d.reduce_b = 1;
-    d.ragged = 2; d.ragged_total = Cin * N; d.ragged_nominal = g * N;
-    d.A = {(long)Cin * N * heads, (long)g * N * heads, 0, 1, (long)heads};
-    d.Bm = {(long)Cin * N * D, (long)g * N * D, 0, (long)D, 1};
-    d.C = {0, (long)heads * D, 0, (long)D, 1};
-    d.scale = 1.f;
-    if ((rc = launch_gemm<float, T, float>(d, dalpha, zin, nullptr, r, st))) return rc;
-  }
   if (gr->dWk) {
-    k_outer_rows<float, T><<<dim3((D + 255) / 256, D, G), 256, 0, st>>>(D, dh, 1.f / sqrtf((float)dh), Qp, r,
+    k_outer_rows<float, T><<<dim3((D + 255) / 256, D, G), 256, 0, st>>>(D, dh, 1.f / sqrtf((float)dh), lb.Qp, r,
                                                                         static_cast<T*>(gr->dWk));
     if ((rc = launch_status())) return rc;
   }
-  if (!gr->dWq && !gr->dbq && !gr->dquery) return DCHAG_OK;
+  if (!want_q) return DCHAG_OK;
   k_query_grad<T><<<dim3((D + 3) / 4, G), 256, 0, st>>>(D, heads, static_cast<const T*>(lv->Wk), r, dQ,
                                                         static_cast<T*>(gr->dbq));
   if ((rc = launch_status())) return rc;
@@ -309,7 +516,6 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
   }
   return DCHAG_OK;
 }
-
 template <typename T>
 int linear_level_backward(int B, int Cin, int N, int D, const dchag_level* lv, const dchag_level_grads* gr,
                           const T* zin, const T* dy, T* dz, hipStream_t st) {
@@ -348,7 +554,7 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
     d.Bm = {(long)C * N * pp, (long)N * pp, 0, (long)pp, 1};
     d.C = {0, (long)D * pp, 0, (long)pp, 1};
     d.scale = 1.f;
-    if ((rc = launch_gemm<T, T, T>(d, dt_, patches, nullptr, dWe, st))) return rc;
+    if ((rc = gemm_tt(d, dt_, patches, nullptr, dWe, st))) return rc;
   }
   if (dx) {
     GemmDesc d{};                                               // dpatch[b,c,n,kk] = sum_d dt[b,c,n,d] We[c][d][kk]
@@ -357,7 +563,7 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
     d.Bm = {0, (long)D * pp, 0, (long)pp, 1};
     d.C = {(long)C * N * pp, (long)N * pp, 0, (long)pp, 1};
     d.scale = 1.f;
-    if ((rc = launch_gemm<T, T, T>(d, dt_, We, nullptr, patches, st))) return rc;
+    if ((rc = gemm_tt(d, dt_, We, nullptr, patches, st))) return rc;
     k_patch_rows<T, true><<<dim3((unsigned)((pixels + 255) / 256)), 256, 0, st>>>(pixels, H, W, p, dx, patches);
     if ((rc = launch_status())) return rc;
   }
@@ -374,6 +580,8 @@ int backward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
   g_level = 0;
   int rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st);
   if (rc) return rc;
+  const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
+  const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
   const T* zins[16];
   KeptLevel kl[16];
   int cins[17];
@@ -388,10 +596,8 @@ int backward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     if (linear)
       rc = run_level_linear<T>(B, cins[l], N, D, &levels[l], zins[l], y, st);
     else
-      rc = folded_level_forward<T>(B, cins[l], N, D, heads, &levels[l], zins[l], y,
-                                   reinterpret_cast<float*>(lw + kl[l].qp), reinterpret_cast<float*>(lw + kl[l].mf),
-                                   reinterpret_cast<float*>(lw + kl[l].alpha), reinterpret_cast<T*>(lw + kl[l].u),
-                                   reinterpret_cast<T*>(lw + kl[l].o), st);
+      rc = folded_level_forward<T>(dt, B, cins[l], N, D, heads, &levels[l], zins[l], y, level_bufs<T>(lw, kl[l]), st,
+                                   (l == 0 && use_px) ? &px : nullptr);
     if (rc) return rc;
     cins[l + 1] = groups_of(cins[l], gs[l]);
     zins[l + 1] = y;
@@ -406,13 +612,10 @@ int backward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
       rc = linear_level_backward<T>(B, cins[l], N, D, &levels[l], &grads[l], zins[l], dy, dz, st);
     else
       rc = attention_level_backward<T>(B, cins[l], N, D, heads, &levels[l], &grads[l], zins[l], dy, dz,
-                                       reinterpret_cast<const float*>(lw + kl[l].qp),
-                                       reinterpret_cast<const float*>(lw + kl[l].mf),
-                                       reinterpret_cast<const float*>(lw + kl[l].alpha),
-                                       reinterpret_cast<const T*>(lw + kl[l].u), reinterpret_cast<const T*>(lw + kl[l].o),
-                                       reinterpret_cast<float*>(ws + w.dalpha), reinterpret_cast<T*>(ws + w.w),
-                                       reinterpret_cast<T*>(ws + w.d_o), reinterpret_cast<float*>(ws + w.r),
-                                       reinterpret_cast<float*>(ws + w.dq), st);
+                                       level_bufs<T>(lw, kl[l]), reinterpret_cast<float*>(ws + w.dalpha),
+                                       reinterpret_cast<T*>(ws + w.w), reinterpret_cast<T*>(ws + w.d_o),
+                                       reinterpret_cast<float*>(ws + w.r), reinterpret_cast<float*>(ws + w.dq),
+                                       reinterpret_cast<float*>(ws + w.rpart), st);
     if (rc) return rc;
     dy = dz;
   }

@@ -10,6 +10,7 @@
 // so the value projection can run once per (group, patch, head) on u instead of once per member.
 #pragma once
 #include "dchag_dev.h"
+#include "k_mfma.h"
 
 namespace dchag {
 
@@ -382,6 +383,428 @@ __global__ __launch_bounds__(256) void k_channel_mix_dw(int B, int Cin, int N, i
   if (wave > 0) part[wave - 1][lane] = acc;
   __syncthreads();
   if (wave == 0 && d < D) dw[(size_t)kc * D + d] = from_f32<T>(acc + part[0][lane] + part[1][lane] + part[2][lane]);
+}
+
+}  // namespace dchag
+
+// =======================================================================================
+// bf16 MFMA kernels of the folded forward and of the backward
+// =======================================================================================
+namespace dchag {
+
+// ---------------------------------------------------------------------------------------
+// Strided batched matrix product on bf16 MFMA (32x32x16, fp32 accumulation), 128x128x64 tiles,
+// four wavefronts (2 x 2), operands staged through XOR-swizzled LDS rows of 64 contraction elements.
+// Same contract as k_gemm_generic (GemmDesc), restricted to:
+//   K % 64 == 0 (no ragged K), every operand has one unit stride, 16-byte aligned rows.
+// An operand whose unit stride is the contraction index is copied chunk by chunk (AT / BT = false);
+// one whose unit stride is its row index m (or n) is read as 8 x 8 blocks (8 contraction steps x 8
+// rows), transposed in registers and written as whole 16-byte LDS chunks (AT / BT = true).
+// grid (ceil(N/128), ceil(M/128), batch), block 256, dynamic LDS 2 x 256 x 128 bytes.
+// ---------------------------------------------------------------------------------------
+template <bool AT, bool BT, typename TC>
+__global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __restrict__ A, const bf16* __restrict__ Bm,
+                                                   const bf16* __restrict__ bias, TC* __restrict__ C) {
+  constexpr int BM = 128, BN = 128;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16x8* As = reinterpret_cast<bf16x8*>(smem);           // [2][BM * 8]
+  bf16x8* Bs = As + 2 * BM * 8;                           // [2][BN * 8]
+  int z = blockIdx.z;
+  const int a = z % d.na;
+  z /= d.na;
+  const int k = z % d.nk;
+  const int b0 = d.reduce_b ? 0 : z / d.nk;
+  const int b1 = d.reduce_b ? d.nb : b0 + 1;
+  int M = d.M;
+  if (d.ragged == 1) {
+    const int left = d.ragged_total - k * d.ragged_nominal;
+    M = left < d.ragged_nominal ? left : d.ragged_nominal;
+  }
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  if (m0 >= M) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lhi = lane >> 5;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // staging registers: 4 chunks per thread (copied operand) or one 8 x 8 block on half of the threads
+  bf16x8 a_reg[AT ? 8 : 4], b_reg[BT ? 8 : 4];
+  const int KT = d.K / 64;
+  const int steps = (b1 - b0) * KT;
+
+  auto load = [&](int s) {
+    const int b = b0 + s / KT, k0 = (s % KT) * 64;
+    const bf16* Ab = A + d.A.sb * b + d.A.sk * k + d.A.sa * a;
+    const bf16* Bb = Bm + d.Bm.sb * b + d.Bm.sk * k + d.Bm.sa * a;
+    if (!AT) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
+        const int gr = min(m0 + row, M - 1);
+        a_reg[i] = *reinterpret_cast<const bf16x8*>(Ab + d.A.s0 * gr + k0 + ch * 8);
+      }
+    } else if (tid < 128) {
+      const int mc = tid & 15, kc = tid >> 4;              // 8 rows m0 + 8 mc .., contraction steps k0 + 8 kc ..
+      const int gm = min(m0 + mc * 8, M - 8);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a_reg[i] = *reinterpret_cast<const bf16x8*>(Ab + d.A.s1 * (k0 + kc * 8 + i) + gm);
+    }
+    if (!BT) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
+        const int gr = min(n0 + row, d.N - 1);
+        b_reg[i] = *reinterpret_cast<const bf16x8*>(Bb + d.Bm.s1 * gr + k0 + ch * 8);
+      }
+    } else if (tid >= 128) {
+      const int t = tid - 128, nc = t & 15, kc = t >> 4;
+      const int gn = min(n0 + nc * 8, d.N - 8);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) b_reg[i] = *reinterpret_cast<const bf16x8*>(Bb + d.Bm.s0 * (k0 + kc * 8 + i) + gn);
+    }
+  };
+  auto store = [&](int buf) {
+    bf16x8* Ad = As + buf * BM * 8;
+    bf16x8* Bd = Bs + buf * BN * 8;
+    if (!AT) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
+        Ad[lds_slot<1>(row, ch)] = a_reg[i];
+      }
+    } else if (tid < 128) {
+      const int mc = tid & 15, kc = tid >> 4;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        bf16x8 v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = a_reg[i][r];
+        Ad[lds_slot<1>(mc * 8 + r, kc)] = v;
+      }
+    }
+    if (!BT) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
+        Bd[lds_slot<1>(row, ch)] = b_reg[i];
+      }
+    } else if (tid >= 128) {
+      const int t = tid - 128, nc = t & 15, kc = t >> 4;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        bf16x8 v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = b_reg[i][r];
+        Bd[lds_slot<1>(nc * 8 + r, kc)] = v;
+      }
+    }
+  };
+
+  load(0);
+  store(0);
+  __syncthreads();
+  for (int s = 0; s < steps; ++s) {
+    const int cur = s & 1;
+    if (s + 1 < steps) load(s + 1);
+    const bf16x8* Ac = As + cur * BM * 8;
+    const bf16x8* Bc = Bs + cur * BN * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[2], bfr[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) af[i] = Ac[lds_slot<1>(wm * 64 + i * 32 + l32, kk * 2 + lhi)];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bfr[j] = Bc[lds_slot<1>(wn * 64 + j * 32 + l32, kk * 2 + lhi)];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (s + 1 < steps) store(cur ^ 1);
+    __syncthreads();
+  }
+
+  // 32x32 accumulator block: lane holds column (lane % 32); register r holds row 8 (r / 4) + 4 (lane / 32) + r % 4
+  TC* Cb = C + d.C.sb * b0 + d.C.sk * k + d.C.sa * a;
+  const bf16* bs = bias ? bias + d.bias_sk * k + d.bias_sa * a : nullptr;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = n0 + wn * 64 + j * 32 + l32;
+    if (n >= d.N) continue;
+    const float bv = bs ? (float)bs[n] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+        if (m < M) Cb[d.C.s0 * m + d.C.s1 * n] = from_f32<TC>(acc[i][j][r] * d.scale + bv);
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Softmax weights from the layout of the forward kernels, alpha_f[b][k][cl][head][n] (pitch Np, gpad
+// members per group), to token-major alpha[b,c,n,head].  One thread per output element.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_alpha_token_major(long total, int Cin, int N, int heads, int g, int gpad,
+                                                           int G, int Np, const float* __restrict__ alpha_f,
+                                                           float* __restrict__ alpha) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;      // ((b * Cin + c) * N + n) * heads + a
+  if (idx >= total) return;
+  const int a = (int)(idx % heads);
+  long t = idx / heads;
+  const int n = (int)(t % N);
+  t /= N;
+  const int c = (int)(t % Cin), b = (int)(t / Cin);
+  const int k = c / g, cl = c % g;
+  alpha[idx] = alpha_f[((((size_t)b * G + k) * gpad + cl) * heads + a) * Np + n];
+}
+
+// ---------------------------------------------------------------------------------------
+// Per-head weighted token sums, bf16, heads <= 16, D % 4 == 0:
+//   u[b,k,n,a,:] = sum_{c in group k} alpha[b,c,n,a] * z[b,c,n,:]
+// grid (N, G, B), block 256: a thread owns 4 adjacent columns (and every 1024th after them) and
+// keeps one fp32 sum per head; the group's weights for this patch sit in LDS.  Bound by the read
+// of z (2 D bytes per token) and the write of u.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_head_sums_bf16(int Cin, int N, int D, int heads, int g,
+                                                        const float* __restrict__ alpha, const bf16* __restrict__ z,
+                                                        bf16* __restrict__ u) {
+  extern __shared__ __attribute__((aligned(16))) float al[];      // [gk][16]
+  const int n = blockIdx.x, k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  for (int idx = threadIdx.x; idx < gk * 16; idx += 256) {
+    const int cl = idx >> 4, a = idx & 15;
+    al[idx] = a < heads ? alpha[(((size_t)b * Cin + c0 + cl) * N + n) * heads + a] : 0.f;
+  }
+  __syncthreads();
+  const size_t cstride = (size_t)N * D;
+  for (int d0 = threadIdx.x * 4; d0 < D; d0 += 1024) {
+    const bf16* zp = z + (((size_t)b * Cin + c0) * N + n) * D + d0;
+    float acc[16][4];
+#pragma unroll
+    for (int a = 0; a < 16; ++a)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[a][e] = 0.f;
+    int cl = 0;
+    for (; cl + 4 <= gk; cl += 4) {
+      bf16x4 zv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) zv[i] = *reinterpret_cast<const bf16x4*>(zp + (size_t)(cl + i) * cstride);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const f32x4* ar = reinterpret_cast<const f32x4*>(al + (cl + i) * 16);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 av = ar[q];
+#pragma unroll
+          for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[q * 4 + a][e] += av[a] * (float)zv[i][e];
+        }
+      }
+    }
+    for (; cl < gk; ++cl) {
+      const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zp + (size_t)cl * cstride);
+#pragma unroll
+      for (int a = 0; a < 16; ++a)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[a][e] += al[cl * 16 + a] * (float)zv[e];
+    }
+    bf16* up = u + ((((size_t)b * G + k) * N + n) * heads) * D + d0;
+#pragma unroll
+    for (int a = 0; a < 16; ++a)
+      if (a < heads) {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[a][e];
+        *reinterpret_cast<bf16x4*>(up + (size_t)a * D) = o;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// d alpha and the softmax Jacobian in one kernel (bf16, D % 32 == 0, group size <= 16 MT):
+//   dalpha[c,a] = w[b,k,n,a,:] . z[b,c,n,:]            (16x16x32 MFMA: 16 members x 16 heads per block)
+//   ds[c,a]     = alpha[c,a] * (dalpha[c,a] - sum_c' alpha[c',a] dalpha[c',a])
+// One wavefront per (b, k, n): its A fragments are 16 member rows of z (64 contiguous bytes per row and
+// step), its B fragments the head rows of w at this patch.  Accumulator block: lane holds head lane % 16,
+// members 4 (lane / 16) + 0..3 of the tile.  grid ceil(B G N / 4), block 256.  Heads beyond 16 take
+// further passes.  ds is written token-major [B,Cin,N,heads] like alpha.
+// ---------------------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(256) void k_dalpha_softmax_mfma(long items, int Cin, int N, int D, int heads, int g,
+                                                             int G, const bf16* __restrict__ z,
+                                                             const bf16* __restrict__ w,
+                                                             const float* __restrict__ alpha,
+                                                             float* __restrict__ ds) {
+  const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);     // (b * G + k) * N + n
+  if (item >= items) return;
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+  const int n = (int)(item % N);
+  const int k = (int)((item / N) % G), b = (int)(item / ((long)N * G));
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  const size_t cstride = (size_t)N * D;
+  const bf16* zb = z + (((size_t)b * Cin + c0) * N + n) * D + lq * 8;
+  for (int a0 = 0; a0 < heads; a0 += 16) {
+    const int head = min(a0 + l16, heads - 1);
+    const bf16* wr = w + ((size_t)item * heads + head) * D + lq * 8;
+    const bf16* zr[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) zr[mt] = zb + (size_t)min(mt * 16 + l16, gk - 1) * cstride;
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < D; t += 128) {                             // four steps of 32 per trip, loads first
+      bf16x8 wf[4], zf[MT][4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int tt = min(t + q * 32, D - 32);
+        wf[q] = *reinterpret_cast<const bf16x8*>(wr + tt);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) zf[mt][q] = *reinterpret_cast<const bf16x8*>(zr[mt] + tt);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (t + q * 32 < D) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf[mt][q], wf[q], acc[mt], 0, 0, 0);
+        }
+    }
+    // softmax Jacobian over the members (registers and the four lane groups of a head)
+    float al[MT][4];
+    float dot = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int cl = mt * 16 + lq * 4 + r;
+        al[mt][r] = (cl < gk && a0 + l16 < heads)
+                        ? alpha[(((size_t)b * Cin + c0 + cl) * N + n) * heads + a0 + l16] : 0.f;
+        dot += al[mt][r] * acc[mt][r];
+      }
+    dot += __shfl_xor(dot, 16, kWave);
+    dot += __shfl_xor(dot, 32, kWave);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int cl = mt * 16 + lq * 4 + r;
+        if (cl < gk && a0 + l16 < heads)
+          ds[(((size_t)b * Cin + c0 + cl) * N + n) * heads + a0 + l16] = al[mt][r] * (acc[mt][r] - dot);
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Gradient at the input tokens and the key-path sums, bf16, heads <= 16, D % 4 == 0:
+//   dz[b,c,n,:]   = sum_a alpha[b,c,n,a] * w[b,k,n,a,:] + ds[b,c,n,a] * M[k][a][:]
+//   rpart[b,k,t][a][:] = sum over the PT patches of tile t and the members c of  ds[b,c,n,a] * z[b,c,n,:]
+// grid (ceil(N/PT) * ceil(D/1024), G, B), block 256: a thread owns 4 adjacent columns, keeps the 16 rows
+// of M and (per patch) of w for them in registers, and walks the members.  The softmax weights and ds of
+// the whole tile sit in LDS (dynamic, 2 * PT * g * 16 floats).  The partial sums are added up in a fixed
+// order by k_sum_partials.
+// ---------------------------------------------------------------------------------------
+constexpr int kDzPatches = 8;
+__global__ __launch_bounds__(256) void k_dz_rpart_bf16(int Cin, int N, int D, int heads, int g, int n_tiles,
+                                                       const float* __restrict__ alpha, const float* __restrict__ ds,
+                                                       const bf16* __restrict__ z, const bf16* __restrict__ w,
+                                                       const bf16* __restrict__ Mb, bf16* __restrict__ dz,
+                                                       float* __restrict__ rpart) {
+  constexpr int PT = kDzPatches;
+  extern __shared__ __attribute__((aligned(16))) float sm[];       // al[PT][gk][16], then dsv[PT][gk][16]
+  const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
+  const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  const int n0 = tile * PT, np = min(PT, N - n0);
+  float* al = sm;
+  float* dsv = sm + PT * g * 16;
+  for (int idx = threadIdx.x; idx < np * gk * 16; idx += 256) {
+    const int a = idx & 15, cl = (idx >> 4) % gk, pi = (idx >> 4) / gk;
+    const size_t src = (((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a;
+    al[(pi * g + cl) * 16 + a] = a < heads ? alpha[src] : 0.f;
+    dsv[(pi * g + cl) * 16 + a] = a < heads ? ds[src] : 0.f;
+  }
+  __syncthreads();
+  const int d0 = cb * 1024 + threadIdx.x * 4;
+  if (d0 >= D) return;
+  float mr[16][4], racc[16][4];
+#pragma unroll
+  for (int a = 0; a < 16; ++a) {
+    bf16x4 mv = {};
+    if (a < heads) mv = *reinterpret_cast<const bf16x4*>(Mb + ((size_t)k * heads + a) * D + d0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      mr[a][e] = (float)mv[e];
+      racc[a][e] = 0.f;
+    }
+  }
+  const size_t cstride = (size_t)N * D;
+  for (int pi = 0; pi < np; ++pi) {
+    const int n = n0 + pi;
+    float wr[16][4];
+    const bf16* wp = w + ((((size_t)b * G + k) * N + n) * heads) * D + d0;
+#pragma unroll
+    for (int a = 0; a < 16; ++a) {
+      bf16x4 wv = {};
+      if (a < heads) wv = *reinterpret_cast<const bf16x4*>(wp + (size_t)a * D);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) wr[a][e] = (float)wv[e];
+    }
+    const bf16* zp = z + (((size_t)b * Cin + c0) * N + n) * D + d0;
+    bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n) * D + d0;
+    bf16x4 znext = *reinterpret_cast<const bf16x4*>(zp);
+    for (int cl = 0; cl < gk; ++cl) {
+      const bf16x4 zv = znext;
+      if (cl + 1 < gk) znext = *reinterpret_cast<const bf16x4*>(zp + (size_t)(cl + 1) * cstride);
+      const f32x4* ar = reinterpret_cast<const f32x4*>(al + (pi * g + cl) * 16);
+      const f32x4* dr = reinterpret_cast<const f32x4*>(dsv + (pi * g + cl) * 16);
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+      float zf[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) zf[e] = (float)zv[e];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 av = ar[q], dv = dr[q];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[e] += av[a] * wr[q * 4 + a][e] + dv[a] * mr[q * 4 + a][e];
+            racc[q * 4 + a][e] += dv[a] * zf[e];
+          }
+      }
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[e];
+      *reinterpret_cast<bf16x4*>(dzp + (size_t)cl * cstride) = o;
+    }
+  }
+  float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads) * D + d0;
+#pragma unroll
+  for (int a = 0; a < 16; ++a)
+    if (a < heads) *reinterpret_cast<f32x4*>(rp + (size_t)a * D) = f32x4{racc[a][0], racc[a][1], racc[a][2], racc[a][3]};
+}
+
+// r[k][i] = sum_b sum_t rpart[b][k][t][i]   (i over heads * D), fixed order.  One thread per (k, i).
+__global__ __launch_bounds__(256) void k_sum_partials(int B, int G, int n_tiles, long per, const float* __restrict__ rpart,
+                                                      float* __restrict__ r) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  const int k = blockIdx.y;
+  if (i >= per) return;
+  float acc = 0.f;
+  for (int b = 0; b < B; ++b)
+    for (int t = 0; t < n_tiles; ++t) acc += rpart[(((size_t)b * G + k) * n_tiles + t) * per + i];
+  r[(size_t)k * per + i] = acc;
 }
 
 }  // namespace dchag

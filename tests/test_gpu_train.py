@@ -66,6 +66,11 @@ SMALL = [
     dict(dtype="bf16", B=1, C=10, H=80, W=72, p=8, D=320, heads=20, group_sizes=(5, 2)),    # 20 heads (two head passes), N = 90
     dict(dtype="bf16", B=2, C=12, H=16, W=16, p=4, D=256, heads=2, group_sizes=(3, 2, 2),
          level_kinds=("linear", "linear", "attention")),
+    # N = 192 patches (a multiple of 64: the products over patches take the MFMA kernel, 1.5 row tiles of 128),
+    # 16 heads of 16 (not a fast-level shape: generic scores, MFMA products), groups 5 + 5 + 3
+    dict(dtype="bf16", B=2, C=13, H=32, W=96, p=4, D=256, heads=16, group_sizes=(5, 3)),
+    # fast level: D = 512, 16 heads of 32, N = 128, groups of 20 + 20 + 3 (two member tiles, ragged last group)
+    dict(dtype="bf16", B=1, C=43, H=64, W=128, p=8, D=512, heads=16, group_sizes=(20, 3)),
 ]
 
 
@@ -174,6 +179,21 @@ def test_backward_matches_oracle(kw):
     bs = np.repeat(np.arange(cfg.B), cfg.N)
     ns = np.tile(np.arange(cfg.N), cfg.B)
     compare_grads(cfg, pr, got, want, TOL[cfg.dtype], bs, ns)
+
+
+@pytest.mark.parametrize("env", ["DCHAG_GENERIC_LEVEL", "DCHAG_GEMM_GENERIC"])
+def test_backward_generic_bf16_kernels_still_match(monkeypatch, env):
+    """The shape-generic bf16 kernels (taken for shapes the MFMA and streaming kernels do not tile) on a shape
+    the fast kernels would take, forced through the library's debug switches."""
+    monkeypatch.setenv(env, "1")
+    cfg = cfg_of(dtype="bf16", B=2, C=20, H=32, W=64, p=4, D=256, heads=4, group_sizes=(8, 3))
+    pr = make_problem(cfg)
+    from workloads import round_to_bf16
+    dout = round_to_bf16(np.random.Generator(np.random.PCG64(47)).standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32))
+    got = run_backward(pr, dout)
+    want = oracle.backward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads,
+                           dout.reshape(cfg.B * cfg.N, cfg.D).astype(np.float64))
+    compare_grads(cfg, pr, got, want, TOL["bf16"], np.repeat(np.arange(cfg.B), cfg.N), np.tile(np.arange(cfg.N), cfg.B))
 
 
 def test_backward_skips_gradients_that_are_not_asked_for():
