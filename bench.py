@@ -66,9 +66,13 @@ def stage_model(cfg, levels_in, stage, level):
     if stage == "head_sums":
         return "hbm", tok * D * es + tok * h * 4 + uw
     if stage == "head_vproj":
-        return "mfma", 2.0 * B * G * N * D * D
-    if stage in ("bwd_oproj", "bwd_value"):
+        # every u row (D values) yields only D/heads outputs: 2*D/heads flops per byte of u, far below the ridge
+        return "hbm", uw + B * G * N * D * es + G * D * D * es
+    if stage == "bwd_oproj":
         return "mfma", 4.0 * B * G * N * D * D
+    if stage == "bwd_value":
+        # dWv reads u and d_o, w = Wv_a^T d_o_a is written once: bound by the two per-head tensors
+        return "hbm", 2 * uw + 2 * B * G * N * D * es + 2 * G * D * D * es
     if stage == "bwd_softmax":
         return "hbm", tok * D * es + uw + 3 * tok * h * 4
     if stage == "bwd_tokens":

@@ -150,21 +150,30 @@ inline bool gemm_mfma_ok(const GemmDesc& d) {
          mult8(d.Bm.sk) && mult8(d.Bm.sa) && mult8(bt ? d.Bm.s0 : d.Bm.s1);
 }
 
-template <typename TC>
-int launch_gemm_bf16(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st) {
-  if (!gemm_mfma_ok(d)) return launch_gemm<bf16, bf16, TC>(d, A, Bm, bias, C, st);
+template <int BM, int BN, int WM, int WN, typename TC>
+int launch_gemm_mfma_tile(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st) {
   const long batch = (long)(d.reduce_b ? 1 : d.nb) * d.nk * d.na;
-  const long mt = (d.M + 127) / 128;
+  const long mt = (d.M + BM - 1) / BM;
   if (batch > 65535 || mt > 65535 || d.M < 1 || d.N < 1) return DCHAG_ERR_SHAPE;
   const bool at = d.A.s1 != 1, bt = d.Bm.s0 != 1;
-  auto kern = at ? (bt ? k_gemm_mfma<true, true, TC> : k_gemm_mfma<true, false, TC>)
-                 : (bt ? k_gemm_mfma<false, true, TC> : k_gemm_mfma<false, false, TC>);
-  constexpr int lds = 2 * 256 * 128;
+  auto kern = at ? (bt ? k_gemm_mfma<BM, BN, WM, WN, true, true, TC> : k_gemm_mfma<BM, BN, WM, WN, true, false, TC>)
+                 : (bt ? k_gemm_mfma<BM, BN, WM, WN, false, true, TC> : k_gemm_mfma<BM, BN, WM, WN, false, false, TC>);
+  constexpr int lds = 2 * (BM + BN) * 128;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
       hipSuccess)
     return DCHAG_ERR_LAUNCH;
-  kern<<<dim3((d.N + 127) / 128, (unsigned)mt, (unsigned)batch), 256, lds, st>>>(d, A, Bm, bias, C);
+  kern<<<dim3((d.N + BN - 1) / BN, (unsigned)mt, (unsigned)batch), 256, lds, st>>>(d, A, Bm, bias, C);
   return launch_status();
+}
+
+// Tile shape by the extent of the output: a narrow N (one head, one patch of pixels) or a short M (the rows
+// of one head) takes the 64-wide tile on that side.
+template <typename TC>
+int launch_gemm_bf16(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st) {
+  if (!gemm_mfma_ok(d)) return launch_gemm<bf16, bf16, TC>(d, A, Bm, bias, C, st);
+  if (d.N <= 64) return launch_gemm_mfma_tile<128, 64, 4, 1, TC>(d, A, Bm, bias, C, st);
+  if (d.M <= 64) return launch_gemm_mfma_tile<64, 128, 1, 4, TC>(d, A, Bm, bias, C, st);
+  return launch_gemm_mfma_tile<128, 128, 2, 2, TC>(d, A, Bm, bias, C, st);
 }
 
 // Same-type products of the level kernels: MFMA for bf16 where it tiles, the fp32-FMA kernel otherwise.
@@ -338,7 +347,7 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
 
 template <typename T>
 int colsum(int B, int D, RowBlocks rb, const T* X, T* out, hipStream_t st) {
-  k_colsum<T, T><<<dim3((D + 63) / 64, rb.G), 256, 0, st>>>(B, D, rb, X, out);
+  k_colsum<T, T><<<dim3((D + 255) / 256, rb.G), 1024, 0, st>>>(B, D, rb, X, out);
   return launch_status();
 }
 
@@ -510,7 +519,7 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
     if ((rc = launch_status())) return rc;
   }
   if (gr->dquery) {
-    k_query_input_grad<T><<<dim3((D + 255) / 256, G), 256, 0, st>>>(D, static_cast<const T*>(lv->Wq), dQ,
+    k_query_input_grad<T><<<dim3((D + 255) / 256, G), 1024, 0, st>>>(D, static_cast<const T*>(lv->Wq), dQ,
                                                                    static_cast<T*>(gr->dquery));
     if ((rc = launch_status())) return rc;
   }
@@ -535,6 +544,19 @@ int linear_level_backward(int B, int Cin, int N, int D, const dchag_level* lv, c
   return DCHAG_OK;
 }
 
+// Copy between the image layout and patch rows, in runs of 8, 4, 2 or 1 pixels (the widest that divides p).
+template <typename T, bool TO_IMAGE>
+int patch_rows(long pixels, int H, int W, int p, T* img, T* patches, hipStream_t st) {
+  const int V = (p % 8 == 0 && sizeof(T) == 2) ? 8 : (p % 4 == 0 ? 4 : (p % 2 == 0 ? 2 : 1));
+  const long runs = pixels / V;
+  const dim3 grid((unsigned)((runs + 255) / 256));
+  if (V == 8) k_patch_rows<T, 8, TO_IMAGE><<<grid, 256, 0, st>>>(runs, H, W, p, img, patches);
+  else if (V == 4) k_patch_rows<T, 4, TO_IMAGE><<<grid, 256, 0, st>>>(runs, H, W, p, img, patches);
+  else if (V == 2) k_patch_rows<T, 2, TO_IMAGE><<<grid, 256, 0, st>>>(runs, H, W, p, img, patches);
+  else k_patch_rows<T, 1, TO_IMAGE><<<grid, 256, 0, st>>>(runs, H, W, p, img, patches);
+  return launch_status();
+}
+
 template <typename T>
 int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, const T* We, const T* dt_, T* dx,
                        T* dWe, T* dtok_bias, T* patches, hipStream_t st) {
@@ -545,9 +567,7 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
   const long pixels = (long)B * C * H * W;
   if (pixels > ((long)1 << 39)) return DCHAG_ERR_SHAPE;
   if (dWe) {
-    k_patch_rows<T, false><<<dim3((unsigned)((pixels + 255) / 256)), 256, 0, st>>>(pixels, H, W, p, const_cast<T*>(x),
-                                                                                  patches);
-    if ((rc = launch_status())) return rc;
+    if ((rc = patch_rows<T, false>(pixels, H, W, p, const_cast<T*>(x), patches, st))) return rc;
     GemmDesc d{};                                               // dWe[c][d][kk] = sum_{b,n} dt[b,c,n,d] patch[b,c,n,kk]
     d.M = D; d.N = pp; d.K = N; d.nb = B; d.nk = C; d.na = 1; d.reduce_b = 1;
     d.A = {(long)C * N * D, (long)N * D, 0, 1, (long)D};
@@ -564,8 +584,7 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
     d.C = {(long)C * N * pp, (long)N * pp, 0, (long)pp, 1};
     d.scale = 1.f;
     if ((rc = gemm_tt(d, dt_, We, nullptr, patches, st))) return rc;
-    k_patch_rows<T, true><<<dim3((unsigned)((pixels + 255) / 256)), 256, 0, st>>>(pixels, H, W, p, dx, patches);
-    if ((rc = launch_status())) return rc;
+    if ((rc = patch_rows<T, true>(pixels, H, W, p, dx, patches, st))) return rc;
   }
   return DCHAG_OK;
 }

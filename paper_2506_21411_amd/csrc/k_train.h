@@ -239,25 +239,37 @@ __global__ __launch_bounds__(256) void k_dz_attention(int Cin, int N, int D, int
 
 // ---------------------------------------------------------------------------------------
 // Column sums over the rows of every group:  out[k][i] = sum_b sum_{r < rows_of(k)} X[first_row(b,k) + r][i]
-// grid (ceil(D/64), G), block 256: the four waves take every fourth row and meet in LDS in a fixed order.
-// ---------------------------------------------------------------------------------------
+// grid (ceil(D/256), G), block 1024: lane l of every wavefront owns the 4 columns 256 x + 4 l .. (one 8- or
+// 16-byte load per row), the 16 wavefronts take every 16th row and meet in LDS in a fixed order.  D % 4 == 0.
 template <typename T, typename TO>
-__global__ __launch_bounds__(256) void k_colsum(int B, int D, RowBlocks rb, const T* __restrict__ X,
-                                                TO* __restrict__ out) {
-  __shared__ float part[3][64];
+__global__ __launch_bounds__(1024) void k_colsum(int B, int D, RowBlocks rb, const T* __restrict__ X,
+                                                 TO* __restrict__ out) {
+  typedef __attribute__((ext_vector_type(4))) T vec4;
+  __shared__ float part[16][256];
   const int k = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i = blockIdx.x * 64 + lane;
+  const int i = blockIdx.x * 256 + lane * 4;
   const int rows = rb.rows_of(k);
-  float acc = 0.f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (i < D)
     for (int b = 0; b < B; ++b) {
       const T* xb = X + (size_t)rb.first_row(b, k) * D + i;
-      for (int r = wave; r < rows; r += 4) acc += to_f32(xb[(size_t)r * D]);
+      for (int r = wave; r < rows; r += 16) {
+        const vec4 v = *reinterpret_cast<const vec4*>(xb + (size_t)r * D);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += to_f32(v[e]);
+      }
     }
-  if (wave > 0) part[wave - 1][lane] = acc;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) part[wave][lane * 4 + e] = acc[e];
   __syncthreads();
-  if (wave == 0 && i < D) out[(size_t)k * D + i] = from_f32<TO>(acc + part[0][lane] + part[1][lane] + part[2][lane]);
+  if (threadIdx.x < 256) {
+    const int ii = blockIdx.x * 256 + threadIdx.x;
+    float sum = 0.f;
+#pragma unroll
+    for (int w16 = 0; w16 < 16; ++w16) sum += part[w16][threadIdx.x];
+    if (ii < D) out[(size_t)k * D + ii] = from_f32<TO>(sum);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -285,18 +297,36 @@ __global__ __launch_bounds__(256) void k_query_grad(int D, int heads, const T* _
   }
 }
 
-// dquery[k][j] = sum_i Wq[k][i][j] * dQ[k][i];  grid (ceil(D/256), G), block 256.
+// dquery[k][j] = sum_i Wq[k][i][j] * dQ[k][i].  grid (ceil(D/256), G), block 1024: lane l of every wavefront owns
+// the 4 columns 256 x + 4 l .., the 16 wavefronts take every 16th row and meet in LDS in a fixed order.
+// Requires D % 4 == 0.
 template <typename T>
-__global__ __launch_bounds__(256) void k_query_input_grad(int D, const T* __restrict__ Wq,
-                                                          const float* __restrict__ dQ, T* __restrict__ dquery) {
+__global__ __launch_bounds__(1024) void k_query_input_grad(int D, const T* __restrict__ Wq,
+                                                           const float* __restrict__ dQ, T* __restrict__ dquery) {
+  __shared__ float part[16][256];
   const int k = blockIdx.y;
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= D) return;
-  const T* w = Wq + (size_t)k * D * D + j;
-  const float* dq = dQ + (size_t)k * D;
-  float acc = 0.f;
-  for (int i = 0; i < D; ++i) acc += to_f32(w[(size_t)i * D]) * dq[i];
-  dquery[(size_t)k * D + j] = from_f32<T>(acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 256 + lane * 4;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (j < D) {
+    const T* w = Wq + (size_t)k * D * D + j;
+    const float* dq = dQ + (size_t)k * D;
+    for (int i = wave; i < D; i += 16) {
+      const float q = dq[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] += to_f32(w[(size_t)i * D + e]) * q;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) part[wave][lane * 4 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < 256) {
+    const int jj = blockIdx.x * 256 + threadIdx.x;
+    float sum = 0.f;
+#pragma unroll
+    for (int w16 = 0; w16 < 16; ++w16) sum += part[w16][threadIdx.x];
+    if (jj < D) dquery[(size_t)k * D + jj] = from_f32<T>(sum);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -325,22 +355,31 @@ __global__ __launch_bounds__(256) void k_fill_zero(long n, T* __restrict__ out) 
 
 // ---------------------------------------------------------------------------------------
 // Patches as rows:  patches[b,c,n,kk] = pixel kk (row by row) of patch n of x[b,c]   and the reverse
-// scatter of patch rows back into an image.  One thread per pixel.
+// scatter of patch rows back into an image.  One thread per run of V adjacent pixels of one patch row
+// (V divides p: both sides of the copy are V contiguous elements).  `total` counts runs.
 // ---------------------------------------------------------------------------------------
-template <typename T, bool TO_IMAGE>
+template <typename T, int V, bool TO_IMAGE>
 __global__ __launch_bounds__(256) void k_patch_rows(long total, int H, int W, int p, T* __restrict__ img,
                                                     T* __restrict__ patches) {
-  const long idx = (long)blockIdx.x * 256 + threadIdx.x;      // pixel index in [B*C, H, W]
+  typedef __attribute__((ext_vector_type(V))) T vec;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;      // run index in [B*C, H, W / V]
   if (idx >= total) return;
-  const int wx = (int)(idx % W);
-  long t = idx / W;
+  const int wv = W / V;
+  const int wx = (int)(idx % wv) * V;
+  long t = idx / wv;
   const int hy = (int)(t % H);
   const long bc = t / H;
   const int pw = W / p, pp = p * p;
   const int n = (hy / p) * pw + wx / p, kk = (hy % p) * p + wx % p;
   const size_t pi = ((size_t)bc * (H / p) * pw + n) * pp + kk;
-  if (TO_IMAGE) img[idx] = patches[pi];
-  else patches[pi] = img[idx];
+  const size_t ii = ((size_t)bc * H + hy) * W + wx;
+  if (V == 1) {
+    if (TO_IMAGE) img[ii] = patches[pi];
+    else patches[pi] = img[ii];
+  } else {
+    if (TO_IMAGE) *reinterpret_cast<vec*>(img + ii) = *reinterpret_cast<const vec*>(patches + pi);
+    else *reinterpret_cast<vec*>(patches + pi) = *reinterpret_cast<const vec*>(img + ii);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -393,19 +432,22 @@ __global__ __launch_bounds__(256) void k_channel_mix_dw(int B, int Cin, int N, i
 namespace dchag {
 
 // ---------------------------------------------------------------------------------------
-// Strided batched matrix product on bf16 MFMA (32x32x16, fp32 accumulation), 128x128x64 tiles,
-// four wavefronts (2 x 2), operands staged through XOR-swizzled LDS rows of 64 contraction elements.
+// Strided batched matrix product on bf16 MFMA (32x32x16, fp32 accumulation), BM x BN x 64 tiles,
+// four wavefronts (WM x WN), operands staged through XOR-swizzled LDS rows of 64 contraction elements.
 // Same contract as k_gemm_generic (GemmDesc), restricted to:
 //   K % 64 == 0 (no ragged K), every operand has one unit stride, 16-byte aligned rows.
 // An operand whose unit stride is the contraction index is copied chunk by chunk (AT / BT = false);
 // one whose unit stride is its row index m (or n) is read as 8 x 8 blocks (8 contraction steps x 8
-// rows), transposed in registers and written as whole 16-byte LDS chunks (AT / BT = true).
-// grid (ceil(N/128), ceil(M/128), batch), block 256, dynamic LDS 2 x 256 x 128 bytes.
+// rows), transposed in registers and written as whole 16-byte LDS chunks (AT / BT = true; threads
+// 0 .. BM-1 take A's blocks, the last BN threads B's).
+// grid (ceil(N/BN), ceil(M/BM), batch), block 256, dynamic LDS 2 x (BM + BN) x 128 bytes.
 // ---------------------------------------------------------------------------------------
-template <bool AT, bool BT, typename TC>
+template <int BM, int BN, int WM, int WN, bool AT, bool BT, typename TC>
 __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __restrict__ A, const bf16* __restrict__ Bm,
                                                    const bf16* __restrict__ bias, TC* __restrict__ C) {
-  constexpr int BM = 128, BN = 128;
+  static_assert(WM * WN == 4 && BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BM <= 128 && BN <= 128, "tile");
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;          // 16-byte chunks per thread and stage (copied)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16x8* As = reinterpret_cast<bf16x8*>(smem);           // [2][BM * 8]
   bf16x8* Bs = As + 2 * BM * 8;                           // [2][BN * 8]
@@ -423,21 +465,21 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   if (m0 >= M) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, lhi = lane >> 5;
 
-  f32x16 acc[2][2];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // staging registers: 4 chunks per thread (copied operand) or one 8 x 8 block on half of the threads
-  bf16x8 a_reg[AT ? 8 : 4], b_reg[BT ? 8 : 4];
+  bf16x8 a_reg[AT ? 8 : A_CH], b_reg[BT ? 8 : B_CH];
   const int KT = d.K / 64;
   const int steps = (b1 - b0) * KT;
+  const int tb = tid - (256 - BN);                          // B's transposing threads: tb >= 0
 
   auto load = [&](int s) {
     const int b = b0 + s / KT, k0 = (s % KT) * 64;
@@ -445,26 +487,26 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
     const bf16* Bb = Bm + d.Bm.sb * b + d.Bm.sk * k + d.Bm.sa * a;
     if (!AT) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < A_CH; ++i) {
         const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
         const int gr = min(m0 + row, M - 1);
         a_reg[i] = *reinterpret_cast<const bf16x8*>(Ab + d.A.s0 * gr + k0 + ch * 8);
       }
-    } else if (tid < 128) {
-      const int mc = tid & 15, kc = tid >> 4;              // 8 rows m0 + 8 mc .., contraction steps k0 + 8 kc ..
+    } else if (tid < BM) {
+      const int mc = tid % (BM / 8), kc = tid / (BM / 8);  // 8 rows m0 + 8 mc .., contraction steps k0 + 8 kc ..
       const int gm = min(m0 + mc * 8, M - 8);
 #pragma unroll
       for (int i = 0; i < 8; ++i) a_reg[i] = *reinterpret_cast<const bf16x8*>(Ab + d.A.s1 * (k0 + kc * 8 + i) + gm);
     }
     if (!BT) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < B_CH; ++i) {
         const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
         const int gr = min(n0 + row, d.N - 1);
         b_reg[i] = *reinterpret_cast<const bf16x8*>(Bb + d.Bm.s1 * gr + k0 + ch * 8);
       }
-    } else if (tid >= 128) {
-      const int t = tid - 128, nc = t & 15, kc = t >> 4;
+    } else if (tb >= 0) {
+      const int nc = tb % (BN / 8), kc = tb / (BN / 8);
       const int gn = min(n0 + nc * 8, d.N - 8);
 #pragma unroll
       for (int i = 0; i < 8; ++i) b_reg[i] = *reinterpret_cast<const bf16x8*>(Bb + d.Bm.s0 * (k0 + kc * 8 + i) + gn);
@@ -475,12 +517,12 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
     bf16x8* Bd = Bs + buf * BN * 8;
     if (!AT) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < A_CH; ++i) {
         const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
         Ad[lds_slot<1>(row, ch)] = a_reg[i];
       }
-    } else if (tid < 128) {
-      const int mc = tid & 15, kc = tid >> 4;
+    } else if (tid < BM) {
+      const int mc = tid % (BM / 8), kc = tid / (BM / 8);
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
         bf16x8 v;
@@ -491,12 +533,12 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
     }
     if (!BT) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < B_CH; ++i) {
         const int idx = tid + i * 256, row = idx >> 3, ch = idx & 7;
         Bd[lds_slot<1>(row, ch)] = b_reg[i];
       }
-    } else if (tid >= 128) {
-      const int t = tid - 128, nc = t & 15, kc = t >> 4;
+    } else if (tb >= 0) {
+      const int nc = tb % (BN / 8), kc = tb / (BN / 8);
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
         bf16x8 v;
@@ -517,15 +559,15 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
     const bf16x8* Bc = Bs + cur * BN * 8;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[2], bfr[2];
+      bf16x8 af[TM], bfr[TN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) af[i] = Ac[lds_slot<1>(wm * 64 + i * 32 + l32, kk * 2 + lhi)];
+      for (int i = 0; i < TM; ++i) af[i] = Ac[lds_slot<1>(wm * (BM / WM) + i * 32 + l32, kk * 2 + lhi)];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[j] = Bc[lds_slot<1>(wn * 64 + j * 32 + l32, kk * 2 + lhi)];
+      for (int j = 0; j < TN; ++j) bfr[j] = Bc[lds_slot<1>(wn * (BN / WN) + j * 32 + l32, kk * 2 + lhi)];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
     if (s + 1 < steps) store(cur ^ 1);
@@ -536,15 +578,15 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
   TC* Cb = C + d.C.sb * b0 + d.C.sk * k + d.C.sa * a;
   const bf16* bs = bias ? bias + d.bias_sk * k + d.bias_sa * a : nullptr;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + j * 32 + l32;
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn * (BN / WN) + j * 32 + l32;
     if (n >= d.N) continue;
     const float bv = bs ? (float)bs[n] : 0.f;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+        const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
         if (m < M) Cb[d.C.s0 * m + d.C.s1 * n] = from_f32<TC>(acc[i][j][r] * d.scale + bv);
       }
   }
