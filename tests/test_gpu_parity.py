@@ -319,7 +319,8 @@ def test_forward_is_deterministic():
 
 
 @pytest.mark.parametrize("name,per_batch", [("weather", 8), ("hyperspectral", 6), ("wide", 3), ("deep", 2),
-                                            ("deep1000", 2), ("hyperspectral_linear", 6)])
+                                            ("deep1000", 2), ("hyperspectral_linear", 6),
+                                            ("hyperspectral_flat", 4)])
 def test_forward_full_size_on_sampled_patches(name, per_batch):
     """The configurations of the benchmark at full size, in the launch configuration the benchmark
     times; the oracle computes a seeded sample of patches (every weight takes part in every patch)."""

@@ -72,6 +72,8 @@ CONFIGS = {
     "wide": ShapeCfg("wide", "bf16", 1, 256, 256, 512, 8, 4096, 32, (32, 8), "gauss", 3),
     "deep": ShapeCfg("deep", "bf16", 2, 1024, 128, 128, 8, 2048, 16, (16, 8, 8), "ar1", 4),
     "deep1000": ShapeCfg("deep1000", "bf16", 2, 1000, 128, 128, 8, 2048, 16, (16, 8, 8), "ar1", 4),
+    # the flat baseline the hierarchy is compared with (Sections 2.1, 3.2): one cross-attention layer over all channels
+    "hyperspectral_flat": ShapeCfg("hyperspectral_flat", "bf16", 4, 512, 128, 128, 8, 1024, 16, (512,), "ar1", 2),
     # D-CHAG-L (Section 4.5): linear partial-aggregation layers, cross-attention only at the top
     "hyperspectral_linear": ShapeCfg("hyperspectral_linear", "bf16", 4, 512, 128, 128, 8, 1024, 16, (32, 16), "ar1", 2,
                                      ("linear", "attention")),
