@@ -244,17 +244,32 @@ def test_backward_full_size_with_upstream_gradient_on_sampled_patches(name, per_
     compare_grads(cfg, pr, got, want, TOL[cfg.dtype], bs, ns)
 
 
-def test_backward_full_size_output_bias_gradient_is_the_sum_of_the_upstream_gradient():
-    """A property that holds at any size, with a dense upstream gradient: the last level's output-bias
-    gradient is the plain sum of dout over all patches."""
-    cfg = get_config("weather")
+@pytest.mark.parametrize("name", ["weather", "wide", "deep", "deep1000", "hyperspectral_linear", "hyperspectral_flat"])
+def test_backward_full_size_identities_with_a_dense_upstream_gradient(name):
+    """Properties that hold at any size, with a dense upstream gradient, on every benchmark configuration:
+    the last level's output-bias gradient is the plain sum of dout over all patches; the value-bias gradient
+    of every attention level is Wo^T times its output-bias gradient (softmax weights sum to one, so bv
+    reaches the output as Wo bv); the key-bias gradient is zero; everything is finite."""
+    cfg = get_config(name)
+    say(f"backward identities {name}: generating inputs")
     pr = make_problem(cfg)
     rng = np.random.Generator(np.random.PCG64(44))
     dout = rng.standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32)
+    say(f"backward identities {name}: GPU")
     got = run_backward(pr, dout, want_dx=False)
     from workloads import round_to_bf16
     want = round_to_bf16(dout).astype(np.float64).sum(axis=(0, 1))
     assert rel_err(host(got[3][-1].dbo)[0], want) < TOL["bf16"]
-    for g in got[3]:
-        for n in ("dWq", "dWk", "dWv", "dWo", "dquery"):
-            assert torch.isfinite(getattr(g, n).float()).all()
+    for li, (lv, g) in enumerate(zip(pr.levels, got[3])):
+        if lv.kind == "linear":
+            assert torch.isfinite(g.dWv.float()).all() and torch.isfinite(g.dbv.float()).all()
+            continue
+        for n in ("dWq", "dWk", "dWv", "dWo", "dquery", "dbq", "dbv", "dbo"):
+            assert torch.isfinite(getattr(g, n).float()).all(), (li, n)
+        assert float(g.dbk.float().abs().max()) == 0.0
+        Wo = torch.from_numpy(lv.Wo).to("cuda", torch.float64)
+        ref = torch.einsum("kij,ki->kj", Wo, g.dbo.to(torch.float64))
+        err = float((g.dbv.to(torch.float64) - ref).abs().max() / ref.abs().max())
+        say(f"  level {li}: |dbv - Wo^T dbo| / max = {err:.2e}")
+        assert err < TOL["bf16"]
+    assert torch.isfinite(got[1].float()).all() and torch.isfinite(got[2].float()).all()
