@@ -83,6 +83,16 @@ inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, in
   return w;
 }
 
+// Patches per block of the token-gradient kernels: 16 (the softmax weights and ds of a tile must fit 64 KiB of
+// LDS), fewer while that leaves compute units without a block.
+inline int dz_patches(int B, int G, int N, int D, int g) {
+  int pt = 16;
+  if (const char* e = getenv("DCHAG_DZ_PT")) pt = atoi(e) > 0 ? atoi(e) : pt;
+  while (pt > 1 && (size_t)2 * pt * g * 16 * 4 > 64 * 1024) pt >>= 1;
+  while (pt > 1 && (long)B * G * ((N + pt - 1) / pt) * ((D + 1023) / 1024) < 2L * compute_units()) pt >>= 1;
+  return pt;
+}
+
 struct BackwardWs {
   size_t tokens, patches, kept[16], dz[2], dalpha, w, d_o, r, dq, rpart, ms, msb, cs, mft, total;
 };
@@ -111,7 +121,8 @@ inline BackwardWs backward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D
       dov = std::max(dov, align_up((size_t)B * G * N * D * es));
       rv = std::max(rv, align_up((size_t)G * heads * D * 4));
       dqv = std::max(dqv, align_up((size_t)G * D * 4));
-      rp = std::max(rp, align_up((size_t)B * G * ((N + kDzPatches - 1) / kDzPatches) * heads * D * 4));
+      const int pt = dz_patches(B, G, N, D, g);
+      rp = std::max(rp, align_up((size_t)B * G * ((N + pt - 1) / pt) * heads * D * 4));
     }
     c_in = G;
   }
@@ -416,24 +427,37 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
                            const float* alpha, const float* ds, const float* Mf, const bf16* Mb, bf16* dz, float* r,
                            float* rpart, bool want_r, hipStream_t st) {
   const int G = groups_of(Cin, g);
-  const size_t lds = (size_t)2 * kDzPatches * g * 16 * 4;
+  const int pt = dz_patches(B, G, N, D, g);
+  const size_t lds = (size_t)2 * pt * g * 16 * 4;
   if (heads > 16 || D % 4 || lds > 128 * 1024 || getenv("DCHAG_GENERIC_LEVEL"))
     return tokens_backward_generic<bf16>(B, Cin, N, D, heads, g, zin, w, alpha, ds, Mf, dz, r, want_r, st);
-  const int n_tiles = (N + kDzPatches - 1) / kDzPatches;
+  const int n_tiles = (N + pt - 1) / pt;
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_BWD_TOKENS, st);
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dz_rpart_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
-    k_dz_rpart_bf16<<<dim3((unsigned)(n_tiles * ((D + 1023) / 1024)), G, B), 256, lds, st>>>(
-        Cin, N, D, heads, g, n_tiles, alpha, ds, zin, w, Mb, dz, rpart);
-    if ((rc = launch_status())) return rc;
+    const dim3 grid((unsigned)(n_tiles * ((D + 1023) / 1024)), G, B);
+    if (D % 256 == 0 && !getenv("DCHAG_DZ_VALU")) {
+      k_dz_mfma<<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
+      if ((rc = launch_status())) return rc;
+      if (want_r) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_rpart_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)(lds / 2)) != hipSuccess)
+          return DCHAG_ERR_LAUNCH;
+        k_rpart_bf16<<<grid, 256, lds / 2, st>>>(Cin, N, D, heads, g, n_tiles, pt, ds, zin, rpart);
+        if ((rc = launch_status())) return rc;
+      }
+    } else {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dz_rpart_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds) != hipSuccess)
+        return DCHAG_ERR_LAUNCH;
+      k_dz_rpart_bf16<<<grid, 256, lds, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, zin, w, Mb, dz, rpart);
+      if ((rc = launch_status())) return rc;
+    }
   }
   if (!want_r) return DCHAG_OK;
   StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);
   const long per = (long)heads * D;
-  k_sum_partials<<<dim3((unsigned)((per + 255) / 256), G), 256, 0, st>>>(B, G, n_tiles, per, rpart, r);
+  k_sum_partials<<<dim3((unsigned)((per + 63) / 64), G), 256, 0, st>>>(B, G, n_tiles, per, rpart, r);
   return launch_status();
 }
 

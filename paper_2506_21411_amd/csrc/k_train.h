@@ -751,19 +751,17 @@ __global__ __launch_bounds__(256) void k_dalpha_softmax_mfma(long items, int Cin
 // Gradient at the input tokens and the key-path sums, bf16, heads <= 16, D % 4 == 0:
 //   dz[b,c,n,:]   = sum_a alpha[b,c,n,a] * w[b,k,n,a,:] + ds[b,c,n,a] * M[k][a][:]
 //   rpart[b,k,t][a][:] = sum over the PT patches of tile t and the members c of  ds[b,c,n,a] * z[b,c,n,:]
-// grid (ceil(N/PT) * ceil(D/1024), G, B), block 256: a thread owns 4 adjacent columns, keeps the 16 rows
+// grid (n_tiles * ceil(D/1024), G, B), n_tiles = ceil(N/PT), block 256: a thread owns 4 adjacent columns, keeps the 16 rows
 // of M and (per patch) of w for them in registers, and walks the members.  The softmax weights and ds of
-// the whole tile sit in LDS (dynamic, 2 * PT * g * 16 floats).  The partial sums are added up in a fixed
+// the whole tile of PT patches sit in LDS (dynamic, 2 * PT * g * 16 floats).  The partial sums are added up in a fixed
 // order by k_sum_partials.
 // ---------------------------------------------------------------------------------------
-constexpr int kDzPatches = 8;
-__global__ __launch_bounds__(256) void k_dz_rpart_bf16(int Cin, int N, int D, int heads, int g, int n_tiles,
+__global__ __launch_bounds__(256) void k_dz_rpart_bf16(int Cin, int N, int D, int heads, int g, int n_tiles, int PT,
                                                        const float* __restrict__ alpha, const float* __restrict__ ds,
                                                        const bf16* __restrict__ z, const bf16* __restrict__ w,
                                                        const bf16* __restrict__ Mb, bf16* __restrict__ dz,
                                                        float* __restrict__ rpart) {
-  constexpr int PT = kDzPatches;
-  extern __shared__ __attribute__((aligned(16))) float sm[];       // al[PT][gk][16], then dsv[PT][gk][16]
+  extern __shared__ __attribute__((aligned(16))) float sm[];       // al[PT][g][16], then dsv[PT][g][16]
   const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
   const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
   const int c0 = k * g, gk = min(g, Cin - c0);
@@ -837,16 +835,210 @@ __global__ __launch_bounds__(256) void k_dz_rpart_bf16(int Cin, int N, int D, in
     if (a < heads) *reinterpret_cast<f32x4*>(rp + (size_t)a * D) = f32x4{racc[a][0], racc[a][1], racc[a][2], racc[a][3]};
 }
 
-// r[k][i] = sum_b sum_t rpart[b][k][t][i]   (i over heads * D), fixed order.  One thread per (k, i).
+// ---------------------------------------------------------------------------------------
+// The same two results as two kernels for D % 256 == 0 (bf16, heads <= 16): the token gradients on MFMA
+// (reads w, writes dz) and the key-path sums on the vector ALUs (reads z); neither needs the other's stream.
+//
+// k_dz_mfma:  dz[b, c0 + m, n, :] = [alpha | ds](m, 0..31) . [w ; M](0..31, :)   one 32x32x16 product per 32
+// columns, alpha and ds split in two bf16 parts each (hi + lo) so that the fp32 softmax weights lose nothing.
+// A wavefront owns 256 columns, lane l the four columns 4 l .. 4 l + 3 of them: it loads the 16 head rows of
+// w (per patch) and of M (once) for its columns, packs them into 8-head chunks and swaps one chunk per column
+// with lane l ^ 32, which gives both half-wavefronts the B fragments (column, heads 8 (l / 32) ..) of the eight
+// 32-column tiles {4 (j + 32 half) + e : j < 32}.  Accumulator block (half, e): lane holds column
+// 4 (l % 32 + 32 half) + e, register r member 8 (r / 4) + 4 (l / 32) + r % 4: four blocks give a lane four
+// adjacent columns of a member row (one 8-byte store).  The A fragments (member row, 8 heads) come straight
+// from the token-major alpha / ds.  grid (n_tiles * ceil(D/1024), G, B), block 256, pt patches per block.
+// ---------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// B fragments of the eight column tiles from 16 rows (heads) of a [heads][D] bf16 matrix at this lane's 4 columns.
+__device__ __forceinline__ void head_row_frags(const bf16* __restrict__ base, int D, int heads, int lhi,
+                                               bf16x8 (&frag)[2][4]) {
+  bf16x4 rows[16];
+#pragma unroll
+  for (int a = 0; a < 16; ++a) {
+    rows[a] = bf16x4{};
+    if (a < heads) rows[a] = *reinterpret_cast<const bf16x4*>(base + (size_t)a * D);
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    bf16x8 c0, c1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      c0[i] = rows[i][e];
+      c1[i] = rows[8 + i][e];
+    }
+    const i32x4 v0 = __builtin_bit_cast(i32x4, c0), v1 = __builtin_bit_cast(i32x4, c1);
+    i32x4 own, snd, rcv;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      own[q] = lhi ? v1[q] : v0[q];                      // the chunk this half-wavefront multiplies for its own columns
+      snd[q] = lhi ? v0[q] : v1[q];                      // the chunk the other half needs for these columns
+      rcv[q] = __shfl_xor(snd[q], 32, kWave);
+    }
+    const bf16x8 o8 = __builtin_bit_cast(bf16x8, own), r8 = __builtin_bit_cast(bf16x8, rcv);
+    frag[0][e] = lhi ? r8 : o8;                          // tile of the lower half's columns
+    frag[1][e] = lhi ? o8 : r8;                          // tile of the upper half's columns
+  }
+}
+
+__device__ __forceinline__ void split_bf16(const f32x4& x0, const f32x4& x1, bf16x8& hi, bf16x8& lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hi[i] = (bf16)x0[i];
+    lo[i] = (bf16)(x0[i] - (float)hi[i]);
+    hi[4 + i] = (bf16)x1[i];
+    lo[4 + i] = (bf16)(x1[i] - (float)hi[4 + i]);
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void k_dz_mfma(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
+                                                 const float* __restrict__ alpha, const float* __restrict__ ds,
+                                                 const bf16* __restrict__ w, const bf16* __restrict__ Mb,
+                                                 bf16* __restrict__ dz) {
+  const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
+  const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  const int n0 = tile * pt, np = min(pt, N - n0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+  const int col0 = cb * 1024 + wave * 256;
+  if (col0 >= D) return;
+  const int d0 = col0 + 4 * lane;
+  bf16x8 mfrag[2][4];
+  head_row_frags(Mb + (size_t)k * heads * D + d0, D, heads, lhi, mfrag);
+  const size_t cstride = (size_t)N * D;
+  const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const bool h8 = heads % 8 == 0;                        // then a lane's 8 heads are two aligned 16-byte loads
+  for (int pi = 0; pi < np; ++pi) {
+    const int n = n0 + pi;
+    bf16x8 wfrag[2][4];
+    head_row_frags(w + ((((size_t)b * G + k) * N + n) * heads) * D + d0, D, heads, lhi, wfrag);
+    for (int m0 = 0; m0 < gk; m0 += 32) {
+      const int row = m0 + l32;
+      const size_t src = (((size_t)b * Cin + c0 + min(row, gk - 1)) * N + n) * heads + 8 * lhi;
+      f32x4 a0 = z4, a1 = z4, e0 = z4, e1 = z4;
+      if (row < gk) {
+        if (h8) {
+          if (8 * lhi < heads) {
+            a0 = *reinterpret_cast<const f32x4*>(alpha + src);
+            a1 = *reinterpret_cast<const f32x4*>(alpha + src + 4);
+            e0 = *reinterpret_cast<const f32x4*>(ds + src);
+            e1 = *reinterpret_cast<const f32x4*>(ds + src + 4);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (8 * lhi + i < heads) { a0[i] = alpha[src + i]; e0[i] = ds[src + i]; }
+            if (8 * lhi + 4 + i < heads) { a1[i] = alpha[src + 4 + i]; e1[i] = ds[src + 4 + i]; }
+          }
+        }
+      }
+      bf16x8 ahi, alo, dhi, dlo;
+      split_bf16(a0, a1, ahi, alo);
+      split_bf16(e0, e1, dhi, dlo);
+      auto tiles_of_half = [&](const bf16x8 (&wf)[4], const bf16x8 (&mf)[4], int half) {
+        f32x16 acc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, wf[e], zero, 0, 0, 0);
+          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, wf[e], acc[e], 0, 0, 0);
+          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dhi, mf[e], acc[e], 0, 0, 0);
+          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dlo, mf[e], acc[e], 0, 0, 0);
+        }
+        bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n) * D + col0 + 4 * (l32 + 32 * half);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+          if (m < gk) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[e][r];
+            *reinterpret_cast<bf16x4*>(dzp + (size_t)m * cstride) = o;
+          }
+        }
+      };
+      tiles_of_half(wfrag[0], mfrag[0], 0);
+      tiles_of_half(wfrag[1], mfrag[1], 1);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// k_rpart_bf16:  rpart[b,k,t][a][:] = sum over the pt patches of tile t and the members c of ds[b,c,n,a] * z[b,c,n,:]
+// grid (n_tiles * ceil(D/1024), G, B), block 256: a thread owns 4 adjacent columns and one fp32 sum per head;
+// ds of the whole tile sits in LDS (dynamic, pt * g * 16 floats).  Bound by the read of z.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_rpart_bf16(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
+                                                    const float* __restrict__ ds, const bf16* __restrict__ z,
+                                                    float* __restrict__ rpart) {
+  extern __shared__ __attribute__((aligned(16))) float dsv[];      // [pt][g][16]
+  const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
+  const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  const int n0 = tile * pt, np = min(pt, N - n0);
+  for (int idx = threadIdx.x; idx < np * gk * 16; idx += 256) {
+    const int a = idx & 15, cl = (idx >> 4) % gk, pi = (idx >> 4) / gk;
+    dsv[(pi * g + cl) * 16 + a] = a < heads ? ds[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a] : 0.f;
+  }
+  __syncthreads();
+  const int d0 = cb * 1024 + threadIdx.x * 4;
+  if (d0 >= D) return;
+  float racc[16][4];
+#pragma unroll
+  for (int a = 0; a < 16; ++a)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) racc[a][e] = 0.f;
+  const size_t cstride = (size_t)N * D;
+  for (int pi = 0; pi < np; ++pi) {
+    const bf16* zp = z + (((size_t)b * Cin + c0) * N + n0 + pi) * D + d0;
+    int cl = 0;
+    for (; cl + 8 <= gk; cl += 8) {
+      bf16x4 zv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) zv[i] = *reinterpret_cast<const bf16x4*>(zp + (size_t)(cl + i) * cstride);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const f32x4* dr = reinterpret_cast<const f32x4*>(dsv + (pi * g + cl + i) * 16);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 dv = dr[q];
+#pragma unroll
+          for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) racc[q * 4 + a][e] += dv[a] * (float)zv[i][e];
+        }
+      }
+    }
+    for (; cl < gk; ++cl) {
+      const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zp + (size_t)cl * cstride);
+#pragma unroll
+      for (int a = 0; a < 16; ++a)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) racc[a][e] += dsv[(pi * g + cl) * 16 + a] * (float)zv[e];
+    }
+  }
+  float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads) * D + d0;
+#pragma unroll
+  for (int a = 0; a < 16; ++a)
+    if (a < heads) *reinterpret_cast<f32x4*>(rp + (size_t)a * D) = f32x4{racc[a][0], racc[a][1], racc[a][2], racc[a][3]};
+}
+
+// r[k][i] = sum_b sum_t rpart[b][k][t][i]   (i over heads * D), fixed order.  grid (ceil(per/64), G), block 256:
+// 64 adjacent i per block, the four wavefronts take every fourth partial and meet in LDS.
 __global__ __launch_bounds__(256) void k_sum_partials(int B, int G, int n_tiles, long per, const float* __restrict__ rpart,
                                                       float* __restrict__ r) {
-  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  __shared__ float part[3][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long i = (long)blockIdx.x * 64 + lane;
   const int k = blockIdx.y;
-  if (i >= per) return;
   float acc = 0.f;
-  for (int b = 0; b < B; ++b)
-    for (int t = 0; t < n_tiles; ++t) acc += rpart[(((size_t)b * G + k) * n_tiles + t) * per + i];
-  r[(size_t)k * per + i] = acc;
+  if (i < per)
+    for (int b = 0; b < B; ++b)
+      for (int t = wave; t < n_tiles; t += 4) acc += rpart[(((size_t)b * G + k) * n_tiles + t) * per + i];
+  if (wave > 0) part[wave - 1][lane] = acc;
+  __syncthreads();
+  if (wave == 0 && i < per) r[(size_t)k * per + i] = acc + part[0][lane] + part[1][lane] + part[2][lane];
 }
 
 }  // namespace dchag
