@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
-"""Benchmark of the D-CHAG forward hot path on one MI355X.
+"""Benchmark of the D-CHAG hot path on one MI355X.
 
 One "step" is one dchag_forward call (tokenize + every aggregation level) over one batch of
 seeded synthetic input that is already resident in HBM.  The metric is aggregated
-channel-patch tokens per second, B*C*N / time.  Prints ONE JSON line.
+channel-patch tokens per second, B*C*N / time.  Prints ONE JSON line.  --mode folded / backward
+times dchag_forward_folded / dchag_backward the same way (the default run reports them as side lines).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload hyperspectral|weather|...]
+                    [--mode forward|folded|backward]
 """
 from __future__ import annotations
 

@@ -522,7 +522,7 @@ int check_level_shape(int B, int Cin, int N, int D, int heads, int g) {
 
 extern "C" {
 
-const char* dchag_version(void) { return "0.1"; }
+const char* dchag_version(void) { return "0.2"; }
 
 int dchag_profile_begin(void) {
   for (StageRecord& r : g_records) {

@@ -318,6 +318,44 @@ def test_forward_is_deterministic():
     assert torch.equal(a, b)
 
 
+def test_forward_can_be_captured_in_a_graph_and_replayed():
+    """dchag_forward allocates nothing and synchronises nothing, so a caller may capture it in a HIP graph.
+    Every replay, with eager work and synchronisations in between, must reproduce the eager result bit for bit."""
+    cfg = cfg_of(dtype="bf16", B=2, C=20, H=32, W=48, p=4, D=256, heads=4, group_sizes=(8, 3))
+    pr = make_problem(cfg)
+    d = "bf16"
+    x, We, be, ce = dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d)
+    levels = [dev_level(lv, d) for lv in pr.levels]
+    wsb = dchag.dchag_workspace_bytes(dchag.DCHAG_BF16, cfg.B, cfg.C, cfg.H, cfg.W, cfg.p, cfg.D, cfg.heads,
+                                      list(cfg.group_sizes), 1)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    out = torch.empty((cfg.B, cfg.N, cfg.D), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        dchag.dchag_forward(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                            # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, capture_error_mode="relaxed"):
+        step()
+    for rep in range(3):
+        out.zero_()
+        ws.random_(0, 255)                                # the workspace holds nothing a replay depends on
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+        step()                                            # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+
+
 @pytest.mark.parametrize("name,per_batch", [("weather", 8), ("hyperspectral", 6), ("wide", 3), ("deep", 2),
                                             ("deep1000", 2), ("hyperspectral_linear", 6),
                                             ("hyperspectral_flat", 4)])
