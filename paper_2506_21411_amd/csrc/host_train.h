@@ -162,7 +162,8 @@ inline bool gemm_mfma_ok(const GemmDesc& d) {
 }
 
 template <int BM, int BN, int WM, int WN, typename TC>
-int launch_gemm_mfma_tile(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st) {
+int launch_gemm_mfma_tile(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, TC* rowsum,
+                          hipStream_t st) {
   const long batch = (long)(d.reduce_b ? 1 : d.nb) * d.nk * d.na;
   const long mt = (d.M + BM - 1) / BM;
   if (batch > 65535 || mt > 65535 || d.M < 1 || d.N < 1) return DCHAG_ERR_SHAPE;
@@ -173,19 +174,23 @@ int launch_gemm_mfma_tile(const GemmDesc& d, const bf16* A, const bf16* Bm, cons
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
       hipSuccess)
     return DCHAG_ERR_LAUNCH;
-  kern<<<dim3((d.N + BN - 1) / BN, (unsigned)mt, (unsigned)batch), 256, lds, st>>>(d, A, Bm, bias, C);
+  kern<<<dim3((d.N + BN - 1) / BN, (unsigned)mt, (unsigned)batch), 256, lds, st>>>(d, A, Bm, bias, C, rowsum);
   return launch_status();
 }
 
 // Tile shape by the extent of the output: a narrow N (one head, one patch of pixels) or a short M (the rows
 // of one head) takes the 64-wide tile on that side.
+// rowsum (optional, only with a transposed A on the MFMA kernel: see gemm_rowsum_ok): sums of A's rows.
 template <typename TC>
-int launch_gemm_bf16(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st) {
+int launch_gemm_bf16(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st,
+                     TC* rowsum = nullptr) {
   if (!gemm_mfma_ok(d)) return launch_gemm<bf16, bf16, TC>(d, A, Bm, bias, C, st);
-  if (d.N <= 64) return launch_gemm_mfma_tile<128, 64, 4, 1, TC>(d, A, Bm, bias, C, st);
-  if (d.M <= 64) return launch_gemm_mfma_tile<64, 128, 1, 4, TC>(d, A, Bm, bias, C, st);
-  return launch_gemm_mfma_tile<128, 128, 2, 2, TC>(d, A, Bm, bias, C, st);
+  if (d.N <= 64) return launch_gemm_mfma_tile<128, 64, 4, 1, TC>(d, A, Bm, bias, C, rowsum, st);
+  if (d.M <= 64) return launch_gemm_mfma_tile<64, 128, 1, 4, TC>(d, A, Bm, bias, C, rowsum, st);
+  return launch_gemm_mfma_tile<128, 128, 2, 2, TC>(d, A, Bm, bias, C, rowsum, st);
 }
+// True when launch_gemm_bf16 will deliver the row sums of A along with the product.
+inline bool gemm_rowsum_ok(const GemmDesc& d) { return gemm_mfma_ok(d) && d.A.s1 != 1 && !getenv("DCHAG_COLSUM"); }
 
 // Same-type products of the level kernels: MFMA for bf16 where it tiles, the fp32-FMA kernel otherwise.
 inline int gemm_tt(const GemmDesc& d, const float* A, const float* Bm, const float* bias, float* C, hipStream_t st) {
@@ -193,6 +198,29 @@ inline int gemm_tt(const GemmDesc& d, const float* A, const float* Bm, const flo
 }
 inline int gemm_tt(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, bf16* C, hipStream_t st) {
   return launch_gemm_bf16<bf16>(d, A, Bm, bias, C, st);
+}
+
+// A weight gradient  dW = sum over rows of X^T Y  together with the bias gradient  db = sum over rows of X
+// (the row sums of the product's transposed A operand).  rb describes the rows for the separate column-sum
+// kernel, which runs when the product kernel cannot deliver the sums.
+inline int gemm_with_bias_grad(GemmDesc d, int B, int D, RowBlocks rb, const float* X, const float* Y, float* dW,
+                               float* db, hipStream_t st) {
+  int rc = DCHAG_OK;
+  if (db) {
+    k_colsum<float, float><<<dim3((D + 255) / 256, rb.G), 1024, 0, st>>>(B, D, rb, X, db);
+    if ((rc = launch_status())) return rc;
+  }
+  return dW ? launch_gemm<float, float, float>(d, X, Y, nullptr, dW, st) : DCHAG_OK;
+}
+inline int gemm_with_bias_grad(GemmDesc d, int B, int D, RowBlocks rb, const bf16* X, const bf16* Y, bf16* dW, bf16* db,
+                               hipStream_t st) {
+  if (dW && db && gemm_rowsum_ok(d)) return launch_gemm_bf16<bf16>(d, X, Y, nullptr, dW, st, db);
+  int rc = DCHAG_OK;
+  if (db) {
+    k_colsum<bf16, bf16><<<dim3((D + 255) / 256, rb.G), 1024, 0, st>>>(B, D, rb, X, db);
+    if ((rc = launch_status())) return rc;
+  }
+  return dW ? launch_gemm_bf16<bf16>(d, X, Y, nullptr, dW, st) : DCHAG_OK;
 }
 
 // Buffers of one attention level (see KeptLevel); alpha_f and Mb are used by the bf16 kernels only.
@@ -476,15 +504,16 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_BWD_OPROJ, st);
-    if (gr->dbo && (rc = colsum<T>(B, D, rbo, dy, static_cast<T*>(gr->dbo), st))) return rc;
-    if (gr->dWo) {                                              // dWo[k][i][j] = sum_{b,n} dy[..,i] o[..,j]
+    {                                                           // dWo[k][i][j] = sum_{b,n} dy[..,i] o[..,j];  dbo = sum dy
       GemmDesc d{};
       d.M = D; d.N = D; d.K = N; d.nb = B; d.nk = G; d.na = 1; d.reduce_b = 1;
       d.A = {sBG, sG, 0, 1, (long)D};
       d.Bm = {sBG, sG, 0, (long)D, 1};
       d.C = {0, (long)D * D, 0, (long)D, 1};
       d.scale = 1.f;
-      if ((rc = gemm_tt(d, dy, lb.o, nullptr, static_cast<T*>(gr->dWo), st))) return rc;
+      d.rs_sk = D;
+      if ((rc = gemm_with_bias_grad(d, B, D, rbo, dy, lb.o, static_cast<T*>(gr->dWo), static_cast<T*>(gr->dbo), st)))
+        return rc;
     }
     GemmDesc d{};                                               // d_o[.., j] = sum_i dy[.., i] Wo[k][i][j]
     d.M = N; d.N = D; d.K = D; d.nb = B; d.nk = G; d.na = 1;
@@ -496,15 +525,16 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
   }
   {
     StageTimer tm(DCHAG_STAGE_BWD_VALUE, st);
-    if (gr->dbv && (rc = colsum<T>(B, D, rbo, d_o, static_cast<T*>(gr->dbv), st))) return rc;
-    if (gr->dWv) {                                              // dWv[k][a*dh+i][j] = sum_{b,n} d_o[.., a*dh+i] u[.., a, j]
-      GemmDesc d{};
+    {                                                           // dWv[k][a*dh+i][j] = sum_{b,n} d_o[.., a*dh+i] u[.., a, j]
+      GemmDesc d{};                                             // dbv = sum d_o
       d.M = dh; d.N = D; d.K = N; d.nb = B; d.nk = G; d.na = heads; d.reduce_b = 1;
       d.A = {sBG, sG, (long)dh, 1, (long)D};
       d.Bm = {uB, uG, (long)D, (long)heads * D, 1};
       d.C = {0, (long)D * D, (long)dh * D, (long)D, 1};
       d.scale = 1.f;
-      if ((rc = gemm_tt(d, d_o, lb.u, nullptr, static_cast<T*>(gr->dWv), st))) return rc;
+      d.rs_sk = D; d.rs_sa = dh;
+      if ((rc = gemm_with_bias_grad(d, B, D, rbo, d_o, lb.u, static_cast<T*>(gr->dWv), static_cast<T*>(gr->dbv), st)))
+        return rc;
     }
     GemmDesc d{};                                               // w[.., a, j] = sum_i d_o[.., a*dh+i] Wv[k][a*dh+i][j]
     d.M = N; d.N = D; d.K = dh; d.nb = B; d.nk = G; d.na = heads;
@@ -587,18 +617,18 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
   const int N = (H / p) * (W / p), pp = p * p;
   int rc;
   StageTimer tm(DCHAG_STAGE_BWD_TOKENIZE, st);
-  if (dtok_bias && (rc = colsum<T>(B, D, RowBlocks{C, C * N, N}, dt_, dtok_bias, st))) return rc;
   const long pixels = (long)B * C * H * W;
   if (pixels > ((long)1 << 39)) return DCHAG_ERR_SHAPE;
-  if (dWe) {
-    if ((rc = patch_rows<T, false>(pixels, H, W, p, const_cast<T*>(x), patches, st))) return rc;
+  if (dWe && (rc = patch_rows<T, false>(pixels, H, W, p, const_cast<T*>(x), patches, st))) return rc;
+  {
     GemmDesc d{};                                               // dWe[c][d][kk] = sum_{b,n} dt[b,c,n,d] patch[b,c,n,kk]
-    d.M = D; d.N = pp; d.K = N; d.nb = B; d.nk = C; d.na = 1; d.reduce_b = 1;
+    d.M = D; d.N = pp; d.K = N; d.nb = B; d.nk = C; d.na = 1; d.reduce_b = 1;   // dtok_bias[c][d] = sum_{b,n} dt
     d.A = {(long)C * N * D, (long)N * D, 0, 1, (long)D};
     d.Bm = {(long)C * N * pp, (long)N * pp, 0, (long)pp, 1};
     d.C = {0, (long)D * pp, 0, (long)pp, 1};
     d.scale = 1.f;
-    if ((rc = gemm_tt(d, dt_, patches, nullptr, dWe, st))) return rc;
+    d.rs_sk = D;
+    if ((rc = gemm_with_bias_grad(d, B, D, RowBlocks{C, C * N, N}, dt_, patches, dWe, dtok_bias, st))) return rc;
   }
   if (dx) {
     GemmDesc d{};                                               // dpatch[b,c,n,kk] = sum_d dt[b,c,n,d] We[c][d][kk]

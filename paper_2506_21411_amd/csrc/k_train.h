@@ -34,6 +34,7 @@ struct GemmDesc {
   GemmOperand A, Bm, C;
   long bias_sk, bias_sa;
   float scale;
+  long rs_sk, rs_sa;   // k_gemm_mfma with a transposed A: optional row sums of A over the contraction, per (k, a)
 };
 
 template <typename TA, typename TB, typename TC>
@@ -440,11 +441,14 @@ namespace dchag {
 // one whose unit stride is its row index m (or n) is read as 8 x 8 blocks (8 contraction steps x 8
 // rows), transposed in registers and written as whole 16-byte LDS chunks (AT / BT = true; threads
 // 0 .. BM-1 take A's blocks, the last BN threads B's).
+// With a transposed A the kernel can also write the sums of A's rows over the whole contraction (all batch
+// elements when reduce_b is set): the bias gradients that go with a weight gradient, at no extra pass over A.
 // grid (ceil(N/BN), ceil(M/BM), batch), block 256, dynamic LDS 2 x (BM + BN) x 128 bytes.
 // ---------------------------------------------------------------------------------------
 template <int BM, int BN, int WM, int WN, bool AT, bool BT, typename TC>
 __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __restrict__ A, const bf16* __restrict__ Bm,
-                                                   const bf16* __restrict__ bias, TC* __restrict__ C) {
+                                                   const bf16* __restrict__ bias, TC* __restrict__ C,
+                                                   TC* __restrict__ rowsum) {
   static_assert(WM * WN == 4 && BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BM <= 128 && BN <= 128, "tile");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;          // 16-byte chunks per thread and stage (copied)
@@ -480,6 +484,11 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
   const int KT = d.K / 64;
   const int steps = (b1 - b0) * KT;
   const int tb = tid - (256 - BN);                          // B's transposing threads: tb >= 0
+
+  // optional by-product with a transposed A: rsum[r] collects sum over the contraction of A(row 8 mc + r, .)
+  // for this thread's share of the contraction steps (only the blocks of the first column tile do it)
+  const bool want_rs = AT && rowsum != nullptr && blockIdx.x == 0;
+  float rsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   auto load = [&](int s) {
     const int b = b0 + s / KT, k0 = (s % KT) * 64;
@@ -529,6 +538,10 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = a_reg[i][r];
         Ad[lds_slot<1>(mc * 8 + r, kc)] = v;
+        if (want_rs) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) rsum[r] += (float)a_reg[i][r];
+        }
       }
     }
     if (!BT) {
@@ -572,6 +585,22 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
     }
     if (s + 1 < steps) store(cur ^ 1);
     __syncthreads();
+  }
+
+  if (AT && rowsum != nullptr && blockIdx.x == 0) {       // block-uniform: the eight shares of a row meet in LDS
+    float* part = reinterpret_cast<float*>(smem);         // [8 shares][BM rows]; the stages are no longer read
+    if (tid < BM) {
+      const int mc = tid % (BM / 8), kc = tid / (BM / 8);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) part[kc * BM + mc * 8 + r] = rsum[r];
+    }
+    __syncthreads();
+    if (tid < BM && m0 + tid < M) {
+      float sum = 0.f;
+#pragma unroll
+      for (int kc = 0; kc < 8; ++kc) sum += part[kc * BM + tid];
+      rowsum[d.rs_sk * k + d.rs_sa * a + m0 + tid] = from_f32<TC>(sum);
+    }
   }
 
   // 32x32 accumulator block: lane holds column (lane % 32); register r holds row 8 (r / 4) + 4 (lane / 32) + r % 4
@@ -967,19 +996,20 @@ __global__ __launch_bounds__(256, 2) void k_dz_mfma(int Cin, int N, int D, int h
 // ---------------------------------------------------------------------------------------
 // k_rpart_bf16:  rpart[b,k,t][a][:] = sum over the pt patches of tile t and the members c of ds[b,c,n,a] * z[b,c,n,:]
 // grid (n_tiles * ceil(D/1024), G, B), block 256: a thread owns 4 adjacent columns and one fp32 sum per head;
-// ds of the whole tile sits in LDS (dynamic, pt * g * 16 floats).  Bound by the read of z.
+// ds of the whole tile sits in LDS (dynamic, pt * g * 16 floats).
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_rpart_bf16(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
                                                     const float* __restrict__ ds, const bf16* __restrict__ z,
                                                     float* __restrict__ rpart) {
-  extern __shared__ __attribute__((aligned(16))) float dsv[];      // [pt][g][16]
+  extern __shared__ __attribute__((aligned(16))) float dsv[];      // [np * gk rows in (patch, member) order][16]
   const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
   const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
   const int c0 = k * g, gk = min(g, Cin - c0);
   const int n0 = tile * pt, np = min(pt, N - n0);
-  for (int idx = threadIdx.x; idx < np * gk * 16; idx += 256) {
+  const int rows = np * gk;
+  for (int idx = threadIdx.x; idx < rows * 16; idx += 256) {
     const int a = idx & 15, cl = (idx >> 4) % gk, pi = (idx >> 4) / gk;
-    dsv[(pi * g + cl) * 16 + a] = a < heads ? ds[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a] : 0.f;
+    dsv[idx] = a < heads ? ds[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a] : 0.f;
   }
   __syncthreads();
   const int d0 = cb * 1024 + threadIdx.x * 4;
@@ -990,33 +1020,37 @@ __global__ __launch_bounds__(256) void k_rpart_bf16(int Cin, int N, int D, int h
 #pragma unroll
     for (int e = 0; e < 4; ++e) racc[a][e] = 0.f;
   const size_t cstride = (size_t)N * D;
-  for (int pi = 0; pi < np; ++pi) {
-    const bf16* zp = z + (((size_t)b * Cin + c0) * N + n0 + pi) * D + d0;
-    int cl = 0;
-    for (; cl + 8 <= gk; cl += 8) {
-      bf16x4 zv[8];
+  const bf16* zb = z + (((size_t)b * Cin + c0) * N + n0) * D + d0;
+  // the rows of the tile are walked eight at a time, the next eight already in flight while these are summed
+  int pcl = 0, ppi = 0;                                  // (member, patch) of the next row to fetch
+  bf16x4 cur[8], nxt[8];
+  auto fetch = [&](bf16x4 (&buf)[8]) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) zv[i] = *reinterpret_cast<const bf16x4*>(zp + (size_t)(cl + i) * cstride);
+    for (int i = 0; i < 8; ++i) {
+      buf[i] = bf16x4{};
+      if (ppi < np) buf[i] = *reinterpret_cast<const bf16x4*>(zb + (size_t)ppi * D + (size_t)pcl * cstride);
+      if (++pcl == gk) { pcl = 0; ++ppi; }
+    }
+  };
+  fetch(cur);
+  for (int base = 0; base < rows; base += 8) {
+    fetch(nxt);                                          // past the end: nothing is loaded
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const f32x4* dr = reinterpret_cast<const f32x4*>(dsv + (pi * g + cl + i) * 16);
+    for (int i = 0; i < 8; ++i) {
+      if (base + i < rows) {
+        const f32x4* dr = reinterpret_cast<const f32x4*>(dsv + (base + i) * 16);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const f32x4 dv = dr[q];
 #pragma unroll
           for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) racc[q * 4 + a][e] += dv[a] * (float)zv[i][e];
+            for (int e = 0; e < 4; ++e) racc[q * 4 + a][e] += dv[a] * (float)cur[i][e];
         }
       }
     }
-    for (; cl < gk; ++cl) {
-      const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zp + (size_t)cl * cstride);
 #pragma unroll
-      for (int a = 0; a < 16; ++a)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) racc[a][e] += dsv[(pi * g + cl) * 16 + a] * (float)zv[e];
-    }
+    for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
   }
   float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads) * D + d0;
 #pragma unroll
