@@ -96,6 +96,9 @@ def main() -> int:
                     help="what one step is: dchag_forward (the headline), dchag_forward_folded, or dchag_backward")
     ap.add_argument("--cpu-patches", type=int, default=64, help="patches the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-other", action="store_true", help="skip the short weather-like side measurement")
+    ap.add_argument("--flat-sweep", action="store_true",
+                    help="also time the hyperspectral shape at C = 128 .. 1024 channels as one flat layer and as the "
+                         "two-level hierarchy (groups of 32), forward")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy kernel (reads 1 GiB, writes 1 GiB): the yardstick "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
@@ -284,6 +287,22 @@ def main() -> int:
                       "tokens": cfg.tokens, "ms_per_step": round(msb, 4), "value": cfg.tokens / (msb * 1e-3),
                       "unit": "tokens/s"})
         mode["name"], mode["bwd"] = "forward", None
+        # the forward with the positional embedding added in the last projection's epilogue
+        xx, Wee, bee, cee, lvls, wss, outt = t
+        pos = torch.randn((cfg.N, cfg.D), device="cuda", dtype=torch.float32).to(outt.dtype)
+        for _ in range(3):
+            dchag.dchag_forward_pos(xx, Wee, bee, cee, lvls, cfg.p, cfg.heads, pos, out=outt, workspace=wss)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dchag.dchag_forward_pos(xx, Wee, bee, cee, lvls, cfg.p, cfg.heads, pos, out=outt, workspace=wss)
+        e1.record()
+        torch.cuda.synchronize()
+        msp = e0.elapsed_time(e1) / 10
+        other.append({"workload": "hyperspectral", "call": "dchag_forward_pos", "tokens": cfg.tokens,
+                      "ms_per_step": round(msp, 4), "value": cfg.tokens / (msp * 1e-3), "unit": "tokens/s"})
+        del xx, Wee, bee, cee, lvls, wss, outt, pos
         del t
         torch.cuda.empty_cache()
         c2 = get_config("weather")
@@ -303,6 +322,25 @@ def main() -> int:
                           "value": c3.tokens / (ms3 * 1e-3), "unit": "tokens/s"})
             del t3
             torch.cuda.empty_cache()
+
+    # hierarchy against the flat single layer over the channel count (forward, hyperspectral shape otherwise)
+    sweep = []
+    if args.flat_sweep:
+        from workloads import ShapeCfg
+        base = get_config("hyperspectral")
+        torch.cuda.empty_cache()
+        for C in (128, 256, 512, 1024):
+            row = {"C": C}
+            for kind, gsz in (("flat", (C,)), ("hier_g32", (32, C // 32))):
+                c4 = ShapeCfg(f"sweep_{kind}_{C}", "bf16", base.B, C, base.H, base.W, base.p, base.D, base.heads, gsz,
+                              "ar1", 2)
+                _, t4 = prepare(c4)
+                ms4, _, _ = timed(c4, t4, 3, 10, profile=False)
+                row[kind + "_ms"] = round(ms4, 4)
+                row[kind + "_tokens_per_s"] = c4.tokens / (ms4 * 1e-3)
+                del t4
+                torch.cuda.empty_cache()
+            sweep.append(row)
 
     line = {
         "metric": "aggregated channel-patch tokens/sec (B*C*N) through tokenize + hierarchical aggregation, "
@@ -324,6 +362,8 @@ def main() -> int:
         "staged_entry_points": staged,
         "other_workloads": other,
     }
+    if sweep:
+        line["flat_sweep"] = sweep
     print(json.dumps(line))
     return 0
 

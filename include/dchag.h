@@ -137,6 +137,21 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * dchag_forward with the positional embedding added in the epilogue of the last output projection
+ * (paper Section 2.1: the aggregated token of every patch receives positional and metadata tokens before it
+ * enters the ViT; the learned positional embedding is one vector per patch, shared by the batch):
+ *
+ *   out[b,n,:] = dchag_forward(...)[b,n,:] + pos[n,:]          pos [N,D] in, required
+ *
+ * The sum is taken in fp32 before the one rounding of the output; no extra pass over `out` is made.
+ * Everything else as dchag_forward (same workspace, which = 1).
+ */
+int dchag_forward_pos(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
+                      const void *x, const void *We, const void *be, const void *ce,
+                      int n_levels, const dchag_level *levels, const void *pos, void *out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The whole path with the value projection moved behind the softmax-weighted sum (an inference
  * variant; same arguments, same result up to rounding as dchag_forward).  The weights of a softmax
  * sum to one, so for every head a

@@ -85,6 +85,8 @@ def _load():
         lib.oracle_forward.restype = ctypes.c_int
         lib.oracle_forward.argtypes = ([ctypes.c_int] * 7 + [_f32p] * 4 + [ctypes.c_int, ctypes.POINTER(_CLevel)]
                                        + [ctypes.c_int, _i32p, _i32p, _f64p])
+        lib.oracle_add_positional.restype = ctypes.c_int
+        lib.oracle_add_positional.argtypes = [ctypes.c_int] * 3 + [_i32p, _f32p, _f64p]
         lib.oracle_backward.restype = ctypes.c_int
         lib.oracle_backward.argtypes = ([ctypes.c_int] * 7 + [_f32p] * 4 + [ctypes.c_int, ctypes.POINTER(_CLevel)]
                                         + [ctypes.c_int, _i32p, _i32p, _f64p, _f64p, _f64p, _f64p,
@@ -191,8 +193,9 @@ def aggregate_level(z, lv, heads: int, want_alpha: bool = False, want_pre: bool 
     return res[0] if len(res) == 1 else res
 
 
-def forward(x, We, be, ce, levels: Sequence, p: int, heads: int, sample=None) -> np.ndarray:
-    """The whole path on the sampled patches: float64 [S, D] (S = B*N in (b, n) order if sample is None)."""
+def forward(x, We, be, ce, levels: Sequence, p: int, heads: int, sample=None, pos=None) -> np.ndarray:
+    """The whole path on the sampled patches: float64 [S, D] (S = B*N in (b, n) order if sample is None);
+    with pos [N, D] the positional embedding of each patch is added to its output."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     B, C, H, W = x.shape
     We = np.ascontiguousarray(We, dtype=np.float32)
@@ -214,6 +217,11 @@ def forward(x, We, be, ce, levels: Sequence, p: int, heads: int, sample=None) ->
                                 out.ctypes.data_as(_f64p))
     if rc != 0:
         raise ValueError(f"oracle_forward rejected the shape (rc={rc})")
+    if pos is not None:
+        pa, pp_ = _f32(pos, (N, D), keep)
+        rc = _load().oracle_add_positional(N, D, sb.size, sn.ctypes.data_as(_i32p), pp_, out.ctypes.data_as(_f64p))
+        if rc != 0:
+            raise ValueError(f"oracle_add_positional rejected the sample (rc={rc})")
     return out
 
 

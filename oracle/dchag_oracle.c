@@ -274,6 +274,19 @@ int oracle_forward(int B, int C, int H, int W, int p, int D, int heads, const fl
   return 0;
 }
 
+/*
+ * Positional embedding (Section 2.1: before the aggregated tokens enter the ViT they receive a positional
+ * embedding): one learned vector per patch, shared by all batch items, added to the path's output.
+ *   out[i][:] += pos[sample_n[i]][:]          pos is [N, D]
+ */
+int oracle_add_positional(int N, int D, int S, const int32_t *sample_n, const float *pos, double *out) {
+  for (int i = 0; i < S; ++i) {
+    if (sample_n[i] < 0 || sample_n[i] >= N) return -2;
+    for (int d = 0; d < D; ++d) out[(size_t)i * D + d] += (double)pos[(size_t)sample_n[i] * D + d];
+  }
+  return 0;
+}
+
 /* ==========================================================================================
  * Backward pass (the paper trains through this module: Section 3.3 notes that the backward
  * of the partial-channel aggregation needs no communication, i.e. it is the plain reverse of

@@ -107,6 +107,8 @@ def load_library():
     lib.dchag_aggregate_level.argtypes = [i] * 6 + [ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
     lib.dchag_forward.restype = i
     lib.dchag_forward.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, sz, vp]
+    lib.dchag_forward_pos.restype = i
+    lib.dchag_forward_pos.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
     lib.dchag_forward_folded.restype = i
     lib.dchag_forward_folded.argtypes = lib.dchag_forward.argtypes
     lib.dchag_backward.restype = i
@@ -224,6 +226,32 @@ def dchag_forward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor],
     _check(load_library().dchag_forward(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x), _ptr(ce, x),
                                         len(levels), arr, _ptr(out, x), ctypes.c_void_p(workspace.data_ptr()),
                                         workspace.numel(), _stream(stream)))
+    return out
+
+
+def dchag_forward_pos(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                      levels: List[LevelWeights], p: int, heads: int, pos: torch.Tensor,
+                      out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                      stream=None) -> torch.Tensor:
+    """out[B,N,D] = dchag_forward(...) + pos[N,D], the sum taken in the last projection's epilogue."""
+    B, C, H, W = x.shape
+    D = We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    N = (H // p) * (W // p) if p > 0 else 0
+    if tuple(pos.shape) != (N, D):
+        raise ValueError("pos must be [N, D]")
+    dt = _dt(x)
+    if workspace is None:
+        workspace = _workspace(dchag_workspace_bytes(dt, B, C, H, W, p, D, heads, [lv.group_size for lv in levels], 1),
+                               x.device)
+    if out is None:
+        out = torch.empty((B, N, D), dtype=x.dtype, device=x.device)
+    arr = (_CLevel * len(levels))(*[_clevel(lv, x) for lv in levels])
+    _check(load_library().dchag_forward_pos(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x),
+                                            _ptr(ce, x), len(levels), arr, _ptr(pos, x), _ptr(out, x),
+                                            ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                            _stream(stream)))
     return out
 
 

@@ -198,15 +198,15 @@ int launch_tokenize_mfma(int B, int C, int H, int W, int p, int D, const bf16* x
 
 template <typename T>
 int launch_linear_generic(int B, int D, RowBlocks rb, const T* A, const T* Wt, const T* bias, T* Y,
-                          hipStream_t st) {
+                          hipStream_t st, const T* rowadd = nullptr) {
   dim3 grid((D + 63) / 64, (rb.rows_per_group + 63) / 64, B * rb.G);
-  k_linear_generic<T><<<grid, 256, 0, st>>>(D, rb, A, Wt, bias, Y);
+  k_linear_generic<T><<<grid, 256, 0, st>>>(D, rb, A, Wt, bias, Y, rowadd);
   return launch_status();
 }
 
 template <int BM, int BN, int WM, int WN, int SH>
 int launch_linear_mfma_cfg(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, const bf16* bias,
-                           bf16* Y, hipStream_t st) {
+                           bf16* Y, hipStream_t st, const bf16* rowadd = nullptr) {
   TileWork tw;
   tw.n_tiles = D / BN;
   tw.m_tiles = (rb.rows_per_group + BM - 1) / BM;
@@ -222,7 +222,7 @@ int launch_linear_mfma_cfg(int B, int D, RowBlocks rb, const bf16* A, const bf16
       return DCHAG_ERR_LAUNCH;
     attr_set = true;
   }
-  kern<<<dim3(per * kXcds), dim3(WM * WN * 64), lds, st>>>(D, rb, tw, A, Wt, bias, Y);
+  kern<<<dim3(per * kXcds), dim3(WM * WN * 64), lds, st>>>(D, rb, tw, A, Wt, bias, Y, rowadd);
   return launch_status();
 }
 
@@ -233,34 +233,35 @@ int mfma_variant() {
 }
 
 template <typename T>
-int launch_linear(int B, int D, RowBlocks rb, const T* A, const T* Wt, const T* bias, T* Y, hipStream_t st);
+int launch_linear(int B, int D, RowBlocks rb, const T* A, const T* Wt, const T* bias, T* Y, hipStream_t st,
+                  const T* rowadd = nullptr);
 
 template <>
 int launch_linear<float>(int B, int D, RowBlocks rb, const float* A, const float* Wt, const float* bias,
-                         float* Y, hipStream_t st) {
-  return launch_linear_generic<float>(B, D, rb, A, Wt, bias, Y, st);
+                         float* Y, hipStream_t st, const float* rowadd) {
+  return launch_linear_generic<float>(B, D, rb, A, Wt, bias, Y, st, rowadd);
 }
 
 template <>
 int launch_linear<bf16>(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, const bf16* bias, bf16* Y,
-                        hipStream_t st) {
+                        hipStream_t st, const bf16* rowadd) {
   if (D % 256 == 0 && !force_generic()) {
     switch (mfma_variant()) {
-      case 1: return launch_linear_mfma_cfg<256, 256, 2, 4, 0>(B, D, rb, A, Wt, bias, Y, st);
-      case 2: return launch_linear_mfma_cfg<256, 128, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st);
-      case 3: return launch_linear_mfma_cfg<128, 128, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st);
-      case 4: return launch_linear_mfma_cfg<256, 256, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st);
-      default: return launch_linear_mfma_cfg<256, 256, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st);
+      case 1: return launch_linear_mfma_cfg<256, 256, 2, 4, 0>(B, D, rb, A, Wt, bias, Y, st, rowadd);
+      case 2: return launch_linear_mfma_cfg<256, 128, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st, rowadd);
+      case 3: return launch_linear_mfma_cfg<128, 128, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st, rowadd);
+      case 4: return launch_linear_mfma_cfg<256, 256, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st, rowadd);
+      default: return launch_linear_mfma_cfg<256, 256, 2, 2, 0>(B, D, rb, A, Wt, bias, Y, st, rowadd);
     }
   }
-  return launch_linear_generic<bf16>(B, D, rb, A, Wt, bias, Y, st);
+  return launch_linear_generic<bf16>(B, D, rb, A, Wt, bias, Y, st, rowadd);
 }
 
 // One aggregation level: weight-only prep, scores, value projection, softmax-weighted sum,
 // output projection.
 template <typename T>
 int run_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dchag_level* lv, const T* zin,
-              T* zout, unsigned char* ws, hipStream_t st) {
+              T* zout, unsigned char* ws, hipStream_t st, const T* rowadd = nullptr) {
   const int g = lv->group_size;
   const int G = groups_of(Cin, g);
   const LevelWs w = level_ws(dt, B, Cin, N, D, heads, g);
@@ -303,23 +304,24 @@ int run_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dch
   }
   StageTimer tm(DCHAG_STAGE_OPROJ, st);
   RowBlocks rbo{G, G * N, N};
-  return launch_linear<T>(B, D, rbo, O, static_cast<const T*>(lv->Wo), static_cast<const T*>(lv->bo), zout, st);
+  return launch_linear<T>(B, D, rbo, O, static_cast<const T*>(lv->Wo), static_cast<const T*>(lv->bo), zout, st,
+                          rowadd);
 }
 
 int launch_linear_dl(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, const bf16* bias, bf16* Y,
-                     hipStream_t st) {
+                     hipStream_t st, const bf16* rowadd = nullptr) {
   TileWork tw;
   tw.n_tiles = D / kGemmBN;
   tw.m_tiles = (rb.rows_per_group + kGemmBM - 1) / kGemmBM;
   tw.nb = B;
   tw.total = tw.n_tiles * tw.m_tiles * B * rb.G;
   if (tw.total * 2 < compute_units())                    // too few 256x256 tiles to fill the chip: 128x128 tiles
-    return launch_linear_mfma_cfg<128, 128, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st);
+    return launch_linear_mfma_cfg<128, 128, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st, rowadd);
   const int per = (tw.total + kXcds - 1) / kXcds;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_linear_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
                           kGemmRingBytes) != hipSuccess)
     return DCHAG_ERR_LAUNCH;
-  k_linear_dl<<<dim3(per * kXcds), dim3(512), kGemmRingBytes, st>>>(D, rb, tw, A, Wt, bias, Y);
+  k_linear_dl<<<dim3(per * kXcds), dim3(512), kGemmRingBytes, st>>>(D, rb, tw, A, Wt, bias, Y, rowadd);
   return launch_status();
 }
 
@@ -433,7 +435,7 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
 // from the pixels at the first level of a forward call), softmax over the group, value projection
 // fused with the weighted sum over the group, output projection.
 int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, bf16* zout,
-                   unsigned char* ws, hipStream_t st, const PixelScores* px = nullptr) {
+                   unsigned char* ws, hipStream_t st, const PixelScores* px = nullptr, const bf16* rowadd = nullptr) {
   const int g = lv->group_size;
   const int G = groups_of(Cin, g);
   const int gpad = round_up(g, 8), Np = round_up(N, 32);
@@ -467,7 +469,8 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
   }
   StageTimer tm(DCHAG_STAGE_OPROJ, st);
   RowBlocks rbo{G, G * N, N};
-  return launch_linear_dl(B, D, rbo, O, static_cast<const bf16*>(lv->Wo), static_cast<const bf16*>(lv->bo), zout, st);
+  return launch_linear_dl(B, D, rbo, O, static_cast<const bf16*>(lv->Wo), static_cast<const bf16*>(lv->bo), zout, st,
+                          rowadd);
 }
 
 // A linear (D-CHAG-L) level: one memory-bound mixing kernel, no workspace.
@@ -635,9 +638,11 @@ int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int head
                          static_cast<bf16*>(tokens_out), ws, st);
 }
 
-int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
-                  const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
-                  void* out, void* workspace, size_t workspace_bytes, void* stream) {
+// dchag_forward and dchag_forward_pos: pos (or NULL) is added to the output in the epilogue of the last level's
+// output projection.
+static int forward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                        const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                        const void* pos, void* out, void* workspace, size_t workspace_bytes, void* stream) {
   if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
   if (!x || !We || !out || !levels) return DCHAG_ERR_NULL;
   if (n_levels < 1 || n_levels > 16) return DCHAG_ERR_SHAPE;
@@ -653,7 +658,8 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     c_in = groups_of(c_in, gs[l]);
   }
   if (c_in != 1 || levels[n_levels - 1].kind != DCHAG_LEVEL_ATTENTION) return DCHAG_ERR_SHAPE;
-  if (misaligned(x) || misaligned(We) || misaligned(be) || misaligned(ce) || misaligned(out)) return DCHAG_ERR_ALIGN;
+  if (misaligned(x) || misaligned(We) || misaligned(be) || misaligned(ce) || misaligned(out) || misaligned(pos))
+    return DCHAG_ERR_ALIGN;
   const ForwardWs w = forward_ws(dt, B, C, N, p * p, D, heads, n_levels, gs);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
       workspace_bytes < w.total)
@@ -693,6 +699,7 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
   for (int l = first; l < n_levels; ++l) {
     g_level = l + 1;
     void* zout = (l + 1 == n_levels) ? out : static_cast<void*>(ws + ((l & 1) ? w.pong : w.ping));
+    const void* rowadd = (l + 1 == n_levels) ? pos : nullptr;
     if (levels[l].kind == DCHAG_LEVEL_LINEAR)
       rc = (dt == DCHAG_F32) ? run_level_linear<float>(B, c_in, N, D, &levels[l], static_cast<const float*>(zin),
                                                        static_cast<float*>(zout), st)
@@ -700,7 +707,7 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
                                                       static_cast<bf16*>(zout), st);
     else if (dt == DCHAG_F32)
       rc = run_level<float>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const float*>(zin),
-                            static_cast<float*>(zout), ws + w.level, st);
+                            static_cast<float*>(zout), ws + w.level, st, static_cast<const float*>(rowadd));
     else if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL")) {
       PixelScores px{static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
                      static_cast<const bf16*>(ce), H, W, p, reinterpret_cast<float*>(ws + w.ms),
@@ -708,16 +715,32 @@ int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
                      reinterpret_cast<bf16*>(ws + w.msb)};
       const bool use_px = (l == 0) && pixel_scores_ok(p, heads);
       rc = run_level_fast(B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
-                          static_cast<bf16*>(zout), ws + w.level, st, use_px ? &px : nullptr);
+                          static_cast<bf16*>(zout), ws + w.level, st, use_px ? &px : nullptr,
+                          static_cast<const bf16*>(rowadd));
     }
     else
       rc = run_level<bf16>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
-                           static_cast<bf16*>(zout), ws + w.level, st);
+                           static_cast<bf16*>(zout), ws + w.level, st, static_cast<const bf16*>(rowadd));
     if (rc) return rc;
     zin = zout;
     c_in = groups_of(c_in, gs[l]);
   }
   return DCHAG_OK;
+}
+
+int dchag_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                  const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                  void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_impl(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, nullptr, out, workspace,
+                      workspace_bytes, stream);
+}
+
+int dchag_forward_pos(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                      const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                      const void* pos, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!pos) return DCHAG_ERR_NULL;
+  return forward_impl(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, pos, out, workspace,
+                      workspace_bytes, stream);
 }
 
 // Shared argument checks of the calls that take the whole chain of levels; fills gs / kinds.

@@ -618,12 +618,12 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
 }
 
 // ---------------------------------------------------------------------------------------------
-// Plain per-group projection  Y[r][o] = sum_j A[r][j] * Wt[k][o][j] + bias[k][o]  on the same core.
+// Plain per-group projection  Y[r][o] = sum_j A[r][j] * Wt[k][o][j] + bias[k][o] (+ rowadd[r][o])  on the same core.
 // Requires D % 256 == 0.  Dynamic LDS: the ring (128 KiB).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork tw, const bf16* __restrict__ A,
                                                    const bf16* __restrict__ Wt, const bf16* __restrict__ bias,
-                                                   bf16* __restrict__ Y) {
+                                                   bf16* __restrict__ Y, const bf16* __restrict__ rowadd) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   int k, b, mt, nt;
   if (!tw.decode(blockIdx.x, k, b, mt, nt)) return;
@@ -681,7 +681,8 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = r0 + L.wm * 128 + i * 32 + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
-        if (row < rows) Yb[(size_t)row * D + col] = (bf16)(acc[i][j][r] + bvv);
+        if (row < rows)
+          Yb[(size_t)row * D + col] = (bf16)(acc[i][j][r] + bvv + (rowadd ? (float)rowadd[(size_t)row * D + col] : 0.f));
       }
   }
 }

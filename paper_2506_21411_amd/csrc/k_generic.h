@@ -119,13 +119,14 @@ __global__ __launch_bounds__(256) void k_tokenize_generic(int C, int H, int W, i
 }
 
 // ---------------------------------------------------------------------------------------
-// Batched projection  Y[r][o] = sum_j A[r][j] * Wt[k][o][j] + bias[k][o]   (64x64 tile, fp32 FMA)
+// Batched projection  Y[r][o] = sum_j A[r][j] * Wt[k][o][j] + bias[k][o] (+ rowadd[r][o], r counted inside the
+// batch item's row block: a per-row addend such as a positional embedding)   (64x64 tile, fp32 FMA)
 // grid (ceil(D/64), ceil(max rows/64), B*G), block 256 (16x16 threads, 4x4 outputs each)
 // ---------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_linear_generic(int D, RowBlocks rb, const T* __restrict__ A,
                                                         const T* __restrict__ Wt, const T* __restrict__ bias,
-                                                        T* __restrict__ Y) {
+                                                        T* __restrict__ Y, const T* __restrict__ rowadd) {
   __shared__ float As[16][64 + 1];
   __shared__ float Ws[16][64 + 1];
   const int b = blockIdx.z / rb.G, k = blockIdx.z % rb.G;
@@ -170,7 +171,9 @@ __global__ __launch_bounds__(256) void k_linear_generic(int D, RowBlocks rb, con
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int o = o0 + tx * 4 + j;
-      if (o < D) Yb[(size_t)r * D + o] = from_f32<T>(acc[i][j] + (bias ? to_f32(bias[(size_t)k * D + o]) : 0.f));
+      if (o < D)
+        Yb[(size_t)r * D + o] = from_f32<T>(acc[i][j] + (bias ? to_f32(bias[(size_t)k * D + o]) : 0.f) +
+                                            (rowadd ? to_f32(rowadd[(size_t)r * D + o]) : 0.f));
     }
   }
 }

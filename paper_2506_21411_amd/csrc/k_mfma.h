@@ -44,7 +44,7 @@ struct TileWork {
 };
 
 // ---------------------------------------------------------------------------------------
-// Y[r][o] = sum_j A[r][j] * Wt[k][o][j] + bias[k][o]       bf16 in/out, fp32 accumulate
+// Y[r][o] = sum_j A[r][j] * Wt[k][o][j] + bias[k][o] (+ rowadd[r][o], r inside the row block)   bf16, fp32 accumulate
 //   BM x BN block tile, WM x WN wavefronts, each a (BM/WM) x (BN/WN) tile of 32x32 MFMA blocks.
 //   Requires D % 64 == 0 and D % BN == 0 (checked on the host); rows are ragged (clamped loads,
 //   masked stores).  Dynamic LDS: 2 stages x (BM + BN) x 128 bytes.
@@ -54,7 +54,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_linear_mfma(int D, RowBlocks r
                                                               const bf16* __restrict__ A,
                                                               const bf16* __restrict__ Wt,
                                                               const bf16* __restrict__ bias,
-                                                              bf16* __restrict__ Y) {
+                                                              bf16* __restrict__ Y,
+                                                              const bf16* __restrict__ rowadd) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;   // 16-byte chunks per thread per stage
@@ -159,7 +160,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_linear_mfma(int D, RowBlocks r
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = r0 + wm * (BM / WM) + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-        if (row < rows) Yb[(size_t)row * D + o] = (bf16)(acc[i][j][r] + bv);
+        if (row < rows)
+          Yb[(size_t)row * D + o] = (bf16)(acc[i][j][r] + bv + (rowadd ? (float)rowadd[(size_t)row * D + o] : 0.f));
       }
     }
   }

@@ -30,7 +30,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"dchag_tokenize", "dchag_aggregate_level", "dchag_forward", "dchag_workspace_bytes",
-            "dchag_strerror", "dchag_version", "dchag_forward_folded", "dchag_backward"} <= set(names)
+            "dchag_strerror", "dchag_version", "dchag_forward_folded", "dchag_backward",
+            "dchag_forward_pos"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in dchag.h but not exported"
 
@@ -112,6 +113,16 @@ def test_forward_folded_and_backward_validation(lib):
     assert bw(*bargs(two, 2, ws=None)) == -4
     gr[1].dWv = FAKE + 2
     assert bw(*bargs(two, 2)) == -6                                                     # misaligned gradient
+
+
+def test_forward_pos_validation(lib):
+    two = (_CLevel * 2)(level(4), level(2))
+    f = lib.dchag_forward_pos
+    args = lambda pos, out=FAKE: (0, 1, 8, 32, 64, 4, 128, 4, FAKE, FAKE, None, None, 2, two, pos, out, FAKE, 1 << 40,
+                                  None)
+    assert f(*args(None)) == -1                       # the positional embedding is required by this call
+    assert f(*args(FAKE + 2)) == -6
+    assert f(*args(FAKE, out=None)) == -1
 
 
 def test_workspace_bytes(lib):

@@ -318,6 +318,47 @@ def test_forward_is_deterministic():
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", B=2, C=7, H=8, W=12, p=2, D=32, heads=4, group_sizes=(3, 2, 2)),      # generic projection
+    dict(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3)),     # 128 x 128 MFMA tiles
+    dict(dtype="bf16", B=1, C=6, H=8, W=8, p=2, D=64, heads=2, group_sizes=(2, 2, 2)),      # generic bf16 path
+    dict(dtype="bf16", B=3, C=4, H=160, W=192, p=8, D=256, heads=4, group_sizes=(4,)),      # N = 480: 256 x 256 tiles, ragged
+])
+def test_forward_with_positional_embedding_matches_oracle(kw):
+    cfg = cfg_of(**kw)
+    say(f"forward + positional embedding {kw}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    pos = np.random.Generator(np.random.PCG64(31)).standard_normal((cfg.N, cfg.D)).astype(np.float32)
+    if d == "bf16":
+        from workloads import round_to_bf16
+        pos = round_to_bf16(pos)
+    out = dchag.dchag_forward_pos(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
+                                  [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads, dev(pos, d))
+    torch.cuda.synchronize()
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, pos=pos).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[d]
+
+
+def test_forward_with_positional_embedding_full_size():
+    cfg = get_config("hyperspectral")
+    pr = make_problem(cfg)
+    from workloads import round_to_bf16
+    pos = round_to_bf16(np.random.Generator(np.random.PCG64(32)).standard_normal((cfg.N, cfg.D)).astype(np.float32))
+    d = "bf16"
+    out = dchag.dchag_forward_pos(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
+                                  [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads, dev(pos, d))
+    torch.cuda.synchronize()
+    bs, ns = sample_patches(cfg.B, cfg.N, 4, seed=18)
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns), pos=pos)
+    got = host(out[torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()])
+    err = rel_err(got, want)
+    say(f"full-size positional: err={err:.3e}")
+    assert err < TOL["bf16"]
+
+
 def test_forward_can_be_captured_in_a_graph_and_replayed():
     """dchag_forward allocates nothing and synchronises nothing, so a caller may capture it in a HIP graph.
     Every replay, with eager work and synchronisations in between, must reproduce the eager result bit for bit."""

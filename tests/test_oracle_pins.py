@@ -423,3 +423,19 @@ def test_oracle_rejects_bad_shapes():
         oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, 3)                   # D % heads
     with pytest.raises(ValueError):
         oracle.tokenize(pr.x[:, :, :3], pr.We, pr.be, pr.ce, cfg.p)                      # H % p
+
+
+def test_positional_embedding_is_added_per_patch_and_shared_by_the_batch():
+    """Section 2.1: the aggregated token of a patch receives that patch's positional embedding."""
+    cfg = small_cfg()
+    pr = make_problem(cfg)
+    pos = np.random.default_rng(3).standard_normal((cfg.N, cfg.D)).astype(np.float32)
+    plain = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads)
+    withp = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, pos=pos)
+    want = plain.reshape(cfg.B, cfg.N, cfg.D) + f64(pos)[None]
+    np.testing.assert_allclose(withp.reshape(cfg.B, cfg.N, cfg.D), want, rtol=0, atol=1e-15)
+    # a sample in another order picks the rows of its own patches
+    sb = np.array([1, 0, 1], dtype=np.int32)
+    sn = np.array([cfg.N - 1, 2, 0], dtype=np.int32)
+    some = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(sb, sn), pos=pos)
+    np.testing.assert_allclose(some, want[sb, sn], rtol=0, atol=1e-15)
