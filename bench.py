@@ -286,6 +286,28 @@ def main() -> int:
         other.append({"workload": "hyperspectral", "call": "dchag_backward (recomputes the forward)",
                       "tokens": cfg.tokens, "ms_per_step": round(msb, 4), "value": cfg.tokens / (msb * 1e-3),
                       "unit": "tokens/s"})
+        # a training step that keeps its activations: dchag_forward_keep + dchag_backward_kept on one workspace
+        bw = mode["bwd"]
+        xk, Wk_, bk_, ck_, lvk, _, outk = t
+
+        def train_step():
+            dchag.dchag_forward_keep(xk, Wk_, bk_, ck_, lvk, cfg.p, cfg.heads, bw["ws"], out=outk)
+            dchag.dchag_backward(xk, Wk_, bk_, ck_, lvk, cfg.p, cfg.heads, bw["dout"], bw["grads"], dx=bw["dx"],
+                                 dWe=bw["dWe"], dtok_bias=bw["dtb"], workspace=bw["ws"], kept=True)
+        for _ in range(2):
+            train_step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            train_step()
+        e1.record()
+        torch.cuda.synchronize()
+        mst = e0.elapsed_time(e1) / 5
+        other.append({"workload": "hyperspectral", "call": "dchag_forward_keep + dchag_backward_kept (one training step)",
+                      "tokens": cfg.tokens, "ms_per_step": round(mst, 4), "value": cfg.tokens / (mst * 1e-3),
+                      "unit": "tokens/s"})
+        del xk, Wk_, bk_, ck_, lvk, outk, bw
         mode["name"], mode["bwd"] = "forward", None
         # the forward with the positional embedding added in the last projection's epilogue
         xx, Wee, bee, cee, lvls, wss, outt = t

@@ -208,11 +208,32 @@ int dchag_backward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * A training step without the recomputation: dchag_forward_keep is dchag_forward_folded that leaves, in a
+ * workspace of dchag_backward's size and layout (which = 3), everything the reverse sweep reads (tokens; per
+ * level its inputs, folded keys, softmax weights, per-head token averages, pre-projection outputs), and
+ * dchag_backward_kept is the reverse sweep alone.  dchag_backward_kept must be given the same arguments and the
+ * workspace of the dchag_forward_keep call, untouched in between (the library cannot check that); any number of
+ * dchag_backward_kept calls (different dout) may follow one dchag_forward_keep.  Results equal those of
+ * dchag_forward_folded and dchag_backward bit for bit.  For callers that keep activations between the two passes,
+ * as training loops do; the paper describes the two passes of its module (Section 3.3), not how they share state.
+ */
+int dchag_forward_keep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
+                       const void *x, const void *We, const void *be, const void *ce,
+                       int n_levels, const dchag_level *levels, void *out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+int dchag_backward_kept(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
+                        const void *x, const void *We, const void *be, const void *ce,
+                        int n_levels, const dchag_level *levels, const void *dout,
+                        void *dx, void *dWe, void *dtok_bias, const dchag_level_grads *grads,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Workspace size in bytes (0 on invalid arguments).
  *   which = 0: one dchag_aggregate_level call with Cin = C inputs, N = (H/p)*(W/p)
  *              (pass H = N, W = 1, p = 1 when only N is known), group size group_sizes[0];
  *   which = 1: one dchag_forward call with the n_levels nominal group sizes;
- *   which = 2: one dchag_forward_folded call;   which = 3: one dchag_backward call.
+ *   which = 2: one dchag_forward_folded call;   which = 3: one dchag_backward call, or a
+ *              dchag_forward_keep / dchag_backward_kept pair.
  */
 size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
                              int n_levels, const int32_t *group_sizes, int which);

@@ -114,6 +114,10 @@ def load_library():
     lib.dchag_backward.restype = i
     lib.dchag_backward.argtypes = ([i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, vp, vp,
                                                         ctypes.POINTER(_CLevelGrads), vp, sz, vp])
+    lib.dchag_forward_keep.restype = i
+    lib.dchag_forward_keep.argtypes = lib.dchag_forward.argtypes
+    lib.dchag_backward_kept.restype = i
+    lib.dchag_backward_kept.argtypes = lib.dchag_backward.argtypes
     lib.dchag_workspace_bytes.restype = sz
     lib.dchag_workspace_bytes.argtypes = [i] * 9 + [ctypes.POINTER(ctypes.c_int32), i]
     lib.dchag_strerror.restype = ctypes.c_char_p
@@ -278,12 +282,32 @@ def dchag_forward_folded(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.T
     return out
 
 
+def dchag_forward_keep(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                       levels: List[LevelWeights], p: int, heads: int, workspace: torch.Tensor,
+                       out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """out[B,N,D] as dchag_forward_folded; `workspace` (dchag_workspace_bytes(..., 3) bytes) keeps what
+    dchag_backward_kept reads."""
+    B, C, H, W = x.shape
+    D = We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    N = (H // p) * (W // p) if p > 0 else 0
+    if out is None:
+        out = torch.empty((B, N, D), dtype=x.dtype, device=x.device)
+    arr = (_CLevel * len(levels))(*[_clevel(lv, x) for lv in levels])
+    _check(load_library().dchag_forward_keep(_dt(x), B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x),
+                                             _ptr(ce, x), len(levels), arr, _ptr(out, x),
+                                             ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+    return out
+
+
 def dchag_backward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
                    levels: List[LevelWeights], p: int, heads: int, dout: torch.Tensor,
                    grads: List[LevelGrads], dx: Optional[torch.Tensor] = None, dWe: Optional[torch.Tensor] = None,
                    dtok_bias: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                   stream=None) -> None:
-    """Writes the gradients of <dout, dchag_forward(...)> into the given tensors (None = not wanted)."""
+                   stream=None, kept: bool = False) -> None:
+    """Writes the gradients of <dout, dchag_forward(...)> into the given tensors (None = not wanted).
+    kept=True calls dchag_backward_kept: `workspace` must be the one a dchag_forward_keep call just filled."""
     B, C, H, W = x.shape
     D = We.shape[1]
     if tuple(We.shape) != (C, D, p * p):
@@ -299,10 +323,12 @@ def dchag_backward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor]
     for j, g in enumerate(grads):
         for name in ("dquery", "dWq", "dWk", "dWv", "dWo", "dbq", "dbk", "dbv", "dbo"):
             setattr(garr[j], name, _ptr(getattr(g, name), x))
-    _check(load_library().dchag_backward(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x), _ptr(ce, x),
-                                         len(levels), arr, _ptr(dout, x), _ptr(dx, x), _ptr(dWe, x),
-                                         _ptr(dtok_bias, x), garr, ctypes.c_void_p(workspace.data_ptr()),
-                                         workspace.numel(), _stream(stream)))
+    if kept and workspace is None:
+        raise ValueError("kept=True needs the workspace of the dchag_forward_keep call")
+    fn = load_library().dchag_backward_kept if kept else load_library().dchag_backward
+    _check(fn(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x), _ptr(ce, x),
+              len(levels), arr, _ptr(dout, x), _ptr(dx, x), _ptr(dWe, x), _ptr(dtok_bias, x), garr,
+              ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
 
 
 def dchag_profile_begin() -> None:

@@ -786,33 +786,67 @@ int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int 
   return forward_folded_impl<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out, ws, w, st);
 }
 
+// which: 1 = forward that keeps, 2 = reverse sweep, 3 = both (dchag_backward)
+static int train_call(int which, dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                      const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels, void* out,
+                      const void* dout, void* dx, void* dWe, void* dtok_bias, const dchag_level_grads* grads,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t gs[16], kinds[16];
+  int rc = check_chain(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, kinds);
+  if (rc) return rc;
+  if ((which & 2) && (!dout || !grads)) return DCHAG_ERR_NULL;
+  if (which == 1 && !out) return DCHAG_ERR_NULL;
+  if (misaligned(out) || misaligned(dout) || misaligned(dx) || misaligned(dWe) || misaligned(dtok_bias))
+    return DCHAG_ERR_ALIGN;
+  if (which & 2)
+    for (int l = 0; l < n_levels; ++l) {
+      const void* ps[] = {grads[l].dquery, grads[l].dWq, grads[l].dWk, grads[l].dWv, grads[l].dWo,
+                          grads[l].dbq,    grads[l].dbk, grads[l].dbv, grads[l].dbo};
+      for (const void* q : ps)
+        if (misaligned(q)) return DCHAG_ERR_ALIGN;
+    }
+  const int N = (H / p) * (W / p);
+  const BackwardWs w = backward_ws(dt, B, C, N, p * p, D, heads, n_levels, gs, kinds);
+  // a keep / reverse pair shares one workspace, so both are held to the size dchag_workspace_bytes reports
+  const size_t need = which == 3 ? w.total : backward_ws(dt, B, C, N, p * p, D, heads, n_levels, gs, nullptr).total;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 || workspace_bytes < need)
+    return DCHAG_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  if (which & 1) {
+    rc = dt == DCHAG_F32 ? keep_forward<float>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out, ws, w, st)
+                         : keep_forward<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out, ws, w, st);
+    if (rc) return rc;
+  }
+  if (which & 2)
+    rc = dt == DCHAG_F32 ? reverse_sweep<float>(dt, B, C, H, W, p, D, heads, x, We, n_levels, levels, gs, dout, dx, dWe,
+                                                dtok_bias, grads, ws, w, st)
+                         : reverse_sweep<bf16>(dt, B, C, H, W, p, D, heads, x, We, n_levels, levels, gs, dout, dx, dWe,
+                                               dtok_bias, grads, ws, w, st);
+  return rc;
+}
+
 int dchag_backward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
                    const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
                    const void* dout, void* dx, void* dWe, void* dtok_bias, const dchag_level_grads* grads,
                    void* workspace, size_t workspace_bytes, void* stream) {
-  int32_t gs[16], kinds[16];
-  int rc = check_chain(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, kinds);
-  if (rc) return rc;
-  if (!dout || !grads) return DCHAG_ERR_NULL;
-  if (misaligned(dout) || misaligned(dx) || misaligned(dWe) || misaligned(dtok_bias)) return DCHAG_ERR_ALIGN;
-  for (int l = 0; l < n_levels; ++l) {
-    const void* ps[] = {grads[l].dquery, grads[l].dWq, grads[l].dWk, grads[l].dWv, grads[l].dWo,
-                        grads[l].dbq,    grads[l].dbk, grads[l].dbv, grads[l].dbo};
-    for (const void* q : ps)
-      if (misaligned(q)) return DCHAG_ERR_ALIGN;
-  }
-  const int N = (H / p) * (W / p);
-  const BackwardWs w = backward_ws(dt, B, C, N, p * p, D, heads, n_levels, gs, kinds);
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
-      workspace_bytes < w.total)
-    return DCHAG_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  if (dt == DCHAG_F32)
-    return backward_impl<float>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, dout, dx, dWe,
-                                dtok_bias, grads, ws, w, st);
-  return backward_impl<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, dout, dx, dWe,
-                             dtok_bias, grads, ws, w, st);
+  return train_call(3, dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, nullptr, dout, dx, dWe, dtok_bias,
+                    grads, workspace, workspace_bytes, stream);
+}
+
+int dchag_forward_keep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                       const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                       void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return train_call(1, dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, out, nullptr, nullptr, nullptr,
+                    nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+int dchag_backward_kept(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                        const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                        const void* dout, void* dx, void* dWe, void* dtok_bias, const dchag_level_grads* grads,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  return train_call(2, dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, nullptr, dout, dx, dWe, dtok_bias,
+                    grads, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

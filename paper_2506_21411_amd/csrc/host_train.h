@@ -643,39 +643,57 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
   return DCHAG_OK;
 }
 
+// The two halves of a training step.  keep_forward fills the workspace with what the reverse sweep reads
+// (tokens, and per level: inputs, folded keys, softmax weights, per-head token averages, pre-projection outputs)
+// and, if asked, writes the path's output; reverse_sweep walks the levels backwards over that workspace.
 template <typename T>
-int backward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x, const void* We,
-                  const void* be, const void* ce, int n_levels, const dchag_level* levels, const int32_t* gs,
-                  const void* dout, void* dx, void* dWe, void* dtok_bias, const dchag_level_grads* grads,
-                  unsigned char* ws, const BackwardWs& w, hipStream_t st) {
+int keep_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x, const void* We,
+                 const void* be, const void* ce, int n_levels, const dchag_level* levels, const int32_t* gs, void* out,
+                 unsigned char* ws, const BackwardWs& w, hipStream_t st) {
   const int N = (H / p) * (W / p);
-  // forward sweep, keeping alpha, u, o (and the inputs) of every level
   g_level = 0;
   int rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st);
   if (rc) return rc;
   const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
+  const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
+  int c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    g_level = l + 1;
+    const bool linear = levels[l].kind == DCHAG_LEVEL_LINEAR, last = l + 1 == n_levels;
+    const KeptLevel kl = kept_level(dt, B, c_in, N, D, heads, gs[l], linear, !last);
+    unsigned char* lw = ws + w.kept[l];
+    T* y = last ? static_cast<T*>(out) : reinterpret_cast<T*>(lw + kl.y);     // out may be NULL: the reverse sweep
+    if (linear)                                                               // does not read the last output
+      rc = run_level_linear<T>(B, c_in, N, D, &levels[l], zin, y, st);
+    else
+      rc = folded_level_forward<T>(dt, B, c_in, N, D, heads, &levels[l], zin, y, level_bufs<T>(lw, kl), st,
+                                   (l == 0 && use_px) ? &px : nullptr);
+    if (rc) return rc;
+    c_in = groups_of(c_in, gs[l]);
+    zin = y;
+  }
+  return DCHAG_OK;
+}
+
+template <typename T>
+int reverse_sweep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x, const void* We,
+                  int n_levels, const dchag_level* levels, const int32_t* gs, const void* dout, void* dx, void* dWe,
+                  void* dtok_bias, const dchag_level_grads* grads, unsigned char* ws, const BackwardWs& w,
+                  hipStream_t st) {
+  const int N = (H / p) * (W / p);
   const T* zins[16];
   KeptLevel kl[16];
   int cins[17];
   cins[0] = C;
   zins[0] = reinterpret_cast<const T*>(ws + w.tokens);
   for (int l = 0; l < n_levels; ++l) {
-    g_level = l + 1;
     const bool linear = levels[l].kind == DCHAG_LEVEL_LINEAR, last = l + 1 == n_levels;
     kl[l] = kept_level(dt, B, cins[l], N, D, heads, gs[l], linear, !last);
-    unsigned char* lw = ws + w.kept[l];
-    T* y = last ? nullptr : reinterpret_cast<T*>(lw + kl[l].y);
-    if (linear)
-      rc = run_level_linear<T>(B, cins[l], N, D, &levels[l], zins[l], y, st);
-    else
-      rc = folded_level_forward<T>(dt, B, cins[l], N, D, heads, &levels[l], zins[l], y, level_bufs<T>(lw, kl[l]), st,
-                                   (l == 0 && use_px) ? &px : nullptr);
-    if (rc) return rc;
     cins[l + 1] = groups_of(cins[l], gs[l]);
-    zins[l + 1] = y;
+    zins[l + 1] = last ? nullptr : reinterpret_cast<const T*>(ws + w.kept[l] + kl[l].y);
   }
-  // reverse sweep
+  int rc;
   const T* dy = static_cast<const T*>(dout);
   for (int l = n_levels - 1; l >= 0; --l) {
     g_level = l + 1;

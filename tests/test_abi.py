@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"dchag_tokenize", "dchag_aggregate_level", "dchag_forward", "dchag_workspace_bytes",
             "dchag_strerror", "dchag_version", "dchag_forward_folded", "dchag_backward",
-            "dchag_forward_pos"} <= set(names)
+            "dchag_forward_pos", "dchag_forward_keep", "dchag_backward_kept"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in dchag.h but not exported"
 
@@ -113,6 +113,12 @@ def test_forward_folded_and_backward_validation(lib):
     assert bw(*bargs(two, 2, ws=None)) == -4
     gr[1].dWv = FAKE + 2
     assert bw(*bargs(two, 2)) == -6                                                     # misaligned gradient
+    gr[1].dWv = FAKE
+    bk, fk = lib.dchag_backward_kept, lib.dchag_forward_keep
+    assert bk(*bargs(two, 2, dout=None)) == -1
+    assert bk(*bargs(two, 2, wsb=4096)) == -4
+    assert fk(*args(two, 2, wsb=4096)) == -4
+    assert fk(0, 1, 8, 32, 64, 4, 128, 4, FAKE, FAKE, None, None, 2, two, None, FAKE, 1 << 40, None) == -1   # out
 
 
 def test_forward_pos_validation(lib):

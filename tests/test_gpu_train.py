@@ -196,6 +196,46 @@ def test_backward_generic_bf16_kernels_still_match(monkeypatch, env):
     compare_grads(cfg, pr, got, want, TOL["bf16"], np.repeat(np.arange(cfg.B), cfg.N), np.tile(np.arange(cfg.N), cfg.B))
 
 
+@pytest.mark.parametrize("kw", [SMALL[0], SMALL[3], SMALL[4], SMALL[10]])
+def test_forward_keep_and_backward_kept_equal_the_recomputing_calls(kw):
+    """A training step that keeps its activations: the output equals dchag_forward_folded's and every gradient
+    equals dchag_backward's bit for bit (same kernels on the same buffers), for two upstream gradients in a row
+    after one forward."""
+    cfg = cfg_of(**kw)
+    say(f"keep / kept {kw}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    x, We, be, ce = dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d)
+    lv_dev = [dev_level(lv, d) for lv in pr.levels]
+    dt = dchag.DCHAG_F32 if d == "f32" else dchag.DCHAG_BF16
+    wsb = dchag.dchag_workspace_bytes(dt, cfg.B, cfg.C, cfg.H, cfg.W, cfg.p, cfg.D, cfg.heads, list(cfg.group_sizes), 3)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    out = dchag.dchag_forward_keep(x, We, be, ce, lv_dev, cfg.p, cfg.heads, ws)
+    ref = dchag.dchag_forward_folded(x, We, be, ce, lv_dev, cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    assert rel_err(host(out), want) < TOL[d]
+    for seed in (51, 52):
+        dout = np.random.Generator(np.random.PCG64(seed)).standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32)
+        a = run_backward(pr, dout)                                    # recomputes the forward
+        grads = []
+        for lv in lv_dev:
+            if lv.kind == 1:
+                grads.append(dchag.LevelGrads(dWv=torch.full_like(lv.Wv, 7.0), dbv=torch.full_like(lv.bv, 7.0)))
+            else:
+                grads.append(dchag.LevelGrads(**{"d" + n: torch.full_like(getattr(lv, n), 7.0) for n in ATT}))
+        dx, dWe, dtb = torch.full_like(x, 7.0), torch.full_like(We, 7.0), torch.full_like(ce, 7.0)
+        dchag.dchag_backward(x, We, be, ce, lv_dev, cfg.p, cfg.heads, dev(dout, d), grads, dx=dx, dWe=dWe, dtok_bias=dtb,
+                             workspace=ws, kept=True)
+        torch.cuda.synchronize()
+        assert torch.equal(dx, a[0]) and torch.equal(dWe, a[1]) and torch.equal(dtb, a[2])
+        for g, h in zip(grads, a[3]):
+            for n in ("dquery", "dWq", "dWk", "dWv", "dWo", "dbq", "dbk", "dbv", "dbo"):
+                if getattr(g, n) is not None:
+                    assert torch.equal(getattr(g, n), getattr(h, n)), n
+
+
 def test_backward_skips_gradients_that_are_not_asked_for():
     cfg = cfg_of(dtype="f32", B=1, C=6, H=8, W=8, p=2, D=32, heads=4, group_sizes=(3, 2))
     pr = make_problem(cfg)
