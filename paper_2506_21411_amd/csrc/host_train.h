@@ -12,9 +12,9 @@ struct KeptLevel {
   size_t qp, mf, mb, alpha_f, alpha, u, o, y, total;
 };
 
-// The bf16 kernels of this file keep one fp32 value per head and lane: 16 heads at most.
+// Shapes whose scores go through the score kernels of the bf16 forward path.
 inline bool train_fast(dchag_dtype dt, int D, int heads) {
-  return fast_level(dt, D, heads) && heads <= 16 && !getenv("DCHAG_GENERIC_LEVEL");
+  return fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL");
 }
 
 inline KeptLevel kept_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g, bool linear,
@@ -290,7 +290,7 @@ inline int head_sums(int B, int Cin, int N, int D, int heads, int g, const float
 inline int head_sums(int B, int Cin, int N, int D, int heads, int g, const float* alpha, const bf16* z, bf16* u,
                      hipStream_t st) {
   const size_t lds = (size_t)std::min(g, Cin) * 16 * 4;
-  if (heads <= 16 && D % 4 == 0 && lds <= 160 * 1024 - 4096 && !getenv("DCHAG_GENERIC_LEVEL")) {
+  if (D % 4 == 0 && lds <= 160 * 1024 - 4096 && !getenv("DCHAG_GENERIC_LEVEL")) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_sums_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
       return DCHAG_ERR_LAUNCH;
@@ -457,15 +457,17 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
   const int G = groups_of(Cin, g);
   const int pt = dz_patches(B, G, N, D, g);
   const size_t lds = (size_t)2 * pt * g * 16 * 4;
-  if (heads > 16 || D % 4 || lds > 128 * 1024 || getenv("DCHAG_GENERIC_LEVEL"))
+  const bool mfma = D % 256 == 0 && heads <= 32 && !getenv("DCHAG_DZ_VALU");
+  if ((!mfma && heads > 16) || D % 4 || lds > 128 * 1024 || getenv("DCHAG_GENERIC_LEVEL"))
     return tokens_backward_generic<bf16>(B, Cin, N, D, heads, g, zin, w, alpha, ds, Mf, dz, r, want_r, st);
   const int n_tiles = (N + pt - 1) / pt;
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_BWD_TOKENS, st);
     const dim3 grid((unsigned)(n_tiles * ((D + 1023) / 1024)), G, B);
-    if (D % 256 == 0 && !getenv("DCHAG_DZ_VALU")) {
-      k_dz_mfma<<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
+    if (mfma) {
+      if (heads <= 16) k_dz_mfma<1><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
+      else k_dz_mfma<2><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
       if ((rc = launch_status())) return rc;
       if (want_r) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_rpart_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,

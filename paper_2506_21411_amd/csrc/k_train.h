@@ -640,7 +640,7 @@ __global__ __launch_bounds__(256) void k_alpha_token_major(long total, int Cin, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Per-head weighted token sums, bf16, heads <= 16, D % 4 == 0:
+// Per-head weighted token sums, bf16, D % 4 == 0:
 //   u[b,k,n,a,:] = sum_{c in group k} alpha[b,c,n,a] * z[b,c,n,:]
 // grid (N, G, B), block 256: a thread owns 4 adjacent columns (and every 1024th after them) and
 // keeps one fp32 sum per head; the group's weights for this patch sit in LDS.  Bound by the read
@@ -649,56 +649,59 @@ __global__ __launch_bounds__(256) void k_alpha_token_major(long total, int Cin, 
 __global__ __launch_bounds__(256) void k_head_sums_bf16(int Cin, int N, int D, int heads, int g,
                                                         const float* __restrict__ alpha, const bf16* __restrict__ z,
                                                         bf16* __restrict__ u) {
-  extern __shared__ __attribute__((aligned(16))) float al[];      // [gk][16]
+  extern __shared__ __attribute__((aligned(16))) float al[];      // [gk][16]: the weights of one block of 16 heads
   const int n = blockIdx.x, k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
   const int c0 = k * g, gk = min(g, Cin - c0);
-  for (int idx = threadIdx.x; idx < gk * 16; idx += 256) {
-    const int cl = idx >> 4, a = idx & 15;
-    al[idx] = a < heads ? alpha[(((size_t)b * Cin + c0 + cl) * N + n) * heads + a] : 0.f;
-  }
-  __syncthreads();
   const size_t cstride = (size_t)N * D;
-  for (int d0 = threadIdx.x * 4; d0 < D; d0 += 1024) {
-    const bf16* zp = z + (((size_t)b * Cin + c0) * N + n) * D + d0;
-    float acc[16][4];
-#pragma unroll
-    for (int a = 0; a < 16; ++a)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[a][e] = 0.f;
-    int cl = 0;
-    for (; cl + 4 <= gk; cl += 4) {
-      bf16x4 zv[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) zv[i] = *reinterpret_cast<const bf16x4*>(zp + (size_t)(cl + i) * cstride);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const f32x4* ar = reinterpret_cast<const f32x4*>(al + (cl + i) * 16);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 av = ar[q];
-#pragma unroll
-          for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[q * 4 + a][e] += av[a] * (float)zv[i][e];
-        }
-      }
+  for (int a0 = 0; a0 < heads; a0 += 16) {                        // more than 16 heads: z is walked once per block
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < gk * 16; idx += 256) {
+      const int cl = idx >> 4, a = a0 + (idx & 15);
+      al[idx] = a < heads ? alpha[(((size_t)b * Cin + c0 + cl) * N + n) * heads + a] : 0.f;
     }
-    for (; cl < gk; ++cl) {
-      const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zp + (size_t)cl * cstride);
+    __syncthreads();
+    for (int d0 = threadIdx.x * 4; d0 < D; d0 += 1024) {
+      const bf16* zp = z + (((size_t)b * Cin + c0) * N + n) * D + d0;
+      float acc[16][4];
 #pragma unroll
       for (int a = 0; a < 16; ++a)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[a][e] += al[cl * 16 + a] * (float)zv[e];
-    }
-    bf16* up = u + ((((size_t)b * G + k) * N + n) * heads) * D + d0;
+        for (int e = 0; e < 4; ++e) acc[a][e] = 0.f;
+      int cl = 0;
+      for (; cl + 4 <= gk; cl += 4) {
+        bf16x4 zv[4];
 #pragma unroll
-    for (int a = 0; a < 16; ++a)
-      if (a < heads) {
-        bf16x4 o;
+        for (int i = 0; i < 4; ++i) zv[i] = *reinterpret_cast<const bf16x4*>(zp + (size_t)(cl + i) * cstride);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[a][e];
-        *reinterpret_cast<bf16x4*>(up + (size_t)a * D) = o;
+        for (int i = 0; i < 4; ++i) {
+          const f32x4* ar = reinterpret_cast<const f32x4*>(al + (cl + i) * 16);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4 av = ar[q];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[q * 4 + a][e] += av[a] * (float)zv[i][e];
+          }
+        }
       }
+      for (; cl < gk; ++cl) {
+        const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zp + (size_t)cl * cstride);
+#pragma unroll
+        for (int a = 0; a < 16; ++a)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[a][e] += al[cl * 16 + a] * (float)zv[e];
+      }
+      bf16* up = u + ((((size_t)b * G + k) * N + n) * heads + a0) * D + d0;
+#pragma unroll
+      for (int a = 0; a < 16; ++a)
+        if (a0 + a < heads) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[a][e];
+          *reinterpret_cast<bf16x4*>(up + (size_t)a * D) = o;
+        }
+    }
   }
 }
 
@@ -865,7 +868,7 @@ __global__ __launch_bounds__(256) void k_dz_rpart_bf16(int Cin, int N, int D, in
 }
 
 // ---------------------------------------------------------------------------------------
-// The same two results as two kernels for D % 256 == 0 (bf16, heads <= 16): the token gradients on MFMA
+// The same two results as two kernels for D % 256 == 0 (bf16, heads <= 32): the token gradients on MFMA
 // (reads w, writes dz) and the key-path sums on the vector ALUs (reads z); neither needs the other's stream.
 //
 // k_dz_mfma:  dz[b, c0 + m, n, :] = [alpha | ds](m, 0..31) . [w ; M](0..31, :)   one 32x32x16 product per 32
@@ -887,7 +890,7 @@ __device__ __forceinline__ void head_row_frags(const bf16* __restrict__ base, in
 #pragma unroll
   for (int a = 0; a < 16; ++a) {
     rows[a] = bf16x4{};
-    if (a < heads) rows[a] = *reinterpret_cast<const bf16x4*>(base + (size_t)a * D);
+    if (a < heads) rows[a] = *reinterpret_cast<const bf16x4*>(base + (size_t)a * D);      // heads: rows that exist from base on
   }
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -921,10 +924,11 @@ __device__ __forceinline__ void split_bf16(const f32x4& x0, const f32x4& x1, bf1
   }
 }
 
-__global__ __launch_bounds__(256, 2) void k_dz_mfma(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
-                                                 const float* __restrict__ alpha, const float* __restrict__ ds,
-                                                 const bf16* __restrict__ w, const bf16* __restrict__ Mb,
-                                                 bf16* __restrict__ dz) {
+template <int HB>   // blocks of 16 heads (heads <= 16 HB): the contraction runs over 2 HB steps of 16
+__global__ __launch_bounds__(256, 3 - HB) void k_dz_mfma(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
+                                                         const float* __restrict__ alpha, const float* __restrict__ ds,
+                                                         const bf16* __restrict__ w, const bf16* __restrict__ Mb,
+                                                         bf16* __restrict__ dz) {
   const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
   const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
   const int c0 = k * g, gk = min(g, Cin - c0);
@@ -933,47 +937,59 @@ __global__ __launch_bounds__(256, 2) void k_dz_mfma(int Cin, int N, int D, int h
   const int col0 = cb * 1024 + wave * 256;
   if (col0 >= D) return;
   const int d0 = col0 + 4 * lane;
-  bf16x8 mfrag[2][4];
-  head_row_frags(Mb + (size_t)k * heads * D + d0, D, heads, lhi, mfrag);
+  bf16x8 mfrag[HB][2][4];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb)
+    head_row_frags(Mb + ((size_t)k * heads + 16 * hb) * D + d0, D, heads - 16 * hb, lhi, mfrag[hb]);
   const size_t cstride = (size_t)N * D;
   const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const bool h8 = heads % 8 == 0;                        // then a lane's 8 heads are two aligned 16-byte loads
   for (int pi = 0; pi < np; ++pi) {
     const int n = n0 + pi;
-    bf16x8 wfrag[2][4];
-    head_row_frags(w + ((((size_t)b * G + k) * N + n) * heads) * D + d0, D, heads, lhi, wfrag);
+    bf16x8 wfrag[HB][2][4];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+      head_row_frags(w + ((((size_t)b * G + k) * N + n) * heads + 16 * hb) * D + d0, D, heads - 16 * hb, lhi, wfrag[hb]);
     for (int m0 = 0; m0 < gk; m0 += 32) {
       const int row = m0 + l32;
-      const size_t src = (((size_t)b * Cin + c0 + min(row, gk - 1)) * N + n) * heads + 8 * lhi;
-      f32x4 a0 = z4, a1 = z4, e0 = z4, e1 = z4;
-      if (row < gk) {
-        if (h8) {
-          if (8 * lhi < heads) {
-            a0 = *reinterpret_cast<const f32x4*>(alpha + src);
-            a1 = *reinterpret_cast<const f32x4*>(alpha + src + 4);
-            e0 = *reinterpret_cast<const f32x4*>(ds + src);
-            e1 = *reinterpret_cast<const f32x4*>(ds + src + 4);
-          }
-        } else {
+      bf16x8 ahi[HB], alo[HB], dhi[HB], dlo[HB];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            if (8 * lhi + i < heads) { a0[i] = alpha[src + i]; e0[i] = ds[src + i]; }
-            if (8 * lhi + 4 + i < heads) { a1[i] = alpha[src + 4 + i]; e1[i] = ds[src + 4 + i]; }
+      for (int hb = 0; hb < HB; ++hb) {
+        const int h0 = 16 * hb + 8 * lhi;                // this lane's 8 heads of the block
+        const size_t src = (((size_t)b * Cin + c0 + min(row, gk - 1)) * N + n) * heads + h0;
+        f32x4 a0 = z4, a1 = z4, e0 = z4, e1 = z4;
+        if (row < gk) {
+          if (h8) {
+            if (h0 < heads) {
+              a0 = *reinterpret_cast<const f32x4*>(alpha + src);
+              a1 = *reinterpret_cast<const f32x4*>(alpha + src + 4);
+              e0 = *reinterpret_cast<const f32x4*>(ds + src);
+              e1 = *reinterpret_cast<const f32x4*>(ds + src + 4);
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              if (h0 + i < heads) { a0[i] = alpha[src + i]; e0[i] = ds[src + i]; }
+              if (h0 + 4 + i < heads) { a1[i] = alpha[src + 4 + i]; e1[i] = ds[src + 4 + i]; }
+            }
           }
         }
+        split_bf16(a0, a1, ahi[hb], alo[hb]);
+        split_bf16(e0, e1, dhi[hb], dlo[hb]);
       }
-      bf16x8 ahi, alo, dhi, dlo;
-      split_bf16(a0, a1, ahi, alo);
-      split_bf16(e0, e1, dhi, dlo);
-      auto tiles_of_half = [&](const bf16x8 (&wf)[4], const bf16x8 (&mf)[4], int half) {
+      auto tiles_of_half = [&](int half) {
         f32x16 acc[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, wf[e], zero, 0, 0, 0);
-          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, wf[e], acc[e], 0, 0, 0);
-          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dhi, mf[e], acc[e], 0, 0, 0);
-          acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dlo, mf[e], acc[e], 0, 0, 0);
+          acc[e] = zero;
+#pragma unroll
+          for (int hb = 0; hb < HB; ++hb) {
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi[hb], wfrag[hb][half][e], acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo[hb], wfrag[hb][half][e], acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dhi[hb], mfrag[hb][half][e], acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dlo[hb], mfrag[hb][half][e], acc[e], 0, 0, 0);
+          }
         }
         bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n) * D + col0 + 4 * (l32 + 32 * half);
 #pragma unroll
@@ -987,8 +1003,8 @@ __global__ __launch_bounds__(256, 2) void k_dz_mfma(int Cin, int N, int D, int h
           }
         }
       };
-      tiles_of_half(wfrag[0], mfrag[0], 0);
-      tiles_of_half(wfrag[1], mfrag[1], 1);
+      tiles_of_half(0);
+      tiles_of_half(1);
     }
   }
 }
@@ -1001,61 +1017,64 @@ __global__ __launch_bounds__(256, 2) void k_dz_mfma(int Cin, int N, int D, int h
 __global__ __launch_bounds__(256) void k_rpart_bf16(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
                                                     const float* __restrict__ ds, const bf16* __restrict__ z,
                                                     float* __restrict__ rpart) {
-  extern __shared__ __attribute__((aligned(16))) float dsv[];      // [np * gk rows in (patch, member) order][16]
+  extern __shared__ __attribute__((aligned(16))) float dsv[];      // [np * gk rows in (patch, member) order][16 heads]
   const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
   const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
   const int c0 = k * g, gk = min(g, Cin - c0);
   const int n0 = tile * pt, np = min(pt, N - n0);
   const int rows = np * gk;
-  for (int idx = threadIdx.x; idx < rows * 16; idx += 256) {
-    const int a = idx & 15, cl = (idx >> 4) % gk, pi = (idx >> 4) / gk;
-    dsv[idx] = a < heads ? ds[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a] : 0.f;
-  }
-  __syncthreads();
   const int d0 = cb * 1024 + threadIdx.x * 4;
-  if (d0 >= D) return;
-  float racc[16][4];
-#pragma unroll
-  for (int a = 0; a < 16; ++a)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) racc[a][e] = 0.f;
-  const size_t cstride = (size_t)N * D;
-  const bf16* zb = z + (((size_t)b * Cin + c0) * N + n0) * D + d0;
-  // the rows of the tile are walked eight at a time, the next eight already in flight while these are summed
-  int pcl = 0, ppi = 0;                                  // (member, patch) of the next row to fetch
-  bf16x4 cur[8], nxt[8];
-  auto fetch = [&](bf16x4 (&buf)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      buf[i] = bf16x4{};
-      if (ppi < np) buf[i] = *reinterpret_cast<const bf16x4*>(zb + (size_t)ppi * D + (size_t)pcl * cstride);
-      if (++pcl == gk) { pcl = 0; ++ppi; }
+  for (int a0 = 0; a0 < heads; a0 += 16) {                         // more than 16 heads: one pass over z per block of 16
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < rows * 16; idx += 256) {
+      const int a = a0 + (idx & 15), cl = (idx >> 4) % gk, pi = (idx >> 4) / gk;
+      dsv[idx] = a < heads ? ds[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a] : 0.f;
     }
-  };
-  fetch(cur);
-  for (int base = 0; base < rows; base += 8) {
-    fetch(nxt);                                          // past the end: nothing is loaded
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (base + i < rows) {
-        const f32x4* dr = reinterpret_cast<const f32x4*>(dsv + (base + i) * 16);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 dv = dr[q];
-#pragma unroll
-          for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) racc[q * 4 + a][e] += dv[a] * (float)cur[i][e];
+    __syncthreads();
+    if (d0 >= D) continue;
+    float racc[16][4];
+  #pragma unroll
+    for (int a = 0; a < 16; ++a)
+  #pragma unroll
+      for (int e = 0; e < 4; ++e) racc[a][e] = 0.f;
+    const size_t cstride = (size_t)N * D;
+    const bf16* zb = z + (((size_t)b * Cin + c0) * N + n0) * D + d0;
+    // the rows of the tile are walked eight at a time, the next eight already in flight while these are summed
+    int pcl = 0, ppi = 0;                                  // (member, patch) of the next row to fetch
+    bf16x4 cur[8], nxt[8];
+    auto fetch = [&](bf16x4 (&buf)[8]) {
+  #pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        buf[i] = bf16x4{};
+        if (ppi < np) buf[i] = *reinterpret_cast<const bf16x4*>(zb + (size_t)ppi * D + (size_t)pcl * cstride);
+        if (++pcl == gk) { pcl = 0; ++ppi; }
+      }
+    };
+    fetch(cur);
+    for (int base = 0; base < rows; base += 8) {
+      fetch(nxt);                                          // past the end: nothing is loaded
+  #pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (base + i < rows) {
+          const f32x4* dr = reinterpret_cast<const f32x4*>(dsv + (base + i) * 16);
+  #pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4 dv = dr[q];
+  #pragma unroll
+            for (int a = 0; a < 4; ++a)
+  #pragma unroll
+              for (int e = 0; e < 4; ++e) racc[q * 4 + a][e] += dv[a] * (float)cur[i][e];
+          }
         }
       }
+  #pragma unroll
+      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+    float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads + a0) * D + d0;
+  #pragma unroll
+    for (int a = 0; a < 16; ++a)
+      if (a0 + a < heads) *reinterpret_cast<f32x4*>(rp + (size_t)a * D) = f32x4{racc[a][0], racc[a][1], racc[a][2], racc[a][3]};
   }
-  float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads) * D + d0;
-#pragma unroll
-  for (int a = 0; a < 16; ++a)
-    if (a < heads) *reinterpret_cast<f32x4*>(rp + (size_t)a * D) = f32x4{racc[a][0], racc[a][1], racc[a][2], racc[a][3]};
 }
 
 // r[k][i] = sum_b sum_t rpart[b][k][t][i]   (i over heads * D), fixed order.  grid (ceil(per/64), G), block 256:

@@ -71,6 +71,10 @@ SMALL = [
     dict(dtype="bf16", B=2, C=13, H=32, W=96, p=4, D=256, heads=16, group_sizes=(5, 3)),
     # fast level: D = 512, 16 heads of 32, N = 128, groups of 20 + 20 + 3 (two member tiles, ragged last group)
     dict(dtype="bf16", B=1, C=43, H=64, W=128, p=8, D=512, heads=16, group_sizes=(20, 3)),
+    # 32 heads of 32 (two blocks of 16 heads in the head-sum, token-gradient and key-path kernels), D = 1024
+    dict(dtype="bf16", B=1, C=12, H=32, W=64, p=8, D=1024, heads=32, group_sizes=(6, 2)),
+    # 24 heads: the second head block is half empty
+    dict(dtype="bf16", B=1, C=7, H=16, W=32, p=4, D=768, heads=24, group_sizes=(4, 2)),
 ]
 
 
