@@ -470,10 +470,11 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
       else k_dz_mfma<2><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
       if ((rc = launch_status())) return rc;
       if (want_r) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_rpart_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
+        auto rk = heads <= 16 ? k_rpart_bf16<1> : k_rpart_bf16<2>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(rk), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(lds / 2)) != hipSuccess)
           return DCHAG_ERR_LAUNCH;
-        k_rpart_bf16<<<grid, 256, lds / 2, st>>>(Cin, N, D, heads, g, n_tiles, pt, ds, zin, rpart);
+        rk<<<grid, 256, lds / 2, st>>>(Cin, N, D, heads, g, n_tiles, pt, ds, zin, rpart);
         if ((rc = launch_status())) return rc;
       }
     } else {

@@ -1014,6 +1014,7 @@ __global__ __launch_bounds__(256, 3 - HB) void k_dz_mfma(int Cin, int N, int D, 
 // grid (n_tiles * ceil(D/1024), G, B), block 256: a thread owns 4 adjacent columns and one fp32 sum per head;
 // ds of the whole tile sits in LDS (dynamic, pt * g * 16 floats).
 // ---------------------------------------------------------------------------------------
+template <int HB>   // blocks of 16 heads, heads <= 16 HB
 __global__ __launch_bounds__(256) void k_rpart_bf16(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
                                                     const float* __restrict__ ds, const bf16* __restrict__ z,
                                                     float* __restrict__ rpart) {
@@ -1024,8 +1025,10 @@ __global__ __launch_bounds__(256) void k_rpart_bf16(int Cin, int N, int D, int h
   const int n0 = tile * pt, np = min(pt, N - n0);
   const int rows = np * gk;
   const int d0 = cb * 1024 + threadIdx.x * 4;
-  for (int a0 = 0; a0 < heads; a0 += 16) {                         // more than 16 heads: one pass over z per block of 16
-    __syncthreads();
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {                                // more than 16 heads: one pass over z per block of 16
+    const int a0 = 16 * hb;
+    if (HB > 1) __syncthreads();
     for (int idx = threadIdx.x; idx < rows * 16; idx += 256) {
       const int a = a0 + (idx & 15), cl = (idx >> 4) % gk, pi = (idx >> 4) / gk;
       dsv[idx] = a < heads ? ds[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a] : 0.f;
