@@ -53,7 +53,9 @@ def stage_model(cfg, levels_in, stage, level):
     if stage == "oproj":
         return "mfma", 2.0 * B * G * N * D * D
     if stage == "fused_vagg":
-        return "mfma", 2.0 * tok * D * (D + h)
+        # the value projection itself; the weighted sum in its epilogue runs on the vector ALUs and is not counted
+        # (SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 of the kernel gives exactly this number)
+        return "mfma", 2.0 * tok * D * D
     if stage == "scores":
         if level == 1 and cfg.dtype == "bf16":
             # first level of a forward call: scores come from the pixels through composed weights
