@@ -182,9 +182,12 @@ int launch_gemm_mfma_tile(const GemmDesc& d, const bf16* A, const bf16* Bm, cons
 // of one head) takes the 64-wide tile on that side.
 // rowsum (optional, only with a transposed A on the MFMA kernel: see gemm_rowsum_ok): sums of A's rows.
 template <typename TC>
-int launch_gemm_bf16(const GemmDesc& d, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st,
+int launch_gemm_bf16(const GemmDesc& d0, const bf16* A, const bf16* Bm, const bf16* bias, TC* C, hipStream_t st,
                      TC* rowsum = nullptr) {
-  if (!gemm_mfma_ok(d)) return launch_gemm<bf16, bf16, TC>(d, A, Bm, bias, C, st);
+  if (!gemm_mfma_ok(d0)) return launch_gemm<bf16, bf16, TC>(d0, A, Bm, bias, C, st);
+  GemmDesc d = d0;
+  d.c_vec = sizeof(TC) == 2 && d.C.s1 == 1 && d.N % 8 == 0 && mult8(d.C.sb) && mult8(d.C.sk) && mult8(d.C.sa) &&
+            mult8(d.C.s0) && !(reinterpret_cast<uintptr_t>(C) & 15) && !getenv("DCHAG_GEMM_SCALAR_STORES");
   if (d.N <= 64) return launch_gemm_mfma_tile<128, 64, 4, 1, TC>(d, A, Bm, bias, C, rowsum, st);
   if (d.M <= 64) return launch_gemm_mfma_tile<64, 128, 1, 4, TC>(d, A, Bm, bias, C, rowsum, st);
   return launch_gemm_mfma_tile<128, 128, 2, 2, TC>(d, A, Bm, bias, C, rowsum, st);

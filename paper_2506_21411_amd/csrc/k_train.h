@@ -35,6 +35,7 @@ struct GemmDesc {
   long bias_sk, bias_sa;
   float scale;
   long rs_sk, rs_sa;   // k_gemm_mfma with a transposed A: optional row sums of A over the contraction, per (k, a)
+  int c_vec;           // k_gemm_mfma: C rows are contiguous and 16-byte aligned, N % 8 == 0: store whole 16-byte chunks
 };
 
 template <typename TA, typename TB, typename TC>
@@ -606,6 +607,34 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmDesc d, const bf16* __res
   // 32x32 accumulator block: lane holds column (lane % 32); register r holds row 8 (r / 4) + 4 (lane / 32) + r % 4
   TC* Cb = C + d.C.sb * b0 + d.C.sk * k + d.C.sa * a;
   const bf16* bs = bias ? bias + d.bias_sk * k + d.bias_sa * a : nullptr;
+  if (sizeof(TC) == 2 && d.c_vec) {
+    // the tile goes through LDS (the stages are no longer read) so that rows leave in 16-byte chunks:
+    // a lane's accumulator column is 2 bytes wide, a row of the tile up to 256 bytes
+    constexpr int PITCH = BN + 8;                          // bf16 elements; 16 extra bytes keep the row starts apart
+    bf16* tile = reinterpret_cast<bf16*>(smem);
+    __syncthreads();                                      // (also orders the row-sum scratch before this reuse)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int nl = wn * (BN / WN) + j * 32 + l32;
+      const float bv = (bs && n0 + nl < d.N) ? (float)bs[n0 + nl] : 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int ml = wm * (BM / WM) + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+          tile[ml * PITCH + nl] = (bf16)(acc[i][j][r] * d.scale + bv);
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < BM * (BN / 8); idx += 256) {
+      const int ml = idx / (BN / 8), ch = idx % (BN / 8);
+      const int m = m0 + ml, n = n0 + ch * 8;
+      if (m < M && n < d.N)
+        *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(Cb) + d.C.s0 * m + n) =
+            *reinterpret_cast<const bf16x8*>(tile + ml * PITCH + ch * 8);
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = n0 + wn * (BN / WN) + j * 32 + l32;
