@@ -426,6 +426,40 @@ inline int softmax_backward(int B, int Cin, int N, int D, int heads, int g, cons
   return launch_status();
 }
 
+// True when one kernel (k_tokens_backward_fused) takes the whole reverse step at the tokens of a level -- ds, the token
+// gradients and the key-path partial sums: the shapes of the MFMA token-gradient path with at most 16 heads,
+// D <= 1024 and groups of at most 32 channels.  DCHAG_TOKENS_UNFUSED (debugging aid) keeps the three kernels apart.
+inline bool tokens_fused(int B, int Cin, int N, int D, int heads, int g) {
+  const int G = groups_of(Cin, g);
+  const size_t lds = (size_t)2 * dz_patches(B, G, N, D, g) * g * 16 * 4;
+  return D % 256 == 0 && D <= 1024 && heads <= 16 && std::min(g, Cin) <= 32 && lds <= 128 * 1024 &&
+         !getenv("DCHAG_DZ_VALU") && !getenv("DCHAG_GENERIC_LEVEL") && !getenv("DCHAG_TOKENS_UNFUSED");
+}
+inline int sum_key_path_partials(int B, int G, int n_tiles, int heads, int D, const float* rpart, float* r,
+                                 hipStream_t st) {
+  const long per = (long)heads * D;
+  k_sum_partials<<<dim3((unsigned)((per + 63) / 64), G), 256, 0, st>>>(B, G, n_tiles, per, rpart, r);
+  return launch_status();
+}
+inline int tokens_backward_fused(int B, int Cin, int N, int D, int heads, int g, const bf16* z, const bf16* w,
+                                 const float* alpha, const bf16* Mb, bf16* dz, float* r, float* rpart, hipStream_t st) {
+  const int G = groups_of(Cin, g);
+  const int pt = dz_patches(B, G, N, D, g);
+  const int n_tiles = (N + pt - 1) / pt;
+  int rc;
+  {
+    StageTimer tm(DCHAG_STAGE_BWD_TOKENS, st);
+    const dim3 grid((unsigned)n_tiles, G, B);
+    if (std::min(g, Cin) <= 16)
+      k_tokens_backward_fused<1><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
+    else
+      k_tokens_backward_fused<2><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
+    if ((rc = launch_status())) return rc;
+  }
+  StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);
+  return sum_key_path_partials(B, G, n_tiles, heads, D, rpart, r, st);
+}
+
 // dz (value and key path) and r[k][a][:] = sum over the group's tokens of ds[., a] z[., :].
 template <typename T>
 int tokens_backward_generic(int B, int Cin, int N, int D, int heads, int g, const T* zin, const T* w, const float* alpha,
@@ -490,9 +524,7 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
   }
   if (!want_r) return DCHAG_OK;
   StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);
-  const long per = (long)heads * D;
-  k_sum_partials<<<dim3((unsigned)((per + 63) / 64), G), 256, 0, st>>>(B, G, n_tiles, per, rpart, r);
-  return launch_status();
+  return sum_key_path_partials(B, G, n_tiles, heads, D, rpart, r, st);
 }
 
 // Reverse of one attention level.  dy is the gradient at the level's output [B,G,N,D]; dz receives the
@@ -550,14 +582,23 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
     d.scale = 1.f;
     if ((rc = gemm_tt(d, d_o, Wv, nullptr, w, st))) return rc;
   }
-  {
-    StageTimer tm(DCHAG_STAGE_BWD_SOFTMAX, st);
-    if ((rc = softmax_backward(B, Cin, N, D, heads, g, zin, w, lb.alpha, dalpha, st))) return rc;
-  }
   const bool want_q = gr->dWq || gr->dbq || gr->dquery;
   const bool want_r = gr->dWk || want_q;
-  if ((rc = tokens_backward(B, Cin, N, D, heads, g, zin, w, lb.alpha, dalpha, lb.Mf, lb.Mb, dz, r, rpart, want_r, st)))
-    return rc;
+  bool fused = false;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (want_r && tokens_fused(B, Cin, N, D, heads, g)) {
+      if ((rc = tokens_backward_fused(B, Cin, N, D, heads, g, zin, w, lb.alpha, lb.Mb, dz, r, rpart, st))) return rc;
+      fused = true;
+    }
+  }
+  if (!fused) {
+    {
+      StageTimer tm(DCHAG_STAGE_BWD_SOFTMAX, st);
+      if ((rc = softmax_backward(B, Cin, N, D, heads, g, zin, w, lb.alpha, dalpha, st))) return rc;
+    }
+    if ((rc = tokens_backward(B, Cin, N, D, heads, g, zin, w, lb.alpha, dalpha, lb.Mf, lb.Mb, dz, r, rpart, want_r, st)))
+      return rc;
+  }
   StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);
   if (gr->dbk) {
     const long n = (long)G * D;

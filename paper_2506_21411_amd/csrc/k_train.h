@@ -913,13 +913,17 @@ __global__ __launch_bounds__(256) void k_dz_rpart_bf16(int Cin, int N, int D, in
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 // B fragments of the eight column tiles from 16 rows (heads) of a [heads][D] bf16 matrix at this lane's 4 columns.
+template <bool LAST_USE = false>   // LAST_USE: streaming loads (the rows are not needed in the caches afterwards)
 __device__ __forceinline__ void head_row_frags(const bf16* __restrict__ base, int D, int heads, int lhi,
                                                bf16x8 (&frag)[2][4]) {
   bf16x4 rows[16];
 #pragma unroll
   for (int a = 0; a < 16; ++a) {
     rows[a] = bf16x4{};
-    if (a < heads) rows[a] = *reinterpret_cast<const bf16x4*>(base + (size_t)a * D);      // heads: rows that exist from base on
+    if (a < heads) {                                               // heads: rows that exist from base on
+      const bf16x4* src = reinterpret_cast<const bf16x4*>(base + (size_t)a * D);
+      rows[a] = LAST_USE ? __builtin_nontemporal_load(src) : *src;
+    }
   }
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -1034,6 +1038,226 @@ __global__ __launch_bounds__(256, 3 - HB) void k_dz_mfma(int Cin, int N, int D, 
       };
       tiles_of_half(0);
       tiles_of_half(1);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// The whole reverse step at the tokens of one level in one kernel (bf16, heads <= 16, D % 256 == 0, D <= 1024,
+// group size <= 16 MT <= 32), so that a patch's token rows and its w rows are fetched from HBM once (their second
+// use, a few microseconds later in the same workgroup, finds them in L2) and ds never leaves the compute unit:
+//   ds as in k_dalpha_softmax_mfma;  rpart[b,k,t][a][:] = sum over the pt patches of tile t and the members c of
+//   ds[b,c,n,a] * z[b,c,n,:]  (the partial sums k_sum_partials adds up);  dz as in k_dz_mfma.
+// grid (n_tiles, G, B), block 512, one patch at a time:
+//   d alpha   all eight wavefronts, each an eighth of D; the partial 16x16 blocks meet in LDS in a fixed order, the
+//             first wavefront applies the Jacobian and leaves the softmax weights and ds of the patch in LDS;
+//   sums      wavefronts 0..3, wavefront w columns 256 w .. 256 w + 255: ds^T (heads x 32 members, split in two
+//             bf16 parts) times the 32 member rows on 16x16x32 MFMA; a lane reads 8 members x 8 adjacent columns
+//             (16 bytes per row) and transposes them in registers, which gives it the B fragments (column
+//             8 (lane % 16) + j, members 8 (lane / 16) ..) of eight products j = 0..7; accumulator (half, j): lane
+//             holds column 128 half + 8 (lane % 16) + j, heads 4 (lane / 16) + r;
+//   dz        wavefronts 4..7, wavefront 4 + w the same columns: the body of k_dz_mfma, A fragments from LDS.
+// The two roles are separate loops (same barriers), so neither carries the other's accumulators.
+// ---------------------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, int D, int heads, int g, int pt,
+                                                               const bf16* __restrict__ z, const bf16* __restrict__ w,
+                                                               const float* __restrict__ alpha,
+                                                               const bf16* __restrict__ Mb, bf16* __restrict__ dz,
+                                                               float* __restrict__ rpart) {
+  __shared__ f32x4 part[8][MT][64];
+  __shared__ float dsv[2][32][17];                                 // [patch parity][member][head], padded rows
+  __shared__ float alv[2][32][17];                                 // the softmax weights, same layout
+  const int tile = blockIdx.x, n_tiles = gridDim.x, k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  const int n0 = tile * pt, np = min(pt, N - n0);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l16 = lane & 15, lq = lane >> 4, l32 = lane & 31, lhi = lane >> 5;
+  const size_t cstride = (size_t)N * D;
+  const int kq = D / 8;                                            // this wavefront's share of the contraction
+  const int col0 = (wave & 3) * 256;                               // this wavefront's columns of the sums / of dz
+  const int head = min(l16, heads - 1);
+  const bf16* zg = z + (((size_t)b * Cin + c0) * N + n0) * D;      // member 0 of the group at the tile's first patch
+  const size_t item0 = ((size_t)b * G + k) * N + n0;
+  for (int i = threadIdx.x; i < 2 * 32 * 17; i += 512) {           // members beyond 16 MT stay zero
+    (&dsv[0][0][0])[i] = 0.f;
+    (&alv[0][0][0])[i] = 0.f;
+  }
+  __syncthreads();
+
+  auto dalpha_partial = [&](int pi) {
+    const bf16* wr = w + ((item0 + pi) * heads + head) * D + wave * kq + lq * 8;
+    const bf16* zr[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      zr[mt] = zg + (size_t)pi * D + (size_t)min(mt * 16 + l16, gk - 1) * cstride + wave * kq + lq * 8;
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < kq; t += 128) {                            // four steps of 32 per trip, loads first
+      bf16x8 wf[4], zf[MT][4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int tt = min(t + q * 32, kq - 32);
+        wf[q] = *reinterpret_cast<const bf16x8*>(wr + tt);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) zf[mt][q] = *reinterpret_cast<const bf16x8*>(zr[mt] + tt);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (t + q * 32 < kq) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf[mt][q], wf[q], acc[mt], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) part[wave][mt][lane] = acc[mt];
+  };
+  // the first wavefront fetches the softmax weights of a patch before its share of d alpha, so that they have
+  // arrived when the other wavefronts wait for the Jacobian (lane: head l16, members 4 lq + r of each tile)
+  auto fetch_alpha = [&](int pi, float (&al)[MT][4]) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int cl = mt * 16 + lq * 4 + r;
+        al[mt][r] = (cl < gk && l16 < heads) ? alpha[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + l16] : 0.f;
+      }
+  };
+  auto jacobian = [&](int pi, const float (&al)[MT][4]) {
+    float da[MT][4];
+    float dot = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      f32x4 tot = part[0][mt][lane];
+#pragma unroll
+      for (int v = 1; v < 8; ++v) tot += part[v][mt][lane];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        da[mt][r] = tot[r];
+        dot += al[mt][r] * tot[r];
+      }
+    }
+    dot += __shfl_xor(dot, 16, kWave);
+    dot += __shfl_xor(dot, 32, kWave);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int cl = mt * 16 + lq * 4 + r;
+        dsv[pi & 1][cl][l16] = al[mt][r] * (da[mt][r] - dot);      // 0 for padding members and heads
+        alv[pi & 1][cl][l16] = al[mt][r];
+      }
+  };
+  // Per patch: every wavefront writes its partial block, barrier, the first wavefront fills the tables of parity
+  // pi & 1, barrier, the roles read them.  The next patch writes the other parity, and `part` only after every
+  // wavefront has passed the second barrier of this one.
+  if (wave < 4) {
+    f32x4 racc[2][8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) racc[h][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int pi = 0; pi < np; ++pi) {
+      float al[MT][4];
+      if (wave == 0) fetch_alpha(pi, al);
+      dalpha_partial(pi);
+      __syncthreads();
+      if (wave == 0) jacobian(pi, al);
+      __syncthreads();
+      if (col0 < D) {
+        f32x4 v0, v1;                                              // ds of head l16 at members 8 lq .. 8 lq + 7
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v0[i] = dsv[pi & 1][8 * lq + i][l16];
+          v1[i] = dsv[pi & 1][8 * lq + 4 + i][l16];
+        }
+        bf16x8 dhi, dlo;
+        split_bf16(v0, v1, dhi, dlo);
+        const bf16* zc = zg + (size_t)pi * D + col0 + 8 * l16;
+        bf16x8 rows[2][8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            rows[h][i] = __builtin_nontemporal_load(                // second and last use of the row
+                reinterpret_cast<const bf16x8*>(zc + (size_t)min(8 * lq + i, gk - 1) * cstride + 128 * h));
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            bf16x8 col;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) col[i] = rows[h][i][j];
+            racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dhi, col, racc[h][j], 0, 0, 0);
+            racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dlo, col, racc[h][j], 0, 0, 0);
+          }
+      }
+    }
+    if (col0 < D) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int a = 4 * lq + r;
+        if (a < heads) {
+          float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads + a) * D + col0 + 8 * l16;
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            *reinterpret_cast<f32x4*>(rp + 128 * h) = f32x4{racc[h][0][r], racc[h][1][r], racc[h][2][r], racc[h][3][r]};
+            *reinterpret_cast<f32x4*>(rp + 128 * h + 4) =
+                f32x4{racc[h][4][r], racc[h][5][r], racc[h][6][r], racc[h][7][r]};
+          }
+        }
+      }
+    }
+  } else {
+    const int d0c = col0 + 4 * lane;                               // this lane's 4 columns of the token gradients
+    bf16x8 mfrag[2][4];
+    if (col0 < D) head_row_frags(Mb + ((size_t)k * heads) * D + d0c, D, heads, lhi, mfrag);
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int pi = 0; pi < np; ++pi) {
+      dalpha_partial(pi);
+      __syncthreads();
+      __syncthreads();
+      if (col0 < D) {
+        bf16x8 wfrag[2][4];
+        head_row_frags<true>(w + ((item0 + pi) * heads) * D + d0c, D, heads, lhi, wfrag);
+        f32x4 a0, a1, e0, e1;                                      // member row l32, heads 8 lhi .. 8 lhi + 7
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a0[i] = alv[pi & 1][l32][8 * lhi + i];
+          a1[i] = alv[pi & 1][l32][8 * lhi + 4 + i];
+          e0[i] = dsv[pi & 1][l32][8 * lhi + i];
+          e1[i] = dsv[pi & 1][l32][8 * lhi + 4 + i];
+        }
+        bf16x8 ahi, alo, ehi, elo;
+        split_bf16(a0, a1, ahi, alo);
+        split_bf16(e0, e1, ehi, elo);
+        auto tiles_of_half = [&](int half) {
+          f32x16 acc[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, wfrag[half][e], zero, 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, wfrag[half][e], acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi, mfrag[half][e], acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(elo, mfrag[half][e], acc[e], 0, 0, 0);
+          }
+          bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n0 + pi) * D + col0 + 4 * (l32 + 32 * half);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = 8 * (r >> 2) + 4 * lhi + (r & 3);
+            if (m < gk) {
+              bf16x4 o;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[e][r];
+              // streaming store: dz is not read again here, and the rows to come back from L2 are z's and w's
+              __builtin_nontemporal_store(o, reinterpret_cast<bf16x4*>(dzp + (size_t)m * cstride));
+            }
+          }
+        };
+        tiles_of_half(0);
+        tiles_of_half(1);
+      }
     }
   }
 }
