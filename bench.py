@@ -29,8 +29,9 @@ PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_tflops": 157.3}
 MEASURED_TRAFFIC = {("hyperspectral", "fused_vagg", 1): 1677.9e6}
 
 
-def stage_model(cfg, levels_in, stage, level):
-    """Algorithmic work of one launch of a stage: (bound, amount, unit) with amount in flops or bytes."""
+def stage_model(cfg, levels_in, stage, level, fused_tokens=False):
+    """Algorithmic work of one launch of a stage: (bound, amount, unit) with amount in flops or bytes.
+    fused_tokens: the level's reverse step at the tokens ran as one kernel (no separate softmax stage)."""
     es = 4 if cfg.dtype == "f32" else 2
     B, N, D, h = cfg.B, cfg.N, cfg.D, cfg.heads
     if stage == "tokenize":
@@ -80,6 +81,9 @@ def stage_model(cfg, levels_in, stage, level):
     if stage == "bwd_softmax":
         return "hbm", tok * D * es + uw + 3 * tok * h * 4
     if stage == "bwd_tokens":
+        if fused_tokens:
+            # one kernel: tokens and w in once, token gradients out, softmax weights in, partial key-path sums out
+            return "hbm", uw + 2 * tok * D * es + tok * h * 4
         return "hbm", uw + tok * D * es + 2 * tok * h * 4
     if stage == "bwd_key_query":
         return "hbm", tok * D * es + tok * h * 4 + 3 * G * D * D * es
@@ -216,7 +220,8 @@ def main() -> int:
         a[1] += 1
     stages = []
     for (name, level), (tot, cnt) in agg.items():
-        bound, amount = stage_model(cfg, lv_in, name, level)
+        fused = name == "bwd_tokens" and ("bwd_softmax", level) not in agg
+        bound, amount = stage_model(cfg, lv_in, name, level, fused)
         avg = tot / args.steps                       # per step: a stage may take several launches
         if bound == "mfma":
             ach, peak, unit = amount / (avg * 1e-3) / 1e12, PEAK["mfma_bf16_tflops"] if cfg.dtype == "bf16" else PEAK["fp32_tflops"], "TFLOP/s"

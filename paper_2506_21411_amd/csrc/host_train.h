@@ -527,6 +527,22 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
   return sum_key_path_partials(B, G, n_tiles, heads, D, rpart, r, st);
 }
 
+// Rank-one weight gradient out[k][i][:] = scale * rowv[k][i] * colv[k][i / rows_per_vec][:]: 16 bytes per thread where
+// the rows allow it.
+template <typename TV, typename T>
+int outer_rows(int D, int G, int rows_per_vec, float scale, const float* rowv, const TV* colv, T* out, hipStream_t st) {
+  const bool vec = D % 8 == 0 && !((reinterpret_cast<uintptr_t>(colv) | reinterpret_cast<uintptr_t>(out)) & 15) &&
+                   !getenv("DCHAG_GEMM_SCALAR_STORES");
+  if (vec) {
+    const long chunks = (long)D * (D / 8);
+    k_outer_rows_vec<TV, T><<<dim3((unsigned)((chunks + 2047) / 2048), G), 256, 0, st>>>(D, rows_per_vec, scale, rowv,
+                                                                                       colv, out);
+  } else {
+    k_outer_rows<TV, T><<<dim3((D + 255) / 256, D, G), 256, 0, st>>>(D, rows_per_vec, scale, rowv, colv, out);
+  }
+  return launch_status();
+}
+
 // Reverse of one attention level.  dy is the gradient at the level's output [B,G,N,D]; dz receives the
 // gradient at its input [B,Cin,N,D].
 template <typename T>
@@ -605,22 +621,16 @@ int attention_level_backward(int B, int Cin, int N, int D, int heads, const dcha
     k_fill_zero<T><<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(n, static_cast<T*>(gr->dbk));
     if ((rc = launch_status())) return rc;
   }
-  if (gr->dWk) {
-    k_outer_rows<float, T><<<dim3((D + 255) / 256, D, G), 256, 0, st>>>(D, dh, 1.f / sqrtf((float)dh), lb.Qp, r,
-                                                                        static_cast<T*>(gr->dWk));
-    if ((rc = launch_status())) return rc;
-  }
+  if (gr->dWk && (rc = outer_rows<float, T>(D, G, dh, 1.f / sqrtf((float)dh), lb.Qp, r, static_cast<T*>(gr->dWk), st)))
+    return rc;
   if (!want_q) return DCHAG_OK;
   k_query_grad<T><<<dim3((D + 3) / 4, G), 256, 0, st>>>(D, heads, static_cast<const T*>(lv->Wk), r, dQ,
                                                         static_cast<T*>(gr->dbq));
   if ((rc = launch_status())) return rc;
-  if (gr->dWq) {
-    k_outer_rows<T, T><<<dim3((D + 255) / 256, D, G), 256, 0, st>>>(D, D, 1.f, dQ, static_cast<const T*>(lv->query),
-                                                                    static_cast<T*>(gr->dWq));
-    if ((rc = launch_status())) return rc;
-  }
+  if (gr->dWq && (rc = outer_rows<T, T>(D, G, D, 1.f, dQ, static_cast<const T*>(lv->query), static_cast<T*>(gr->dWq), st)))
+    return rc;
   if (gr->dquery) {
-    k_query_input_grad<T><<<dim3((D + 255) / 256, G), 1024, 0, st>>>(D, static_cast<const T*>(lv->Wq), dQ,
+    k_query_input_grad<T><<<dim3((D + 63) / 64, G), 1024, 0, st>>>(D, static_cast<const T*>(lv->Wq), dQ,
                                                                    static_cast<T*>(gr->dquery));
     if ((rc = launch_status())) return rc;
   }

@@ -299,31 +299,39 @@ __global__ __launch_bounds__(256) void k_query_grad(int D, int heads, const T* _
   }
 }
 
-// dquery[k][j] = sum_i Wq[k][i][j] * dQ[k][i].  grid (ceil(D/256), G), block 1024: lane l of every wavefront owns
-// the 4 columns 256 x + 4 l .., the 16 wavefronts take every 16th row and meet in LDS in a fixed order.
-// Requires D % 4 == 0.
+// dquery[k][j] = sum_i Wq[k][i][j] * dQ[k][i].  grid (ceil(D/64), G), block 1024: a block owns 64 columns; lane l of a
+// wavefront takes the 4 columns 4 (l % 16) .. of row 4 wave + l / 16 and every 64th row after it; the four row groups
+// of a wavefront meet by lane exchange, the 16 wavefronts in LDS, both in a fixed order.  Requires D % 4 == 0.
 template <typename T>
 __global__ __launch_bounds__(1024) void k_query_input_grad(int D, const T* __restrict__ Wq,
                                                            const float* __restrict__ dQ, T* __restrict__ dquery) {
-  __shared__ float part[16][256];
+  __shared__ float part[16][64];
   const int k = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int j = blockIdx.x * 256 + lane * 4;
+  const int cg = lane & 15, rs = lane >> 4;
+  const int j = blockIdx.x * 64 + cg * 4;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (j < D) {
     const T* w = Wq + (size_t)k * D * D + j;
     const float* dq = dQ + (size_t)k * D;
-    for (int i = wave; i < D; i += 16) {
+    for (int i = wave * 4 + rs; i < D; i += 64) {
       const float q = dq[i];
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[e] += to_f32(w[(size_t)i * D + e]) * q;
     }
   }
 #pragma unroll
-  for (int e = 0; e < 4; ++e) part[wave][lane * 4 + e] = acc[e];
+  for (int e = 0; e < 4; ++e) {
+    acc[e] += __shfl_xor(acc[e], 16, kWave);
+    acc[e] += __shfl_xor(acc[e], 32, kWave);
+  }
+  if (rs == 0) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) part[wave][cg * 4 + e] = acc[e];
+  }
   __syncthreads();
-  if (threadIdx.x < 256) {
-    const int jj = blockIdx.x * 256 + threadIdx.x;
+  if (threadIdx.x < 64) {
+    const int jj = blockIdx.x * 64 + threadIdx.x;
     float sum = 0.f;
 #pragma unroll
     for (int w16 = 0; w16 < 16; ++w16) sum += part[w16][threadIdx.x];
@@ -337,6 +345,46 @@ __global__ __launch_bounds__(1024) void k_query_input_grad(int D, const T* __res
 //   query weights: rowv = dQ, colv = the learned query, rows_per_vec = D
 // grid (ceil(D/256), D, G), block 256.
 // ---------------------------------------------------------------------------------------
+// The same for D % 8 == 0 and 16-byte aligned tensors: a thread writes 8 adjacent columns at once and takes 8 such
+// chunks, 256 * 8 chunks per block.  grid (ceil(D * D / 8 / 2048), G), block 256.
+template <typename TV, typename T>
+__global__ __launch_bounds__(256) void k_outer_rows_vec(int D, int rows_per_vec, float scale,
+                                                        const float* __restrict__ rowv, const TV* __restrict__ colv,
+                                                        T* __restrict__ out) {
+  const int k = blockIdx.y;
+  const int cpr = D / 8;                                           // chunks per row
+  const long chunks = (long)D * cpr;
+  const int nvec = D / rows_per_vec;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const long idx = ((long)blockIdx.x * 8 + u) * 256 + threadIdx.x;
+    if (idx >= chunks) return;
+    const int i = (int)(idx / cpr), j = (int)(idx % cpr) * 8;
+    const float rv = rowv[(size_t)k * D + i] * scale;
+    const TV* cv = colv + ((size_t)k * nvec + i / rows_per_vec) * D + j;
+    T* o = out + ((size_t)k * D + i) * D + j;
+    float c[8];
+    if constexpr (sizeof(TV) == 2) {
+      const bf16x8 v = *reinterpret_cast<const bf16x8*>(cv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) c[e] = (float)v[e];
+    } else {
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(cv), v1 = *reinterpret_cast<const f32x4*>(cv + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { c[e] = v0[e]; c[4 + e] = v1[e]; }
+    }
+    if constexpr (sizeof(T) == 2) {
+      bf16x8 r;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r[e] = (bf16)(rv * c[e]);
+      *reinterpret_cast<bf16x8*>(o) = r;
+    } else {
+      *reinterpret_cast<f32x4*>(o) = f32x4{rv * c[0], rv * c[1], rv * c[2], rv * c[3]};
+      *reinterpret_cast<f32x4*>(o + 4) = f32x4{rv * c[4], rv * c[5], rv * c[6], rv * c[7]};
+    }
+  }
+}
+
 template <typename TV, typename T>
 __global__ __launch_bounds__(256) void k_outer_rows(int D, int rows_per_vec, float scale,
                                                     const float* __restrict__ rowv, const TV* __restrict__ colv,
@@ -1048,9 +1096,9 @@ __global__ __launch_bounds__(256, 3 - HB) void k_dz_mfma(int Cin, int N, int D, 
 // use, a few microseconds later in the same workgroup, finds them in L2) and ds never leaves the compute unit:
 //   ds as in k_dalpha_softmax_mfma;  rpart[b,k,t][a][:] = sum over the pt patches of tile t and the members c of
 //   ds[b,c,n,a] * z[b,c,n,:]  (the partial sums k_sum_partials adds up);  dz as in k_dz_mfma.
-// grid (n_tiles, G, B), block 512, one patch at a time:
+// grid (n_tiles, G, B), block 512, PP patches (one) per round of barriers:
 //   d alpha   all eight wavefronts, each an eighth of D; the partial 16x16 blocks meet in LDS in a fixed order, the
-//             first wavefront applies the Jacobian and leaves the softmax weights and ds of the patch in LDS;
+//             first PP wavefronts apply the Jacobian (one patch each) and leave the softmax weights and ds in LDS;
 //   sums      wavefronts 0..3, wavefront w columns 256 w .. 256 w + 255: ds^T (heads x 32 members, split in two
 //             bf16 parts) times the 32 member rows on 16x16x32 MFMA; a lane reads 8 members x 8 adjacent columns
 //             (16 bytes per row) and transposes them in registers, which gives it the B fragments (column
@@ -1065,9 +1113,10 @@ __global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, i
                                                                const float* __restrict__ alpha,
                                                                const bf16* __restrict__ Mb, bf16* __restrict__ dz,
                                                                float* __restrict__ rpart) {
-  __shared__ f32x4 part[8][MT][64];
-  __shared__ float dsv[2][32][17];                                 // [patch parity][member][head], padded rows
-  __shared__ float alv[2][32][17];                                 // the softmax weights, same layout
+  constexpr int PP = 1;                                            // patches per round of barriers (2: no faster)
+  __shared__ f32x4 part[8][PP][MT][64];
+  __shared__ float dsv[2][PP][32][17];                             // [round parity][patch][member][head], padded rows
+  __shared__ float alv[2][PP][32][17];                             // the softmax weights, same layout
   const int tile = blockIdx.x, n_tiles = gridDim.x, k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
   const int c0 = k * g, gk = min(g, Cin - c0);
   const int n0 = tile * pt, np = min(pt, N - n0);
@@ -1079,60 +1128,73 @@ __global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, i
   const int head = min(l16, heads - 1);
   const bf16* zg = z + (((size_t)b * Cin + c0) * N + n0) * D;      // member 0 of the group at the tile's first patch
   const size_t item0 = ((size_t)b * G + k) * N + n0;
-  for (int i = threadIdx.x; i < 2 * 32 * 17; i += 512) {           // members beyond 16 MT stay zero
-    (&dsv[0][0][0])[i] = 0.f;
-    (&alv[0][0][0])[i] = 0.f;
+  for (int i = threadIdx.x; i < 2 * PP * 32 * 17; i += 512) {      // members beyond 16 MT stay zero
+    (&dsv[0][0][0][0])[i] = 0.f;
+    (&alv[0][0][0][0])[i] = 0.f;
   }
   __syncthreads();
 
+  // partial d alpha of patches pi .. pi + PP - 1 (past the tile's end: its last patch again, never used)
   auto dalpha_partial = [&](int pi) {
-    const bf16* wr = w + ((item0 + pi) * heads + head) * D + wave * kq + lq * 8;
-    const bf16* zr[MT];
+    const bf16* wr[PP];
+    const bf16* zr[PP][MT];
+    f32x4 acc[PP][MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      zr[mt] = zg + (size_t)pi * D + (size_t)min(mt * 16 + l16, gk - 1) * cstride + wave * kq + lq * 8;
-    f32x4 acc[MT];
+    for (int q = 0; q < PP; ++q) {
+      const int pq = min(pi + q, np - 1);
+      wr[q] = w + ((item0 + pq) * heads + head) * D + wave * kq + lq * 8;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int t = 0; t < kq; t += 128) {                            // four steps of 32 per trip, loads first
-      bf16x8 wf[4], zf[MT][4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int tt = min(t + q * 32, kq - 32);
-        wf[q] = *reinterpret_cast<const bf16x8*>(wr + tt);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) zf[mt][q] = *reinterpret_cast<const bf16x8*>(zr[mt] + tt);
+      for (int mt = 0; mt < MT; ++mt) {
+        zr[q][mt] = zg + (size_t)pq * D + (size_t)min(mt * 16 + l16, gk - 1) * cstride + wave * kq + lq * 8;
+        acc[q][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
+    }
+    for (int t = 0; t < kq; t += 128) {                            // four steps of 32 per trip, loads first
+      bf16x8 wf[PP][4], zf[PP][MT][4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (t + q * 32 < kq) {
+      for (int q = 0; q < PP; ++q)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf[mt][q], wf[q], acc[mt], 0, 0, 0);
+        for (int s4 = 0; s4 < 4; ++s4) {
+          const int tt = min(t + s4 * 32, kq - 32);
+          wf[q][s4] = *reinterpret_cast<const bf16x8*>(wr[q] + tt);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) zf[q][mt][s4] = *reinterpret_cast<const bf16x8*>(zr[q][mt] + tt);
         }
+#pragma unroll
+      for (int q = 0; q < PP; ++q)
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4)
+          if (t + s4 * 32 < kq) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              acc[q][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf[q][mt][s4], wf[q][s4], acc[q][mt], 0, 0, 0);
+          }
     }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) part[wave][mt][lane] = acc[mt];
+    for (int q = 0; q < PP; ++q)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) part[wave][q][mt][lane] = acc[q][mt];
   };
-  // the first wavefront fetches the softmax weights of a patch before its share of d alpha, so that they have
-  // arrived when the other wavefronts wait for the Jacobian (lane: head l16, members 4 lq + r of each tile)
+  // Wavefront q < PP applies the Jacobian of patch pi + q.  It fetches the softmax weights of that patch before its
+  // share of d alpha, so that they have arrived when the others wait (lane: head l16, members 4 lq + r of each tile).
   auto fetch_alpha = [&](int pi, float (&al)[MT][4]) {
+    const int n = n0 + min(pi + wave, np - 1);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int cl = mt * 16 + lq * 4 + r;
-        al[mt][r] = (cl < gk && l16 < heads) ? alpha[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + l16] : 0.f;
+        al[mt][r] = (cl < gk && l16 < heads) ? alpha[(((size_t)b * Cin + c0 + cl) * N + n) * heads + l16] : 0.f;
       }
   };
-  auto jacobian = [&](int pi, const float (&al)[MT][4]) {
+  auto jacobian = [&](int par, const float (&al)[MT][4]) {
     float da[MT][4];
     float dot = 0.f;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      f32x4 tot = part[0][mt][lane];
+      f32x4 tot = part[0][wave][mt][lane];
 #pragma unroll
-      for (int v = 1; v < 8; ++v) tot += part[v][mt][lane];
+      for (int v = 1; v < 8; ++v) tot += part[v][wave][mt][lane];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         da[mt][r] = tot[r];
@@ -1146,53 +1208,55 @@ __global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, i
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int cl = mt * 16 + lq * 4 + r;
-        dsv[pi & 1][cl][l16] = al[mt][r] * (da[mt][r] - dot);      // 0 for padding members and heads
-        alv[pi & 1][cl][l16] = al[mt][r];
+        dsv[par][wave][cl][l16] = al[mt][r] * (da[mt][r] - dot);   // 0 for padding members and heads
+        alv[par][wave][cl][l16] = al[mt][r];
       }
   };
-  // Per patch: every wavefront writes its partial block, barrier, the first wavefront fills the tables of parity
-  // pi & 1, barrier, the roles read them.  The next patch writes the other parity, and `part` only after every
-  // wavefront has passed the second barrier of this one.
+  // Per round of PP patches: every wavefront writes its partial blocks, barrier, wavefronts 0 .. PP-1 fill the tables
+  // of the round's parity, barrier, the roles read them.  The next round writes the other parity, and `part` only
+  // after every wavefront has passed the second barrier of this one.
   if (wave < 4) {
     f32x4 racc[2][8];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int j = 0; j < 8; ++j) racc[h][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int pi = 0; pi < np; ++pi) {
+    for (int pi = 0, par = 0; pi < np; pi += PP, par ^= 1) {
       float al[MT][4];
-      if (wave == 0) fetch_alpha(pi, al);
+      if (wave < PP) fetch_alpha(pi, al);
       dalpha_partial(pi);
       __syncthreads();
-      if (wave == 0) jacobian(pi, al);
+      if (wave < PP) jacobian(par, al);
       __syncthreads();
       if (col0 < D) {
-        f32x4 v0, v1;                                              // ds of head l16 at members 8 lq .. 8 lq + 7
+        for (int q = 0; q < PP && pi + q < np; ++q) {
+          f32x4 v0, v1;                                            // ds of head l16 at members 8 lq .. 8 lq + 7
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          v0[i] = dsv[pi & 1][8 * lq + i][l16];
-          v1[i] = dsv[pi & 1][8 * lq + 4 + i][l16];
-        }
-        bf16x8 dhi, dlo;
-        split_bf16(v0, v1, dhi, dlo);
-        const bf16* zc = zg + (size_t)pi * D + col0 + 8 * l16;
-        bf16x8 rows[2][8];
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int i = 0; i < 8; ++i)
-            rows[h][i] = __builtin_nontemporal_load(                // second and last use of the row
-                reinterpret_cast<const bf16x8*>(zc + (size_t)min(8 * lq + i, gk - 1) * cstride + 128 * h));
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            bf16x8 col;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) col[i] = rows[h][i][j];
-            racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dhi, col, racc[h][j], 0, 0, 0);
-            racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dlo, col, racc[h][j], 0, 0, 0);
+          for (int i = 0; i < 4; ++i) {
+            v0[i] = dsv[par][q][8 * lq + i][l16];
+            v1[i] = dsv[par][q][8 * lq + 4 + i][l16];
           }
+          bf16x8 dhi, dlo;
+          split_bf16(v0, v1, dhi, dlo);
+          const bf16* zc = zg + (size_t)(pi + q) * D + col0 + 8 * l16;
+          bf16x8 rows[2][8];
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              rows[h][i] = __builtin_nontemporal_load(              // second and last use of the row
+                  reinterpret_cast<const bf16x8*>(zc + (size_t)min(8 * lq + i, gk - 1) * cstride + 128 * h));
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              bf16x8 col;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) col[i] = rows[h][i][j];
+              racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dhi, col, racc[h][j], 0, 0, 0);
+              racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dlo, col, racc[h][j], 0, 0, 0);
+            }
+        }
       }
     }
     if (col0 < D) {
@@ -1215,48 +1279,50 @@ __global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, i
     bf16x8 mfrag[2][4];
     if (col0 < D) head_row_frags(Mb + ((size_t)k * heads) * D + d0c, D, heads, lhi, mfrag);
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int pi = 0; pi < np; ++pi) {
+    for (int pi = 0, par = 0; pi < np; pi += PP, par ^= 1) {
       dalpha_partial(pi);
       __syncthreads();
       __syncthreads();
       if (col0 < D) {
-        bf16x8 wfrag[2][4];
-        head_row_frags<true>(w + ((item0 + pi) * heads) * D + d0c, D, heads, lhi, wfrag);
-        f32x4 a0, a1, e0, e1;                                      // member row l32, heads 8 lhi .. 8 lhi + 7
+        for (int q = 0; q < PP && pi + q < np; ++q) {
+          bf16x8 wfrag[2][4];
+          head_row_frags<true>(w + ((item0 + pi + q) * heads) * D + d0c, D, heads, lhi, wfrag);
+          f32x4 a0, a1, e0, e1;                                    // member row l32, heads 8 lhi .. 8 lhi + 7
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          a0[i] = alv[pi & 1][l32][8 * lhi + i];
-          a1[i] = alv[pi & 1][l32][8 * lhi + 4 + i];
-          e0[i] = dsv[pi & 1][l32][8 * lhi + i];
-          e1[i] = dsv[pi & 1][l32][8 * lhi + 4 + i];
-        }
-        bf16x8 ahi, alo, ehi, elo;
-        split_bf16(a0, a1, ahi, alo);
-        split_bf16(e0, e1, ehi, elo);
-        auto tiles_of_half = [&](int half) {
-          f32x16 acc[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, wfrag[half][e], zero, 0, 0, 0);
-            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, wfrag[half][e], acc[e], 0, 0, 0);
-            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi, mfrag[half][e], acc[e], 0, 0, 0);
-            acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(elo, mfrag[half][e], acc[e], 0, 0, 0);
+          for (int i = 0; i < 4; ++i) {
+            a0[i] = alv[par][q][l32][8 * lhi + i];
+            a1[i] = alv[par][q][l32][8 * lhi + 4 + i];
+            e0[i] = dsv[par][q][l32][8 * lhi + i];
+            e1[i] = dsv[par][q][l32][8 * lhi + 4 + i];
           }
-          bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n0 + pi) * D + col0 + 4 * (l32 + 32 * half);
+          bf16x8 ahi, alo, ehi, elo;
+          split_bf16(a0, a1, ahi, alo);
+          split_bf16(e0, e1, ehi, elo);
+          auto tiles_of_half = [&](int half) {
+            f32x16 acc[4];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int m = 8 * (r >> 2) + 4 * lhi + (r & 3);
-            if (m < gk) {
-              bf16x4 o;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[e][r];
-              // streaming store: dz is not read again here, and the rows to come back from L2 are z's and w's
-              __builtin_nontemporal_store(o, reinterpret_cast<bf16x4*>(dzp + (size_t)m * cstride));
+            for (int e = 0; e < 4; ++e) {
+              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, wfrag[half][e], zero, 0, 0, 0);
+              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, wfrag[half][e], acc[e], 0, 0, 0);
+              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi, mfrag[half][e], acc[e], 0, 0, 0);
+              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(elo, mfrag[half][e], acc[e], 0, 0, 0);
             }
-          }
-        };
-        tiles_of_half(0);
-        tiles_of_half(1);
+            bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n0 + pi + q) * D + col0 + 4 * (l32 + 32 * half);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int m = 8 * (r >> 2) + 4 * lhi + (r & 3);
+              if (m < gk) {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[e][r];
+                // streaming store: dz is not read again here, and the rows to come back from L2 are z's and w's
+                __builtin_nontemporal_store(o, reinterpret_cast<bf16x4*>(dzp + (size_t)m * cstride));
+              }
+            }
+          };
+          tiles_of_half(0);
+          tiles_of_half(1);
+        }
       }
     }
   }
