@@ -417,6 +417,15 @@ inline int softmax_backward(int B, int Cin, int N, int D, int heads, int g, cons
     else k_dalpha_softmax_mfma<4><<<grid, 256, 0, st>>>(items, Cin, N, D, heads, g, G, z, w, alpha, ds);
     return launch_status();
   }
+  const size_t big_lds = ((size_t)16 * ((std::min(g, Cin) + 15) / 16) + 17) * 16 * 4;
+  const long items = (long)B * G * N;
+  if (D % 32 == 0 && big_lds <= 128 * 1024 && items <= 0x7fffffffL && !getenv("DCHAG_GENERIC_LEVEL")) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dalpha_softmax_group),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)big_lds) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    k_dalpha_softmax_group<<<dim3((unsigned)items), 256, big_lds, st>>>(Cin, N, D, heads, g, G, z, w, alpha, ds);
+    return launch_status();
+  }
   const long T_total = (long)B * Cin * N;
   k_dalpha<bf16><<<dim3((unsigned)((T_total + 3) / 4)), 256, 0, st>>>(T_total, Cin, N, D, heads, g, G, z, w, ds);
   int rc = launch_status();
@@ -433,7 +442,8 @@ inline bool tokens_fused(int B, int Cin, int N, int D, int heads, int g) {
   const int G = groups_of(Cin, g);
   const size_t lds = (size_t)2 * dz_patches(B, G, N, D, g) * g * 16 * 4;
   return D % 256 == 0 && D <= 1024 && heads <= 16 && std::min(g, Cin) <= 32 && lds <= 128 * 1024 &&
-         !getenv("DCHAG_DZ_VALU") && !getenv("DCHAG_GENERIC_LEVEL") && !getenv("DCHAG_TOKENS_UNFUSED");
+         !getenv("DCHAG_DZ_VALU") && !getenv("DCHAG_GENERIC_LEVEL") && !getenv("DCHAG_TOKENS_UNFUSED") &&
+         !getenv("DCHAG_RPART_VALU");
 }
 inline int sum_key_path_partials(int B, int G, int n_tiles, int heads, int D, const float* rpart, float* r,
                                  hipStream_t st) {
@@ -506,12 +516,16 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
       if (heads <= 16) k_dz_mfma<1><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
       else k_dz_mfma<2><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
       if ((rc = launch_status())) return rc;
-      if (want_r) {
-        auto rk = heads <= 16 ? k_rpart_bf16<1> : k_rpart_bf16<2>;
+      if (want_r) {                                               // DCHAG_RPART_VALU (debugging aid): vector-ALU sums
+        const bool valu = getenv("DCHAG_RPART_VALU") != nullptr;
+        const size_t rl = (size_t)pt * g * (heads <= 16 ? 16 : 32) * 4;
+        auto rk = valu ? (heads <= 16 ? k_rpart_bf16<1> : k_rpart_bf16<2>)
+                       : (heads <= 16 ? k_rpart_mfma<1> : k_rpart_mfma<2>);
+        const size_t rlds = valu ? lds / 2 : rl;
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(rk), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(lds / 2)) != hipSuccess)
+                                (int)rlds) != hipSuccess)
           return DCHAG_ERR_LAUNCH;
-        rk<<<grid, 256, lds / 2, st>>>(Cin, N, D, heads, g, n_tiles, pt, ds, zin, rpart);
+        rk<<<grid, 256, rlds, st>>>(Cin, N, D, heads, g, n_tiles, pt, ds, zin, rpart);
         if ((rc = launch_status())) return rc;
       }
     } else {

@@ -857,6 +857,77 @@ __global__ __launch_bounds__(256) void k_dalpha_softmax_mfma(long items, int Cin
 }
 
 // ---------------------------------------------------------------------------------------
+// The same for groups of any size (the flat single-layer baseline has one group of all channels), bf16, D % 32 == 0:
+// one block of four wavefronts per (b, k, n).  The wavefronts take the tiles of 16 members in turn (16x16x32 MFMA as
+// above, the head rows of w re-read from L1 per tile) and leave d alpha of the whole group in LDS; then the sums
+// sum_c alpha dalpha per head are formed in a fixed order and ds is written.  grid B G N, block 256, dynamic LDS
+// (16 ceil(g/16) + 17) * 16 floats.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_dalpha_softmax_group(int Cin, int N, int D, int heads, int g, int G,
+                                                              const bf16* __restrict__ z, const bf16* __restrict__ w,
+                                                              const float* __restrict__ alpha, float* __restrict__ ds) {
+  extern __shared__ __attribute__((aligned(16))) float sm[];       // da[16 ntile][16], red[16][16], dot[16]
+  const long item = blockIdx.x;                                    // (b * G + k) * N + n
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, lq = lane >> 4;
+  const int n = (int)(item % N);
+  const int k = (int)((item / N) % G), b = (int)(item / ((long)N * G));
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  const int ntile = (gk + 15) / 16;
+  float* da = sm;
+  float* red = sm + ntile * 256;
+  float* dot = red + 256;
+  const size_t cstride = (size_t)N * D;
+  const bf16* zb = z + (((size_t)b * Cin + c0) * N + n) * D + lq * 8;
+  const float* ab = alpha + (((size_t)b * Cin + c0) * N + n) * heads;   // member cl: + cl * N * heads
+  float* dsb = ds + (((size_t)b * Cin + c0) * N + n) * heads;
+  const size_t astride = (size_t)N * heads;
+  for (int a0 = 0; a0 < heads; a0 += 16) {
+    const int head = min(a0 + l16, heads - 1);
+    const bf16* wr = w + ((size_t)item * heads + head) * D + lq * 8;
+    for (int tile = wave; tile < ntile; tile += 4) {
+      const bf16* zr = zb + (size_t)min(tile * 16 + l16, gk - 1) * cstride;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < D; t += 128) {                           // four steps of 32 per trip, loads first
+        bf16x8 wf[4], zf[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int tt = min(t + q * 32, D - 32);
+          wf[q] = *reinterpret_cast<const bf16x8*>(wr + tt);
+          zf[q] = *reinterpret_cast<const bf16x8*>(zr + tt);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (t + q * 32 < D) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf[q], wf[q], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) da[(tile * 16 + lq * 4 + r) * 16 + l16] = acc[r];   // lane: head l16, members 4 lq + r
+    }
+    __syncthreads();
+    {
+      const int hd = threadIdx.x & 15, part = threadIdx.x >> 4;
+      float p = 0.f;
+      if (a0 + hd < heads)
+        for (int cl = part; cl < gk; cl += 16) p += ab[(size_t)cl * astride + a0 + hd] * da[cl * 16 + hd];
+      red[part * 16 + hd] = p;
+    }
+    __syncthreads();
+    if (threadIdx.x < 16) {
+      float sum = 0.f;
+#pragma unroll
+      for (int part = 0; part < 16; ++part) sum += red[part * 16 + threadIdx.x];
+      dot[threadIdx.x] = sum;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < gk * 16; idx += 256) {
+      const int cl = idx >> 4, hd = idx & 15;
+      if (a0 + hd < heads)
+        dsb[(size_t)cl * astride + a0 + hd] = ab[(size_t)cl * astride + a0 + hd] * (da[idx] - dot[hd]);
+    }
+    __syncthreads();                                               // the next block of heads overwrites da
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Gradient at the input tokens and the key-path sums, bf16, heads <= 16, D % 4 == 0:
 //   dz[b,c,n,:]   = sum_a alpha[b,c,n,a] * w[b,k,n,a,:] + ds[b,c,n,a] * M[k][a][:]
 //   rpart[b,k,t][a][:] = sum over the PT patches of tile t and the members c of  ds[b,c,n,a] * z[b,c,n,:]
@@ -1397,6 +1468,94 @@ __global__ __launch_bounds__(256) void k_rpart_bf16(int Cin, int N, int D, int h
     for (int a = 0; a < 16; ++a)
       if (a0 + a < heads) *reinterpret_cast<f32x4*>(rp + (size_t)a * D) = f32x4{racc[a][0], racc[a][1], racc[a][2], racc[a][3]};
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// k_rpart_mfma: the same partial sums on 16x16x32 MFMA for D % 256 == 0 (bf16, heads <= 16 HB), as in
+// k_tokens_backward_fused: per patch and block of 32 members, ds^T (16 heads x 32 members, hi + lo bf16 parts) times
+// the 32 member rows; a lane reads 8 members x 8 adjacent columns and transposes them in registers.
+// grid (n_tiles * ceil(D/1024), G, B), block 256: wavefront w owns columns 1024 cb + 256 w .. + 255.  ds of the whole
+// tile sits in LDS (dynamic, pt * g * 16 HB floats, rows in (patch, member) order).
+// ---------------------------------------------------------------------------------------
+template <int HB>
+__global__ __launch_bounds__(256, 2) void k_rpart_mfma(int Cin, int N, int D, int heads, int g, int n_tiles, int pt,
+                                                       const float* __restrict__ ds, const bf16* __restrict__ z,
+                                                       float* __restrict__ rpart) {
+  extern __shared__ __attribute__((aligned(16))) float dsv[];      // [np * gk rows][16 HB heads]
+  constexpr int HP = 16 * HB;
+  const int tile = blockIdx.x % n_tiles, cb = blockIdx.x / n_tiles;
+  const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, Cin - c0);
+  const int n0 = tile * pt, np = min(pt, N - n0);
+  const int rows = np * gk;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, lq = lane >> 4;
+  const int col0 = cb * 1024 + wave * 256;
+  for (int idx = threadIdx.x; idx < rows * HP; idx += 256) {
+    const int a = idx % HP, cl = (idx / HP) % gk, pi = (idx / HP) / gk;
+    dsv[idx] = a < heads ? ds[(((size_t)b * Cin + c0 + cl) * N + n0 + pi) * heads + a] : 0.f;
+  }
+  __syncthreads();
+  if (col0 >= D) return;
+  f32x4 racc[HB][2][8];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) racc[hb][h][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const size_t cstride = (size_t)N * D;
+  const bf16* zb = z + (((size_t)b * Cin + c0) * N + n0) * D + col0 + 8 * l16;
+  for (int pi = 0; pi < np; ++pi)
+    for (int m0 = 0; m0 < gk; m0 += 32) {                          // members m0 + 8 lq .. + 7 are this lane's
+      bf16x8 dhi[HB], dlo[HB];
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) {
+        f32x4 v0, v1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int cl = m0 + 8 * lq + i;
+          const float v = cl < gk ? dsv[(pi * gk + cl) * HP + 16 * hb + l16] : 0.f;
+          if (i < 4) v0[i] = v; else v1[i - 4] = v;
+        }
+        split_bf16(v0, v1, dhi[hb], dlo[hb]);
+      }
+      bf16x8 zr[2][8];
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          zr[h][i] = *reinterpret_cast<const bf16x8*>(zb + (size_t)pi * D + (size_t)min(m0 + 8 * lq + i, gk - 1) * cstride +
+                                                     128 * h);
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          bf16x8 col;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) col[i] = zr[h][i][j];
+#pragma unroll
+          for (int hb = 0; hb < HB; ++hb) {
+            racc[hb][h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dhi[hb], col, racc[hb][h][j], 0, 0, 0);
+            racc[hb][h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dlo[hb], col, racc[hb][h][j], 0, 0, 0);
+          }
+        }
+    }
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int a = 16 * hb + 4 * lq + r;
+      if (a < heads) {
+        float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads + a) * D + col0 + 8 * l16;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          *reinterpret_cast<f32x4*>(rp + 128 * h) =
+              f32x4{racc[hb][h][0][r], racc[hb][h][1][r], racc[hb][h][2][r], racc[hb][h][3][r]};
+          *reinterpret_cast<f32x4*>(rp + 128 * h + 4) =
+              f32x4{racc[hb][h][4][r], racc[hb][h][5][r], racc[hb][h][6][r], racc[hb][h][7][r]};
+        }
+      }
+    }
 }
 
 // r[k][i] = sum_b sum_t rpart[b][k][t][i]   (i over heads * D), fixed order.  grid (ceil(per/64), G), block 256:

@@ -75,6 +75,10 @@ SMALL = [
     dict(dtype="bf16", B=1, C=12, H=32, W=64, p=8, D=1024, heads=32, group_sizes=(6, 2)),
     # 24 heads: the second head block is half empty
     dict(dtype="bf16", B=1, C=7, H=16, W=32, p=4, D=768, heads=24, group_sizes=(4, 2)),
+    # groups of more than 64 channels (70 + 5): the d-alpha kernel for groups of any size, five member tiles
+    dict(dtype="bf16", B=1, C=75, H=16, W=16, p=4, D=256, heads=4, group_sizes=(70, 2)),
+    # one flat layer over 75 channels with 20 heads (two head passes of that kernel)
+    dict(dtype="bf16", B=1, C=75, H=8, W=16, p=4, D=320, heads=20, group_sizes=(75,)),
 ]
 
 
@@ -186,7 +190,7 @@ def test_backward_matches_oracle(kw):
 
 
 @pytest.mark.parametrize("env", ["DCHAG_GENERIC_LEVEL", "DCHAG_GEMM_GENERIC", "DCHAG_DZ_VALU", "DCHAG_COLSUM",
-                                 "DCHAG_GEMM_SCALAR_STORES", "DCHAG_TOKENS_UNFUSED"])
+                                 "DCHAG_GEMM_SCALAR_STORES", "DCHAG_TOKENS_UNFUSED", "DCHAG_RPART_VALU"])
 def test_backward_generic_bf16_kernels_still_match(monkeypatch, env):
     """The shape-generic bf16 kernels (taken for shapes the MFMA and streaming kernels do not tile) on a shape
     the fast kernels would take, forced through the library's debug switches."""
