@@ -657,12 +657,24 @@ int linear_level_backward(int B, int Cin, int N, int D, const dchag_level* lv, c
   int rc;
   StageTimer tm(DCHAG_STAGE_BWD_CHANNEL_MIX, st);
   const long total = (long)B * Cin * N * D;
-  k_channel_mix_dz<T><<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(total, Cin, N, D, g, G,
-                                                                            static_cast<const T*>(lv->Wv), dy, dz);
+  const bool vec = D % 8 == 0 && Cin <= 65535 && B <= 65535 && !getenv("DCHAG_GEMM_SCALAR_STORES") &&
+                   !((reinterpret_cast<uintptr_t>(lv->Wv) | reinterpret_cast<uintptr_t>(dy) |
+                      reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(zin) |
+                      reinterpret_cast<uintptr_t>(gr->dWv)) & 15);
+  if (vec)
+    k_channel_mix_dz_vec<T><<<dim3((N + 15) / 16, Cin, B), 256, 0, st>>>(Cin, N, D, g, G, static_cast<const T*>(lv->Wv),
+                                                                        dy, dz);
+  else
+    k_channel_mix_dz<T><<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(total, Cin, N, D, g, G,
+                                                                              static_cast<const T*>(lv->Wv), dy, dz);
   if ((rc = launch_status())) return rc;
   if (gr->dWv) {
-    k_channel_mix_dw<T><<<dim3((D + 63) / 64, G * g), 256, 0, st>>>(B, Cin, N, D, g, G, zin, dy,
-                                                                    static_cast<T*>(gr->dWv));
+    if (vec)
+      k_channel_mix_dw_vec<T><<<dim3((D + 1023) / 1024, G * g), 256, 0, st>>>(B, Cin, N, D, g, G, zin, dy,
+                                                                             static_cast<T*>(gr->dWv));
+    else
+      k_channel_mix_dw<T><<<dim3((D + 63) / 64, G * g), 256, 0, st>>>(B, Cin, N, D, g, G, zin, dy,
+                                                                      static_cast<T*>(gr->dWv));
     if ((rc = launch_status())) return rc;
   }
   if (gr->dbv) return colsum<T>(B, D, RowBlocks{G, G * N, N}, dy, static_cast<T*>(gr->dbv), st);

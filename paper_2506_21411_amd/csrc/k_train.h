@@ -474,6 +474,93 @@ __global__ __launch_bounds__(256) void k_channel_mix_dw(int B, int Cin, int N, i
   if (wave == 0 && d < D) dw[(size_t)kc * D + d] = from_f32<T>(acc + part[0][lane] + part[1][lane] + part[2][lane]);
 }
 
+// The same two kernels for D % 8 == 0 and 16-byte aligned tensors, 8 adjacent columns per thread.
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float (&v)[8]) {
+  if constexpr (sizeof(T) == 2) {
+    const bf16x8 x = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)x[e];
+  } else {
+    const f32x4 x0 = *reinterpret_cast<const f32x4*>(p), x1 = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = x0[e]; v[4 + e] = x1[e]; }
+  }
+}
+template <typename T>
+__device__ __forceinline__ void store8(T* p, const float (&v)[8]) {
+  if constexpr (sizeof(T) == 2) {
+    bf16x8 x;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = (bf16)v[e];
+    *reinterpret_cast<bf16x8*>(p) = x;
+  } else {
+    *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+  }
+}
+
+// dz: grid (ceil(N / 16), Cin, B), block 256: thread t takes the columns 8 (t % (D/8)) .. of every (256 / (D/8))-th
+// patch of the block's 16 when D <= 2048, and walks the columns otherwise; the mixing weights stay in registers.
+template <typename T>
+__global__ __launch_bounds__(256) void k_channel_mix_dz_vec(int Cin, int N, int D, int g, int G,
+                                                            const T* __restrict__ w, const T* __restrict__ dy,
+                                                            T* __restrict__ dz) {
+  const int c = blockIdx.y, b = blockIdx.z, k = c / g, cl = c % g;
+  const int n0 = blockIdx.x * 16, n1 = min(n0 + 16, N);
+  const int d8 = D / 8;
+  const T* wr = w + ((size_t)k * g + cl) * D;
+  const T* yb = dy + (((size_t)b * G + k) * N) * D;
+  T* zb = dz + (((size_t)b * Cin + c) * N) * D;
+  for (int ch = threadIdx.x; ch < 16 * d8; ch += 256) {            // chunk: (patch of the tile, 8 columns)
+    const int n = n0 + ch / d8, d = (ch % d8) * 8;
+    if (n >= n1) break;
+    float wv[8], yv[8];
+    load8(wr + d, wv);
+    load8(yb + (size_t)n * D + d, yv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) yv[e] *= wv[e];
+    store8(zb + (size_t)n * D + d, yv);
+  }
+}
+
+// dw: grid (ceil(D / 1024), G * g), block 256: 128 threads cover 1024 columns, the two halves of the block take the
+// even and the odd rows (b, n) and meet in LDS.
+template <typename T>
+__global__ __launch_bounds__(256) void k_channel_mix_dw_vec(int B, int Cin, int N, int D, int g, int G,
+                                                            const T* __restrict__ z, const T* __restrict__ dy,
+                                                            T* __restrict__ dw) {
+  __shared__ float part[128][9];
+  const int kc = blockIdx.y;
+  const int k = kc / g, cl = kc % g, c = k * g + cl;
+  const int t = threadIdx.x & 127, half = threadIdx.x >> 7;
+  const int d = blockIdx.x * 1024 + t * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const bool live = d < D && c < Cin;
+  if (live) {
+    const long rows = (long)B * N;
+#pragma unroll 4
+    for (long r = half; r < rows; r += 2) {
+      const int b = (int)(r / N), n = (int)(r % N);
+      float zv[8], yv[8];
+      load8(z + (((size_t)b * Cin + c) * N + n) * D + d, zv);
+      load8(dy + (((size_t)b * G + k) * N + n) * D + d, yv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += zv[e] * yv[e];
+    }
+  }
+  if (half == 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[t][e] = acc[e];
+  }
+  __syncthreads();
+  if (half == 0 && d < D) {                                        // members a short last group lacks: zero
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += part[t][e];
+    store8(dw + (size_t)kc * D + d, acc);
+  }
+}
+
 }  // namespace dchag
 
 // =======================================================================================
