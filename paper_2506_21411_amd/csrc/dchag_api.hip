@@ -40,8 +40,25 @@ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // Fast path: alpha holds scores, then softmax weights, as [B][G][gpad][heads][Np] floats.
 // Generic path: s holds scores [B,Cin,N,heads], v the projected values [B,Cin,N,D].
 struct LevelWs {
-  size_t qp, mf, mb, alpha, s, v, o, total;
+  size_t qp, mf, mb, alpha, s, v, o, vpart, total;
 };
+
+int compute_units();
+
+// Items the value GEMM of a level deals a group's chunks of 8 channels to, so that a level of few groups (the flat
+// baseline, the top of a hierarchy) still fills the chip: doubled while there are fewer than two items per compute
+// unit, never more than the chunks of the smallest group, at most 8.  DCHAG_VAGG_SPLIT overrides (still clamped).
+int vagg_splits(int B, int Cin, int N, int D, int g) {
+  const int G = groups_of(Cin, g);
+  const int last = Cin - (G - 1) * g;
+  const int nch_min = (std::min(g, last) + 7) / 8;
+  const long items = (long)(D / 256) * ((N + 31) / 32) * B * G;
+  int S = 1;
+  if (const char* e = getenv("DCHAG_VAGG_SPLIT")) S = std::max(1, atoi(e));
+  else while (items * S < 2L * compute_units() && S < 8) S *= 2;
+  while (S > nch_min) S >>= 1;
+  return std::max(S, 1);
+}
 
 LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g) {
   const int G = groups_of(Cin, g);
@@ -59,6 +76,11 @@ LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g)
     w.v = off;  off += align_up((size_t)B * Cin * N * D * es);
   }
   w.o = off;  off += align_up((size_t)B * G * N * D * es);
+  if (fast) {
+    const int S = vagg_splits(B, Cin, N, D, g);
+    w.vpart = off;
+    if (S > 1) off += align_up((size_t)S * B * G * N * D * 4);
+  }
   w.total = off;
   return w;
 }
@@ -452,7 +474,9 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     tw.n_tiles = D / kGemmBN;
     tw.m_tiles = (N + 31) / 32;
     tw.nb = B;
-    tw.total = tw.n_tiles * tw.m_tiles * B * G;
+    const int S = vagg_splits(B, Cin, N, D, g);
+    float* Opart = reinterpret_cast<float*>(ws + w.vpart);
+    tw.total = tw.n_tiles * tw.m_tiles * B * G * S;
     const int per = (tw.total + kXcds - 1) / kXcds;
     const int dh = D / heads;
     const int NHS = dh >= kGemmBN ? 1 : kGemmBN / dh;
@@ -464,8 +488,14 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     const int slots = per < compute_units() / kXcds ? per : compute_units() / kXcds;
     k_vagg_mfma<<<dim3(slots * kXcds), dim3(512), lds, st>>>(Cin, N, D, heads, g, gpad, G, Np, tw, slots, zin,
                                                             static_cast<const bf16*>(lv->Wv),
-                                                            static_cast<const bf16*>(lv->bv), alpha, O);
+                                                            static_cast<const bf16*>(lv->bv), alpha, O, S, Opart);
     if ((rc = launch_status())) return rc;
+    if (S > 1) {
+      const long per_split = (long)B * G * N * D, quads = per_split / 4;
+      k_vagg_merge<<<dim3((unsigned)((quads + 255) / 256)), 256, 0, st>>>(quads, S, G, N, D, per_split, Opart,
+                                                                         static_cast<const bf16*>(lv->bv), O);
+      if ((rc = launch_status())) return rc;
+    }
   }
   StageTimer tm(DCHAG_STAGE_OPROJ, st);
   RowBlocks rbo{G, G * N, N};

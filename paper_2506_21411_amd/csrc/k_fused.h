@@ -436,13 +436,14 @@ __device__ __forceinline__ void mfma_slice(f32x16 (&acc)[4][2], const unsigned c
 // Dynamic LDS: ring (128 KiB) + 3 alpha tiles of 8 * NHS * 32 floats, used round-robin by chunk.
 // ---------------------------------------------------------------------------------------------
 struct VaggItem {
-  int k, b, n0, o0, c0, gk, nch, h0;
+  int k, b, n0, o0, c0, gk, nch, h0, ch0, split;
 };
 
 __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int heads, int g, int gpad, int G, int Np,
                                                    TileWork tw, int slots, const bf16* __restrict__ z,
                                                    const bf16* __restrict__ Wv, const bf16* __restrict__ bv,
-                                                   const float* __restrict__ alpha, bf16* __restrict__ O) {
+                                                   const float* __restrict__ alpha, bf16* __restrict__ O, int S,
+                                                   float* __restrict__ Opart) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int KT = D / kGemmBK;
   const int dh = D / heads;
@@ -458,12 +459,15 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
     const int w = xcd * per + t * slots + slot;
     if (w >= xcd_end) return false;
     int pt, nt;
-    tw.decode_linear(w, it.k, it.b, pt, nt);
+    it.split = w % S;                                    // the group's chunks are dealt to S items (S <= chunks of any group)
+    tw.decode_linear(w / S, it.k, it.b, pt, nt);
     it.n0 = pt * 32;
     it.o0 = nt * kGemmBN;
     it.c0 = it.k * g;
     it.gk = min(g, Cin - it.c0);
-    it.nch = (it.gk + 7) / 8;
+    const int nch = (it.gk + 7) / 8;
+    it.ch0 = it.split * nch / S;
+    it.nch = (it.split + 1) * nch / S - it.ch0;
     it.h0 = it.o0 / dh;
     return true;
   };
@@ -494,7 +498,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
   auto setup_chunk = [&]() {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int c = ii.c0 + min(ci * 8 + a_ch[i], ii.gk - 1);
+      const int c = ii.c0 + min((ii.ch0 + ci) * 8 + a_ch[i], ii.gk - 1);
       a_cur[i] = zb + (size_t)c * N * D + a_rowoff[i];
       b_cur[i] = b_src[i];
     }
@@ -514,7 +518,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
     if (live) {
       if (ki == 0 && L.wave < NHS) {                     // entering a chunk: fetch its softmax weights
         const int sgm = L.wave * 8 + (L.lane >> 3);      // segment = (channel of the chunk, head of the slice)
-        const int cl = ci * 8 + sgm / NHS, hd = sgm % NHS;
+        const int cl = (ii.ch0 + ci) * 8 + sgm / NHS, hd = sgm % NHS;
         const float* src = alpha + ((((size_t)ii.b * G + ii.k) * gpad + cl) * heads + ii.h0 + hd) * Np + ii.n0 +
                            (L.lane & 7) * 4;
         load16_to_lds(src, alds + (gci % 3) * atile + L.wave * 1024);
@@ -602,19 +606,49 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
         }
       }
     }
-    bf16* Ob = O + (((size_t)ic.b * G + ic.k) * N) * D;
+    if (S == 1) {
+      bf16* Ob = O + (((size_t)ic.b * G + ic.k) * N) * D;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = ic.o0 + L.wn * 64 + j * 32 + L.l32;
-      const float bias = bv ? (float)bv[(size_t)ic.k * D + col] : 0.f;
+      for (int j = 0; j < 2; ++j) {
+        const int col = ic.o0 + L.wn * 64 + j * 32 + L.l32;
+        const float bias = bv ? (float)bv[(size_t)ic.k * D + col] : 0.f;
 #pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int nrow = ic.n0 + 16 * L.wm + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
-        if (nrow < N) Ob[(size_t)nrow * D + col] = (bf16)(o[j][r] + bias);
+        for (int r = 0; r < 8; ++r) {
+          const int nrow = ic.n0 + 16 * L.wm + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
+          if (nrow < N) Ob[(size_t)nrow * D + col] = (bf16)(o[j][r] + bias);
+        }
+      }
+    } else {                                             // partial sum over this item's chunks; k_vagg_merge adds them up
+      float* Pb = Opart + ((((size_t)ic.split * tw.nb + ic.b) * G + ic.k) * N) * D;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = ic.o0 + L.wn * 64 + j * 32 + L.l32;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const int nrow = ic.n0 + 16 * L.wm + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
+          if (nrow < N) Pb[(size_t)nrow * D + col] = o[j][r];
+        }
       }
     }
   }
   wait_vmcnt<0>();                                       // nothing may still target LDS when the block retires
+}
+
+// O[b,k,n,:] = sum over the S partial sums of k_vagg_mfma + bv[k][:], in a fixed order.  One thread per 4 columns.
+__global__ __launch_bounds__(256) void k_vagg_merge(long quads, int S, int G, int N, int D, long per_split,
+                                                    const float* __restrict__ Opart, const bf16* __restrict__ bv,
+                                                    bf16* __restrict__ O) {
+  const long q = (long)blockIdx.x * 256 + threadIdx.x;
+  if (q >= quads) return;
+  const long i = q * 4;                                  // ((b * G + k) * N + n) * D + col
+  const int col = (int)(i % D);
+  const int k = (int)((i / ((long)N * D)) % G);
+  f32x4 acc = *reinterpret_cast<const f32x4*>(Opart + i);
+  for (int sidx = 1; sidx < S; ++sidx) acc += *reinterpret_cast<const f32x4*>(Opart + sidx * per_split + i);
+  bf16x4 out;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) out[e] = (bf16)(acc[e] + (bv ? (float)bv[(size_t)k * D + col + e] : 0.f));
+  *reinterpret_cast<bf16x4*>(O + i) = out;
 }
 
 // ---------------------------------------------------------------------------------------------

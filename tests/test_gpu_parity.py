@@ -176,6 +176,23 @@ def test_aggregate_level_large_enough_for_the_one_kernel_score_route():
     assert torch.isfinite(y.float()).all()
 
 
+@pytest.mark.parametrize("split", ["1", "2", "4", "8"])
+def test_aggregate_level_value_gemm_dealt_to_several_items(monkeypatch, split):
+    """The value GEMM with a group's chunks of 8 channels dealt to 1, 2, 4 items (8 is cut back to 4: a group of 43
+    has 6 chunks), partial sums merged by a second kernel: two groups of 43 channels, 40 patches (a ragged patch tile)."""
+    monkeypatch.setenv("DCHAG_VAGG_SPLIT", split)
+    B, Cin, N, D, heads, g = 2, 86, 40, 256, 4, 43
+    rng = np.random.Generator(np.random.PCG64(431))
+    lv = make_level(rng, n_groups(Cin, g), g, D, "bf16", True)
+    z = make_tokens(B, Cin, N, D, "bf16", seed=13)
+    y = dchag.dchag_aggregate_level(dev(z, "bf16"), dev_level(lv, "bf16"), heads)
+    torch.cuda.synchronize()
+    want = oracle.aggregate_level(z.transpose(0, 2, 1, 3).reshape(B * N, Cin, D), lv, heads)
+    err = rel_err(host(y), want.reshape(B, N, -1, D).transpose(0, 2, 1, 3))
+    say(f"value GEMM dealt to {split} items: err={err:.3e}")
+    assert err < TOL["bf16"]
+
+
 def test_aggregate_level_generic_bf16_kernels_still_match(monkeypatch):
     """The shape-generic bf16 kernels (taken for shapes the MFMA path does not tile) on a shape
     the MFMA path would take, forced through the library's DCHAG_GENERIC_LEVEL switch."""
