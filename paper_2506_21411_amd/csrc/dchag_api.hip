@@ -387,6 +387,20 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
   if (px) {
     StageTimer tm(DCHAG_STAGE_SCORES, st);
     const int pp = px->p * px->p;
+    // MFMA form of the weight composition where the shape allows it (DCHAG_COMPOSE_VALU, a debugging aid, keeps
+    // the vector-ALU kernel): pp = 16 .. 128 in blocks of 8 pixels, groups that are multiples of the block's channels
+    const int cpb = (pp == 16 || pp == 32 || pp == 64 || pp == 128) ? 16 / (pp / 8) : 0;
+    const bool compose_mfma = cpb > 0 && g % cpb == 0 && D % 128 == 0 && heads <= 32 && !getenv("DCHAG_COMPOSE_VALU");
+    if (compose_mfma) {
+      const dim3 cgrid((unsigned)((Cin + cpb - 1) / cpb));
+      if (heads <= 16)
+        k_compose_score_weights_mfma<1><<<cgrid, 256, 0, st>>>(Cin, D, heads, pp, g, Mf, px->We, px->be, px->ce, px->Ms,
+                                                              px->Msb, px->cs);
+      else
+        k_compose_score_weights_mfma<2><<<cgrid, 256, 0, st>>>(Cin, D, heads, pp, g, Mf, px->We, px->be, px->ce, px->Ms,
+                                                              px->Msb, px->cs);
+      if ((rc = launch_status())) return rc;
+    }
     const int ntiles = (heads / 4) * (pp / 4);
     const int TPL = ntiles <= 64 ? 1 : (ntiles <= 128 ? 2 : 4);
     int DQ = 16384 / pp;                                 // 32 KiB of tokenizer weights per block of d
@@ -396,8 +410,10 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(compose), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)clds) != hipSuccess)
       return DCHAG_ERR_LAUNCH;
-    compose<<<dim3(Cin), 256, clds, st>>>(D, heads, pp, g, DQ, px->MfT, px->We, px->be, px->ce, px->Ms, px->Msb, px->cs);
-    if ((rc = launch_status())) return rc;
+    if (!compose_mfma) {
+      compose<<<dim3(Cin), 256, clds, st>>>(D, heads, pp, g, DQ, px->MfT, px->We, px->be, px->ce, px->Ms, px->Msb, px->cs);
+      if ((rc = launch_status())) return rc;
+    }
     k_scores_pixels<<<dim3((N + 127) / 128, Cin, B), 256, 0, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G, Np, px->x,
                                                                  px->Msb, px->cs, alpha);
     if ((rc = launch_status())) return rc;

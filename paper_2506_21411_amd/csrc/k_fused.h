@@ -835,6 +835,116 @@ __global__ __launch_bounds__(256) void k_compose_score_weights(int D, int heads,
   }
 }
 
+// The same weights on 16x16x32 MFMA for pp = 16, 32, 64 or 128 (NKB = pp / 8 blocks of 8 pixels) and group sizes that
+// are multiples of CPB = 16 / NKB: a block takes CPB channels of one group, its four wavefronts a quarter of D each.
+// A fragments: the fp32 folded key rows Mf[k][head][d] split in two bf16 parts (nothing of them is lost); B fragments:
+// a lane reads 8 rows d x 8 adjacent pixels of We[c] (16 bytes per row) and transposes them in registers, which gives
+// it the fragments (column = channel l16 / NKB, pixel 8 (l16 % NKB) + j; d = 8 (lane / 16) ..) of eight products
+// j = 0..7.  The bias part takes two more products per step (be and ce as they are: column = channel).  The partial
+// blocks of the wavefronts meet in LDS in a fixed order.  grid (ceil(C / CPB)), block 256.  D % 128 == 0.
+__device__ __forceinline__ void split_hi_lo(const f32x4& x0, const f32x4& x1, bf16x8& hi, bf16x8& lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hi[i] = (bf16)x0[i];
+    lo[i] = (bf16)(x0[i] - (float)hi[i]);
+    hi[4 + i] = (bf16)x1[i];
+    lo[4 + i] = (bf16)(x1[i] - (float)hi[4 + i]);
+  }
+}
+
+template <int HB>   // blocks of 16 heads (heads <= 16 HB)
+__global__ __launch_bounds__(256) void k_compose_score_weights_mfma(int C, int D, int heads, int pp, int g,
+                                                                    const float* __restrict__ Mf,
+                                                                    const bf16* __restrict__ We,
+                                                                    const bf16* __restrict__ be,
+                                                                    const bf16* __restrict__ ce, float* __restrict__ Ms,
+                                                                    bf16* __restrict__ Msb, float* __restrict__ cs) {
+  __shared__ f32x4 part[3][HB][9][64];
+  const int nkb = pp / 8, cpb = 16 / nkb;
+  const int c0 = blockIdx.x * cpb, k = c0 / g;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, lq = lane >> 4;
+  const int csub = l16 / nkb, kkb = l16 % nkb;
+  const int c = min(c0 + csub, C - 1);                   // a short last block: its repeats are not written
+  const int cbias = min(c0 + l16, C - 1);                // the channel this lane supplies in the bias products
+  const bf16* wsrc = We + (size_t)c * D * pp + kkb * 8;
+  const int dq = D / 4;
+  f32x4 acc[HB][8], bacc[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    bacc[hb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[hb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  for (int d0 = wave * dq; d0 < (wave + 1) * dq; d0 += 32) {
+    const int d = d0 + 8 * lq;                           // this lane's 8 steps of the contraction
+    bf16x8 mhi[HB], mlo[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      const float* mp = Mf + ((size_t)k * heads + min(16 * hb + l16, heads - 1)) * D + d;
+      split_hi_lo(*reinterpret_cast<const f32x4*>(mp), *reinterpret_cast<const f32x4*>(mp + 4), mhi[hb], mlo[hb]);
+    }
+    bf16x8 rows[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) rows[i] = *reinterpret_cast<const bf16x8*>(wsrc + (size_t)(d + i) * pp);
+    bf16x8 bev = {}, cev = {};
+    if (l16 < cpb) {
+      if (be) bev = *reinterpret_cast<const bf16x8*>(be + (size_t)cbias * D + d);
+      if (ce) cev = *reinterpret_cast<const bf16x8*>(ce + (size_t)cbias * D + d);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      bf16x8 col;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) col[i] = rows[i][j];
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) {
+        acc[hb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mhi[hb], col, acc[hb][j], 0, 0, 0);
+        acc[hb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mlo[hb], col, acc[hb][j], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      bacc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mhi[hb], bev, bacc[hb], 0, 0, 0);
+      bacc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mlo[hb], bev, bacc[hb], 0, 0, 0);
+      bacc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mhi[hb], cev, bacc[hb], 0, 0, 0);
+      bacc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mlo[hb], cev, bacc[hb], 0, 0, 0);
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) part[wave - 1][hb][j][lane] = acc[hb][j];
+      part[wave - 1][hb][8][lane] = bacc[hb];
+    }
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  // accumulator block: lane holds column l16, rows (heads) 4 lq + r
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    f32x4 tot[9];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) tot[j] = acc[hb][j] + part[0][hb][j][lane] + part[1][hb][j][lane] + part[2][hb][j][lane];
+    tot[8] = bacc[hb] + part[0][hb][8][lane] + part[1][hb][8][lane] + part[2][hb][8][lane];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int head = 16 * hb + 4 * lq + r;
+      if (head >= heads) continue;
+      if (c0 + csub < C) {
+        const size_t o = ((size_t)(c0 + csub) * heads + head) * pp + kkb * 8;
+        *reinterpret_cast<f32x4*>(Ms + o) = f32x4{tot[0][r], tot[1][r], tot[2][r], tot[3][r]};
+        *reinterpret_cast<f32x4*>(Ms + o + 4) = f32x4{tot[4][r], tot[5][r], tot[6][r], tot[7][r]};
+        bf16x8 b8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) b8[j] = (bf16)tot[j][r];
+        *reinterpret_cast<bf16x8*>(Msb + o) = b8;
+      }
+      if (l16 < cpb && c0 + l16 < C) cs[(size_t)(c0 + l16) * heads + head] = tot[8][r];
+    }
+  }
+}
+
 // Level-1 scores on MFMA: S[b][k][cl][head][n] = u[b,c,n][:] . Msb[c][head][:] + cs[c][head].
 // grid (ceil(N/128), C, B), block 256: wavefront w scores 32 patches of channel c against up to 32 heads
 // with one 32x32x16 MFMA per 16 pixels.  A lane's operand (8 consecutive pixels of a patch) is one

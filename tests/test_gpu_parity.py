@@ -327,6 +327,26 @@ def test_forward_matches_oracle_small(kw):
     assert err < TOL[cfg.dtype]
 
 
+@pytest.mark.parametrize("kw", [
+    dict(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3)),     # 16 pixels: 8 channels per block
+    dict(dtype="bf16", B=1, C=9, H=24, W=40, p=8, D=512, heads=8, group_sizes=(4, 3)),      # 64 pixels: 2 channels per block
+    dict(dtype="bf16", B=1, C=6, H=16, W=32, p=8, D=768, heads=24, group_sizes=(3, 2)),     # odd groups: only the vector-ALU form
+])
+@pytest.mark.parametrize("valu", [False, True])
+def test_forward_score_weight_composition_kernels(monkeypatch, kw, valu):
+    """The level-1 scores come from the pixels through composed weights; both kernels that compose them (MFMA, and the
+    vector-ALU one that shapes the MFMA form does not tile fall back to) against the oracle."""
+    if valu:
+        monkeypatch.setenv("DCHAG_COMPOSE_VALU", "1")
+    cfg = cfg_of(**kw)
+    pr = make_problem(cfg)
+    out = run_forward(pr)
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"compose valu={valu} {kw}: err={err:.3e}")
+    assert err < TOL[cfg.dtype]
+
+
 def test_forward_is_deterministic():
     cfg = cfg_of(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3))
     pr = make_problem(cfg)
