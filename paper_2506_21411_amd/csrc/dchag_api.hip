@@ -366,8 +366,12 @@ bool pixel_scores_ok(int p, int heads) {
 
 // Weight-only prep, scores and softmax of one level on the bf16 MFMA path: leaves the projected query in
 // Qp, the folded keys in Mf / Mb and the softmax weights in alpha, laid out [B][G][gpad][heads][Np].
+// alpha_tm (optional): where the softmax weights are also wanted token-major [B,Cin,N,heads]; *tm_done tells whether
+// they were written (only the one-kernel pixel route does it; otherwise the caller re-lays alpha).
 int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, float* Qp, float* Mf,
-                bf16* Mb, float* alpha, hipStream_t st, const PixelScores* px) {
+                bf16* Mb, float* alpha, hipStream_t st, const PixelScores* px, float* alpha_tm = nullptr,
+                bool* tm_done = nullptr) {
+  if (tm_done) *tm_done = false;
   const int g = lv->group_size;
   const int G = groups_of(Cin, g);
   const int gpad = round_up(g, 8), Np = round_up(N, 32);
@@ -414,11 +418,25 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
       compose<<<dim3(Cin), 256, clds, st>>>(D, heads, pp, g, DQ, px->MfT, px->We, px->be, px->ce, px->Ms, px->Msb, px->cs);
       if ((rc = launch_status())) return rc;
     }
-    k_scores_pixels<<<dim3((N + 127) / 128, Cin, B), 256, 0, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G, Np, px->x,
-                                                                 px->Msb, px->cs, alpha);
-    if ((rc = launch_status())) return rc;
-    k_softmax_alpha<<<dim3((Np + 255) / 256, heads, B * G), 256, 0, st>>>(Cin, N, heads, g, gpad, G, Np, alpha);
-    if ((rc = launch_status())) return rc;
+    // scores and softmax in one kernel while a group's scores of 32 patches fit LDS (DCHAG_PIXEL_SCORES_TWO_KERNELS,
+    // a debugging aid, keeps them apart)
+    const size_t slds = (size_t)std::min(g, Cin) * heads * 33 * 4;
+    if (slds <= 150 * 1024 && B <= 65535 && G <= 65535 && !getenv("DCHAG_PIXEL_SCORES_TWO_KERNELS")) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_pixels_softmax),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds) != hipSuccess)
+        return DCHAG_ERR_LAUNCH;
+      k_scores_pixels_softmax<<<dim3((N + 31) / 32, G, B), 256, slds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G,
+                                                                            Np, px->x, px->Msb, px->cs,
+                                                                            alpha_tm ? nullptr : alpha, alpha_tm);
+      if ((rc = launch_status())) return rc;
+      if (tm_done && alpha_tm) *tm_done = true;
+    } else {
+      k_scores_pixels<<<dim3((N + 127) / 128, Cin, B), 256, 0, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G, Np,
+                                                                   px->x, px->Msb, px->cs, alpha);
+      if ((rc = launch_status())) return rc;
+      k_softmax_alpha<<<dim3((Np + 255) / 256, heads, B * G), 256, 0, st>>>(Cin, N, heads, g, gpad, G, Np, alpha);
+      if ((rc = launch_status())) return rc;
+    }
   } else {
     StageTimer tm(DCHAG_STAGE_SCORES, st);
     const int NB = (heads + 15) / 16;

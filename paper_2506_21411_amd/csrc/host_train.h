@@ -276,8 +276,9 @@ int generic_alpha(int B, int Cin, int N, int D, int heads, const dchag_level* lv
 inline int fast_alpha(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin,
                       const LevelBufs<bf16>& lb, hipStream_t st, const PixelScores* px) {
   const int g = lv->group_size, G = groups_of(Cin, g);
-  int rc = fast_scores(B, Cin, N, D, heads, lv, zin, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, px);
-  if (rc) return rc;
+  bool tm_done = false;
+  int rc = fast_scores(B, Cin, N, D, heads, lv, zin, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, px, lb.alpha, &tm_done);
+  if (rc || tm_done) return rc;
   StageTimer tm(DCHAG_STAGE_SCORES, st);
   const long total = (long)B * Cin * N * heads;
   k_alpha_token_major<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(total, Cin, N, heads, g, round_up(g, 8), G,

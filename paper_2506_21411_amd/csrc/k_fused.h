@@ -993,6 +993,83 @@ __global__ __launch_bounds__(256) void k_scores_pixels(int C, int H, int W, int 
   }
 }
 
+// The same scores with the softmax over the group in the same kernel, for groups whose scores of 32 patches fit LDS
+// (size of the group x heads x 33 floats): grid (ceil(N/32), G, B), block 256.  The wavefronts take the group's
+// channels in turn (the products of k_scores_pixels) and leave the scores in LDS as [member][head][patch, pitch 33];
+// then every (head, patch) is normalised over the members in the order and with the arithmetic of k_softmax_alpha,
+// and the weights are written in the layout of the forward kernels (alpha_f[b][k][cl][head][n], zeros for padding
+// members and the pitch) and / or token-major (alpha_tm[b,c,n,head]), whichever pointer is given.
+__global__ __launch_bounds__(256) void k_scores_pixels_softmax(int C, int H, int W, int p, int heads, int g, int gpad,
+                                                               int G, int Np, const bf16* __restrict__ x,
+                                                               const bf16* __restrict__ Msb,
+                                                               const float* __restrict__ cs,
+                                                               float* __restrict__ alpha_f,
+                                                               float* __restrict__ alpha_tm) {
+  extern __shared__ __attribute__((aligned(16))) float sc[];       // [gk][heads][33]
+  const int pp = p * p, pw = W / p, N = (H / p) * pw;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+  const int k = blockIdx.y, b = blockIdx.z;
+  const int c0 = k * g, gk = min(g, C - c0);
+  const int n0 = blockIdx.x * 32;
+  const int n = min(n0 + l32, N - 1);
+  const int pi = n / pw, pj = n % pw;
+  for (int cl = wave; cl < gk; cl += 4) {
+    const int c = c0 + cl;
+    const bf16* img = x + ((size_t)b * C + c) * H * W + (size_t)(pi * p) * W + pj * p;
+    const bf16* mrow = Msb + ((size_t)c * heads + min(l32, heads - 1)) * pp;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int kc = lhi; kc < pp / 8; kc += 2) {          // 8-pixel chunk of the patch
+      bf16x8 a;
+      if (p == 4) {
+        const bf16x4 lo = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc) * W);
+        const bf16x4 hi = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc + 1) * W);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { a[e] = lo[e]; a[4 + e] = hi[e]; }
+      } else {
+        const int r = (kc * 8) / p, s0 = (kc * 8) % p;
+        a = *reinterpret_cast<const bf16x8*>(img + (size_t)r * W + s0);
+      }
+      bf16x8 m = *reinterpret_cast<const bf16x8*>(mrow + kc * 8);
+      if (l32 >= heads) m = bf16x8{};
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, m, acc, 0, 0, 0);
+    }
+    if (l32 < heads) {                                   // lane: head l32, patches 8 (r / 4) + 4 lhi + r % 4
+      const float add = cs[(size_t)c * heads + l32];
+      float* dst = sc + ((size_t)cl * heads + l32) * 33 + 4 * lhi;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dst[8 * (r >> 2) + (r & 3)] = acc[r] + add;
+    }
+  }
+  __syncthreads();
+  for (int pr = threadIdx.x; pr < heads * 32; pr += 256) {         // (head, patch), patch fastest
+    float* col = sc + (size_t)(pr >> 5) * 33 + (pr & 31);
+    const int stride = heads * 33;
+    float mx = -INFINITY;
+    for (int cl = 0; cl < gk; ++cl) mx = fmaxf(mx, col[cl * stride]);
+    float den = 0.f;
+    for (int cl = 0; cl < gk; ++cl) den += __expf(col[cl * stride] - mx);
+    const float inv = 1.f / den;
+    for (int cl = 0; cl < gk; ++cl) col[cl * stride] = __expf(col[cl * stride] - mx) * inv;
+  }
+  __syncthreads();
+  if (alpha_f) {
+    for (int idx = threadIdx.x; idx < gpad * heads * 32; idx += 256) {      // patch fastest: 128-byte runs
+      const int patch = idx & 31, head = (idx >> 5) % heads, cl = (idx >> 5) / heads;
+      const float v = (cl < gk && n0 + patch < N) ? sc[((size_t)cl * heads + head) * 33 + patch] : 0.f;
+      alpha_f[((((size_t)b * G + k) * gpad + cl) * heads + head) * Np + n0 + patch] = v;
+    }
+  }
+  if (alpha_tm) {
+    for (int idx = threadIdx.x; idx < gk * heads * 32; idx += 256) {        // head fastest: runs of 4 heads bytes
+      const int head = idx % heads, patch = (idx / heads) & 31, cl = idx / (heads * 32);
+      if (n0 + patch < N)
+        alpha_tm[(((size_t)b * C + c0 + cl) * N + n0 + patch) * heads + head] = sc[((size_t)cl * heads + head) * 33 + patch];
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Tokenizer on MFMA (paper Section 2.1: every patch of every channel is embedded on its own by
 // that channel's convolution, kernel = stride = patch):

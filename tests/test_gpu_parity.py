@@ -327,6 +327,22 @@ def test_forward_matches_oracle_small(kw):
     assert err < TOL[cfg.dtype]
 
 
+@pytest.mark.parametrize("two", [False, True])
+def test_forward_pixel_score_routes(monkeypatch, two):
+    """Level-1 scores from the pixels with the softmax in the same kernel (default) and as two kernels."""
+    if two:
+        monkeypatch.setenv("DCHAG_PIXEL_SCORES_TWO_KERNELS", "1")
+    for kw in (dict(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3)),
+               dict(dtype="bf16", B=1, C=11, H=40, W=72, p=8, D=512, heads=16, group_sizes=(4, 3))):   # N = 45: ragged tile
+        cfg = cfg_of(**kw)
+        pr = make_problem(cfg)
+        out = run_forward(pr)
+        want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+        err = rel_err(host(out), want)
+        say(f"pixel scores two_kernels={two} {kw}: err={err:.3e}")
+        assert err < TOL[cfg.dtype]
+
+
 @pytest.mark.parametrize("kw", [
     dict(dtype="bf16", B=2, C=20, H=16, W=24, p=4, D=256, heads=4, group_sizes=(8, 3)),     # 16 pixels: 8 channels per block
     dict(dtype="bf16", B=1, C=9, H=24, W=40, p=8, D=512, heads=8, group_sizes=(4, 3)),      # 64 pixels: 2 channels per block

@@ -190,7 +190,8 @@ def test_backward_matches_oracle(kw):
 
 
 @pytest.mark.parametrize("env", ["DCHAG_GENERIC_LEVEL", "DCHAG_GEMM_GENERIC", "DCHAG_DZ_VALU", "DCHAG_COLSUM",
-                                 "DCHAG_GEMM_SCALAR_STORES", "DCHAG_TOKENS_UNFUSED", "DCHAG_RPART_VALU"])
+                                 "DCHAG_GEMM_SCALAR_STORES", "DCHAG_TOKENS_UNFUSED", "DCHAG_RPART_VALU",
+                                 "DCHAG_PIXEL_SCORES_TWO_KERNELS"])
 def test_backward_generic_bf16_kernels_still_match(monkeypatch, env):
     """The shape-generic bf16 kernels (taken for shapes the MFMA and streaming kernels do not tile) on a shape
     the fast kernels would take, forced through the library's debug switches."""
