@@ -190,6 +190,10 @@ int launch_gemm_bf16(const GemmDesc& d0, const bf16* A, const bf16* Bm, const bf
             mult8(d.C.s0) && !(reinterpret_cast<uintptr_t>(C) & 15) && !getenv("DCHAG_GEMM_SCALAR_STORES");
   if (d.N <= 64) return launch_gemm_mfma_tile<128, 64, 4, 1, TC>(d, A, Bm, bias, C, rowsum, st);
   if (d.M <= 64) return launch_gemm_mfma_tile<64, 128, 1, 4, TC>(d, A, Bm, bias, C, rowsum, st);
+  // a product of few 128 x 128 tiles (the one-group top level) takes 64 x 64 tiles: four times the blocks
+  const long batch = (long)(d.reduce_b ? 1 : d.nb) * d.nk * d.na;
+  if ((long)((d.N + 127) / 128) * ((d.M + 127) / 128) * batch * 2 < compute_units())
+    return launch_gemm_mfma_tile<64, 64, 2, 2, TC>(d, A, Bm, bias, C, rowsum, st);
   return launch_gemm_mfma_tile<128, 128, 2, 2, TC>(d, A, Bm, bias, C, rowsum, st);
 }
 // True when launch_gemm_bf16 will deliver the row sums of A along with the product.
@@ -449,7 +453,7 @@ inline bool tokens_fused(int B, int Cin, int N, int D, int heads, int g) {
 inline int sum_key_path_partials(int B, int G, int n_tiles, int heads, int D, const float* rpart, float* r,
                                  hipStream_t st) {
   const long per = (long)heads * D;
-  k_sum_partials<<<dim3((unsigned)((per + 63) / 64), G), 256, 0, st>>>(B, G, n_tiles, per, rpart, r);
+  k_sum_partials<<<dim3((unsigned)((per + 63) / 64), G), 1024, 0, st>>>(B, G, n_tiles, per, rpart, r);
   return launch_status();
 }
 inline int tokens_backward_fused(int B, int Cin, int N, int D, int heads, int g, const bf16* z, const bf16* w,

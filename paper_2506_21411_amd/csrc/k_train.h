@@ -1645,21 +1645,36 @@ __global__ __launch_bounds__(256, 2) void k_rpart_mfma(int Cin, int N, int D, in
     }
 }
 
-// r[k][i] = sum_b sum_t rpart[b][k][t][i]   (i over heads * D), fixed order.  grid (ceil(per/64), G), block 256:
-// 64 adjacent i per block, the four wavefronts take every fourth partial and meet in LDS.
-__global__ __launch_bounds__(256) void k_sum_partials(int B, int G, int n_tiles, long per, const float* __restrict__ rpart,
-                                                      float* __restrict__ r) {
-  __shared__ float part[3][64];
+// r[k][i] = sum_b sum_t rpart[b][k][t][i]   (i over heads * D), fixed order.  grid (ceil(per/64), G), block 1024:
+// 64 adjacent i per block, the sixteen wavefronts take every sixteenth partial (four in flight each) and meet in LDS.
+__global__ __launch_bounds__(1024) void k_sum_partials(int B, int G, int n_tiles, long per, const float* __restrict__ rpart,
+                                                       float* __restrict__ r) {
+  __shared__ float part[15][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long i = (long)blockIdx.x * 64 + lane;
   const int k = blockIdx.y;
   float acc = 0.f;
   if (i < per)
-    for (int b = 0; b < B; ++b)
-      for (int t = wave; t < n_tiles; t += 4) acc += rpart[(((size_t)b * G + k) * n_tiles + t) * per + i];
+    for (int b = 0; b < B; ++b) {
+      const float* src = rpart + (((size_t)b * G + k) * n_tiles) * per + i;
+      int t = wave;
+      for (; t + 48 < n_tiles; t += 64) {
+        const float v0 = src[(size_t)t * per], v1 = src[(size_t)(t + 16) * per], v2 = src[(size_t)(t + 32) * per],
+                    v3 = src[(size_t)(t + 48) * per];
+        acc += v0;
+        acc += v1;
+        acc += v2;
+        acc += v3;
+      }
+      for (; t < n_tiles; t += 16) acc += src[(size_t)t * per];
+    }
   if (wave > 0) part[wave - 1][lane] = acc;
   __syncthreads();
-  if (wave == 0 && i < per) r[(size_t)k * per + i] = acc + part[0][lane] + part[1][lane] + part[2][lane];
+  if (wave == 0 && i < per) {
+#pragma unroll
+    for (int w = 0; w < 15; ++w) acc += part[w][lane];
+    r[(size_t)k * per + i] = acc;
+  }
 }
 
 }  // namespace dchag
