@@ -442,11 +442,11 @@ inline int softmax_backward(int B, int Cin, int N, int D, int heads, int g, cons
 
 // True when one kernel (k_tokens_backward_fused) takes the whole reverse step at the tokens of a level -- ds, the token
 // gradients and the key-path partial sums: the shapes of the MFMA token-gradient path with at most 16 heads,
-// D <= 1024 and groups of at most 32 channels.  DCHAG_TOKENS_UNFUSED (debugging aid) keeps the three kernels apart.
+// D <= 2048 and groups of at most 32 channels.  DCHAG_TOKENS_UNFUSED (debugging aid) keeps the three kernels apart.
 inline bool tokens_fused(int B, int Cin, int N, int D, int heads, int g) {
   const int G = groups_of(Cin, g);
   const size_t lds = (size_t)2 * dz_patches(B, G, N, D, g) * g * 16 * 4;
-  return D % 256 == 0 && D <= 1024 && heads <= 16 && std::min(g, Cin) <= 32 && lds <= 128 * 1024 &&
+  return D % 256 == 0 && D <= 2048 && heads <= 16 && std::min(g, Cin) <= 32 && lds <= 128 * 1024 &&
          !getenv("DCHAG_DZ_VALU") && !getenv("DCHAG_GENERIC_LEVEL") && !getenv("DCHAG_TOKENS_UNFUSED") &&
          !getenv("DCHAG_RPART_VALU");
 }
@@ -465,10 +465,14 @@ inline int tokens_backward_fused(int B, int Cin, int N, int D, int heads, int g,
   {
     StageTimer tm(DCHAG_STAGE_BWD_TOKENS, st);
     const dim3 grid((unsigned)n_tiles, G, B);
-    if (std::min(g, Cin) <= 16)
-      k_tokens_backward_fused<1><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
-    else
-      k_tokens_backward_fused<2><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
+    const bool small = std::min(g, Cin) <= 16;
+    if (D <= 1024) {
+      if (small) k_tokens_backward_fused<1, 1><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
+      else k_tokens_backward_fused<2, 1><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
+    } else {
+      if (small) k_tokens_backward_fused<1, 2><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
+      else k_tokens_backward_fused<2, 2><<<grid, 512, 0, st>>>(Cin, N, D, heads, g, pt, z, w, alpha, Mb, dz, rpart);
+    }
     if ((rc = launch_status())) return rc;
   }
   StageTimer tm(DCHAG_STAGE_BWD_KEY_QUERY, st);

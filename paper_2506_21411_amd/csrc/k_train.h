@@ -1249,7 +1249,7 @@ __global__ __launch_bounds__(256, 3 - HB) void k_dz_mfma(int Cin, int N, int D, 
 }
 
 // ---------------------------------------------------------------------------------------
-// The whole reverse step at the tokens of one level in one kernel (bf16, heads <= 16, D % 256 == 0, D <= 1024,
+// The whole reverse step at the tokens of one level in one kernel (bf16, heads <= 16, D % 256 == 0, D <= 1024 CB,
 // group size <= 16 MT <= 32), so that a patch's token rows and its w rows are fetched from HBM once (their second
 // use, a few microseconds later in the same workgroup, finds them in L2) and ds never leaves the compute unit:
 //   ds as in k_dalpha_softmax_mfma;  rpart[b,k,t][a][:] = sum over the pt patches of tile t and the members c of
@@ -1257,7 +1257,7 @@ __global__ __launch_bounds__(256, 3 - HB) void k_dz_mfma(int Cin, int N, int D, 
 // grid (n_tiles, G, B), block 512, PP patches (one) per round of barriers:
 //   d alpha   all eight wavefronts, each an eighth of D; the partial 16x16 blocks meet in LDS in a fixed order, the
 //             first PP wavefronts apply the Jacobian (one patch each) and leave the softmax weights and ds in LDS;
-//   sums      wavefronts 0..3, wavefront w columns 256 w .. 256 w + 255: ds^T (heads x 32 members, split in two
+//   sums      wavefronts 0..3, wavefront w columns 256 w .. 256 w + 255 (of each block of 1024 columns): ds^T (heads x 32 members, split in two
 //             bf16 parts) times the 32 member rows on 16x16x32 MFMA; a lane reads 8 members x 8 adjacent columns
 //             (16 bytes per row) and transposes them in registers, which gives it the B fragments (column
 //             8 (lane % 16) + j, members 8 (lane / 16) ..) of eight products j = 0..7; accumulator (half, j): lane
@@ -1265,7 +1265,7 @@ __global__ __launch_bounds__(256, 3 - HB) void k_dz_mfma(int Cin, int N, int D, 
 //   dz        wavefronts 4..7, wavefront 4 + w the same columns: the body of k_dz_mfma, A fragments from LDS.
 // The two roles are separate loops (same barriers), so neither carries the other's accumulators.
 // ---------------------------------------------------------------------------------------
-template <int MT>
+template <int MT, int CB>   // CB: blocks of 1024 columns (D <= 1024 CB)
 __global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, int D, int heads, int g, int pt,
                                                                const bf16* __restrict__ z, const bf16* __restrict__ w,
                                                                const float* __restrict__ alpha,
@@ -1374,11 +1374,13 @@ __global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, i
   // of the round's parity, barrier, the roles read them.  The next round writes the other parity, and `part` only
   // after every wavefront has passed the second barrier of this one.
   if (wave < 4) {
-    f32x4 racc[2][8];
+    f32x4 racc[CB][2][8];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int cbk = 0; cbk < CB; ++cbk)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) racc[h][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) racc[cbk][h][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int pi = 0, par = 0; pi < np; pi += PP, par ^= 1) {
       float al[MT][4];
       if (wave < PP) fetch_alpha(pi, al);
@@ -1386,86 +1388,103 @@ __global__ __launch_bounds__(512) void k_tokens_backward_fused(int Cin, int N, i
       __syncthreads();
       if (wave < PP) jacobian(par, al);
       __syncthreads();
-      if (col0 < D) {
-        for (int q = 0; q < PP && pi + q < np; ++q) {
-          f32x4 v0, v1;                                            // ds of head l16 at members 8 lq .. 8 lq + 7
+      for (int q = 0; q < PP && pi + q < np; ++q) {
+        f32x4 v0, v1;                                              // ds of head l16 at members 8 lq .. 8 lq + 7
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            v0[i] = dsv[par][q][8 * lq + i][l16];
-            v1[i] = dsv[par][q][8 * lq + 4 + i][l16];
+        for (int i = 0; i < 4; ++i) {
+          v0[i] = dsv[par][q][8 * lq + i][l16];
+          v1[i] = dsv[par][q][8 * lq + 4 + i][l16];
+        }
+        bf16x8 dhi, dlo;
+        split_bf16(v0, v1, dhi, dlo);
+#pragma unroll
+        for (int cbk = 0; cbk < CB; ++cbk) {
+          const int colc = col0 + 1024 * cbk;
+          if (colc >= D) continue;
+          const bf16* zc = zg + (size_t)(pi + q) * D + colc + 8 * l16;
+          constexpr int HL = CB == 1 ? 2 : 1;                      // halves of 128 columns fetched together
+#pragma unroll
+          for (int h0 = 0; h0 < 2; h0 += HL) {
+            bf16x8 rows[HL][8];
+#pragma unroll
+            for (int h = 0; h < HL; ++h)
+#pragma unroll
+              for (int i = 0; i < 8; ++i)
+                rows[h][i] = __builtin_nontemporal_load(            // second and last use of the row
+                    reinterpret_cast<const bf16x8*>(zc + (size_t)min(8 * lq + i, gk - 1) * cstride + 128 * (h0 + h)));
+#pragma unroll
+            for (int h = 0; h < HL; ++h)
+#pragma unroll
+              for (int j = 0; j < 8; ++j) {
+                bf16x8 col;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) col[i] = rows[h][i][j];
+                racc[cbk][h0 + h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dhi, col, racc[cbk][h0 + h][j], 0, 0, 0);
+                racc[cbk][h0 + h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dlo, col, racc[cbk][h0 + h][j], 0, 0, 0);
+              }
           }
-          bf16x8 dhi, dlo;
-          split_bf16(v0, v1, dhi, dlo);
-          const bf16* zc = zg + (size_t)(pi + q) * D + col0 + 8 * l16;
-          bf16x8 rows[2][8];
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-              rows[h][i] = __builtin_nontemporal_load(              // second and last use of the row
-                  reinterpret_cast<const bf16x8*>(zc + (size_t)min(8 * lq + i, gk - 1) * cstride + 128 * h));
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              bf16x8 col;
-#pragma unroll
-              for (int i = 0; i < 8; ++i) col[i] = rows[h][i][j];
-              racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dhi, col, racc[h][j], 0, 0, 0);
-              racc[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dlo, col, racc[h][j], 0, 0, 0);
-            }
         }
       }
     }
-    if (col0 < D) {
+#pragma unroll
+    for (int cbk = 0; cbk < CB; ++cbk) {
+      const int colc = col0 + 1024 * cbk;
+      if (colc >= D) continue;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int a = 4 * lq + r;
         if (a < heads) {
-          float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads + a) * D + col0 + 8 * l16;
+          float* rp = rpart + ((((size_t)b * G + k) * n_tiles + tile) * heads + a) * D + colc + 8 * l16;
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            *reinterpret_cast<f32x4*>(rp + 128 * h) = f32x4{racc[h][0][r], racc[h][1][r], racc[h][2][r], racc[h][3][r]};
+            *reinterpret_cast<f32x4*>(rp + 128 * h) =
+                f32x4{racc[cbk][h][0][r], racc[cbk][h][1][r], racc[cbk][h][2][r], racc[cbk][h][3][r]};
             *reinterpret_cast<f32x4*>(rp + 128 * h + 4) =
-                f32x4{racc[h][4][r], racc[h][5][r], racc[h][6][r], racc[h][7][r]};
+                f32x4{racc[cbk][h][4][r], racc[cbk][h][5][r], racc[cbk][h][6][r], racc[cbk][h][7][r]};
           }
         }
       }
     }
   } else {
-    const int d0c = col0 + 4 * lane;                               // this lane's 4 columns of the token gradients
-    bf16x8 mfrag[2][4];
-    if (col0 < D) head_row_frags(Mb + ((size_t)k * heads) * D + d0c, D, heads, lhi, mfrag);
+    const int d0c = col0 + 4 * lane;                               // this lane's 4 columns (of each column block)
+    bf16x8 mfrag[CB][2][4];
+#pragma unroll
+    for (int cbk = 0; cbk < CB; ++cbk)
+      if (col0 + 1024 * cbk < D)
+        head_row_frags(Mb + ((size_t)k * heads) * D + d0c + 1024 * cbk, D, heads, lhi, mfrag[cbk]);
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int pi = 0, par = 0; pi < np; pi += PP, par ^= 1) {
       dalpha_partial(pi);
       __syncthreads();
       __syncthreads();
-      if (col0 < D) {
-        for (int q = 0; q < PP && pi + q < np; ++q) {
-          bf16x8 wfrag[2][4];
-          head_row_frags<true>(w + ((item0 + pi + q) * heads) * D + d0c, D, heads, lhi, wfrag);
-          f32x4 a0, a1, e0, e1;                                    // member row l32, heads 8 lhi .. 8 lhi + 7
+      for (int q = 0; q < PP && pi + q < np; ++q) {
+        f32x4 a0, a1, e0, e1;                                      // member row l32, heads 8 lhi .. 8 lhi + 7
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            a0[i] = alv[par][q][l32][8 * lhi + i];
-            a1[i] = alv[par][q][l32][8 * lhi + 4 + i];
-            e0[i] = dsv[par][q][l32][8 * lhi + i];
-            e1[i] = dsv[par][q][l32][8 * lhi + 4 + i];
-          }
-          bf16x8 ahi, alo, ehi, elo;
-          split_bf16(a0, a1, ahi, alo);
-          split_bf16(e0, e1, ehi, elo);
+        for (int i = 0; i < 4; ++i) {
+          a0[i] = alv[par][q][l32][8 * lhi + i];
+          a1[i] = alv[par][q][l32][8 * lhi + 4 + i];
+          e0[i] = dsv[par][q][l32][8 * lhi + i];
+          e1[i] = dsv[par][q][l32][8 * lhi + 4 + i];
+        }
+        bf16x8 ahi, alo, ehi, elo;
+        split_bf16(a0, a1, ahi, alo);
+        split_bf16(e0, e1, ehi, elo);
+#pragma unroll
+        for (int cbk = 0; cbk < CB; ++cbk) {
+          const int colc = col0 + 1024 * cbk;
+          if (colc >= D) continue;
+          bf16x8 wfrag[2][4];
+          head_row_frags<true>(w + ((item0 + pi + q) * heads) * D + d0c + 1024 * cbk, D, heads, lhi, wfrag);
           auto tiles_of_half = [&](int half) {
             f32x16 acc[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, wfrag[half][e], zero, 0, 0, 0);
               acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, wfrag[half][e], acc[e], 0, 0, 0);
-              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi, mfrag[half][e], acc[e], 0, 0, 0);
-              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(elo, mfrag[half][e], acc[e], 0, 0, 0);
+              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi, mfrag[cbk][half][e], acc[e], 0, 0, 0);
+              acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(elo, mfrag[cbk][half][e], acc[e], 0, 0, 0);
             }
-            bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n0 + pi + q) * D + col0 + 4 * (l32 + 32 * half);
+            bf16* dzp = dz + (((size_t)b * Cin + c0) * N + n0 + pi + q) * D + colc + 4 * (l32 + 32 * half);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int m = 8 * (r >> 2) + 4 * lhi + (r & 3);

@@ -75,6 +75,8 @@ SMALL = [
     dict(dtype="bf16", B=1, C=12, H=32, W=64, p=8, D=1024, heads=32, group_sizes=(6, 2)),
     # 24 heads: the second head block is half empty
     dict(dtype="bf16", B=1, C=7, H=16, W=32, p=4, D=768, heads=24, group_sizes=(4, 2)),
+    # D = 2048: two blocks of 1024 columns per wavefront in the fused token kernel; groups 4 + 3, N = 6
+    dict(dtype="bf16", B=1, C=7, H=16, W=24, p=8, D=2048, heads=16, group_sizes=(4, 2)),
     # 6 heads of 128 (not a multiple of 4 or 8: the head tables of the token kernels are zero-padded), groups 5 + 5 + 1
     dict(dtype="bf16", B=2, C=11, H=16, W=24, p=4, D=768, heads=6, group_sizes=(5, 3)),
     # groups of more than 64 channels (70 + 5): the d-alpha kernel for groups of any size, five member tiles
