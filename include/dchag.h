@@ -234,6 +234,8 @@ int dchag_backward_kept(dchag_dtype dt, int B, int C, int H, int W, int p, int D
  *   which = 1: one dchag_forward call with the n_levels nominal group sizes;
  *   which = 2: one dchag_forward_folded call;   which = 3: one dchag_backward call, or a
  *              dchag_forward_keep / dchag_backward_kept pair.
+ * The size also depends on the current device (how a level's work is split follows its number of compute units;
+ * without a device 256 are assumed): ask on the device and in the process that makes the call.
  */
 size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
                              int n_levels, const int32_t *group_sizes, int which);
