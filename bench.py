@@ -100,7 +100,7 @@ def main() -> int:
     ap.add_argument("--workload", default="hyperspectral")
     ap.add_argument("--mode", default="forward", choices=["forward", "folded", "backward"],
                     help="what one step is: dchag_forward (the headline), dchag_forward_folded, or dchag_backward")
-    ap.add_argument("--cpu-patches", type=int, default=64, help="patches the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-patches", type=int, default=384, help="patches the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-other", action="store_true", help="skip the short weather-like side measurement")
     ap.add_argument("--flat-sweep", action="store_true",
                     help="also time the hyperspectral shape at C = 128 .. 1024 channels as one flat layer and as the "
