@@ -583,6 +583,27 @@ int check_level_shape(int B, int Cin, int N, int D, int heads, int g) {
   return DCHAG_OK;
 }
 
+// Tokenizer and a linear first level in one kernel (bf16, p*p = 16 or 64, D % 256 == 0): the per-channel tokens never
+// reach HBM.  y [B,G,N,D].
+inline bool tokenize_mix_ok(dchag_dtype dt, const dchag_level* levels, int pp, int D) {
+  return dt == DCHAG_BF16 && levels[0].kind == DCHAG_LEVEL_LINEAR && (pp == 16 || pp == 64) && D % 256 == 0 &&
+         !getenv("DCHAG_GENERIC_TOKENIZE");
+}
+int tokenize_mix_forward(int B, int C, int H, int W, int p, int D, const void* x, const void* We, const void* be,
+                         const void* ce, const dchag_level* lv, bf16* y, hipStream_t st) {
+  const int N = (H / p) * (W / p), pp = p * p, g = lv->group_size, G = groups_of(C, g);
+  const size_t lds = (size_t)2 * 64 * (pp * 2 + 16);
+  auto mixk = pp == 16 ? k_tokenize_mix_mfma<1> : k_tokenize_mix_mfma<4>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+      hipSuccess)
+    return DCHAG_ERR_LAUNCH;
+  StageTimer tm(DCHAG_STAGE_TOKENIZE_MIX, st);
+  mixk<<<dim3((unsigned)(((N + 63) / 64) * (D / 256)), G, B), 256, lds, st>>>(
+      C, H, W, p, D, g, static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+      static_cast<const bf16*>(ce), static_cast<const bf16*>(lv->Wv), static_cast<const bf16*>(lv->bv), y);
+  return launch_status();
+}
+
 #include "host_train.h"
 
 }  // namespace
@@ -736,27 +757,12 @@ static int forward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   c_in = C;
   int first = 0;
   const int pp0 = p * p;
-  if (dt == DCHAG_BF16 && levels[0].kind == DCHAG_LEVEL_LINEAR && (pp0 == 16 || pp0 == 64) && D % 256 == 0 &&
-      !getenv("DCHAG_GENERIC_TOKENIZE")) {
-    // tokenizer and linear first level in one kernel: the per-channel tokens never reach HBM
+  if (tokenize_mix_ok(dt, levels, pp0, D)) {
     g_level = 1;
-    const int g = gs[0], G = groups_of(C, g);
     bf16* y = reinterpret_cast<bf16*>(ws + w.ping);
-    const size_t lds = (size_t)2 * 64 * (pp0 * 2 + 16);
-    auto mixk = pp0 == 16 ? k_tokenize_mix_mfma<1> : k_tokenize_mix_mfma<4>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixk), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
-    {
-      StageTimer tm(DCHAG_STAGE_TOKENIZE_MIX, st);
-      mixk<<<dim3((unsigned)(((N + 63) / 64) * (D / 256)), G, B), 256, lds, st>>>(
-          C, H, W, p, D, g, static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
-          static_cast<const bf16*>(ce), static_cast<const bf16*>(levels[0].Wv), static_cast<const bf16*>(levels[0].bv),
-          y);
-    }
-    if ((rc = launch_status())) return rc;
+    if ((rc = tokenize_mix_forward(B, C, H, W, p, D, x, We, be, ce, &levels[0], y, st))) return rc;
     zin = y;
-    c_in = G;
+    c_in = groups_of(C, gs[0]);
     first = 1;
   } else if ((rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, stream)))
     return rc;
@@ -883,9 +889,9 @@ static int train_call(int which, dchag_dtype dt, int B, int C, int H, int W, int
     if (rc) return rc;
   }
   if (which & 2)
-    rc = dt == DCHAG_F32 ? reverse_sweep<float>(dt, B, C, H, W, p, D, heads, x, We, n_levels, levels, gs, dout, dx, dWe,
+    rc = dt == DCHAG_F32 ? reverse_sweep<float>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, dout, dx, dWe,
                                                 dtok_bias, grads, ws, w, st)
-                         : reverse_sweep<bf16>(dt, B, C, H, W, p, D, heads, x, We, n_levels, levels, gs, dout, dx, dWe,
+                         : reverse_sweep<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, dout, dx, dWe,
                                                dtok_bias, grads, ws, w, st);
   return rc;
 }

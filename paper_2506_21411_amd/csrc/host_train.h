@@ -369,13 +369,23 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
                         const int32_t* gs, void* out, unsigned char* ws, const FoldedWs& w, hipStream_t st) {
   const int N = (H / p) * (W / p);
   g_level = 0;
-  int rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st);
-  if (rc) return rc;
+  int rc;
+  const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
+  int c_in = C, first = 0;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (n_levels > 1 && tokenize_mix_ok(dt, levels, p * p, D)) {      // tokenizer and linear first level in one kernel
+      g_level = 1;
+      bf16* y = reinterpret_cast<bf16*>(ws + w.ping);
+      if ((rc = tokenize_mix_forward(B, C, H, W, p, D, x, We, be, ce, &levels[0], y, st))) return rc;
+      zin = y;
+      c_in = groups_of(C, gs[0]);
+      first = 1;
+    }
+  }
+  if (!first && (rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st))) return rc;
   const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
-  const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
-  int c_in = C;
-  for (int l = 0; l < n_levels; ++l) {
+  for (int l = first; l < n_levels; ++l) {
     g_level = l + 1;
     T* zout = (l + 1 == n_levels) ? static_cast<T*>(out) : reinterpret_cast<T*>(ws + ((l & 1) ? w.pong : w.ping));
     if (levels[l].kind == DCHAG_LEVEL_LINEAR)
@@ -735,6 +745,97 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
   return DCHAG_OK;
 }
 
+// A linear first level needs neither its input tokens nor their gradients in HBM (see k_linear_first_grads): true
+// when the reverse sweep takes that route.  The products' intermediates (P fp32, the scaled weights, S) go where the
+// tokens would have been.  DCHAG_LINEAR_TOKENS (debugging aid) keeps the route through the tokens.
+inline bool linear_first_without_tokens(dchag_dtype dt, int B, int C, int N, int pp, int D, int n_levels,
+                                        const dchag_level* levels) {
+  if (dt != DCHAG_BF16 || n_levels < 2 || levels[0].kind != DCHAG_LEVEL_LINEAR || getenv("DCHAG_LINEAR_TOKENS"))
+    return false;
+  const int cpr = pp / 8;
+  if (pp % 8 || (cpr & (cpr - 1)) || cpr > 64 || D % 8) return false;
+  const size_t G = groups_of(C, levels[0].group_size);
+  const size_t need = align_up((size_t)C * D * pp * 4) + align_up((size_t)C * D * pp * 2) + align_up(G * D * 4);
+  return need <= align_up((size_t)B * C * N * D * 2);
+}
+
+// One product per channel with the group's operand shared by its members: full groups in one launch, a short last
+// group in a second one.  dA / dB / dC: element offsets per channel of the three operands (0 for the shared one).
+template <typename TC>
+int gemm_per_channel(GemmDesc d, int C, int g, long a_grp, long b_ch, long c_ch, const bf16* A, const bf16* Bm, TC* Cm,
+                     hipStream_t st) {
+  const int full = C / g, tail = C % g;
+  int rc = DCHAG_OK;
+  d.A.sk = a_grp; d.A.sa = 0;
+  d.Bm.sk = b_ch * g; d.Bm.sa = b_ch;
+  d.C.sk = c_ch * g; d.C.sa = c_ch;
+  if (full) {
+    d.nk = full; d.na = g;
+    if ((rc = launch_gemm_bf16<TC>(d, A, Bm, nullptr, Cm, st))) return rc;
+  }
+  if (tail) {
+    d.nk = 1; d.na = tail;
+    rc = launch_gemm_bf16<TC>(d, A + a_grp * full, Bm + b_ch * g * full, nullptr, Cm + c_ch * g * full, st);
+  }
+  return rc;
+}
+
+// Reverse of (tokenizer, linear first level) given dy [B,G,N,D]: dmix / dbias of the level, dWe, dtok_bias, dx.
+inline int linear_first_backward(int B, int C, int H, int W, int p, int D, const dchag_level* lv,
+                                 const dchag_level_grads* gr, const bf16* x, const bf16* We, const bf16* be,
+                                 const bf16* ce, const bf16* dy, bf16* dx, bf16* dWe, bf16* dtok_bias, bf16* patches,
+                                 unsigned char* scratch, hipStream_t st) {
+  const int N = (H / p) * (W / p), pp = p * p, g = lv->group_size, G = groups_of(C, g);
+  float* P = reinterpret_cast<float*>(scratch);
+  bf16* Ws = reinterpret_cast<bf16*>(scratch + align_up((size_t)C * D * pp * 4));
+  float* S = reinterpret_cast<float*>(scratch + align_up((size_t)C * D * pp * 4) + align_up((size_t)C * D * pp * 2));
+  const long pixels = (long)B * C * H * W;
+  if (pixels > ((long)1 << 39)) return DCHAG_ERR_SHAPE;
+  int rc;
+  bf16* dmix = static_cast<bf16*>(gr->dWv);
+  const bool want_p = dWe || dmix;
+  {
+    StageTimer tm(DCHAG_STAGE_BWD_CHANNEL_MIX, st);
+    k_colsum<bf16, float><<<dim3((D + 255) / 256, G), 1024, 0, st>>>(B, D, RowBlocks{G, G * N, N}, dy, S);
+    if ((rc = launch_status())) return rc;
+    if (gr->dbv && (rc = colsum<bf16>(B, D, RowBlocks{G, G * N, N}, dy, static_cast<bf16*>(gr->dbv), st))) return rc;
+    if (dmix && G * g > C) {                                      // members a short last group lacks: zero
+      const long n = (long)(G * g - C) * D;
+      k_fill_zero<bf16><<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(n, dmix + (size_t)C * D);
+      if ((rc = launch_status())) return rc;
+    }
+  }
+  StageTimer tm(DCHAG_STAGE_BWD_TOKENIZE, st);
+  if (want_p) {
+    if ((rc = patch_rows<bf16, false>(pixels, H, W, p, const_cast<bf16*>(x), patches, st))) return rc;
+    GemmDesc d{};                                                 // P[c][d][kk] = sum_{b,n} dy[b,k,n,d] patch[b,c,n,kk]
+    d.M = D; d.N = pp; d.K = N; d.nb = B; d.reduce_b = 1;
+    d.A = {(long)G * N * D, 0, 0, 1, (long)D};
+    d.Bm = {(long)C * N * pp, 0, 0, (long)pp, 1};
+    d.C = {0, 0, 0, (long)pp, 1};
+    d.scale = 1.f;
+    if ((rc = gemm_per_channel<float>(d, C, g, (long)N * D, (long)N * pp, (long)D * pp, dy, patches, P, st))) return rc;
+  }
+  {
+    const long chunks = (long)C * D * (pp / 8);
+    k_linear_first_grads<<<dim3((unsigned)((chunks + 255) / 256)), 256, 0, st>>>(
+        chunks, C, D, pp, g, want_p ? P : nullptr, S, We, be, ce, static_cast<const bf16*>(lv->Wv), dWe, dtok_bias, dmix,
+        dx ? Ws : nullptr);
+    if ((rc = launch_status())) return rc;
+  }
+  if (dx) {
+    GemmDesc d{};                                                 // dpatch[b,c,n,kk] = sum_d dy[b,k,n,d] Ws[c][d][kk]
+    d.M = N; d.N = pp; d.K = D; d.nb = B;
+    d.A = {(long)G * N * D, 0, 0, (long)D, 1};
+    d.Bm = {0, 0, 0, (long)pp, 1};
+    d.C = {(long)C * N * pp, 0, 0, (long)pp, 1};
+    d.scale = 1.f;
+    if ((rc = gemm_per_channel<bf16>(d, C, g, (long)N * D, (long)D * pp, (long)N * pp, dy, Ws, patches, st))) return rc;
+    if ((rc = patch_rows<bf16, true>(pixels, H, W, p, dx, patches, st))) return rc;
+  }
+  return DCHAG_OK;
+}
+
 // The two halves of a training step.  keep_forward fills the workspace with what the reverse sweep reads
 // (tokens, and per level: inputs, folded keys, softmax weights, per-head token averages, pre-projection outputs)
 // and, if asked, writes the path's output; reverse_sweep walks the levels backwards over that workspace.
@@ -744,13 +845,25 @@ int keep_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int h
                  unsigned char* ws, const BackwardWs& w, hipStream_t st) {
   const int N = (H / p) * (W / p);
   g_level = 0;
-  int rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st);
-  if (rc) return rc;
+  int rc;
+  const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
+  int c_in = C, first = 0;
+  if constexpr (std::is_same<T, bf16>::value) {
+    // a linear first level whose reverse needs no tokens: tokenizer and level in one kernel, nothing else kept
+    if (linear_first_without_tokens(dt, B, C, N, p * p, D, n_levels, levels) && tokenize_mix_ok(dt, levels, p * p, D)) {
+      g_level = 1;
+      const KeptLevel kl = kept_level(dt, B, C, N, D, heads, gs[0], true, true);
+      bf16* y = reinterpret_cast<bf16*>(ws + w.kept[0] + kl.y);
+      if ((rc = tokenize_mix_forward(B, C, H, W, p, D, x, We, be, ce, &levels[0], y, st))) return rc;
+      zin = y;
+      c_in = groups_of(C, gs[0]);
+      first = 1;
+    }
+  }
+  if (!first && (rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st))) return rc;
   const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
-  const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
-  int c_in = C;
-  for (int l = 0; l < n_levels; ++l) {
+  for (int l = first; l < n_levels; ++l) {
     g_level = l + 1;
     const bool linear = levels[l].kind == DCHAG_LEVEL_LINEAR, last = l + 1 == n_levels;
     const KeptLevel kl = kept_level(dt, B, c_in, N, D, heads, gs[l], linear, !last);
@@ -770,7 +883,8 @@ int keep_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int h
 
 template <typename T>
 int reverse_sweep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x, const void* We,
-                  int n_levels, const dchag_level* levels, const int32_t* gs, const void* dout, void* dx, void* dWe,
+                  const void* be, const void* ce, int n_levels, const dchag_level* levels, const int32_t* gs,
+                  const void* dout, void* dx, void* dWe,
                   void* dtok_bias, const dchag_level_grads* grads, unsigned char* ws, const BackwardWs& w,
                   hipStream_t st) {
   const int N = (H / p) * (W / p);
@@ -787,10 +901,23 @@ int reverse_sweep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
   }
   int rc;
   const T* dy = static_cast<const T*>(dout);
+  bool no_tokens = false;
+  if constexpr (std::is_same<T, bf16>::value) no_tokens = linear_first_without_tokens(dt, B, C, N, p * p, D, n_levels, levels);
   for (int l = n_levels - 1; l >= 0; --l) {
     g_level = l + 1;
     unsigned char* lw = ws + w.kept[l];
     T* dz = reinterpret_cast<T*>(ws + w.dz[l & 1]);
+    if constexpr (std::is_same<T, bf16>::value) {
+      if (l == 0 && no_tokens) {
+        rc = linear_first_backward(B, C, H, W, p, D, &levels[0], &grads[0], static_cast<const bf16*>(x),
+                                   static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+                                   static_cast<const bf16*>(ce), dy, static_cast<bf16*>(dx), static_cast<bf16*>(dWe),
+                                   static_cast<bf16*>(dtok_bias), reinterpret_cast<bf16*>(ws + w.patches),
+                                   ws + w.tokens, st);
+        g_level = 0;
+        return rc;
+      }
+    }
     if (levels[l].kind == DCHAG_LEVEL_LINEAR)
       rc = linear_level_backward<T>(B, cins[l], N, D, &levels[l], &grads[l], zins[l], dy, dz, st);
     else

@@ -561,6 +561,63 @@ __global__ __launch_bounds__(256) void k_channel_mix_dw_vec(int B, int Cin, int 
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Gradients of a linear first level and of the tokenizer below it without the tokens (bf16).  With
+//   P[c][d][kk] = sum_{b,n} dy[b,k(c),n,d] * patch[b,c,n,kk]   (one product per channel)   and   S[k][d] = sum_{b,n} dy
+// the token t[c] = We[c] patch + be[c] + ce[c] and the mixing weight s[c] give
+//   dmix[c][d]      = sum_{b,n} t[c][d] dy[d]  = sum_kk We[c][d][kk] P[c][d][kk] + (be + ce)[c][d] S[k][d]
+//   dWe[c][d][kk]   = s[c][d] P[c][d][kk]          dtok_bias[c][d] = s[c][d] S[k][d]
+// and the pixel gradient is dy times the scaled weights  Ws[c][d][kk] = We[c][d][kk] s[c][d], which this kernel also
+// writes.  One thread per 8 pixels of a (c, d) row, pp / 8 threads per row (a power of two <= 64), rows summed by
+// lane exchange.  grid ceil(C D (pp/8) / 256), block 256.  Any output pointer may be NULL.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_linear_first_grads(long chunks, int C, int D, int pp, int g,
+                                                            const float* __restrict__ P, const float* __restrict__ S,
+                                                            const bf16* __restrict__ We, const bf16* __restrict__ be,
+                                                            const bf16* __restrict__ ce, const bf16* __restrict__ mix,
+                                                            bf16* __restrict__ dWe, bf16* __restrict__ dtok_bias,
+                                                            bf16* __restrict__ dmix, bf16* __restrict__ Ws) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;           // ((c * D + d) * (pp / 8) + chunk)
+  const int cpr = pp / 8;
+  const bool live = idx < chunks;
+  const long row = (live ? idx : chunks - 1) / cpr;                // c * D + d
+  const int ch = (int)((live ? idx : chunks - 1) % cpr);
+  const int c = (int)(row / D), d = (int)(row % D);
+  const int k = c / g;
+  const float s = (float)mix[(size_t)c * D + d];                   // mixing weights are [G * g][D], member c = k g + cl
+  const size_t o = (size_t)row * pp + ch * 8;
+  const bf16x8 w8 = *reinterpret_cast<const bf16x8*>(We + o);
+  float dot = 0.f;
+  if (P) {
+    const f32x4 p0 = *reinterpret_cast<const f32x4*>(P + o), p1 = *reinterpret_cast<const f32x4*>(P + o + 4);
+    bf16x8 g8;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      dot += (float)w8[e] * p0[e] + (float)w8[4 + e] * p1[e];
+      g8[e] = (bf16)(s * p0[e]);
+      g8[4 + e] = (bf16)(s * p1[e]);
+    }
+    if (dWe && live) *reinterpret_cast<bf16x8*>(dWe + o) = g8;
+  }
+  if (Ws && live) {
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (bf16)((float)w8[e] * s);
+    *reinterpret_cast<bf16x8*>(Ws + o) = v;
+  }
+  for (int off = 1; off < cpr; off <<= 1) dot += __shfl_xor(dot, off, kWave);     // the cpr threads of a row are adjacent lanes
+  if (live && ch == 0) {
+    const float sv = S[(size_t)k * D + d];
+    if (dmix) {
+      float bias = 0.f;
+      if (be) bias += (float)be[(size_t)c * D + d];
+      if (ce) bias += (float)ce[(size_t)c * D + d];
+      dmix[(size_t)c * D + d] = (bf16)(dot + bias * sv);
+    }
+    if (dtok_bias) dtok_bias[(size_t)c * D + d] = (bf16)(s * sv);
+  }
+}
+
 }  // namespace dchag
 
 // =======================================================================================

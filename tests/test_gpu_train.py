@@ -75,6 +75,11 @@ SMALL = [
     dict(dtype="bf16", B=1, C=12, H=32, W=64, p=8, D=1024, heads=32, group_sizes=(6, 2)),
     # 24 heads: the second head block is half empty
     dict(dtype="bf16", B=1, C=7, H=16, W=32, p=4, D=768, heads=24, group_sizes=(4, 2)),
+    # linear first level taken without tokens (its gradients and the tokenizer's from per-channel products with the
+    # upstream gradient): 13 channels in groups of 4 (a short last group of one), 16 pixels per patch, N = 64
+    dict(dtype="bf16", B=2, C=13, H=32, W=32, p=4, D=256, heads=4, group_sizes=(4, 4), level_kinds=("linear", "attention")),
+    # the same route with 64 pixels per patch, N = 128, groups 2 + 2 + 1
+    dict(dtype="bf16", B=2, C=5, H=64, W=128, p=8, D=512, heads=8, group_sizes=(2, 3), level_kinds=("linear", "attention")),
     # D = 2048: two blocks of 1024 columns per wavefront in the fused token kernel; groups 4 + 3, N = 6
     dict(dtype="bf16", B=1, C=7, H=16, W=24, p=8, D=2048, heads=16, group_sizes=(4, 2)),
     # 6 heads of 128 (not a multiple of 4 or 8: the head tables of the token kernels are zero-padded), groups 5 + 5 + 1
@@ -210,7 +215,22 @@ def test_backward_generic_bf16_kernels_still_match(monkeypatch, env):
     compare_grads(cfg, pr, got, want, TOL["bf16"], np.repeat(np.arange(cfg.B), cfg.N), np.tile(np.arange(cfg.N), cfg.B))
 
 
-@pytest.mark.parametrize("kw", [SMALL[0], SMALL[3], SMALL[4], SMALL[10]])
+def test_backward_linear_first_level_through_the_tokens_still_matches(monkeypatch):
+    """The route of a linear first level that materialises tokens and token gradients (taken when the intermediates of
+    the token-free route do not fit where the tokens would be), forced on a shape the token-free route takes."""
+    monkeypatch.setenv("DCHAG_LINEAR_TOKENS", "1")
+    cfg = cfg_of(dtype="bf16", B=2, C=13, H=32, W=32, p=4, D=256, heads=4, group_sizes=(4, 4),
+                 level_kinds=("linear", "attention"))
+    pr = make_problem(cfg)
+    from workloads import round_to_bf16
+    dout = round_to_bf16(np.random.Generator(np.random.PCG64(48)).standard_normal((cfg.B, cfg.N, cfg.D)).astype(np.float32))
+    got = run_backward(pr, dout)
+    want = oracle.backward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads,
+                           dout.reshape(cfg.B * cfg.N, cfg.D).astype(np.float64))
+    compare_grads(cfg, pr, got, want, TOL["bf16"], np.repeat(np.arange(cfg.B), cfg.N), np.tile(np.arange(cfg.N), cfg.B))
+
+
+@pytest.mark.parametrize("kw", [SMALL[0], SMALL[3], SMALL[4], SMALL[10], SMALL[13]])
 def test_forward_keep_and_backward_kept_equal_the_recomputing_calls(kw):
     """A training step that keeps its activations: the output equals dchag_forward_folded's and every gradient
     equals dchag_backward's bit for bit (same kernels on the same buffers), for two upstream gradients in a row
