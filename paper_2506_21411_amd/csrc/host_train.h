@@ -214,7 +214,7 @@ inline int gemm_with_bias_grad(GemmDesc d, int B, int D, RowBlocks rb, const flo
                                float* db, hipStream_t st) {
   int rc = DCHAG_OK;
   if (db) {
-    k_colsum<float, float><<<dim3((D + 255) / 256, rb.G), 1024, 0, st>>>(B, D, rb, X, db);
+    k_colsum<float, float><<<dim3((D + 63) / 64, rb.G), 1024, 0, st>>>(B, D, rb, X, db);
     if ((rc = launch_status())) return rc;
   }
   return dW ? launch_gemm<float, float, float>(d, X, Y, nullptr, dW, st) : DCHAG_OK;
@@ -224,7 +224,7 @@ inline int gemm_with_bias_grad(GemmDesc d, int B, int D, RowBlocks rb, const bf1
   if (dW && db && gemm_rowsum_ok(d)) return launch_gemm_bf16<bf16>(d, X, Y, nullptr, dW, st, db);
   int rc = DCHAG_OK;
   if (db) {
-    k_colsum<bf16, bf16><<<dim3((D + 255) / 256, rb.G), 1024, 0, st>>>(B, D, rb, X, db);
+    k_colsum<bf16, bf16><<<dim3((D + 63) / 64, rb.G), 1024, 0, st>>>(B, D, rb, X, db);
     if ((rc = launch_status())) return rc;
   }
   return dW ? launch_gemm_bf16<bf16>(d, X, Y, nullptr, dW, st) : DCHAG_OK;
@@ -404,7 +404,7 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
 
 template <typename T>
 int colsum(int B, int D, RowBlocks rb, const T* X, T* out, hipStream_t st) {
-  k_colsum<T, T><<<dim3((D + 255) / 256, rb.G), 1024, 0, st>>>(B, D, rb, X, out);
+  k_colsum<T, T><<<dim3((D + 63) / 64, rb.G), 1024, 0, st>>>(B, D, rb, X, out);
   return launch_status();
 }
 
@@ -796,7 +796,7 @@ inline int linear_first_backward(int B, int C, int H, int W, int p, int D, const
   const bool want_p = dWe || dmix;
   {
     StageTimer tm(DCHAG_STAGE_BWD_CHANNEL_MIX, st);
-    k_colsum<bf16, float><<<dim3((D + 255) / 256, G), 1024, 0, st>>>(B, D, RowBlocks{G, G * N, N}, dy, S);
+    k_colsum<bf16, float><<<dim3((D + 63) / 64, G), 1024, 0, st>>>(B, D, RowBlocks{G, G * N, N}, dy, S);
     if ((rc = launch_status())) return rc;
     if (gr->dbv && (rc = colsum<bf16>(B, D, RowBlocks{G, G * N, N}, dy, static_cast<bf16*>(gr->dbv), st))) return rc;
     if (dmix && G * g > C) {                                      // members a short last group lacks: zero

@@ -241,32 +241,41 @@ __global__ __launch_bounds__(256) void k_dz_attention(int Cin, int N, int D, int
 
 // ---------------------------------------------------------------------------------------
 // Column sums over the rows of every group:  out[k][i] = sum_b sum_{r < rows_of(k)} X[first_row(b,k) + r][i]
-// grid (ceil(D/256), G), block 1024: lane l of every wavefront owns the 4 columns 256 x + 4 l .. (one 8- or
-// 16-byte load per row), the 16 wavefronts take every 16th row and meet in LDS in a fixed order.  D % 4 == 0.
+// grid (ceil(D/64), G), block 1024: a block owns 64 columns; lane l of a wavefront takes the 4 columns 4 (l % 16) .. of
+// row 4 wave + l / 16 and every 64th row after it (one 8- or 16-byte load per row); the four row groups of a
+// wavefront meet by lane exchange, the 16 wavefronts in LDS, both in a fixed order.  D % 4 == 0.
 template <typename T, typename TO>
 __global__ __launch_bounds__(1024) void k_colsum(int B, int D, RowBlocks rb, const T* __restrict__ X,
                                                  TO* __restrict__ out) {
   typedef __attribute__((ext_vector_type(4))) T vec4;
-  __shared__ float part[16][256];
+  __shared__ float part[16][64];
   const int k = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i = blockIdx.x * 256 + lane * 4;
+  const int cg = lane & 15, rs = lane >> 4;               // 4 columns of the block's 64; row wave * 4 + rs, then every 64th
+  const int i = blockIdx.x * 64 + cg * 4;
   const int rows = rb.rows_of(k);
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (i < D)
     for (int b = 0; b < B; ++b) {
       const T* xb = X + (size_t)rb.first_row(b, k) * D + i;
-      for (int r = wave; r < rows; r += 16) {
+      for (int r = wave * 4 + rs; r < rows; r += 64) {
         const vec4 v = *reinterpret_cast<const vec4*>(xb + (size_t)r * D);
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[e] += to_f32(v[e]);
       }
     }
 #pragma unroll
-  for (int e = 0; e < 4; ++e) part[wave][lane * 4 + e] = acc[e];
+  for (int e = 0; e < 4; ++e) {
+    acc[e] += __shfl_xor(acc[e], 16, kWave);
+    acc[e] += __shfl_xor(acc[e], 32, kWave);
+  }
+  if (rs == 0) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) part[wave][cg * 4 + e] = acc[e];
+  }
   __syncthreads();
-  if (threadIdx.x < 256) {
-    const int ii = blockIdx.x * 256 + threadIdx.x;
+  if (threadIdx.x < 64) {
+    const int ii = blockIdx.x * 64 + threadIdx.x;
     float sum = 0.f;
 #pragma unroll
     for (int w16 = 0; w16 < 16; ++w16) sum += part[w16][threadIdx.x];
