@@ -349,6 +349,12 @@ def main() -> int:
             ms3, _, _ = timed(c3, t3, 3, 10, profile=False)
             other.append({"workload": wl, "tokens": c3.tokens, "ms_per_step": round(ms3, 4),
                           "value": c3.tokens / (ms3 * 1e-3), "unit": "tokens/s"})
+            if wl == "hyperspectral_linear":        # and its backward (forward recomputation included)
+                mode["name"], mode["bwd"] = "backward", prepare_backward(c3, t3)
+                ms3b, _, _ = timed(c3, t3, 2, 5, profile=False)
+                other.append({"workload": wl, "call": "dchag_backward (recomputes the forward)", "tokens": c3.tokens,
+                              "ms_per_step": round(ms3b, 4), "value": c3.tokens / (ms3b * 1e-3), "unit": "tokens/s"})
+                mode["name"], mode["bwd"] = "forward", None
             del t3
             torch.cuda.empty_cache()
 
