@@ -96,7 +96,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="hyperspectral")
     ap.add_argument("--mode", default="forward", choices=["forward", "folded", "backward"],
                     help="what one step is: dchag_forward (the headline), dchag_forward_folded, or dchag_backward")
