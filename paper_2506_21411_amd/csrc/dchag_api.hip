@@ -592,13 +592,18 @@ inline bool tokenize_mix_ok(dchag_dtype dt, const dchag_level* levels, int pp, i
 int tokenize_mix_forward(int B, int C, int H, int W, int p, int D, const void* x, const void* We, const void* be,
                          const void* ce, const dchag_level* lv, bf16* y, hipStream_t st) {
   const int N = (H / p) * (W / p), pp = p * p, g = lv->group_size, G = groups_of(C, g);
-  const size_t lds = (size_t)2 * 64 * (pp * 2 + 16);
-  auto mixk = pp == 16 ? k_tokenize_mix_mfma<1> : k_tokenize_mix_mfma<4>;
+  // 128 patches per workgroup (eight wavefronts) while that leaves a workgroup per compute unit, else 64 (four);
+  // DCHAG_MIX_NARROW (debugging aid) keeps the 64-patch kernel
+  const bool wide = N >= 128 && (long)((N + 127) / 128) * (D / 256) * G * B >= compute_units() && !getenv("DCHAG_MIX_NARROW");
+  const int PB = wide ? 128 : 64;
+  const size_t lds = (size_t)2 * PB * (pp * 2 + 16);
+  auto mixk = wide ? (pp == 16 ? k_tokenize_mix_wide<1> : k_tokenize_mix_wide<4>)
+                   : (pp == 16 ? k_tokenize_mix_mfma<1> : k_tokenize_mix_mfma<4>);
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
       hipSuccess)
     return DCHAG_ERR_LAUNCH;
   StageTimer tm(DCHAG_STAGE_TOKENIZE_MIX, st);
-  mixk<<<dim3((unsigned)(((N + 63) / 64) * (D / 256)), G, B), 256, lds, st>>>(
+  mixk<<<dim3((unsigned)(((N + PB - 1) / PB) * (D / 256)), G, B), wide ? 512 : 256, lds, st>>>(
       C, H, W, p, D, g, static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
       static_cast<const bf16*>(ce), static_cast<const bf16*>(lv->Wv), static_cast<const bf16*>(lv->bv), y);
   return launch_status();

@@ -1482,4 +1482,120 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mix_mfma(int C, int H, int 
     }
 }
 
+// The same with 128 patches x 256 columns per workgroup of eight wavefronts (wavefront w: columns 32 w .. 32 w + 31,
+// 4 row blocks): every workgroup re-reads the tokenizer weights of its members and gathers their pixels once per column
+// slice, so the larger patch tile halves the weight traffic at the same pixel traffic.  grid (ceil(N/128) * (D/256), G, B),
+// block 512.  Dynamic LDS: 2 * 128 * (p*p*2 + 16) bytes.
+template <int KSS>
+__global__ __launch_bounds__(512) void k_tokenize_mix_wide(int C, int H, int W, int p, int D, int g,
+                                                              const bf16* __restrict__ x, const bf16* __restrict__ We,
+                                                              const bf16* __restrict__ be, const bf16* __restrict__ ce,
+                                                              const bf16* __restrict__ wmix,
+                                                              const bf16* __restrict__ bias, bf16* __restrict__ y) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  constexpr int pp = 16 * KSS, pieces = pp / 4;
+  constexpr int rbp = pp * 2 + 16;
+  constexpr int PB = 128;                                // patches per workgroup
+  constexpr int NG = (PB * pieces + 511) / 512;          // 8-byte pieces a thread gathers per member
+  const int pw = W / p, N = (H / p) * pw;
+  const int ns_n = D / 256;
+  const int n0 = (blockIdx.x / ns_n) * PB, col_base = (blockIdx.x % ns_n) * 256;
+  const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, C - c0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int d0 = col_base + wave * 32 + l32;             // this lane's column
+
+  // what member cl needs: its patches (gv), its weight fragments (bfrag) and four per-column scalars
+  bf16x4 gv[NG];
+  bf16x8 bfrag[KSS];
+  float w0, a0;
+  // source offsets of this thread's pieces inside a channel image (-1: patch outside the image)
+  int goff[NG];
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    const int idx = tid + 512 * i;
+    const int t = idx / pieces, q = idx % pieces;
+    const int r = (q * 4) / p, s0 = (q * 4) % p;
+    const int n = n0 + t;
+    goff[i] = (idx < PB * pieces && n < N) ? ((n / pw) * p + r) * W + (n % pw) * p + s0 : -1;
+  }
+  auto fetch = [&](int cl) {
+    const int c = c0 + cl;
+    const bf16* img = x + ((size_t)b * C + c) * H * W;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      gv[i] = bf16x4{};
+      if (goff[i] >= 0) gv[i] = *reinterpret_cast<const bf16x4*>(img + goff[i]);
+    }
+    const bf16* wrow = We + ((size_t)c * D + d0) * pp + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk) bfrag[kk] = *reinterpret_cast<const bf16x8*>(wrow + kk * 16);
+    w0 = (float)wmix[((size_t)k * g + cl) * D + d0];
+    a0 = 0.f;
+    if (be) a0 += (float)be[(size_t)c * D + d0];
+    if (ce) a0 += (float)ce[(size_t)c * D + d0];
+  };
+  auto stash = [&](int buf) {
+    unsigned char* u = smem + buf * PB * rbp;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      const int idx = tid + 512 * i;
+      if (idx < PB * pieces) *reinterpret_cast<bf16x4*>(u + (idx / pieces) * rbp + (idx % pieces) * 8) = gv[i];
+    }
+  };
+
+  f32x16 o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+  float cst0 = 0.f;                                      // patch-independent part: sum_c w * (be + ce) + bias
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int cl = 0; cl < gk; ++cl) {
+    const unsigned char* u = smem + (cl & 1) * PB * rbp;
+    // this member's operands move to their own registers; the next member's loads start right away
+    bf16x8 bcur[KSS];
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk) bcur[kk] = bfrag[kk];
+    const float cw0 = w0;
+    cst0 += w0 * a0;
+    if (cl + 1 < gk) fetch(cl + 1);
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; i += 2) {
+      f32x16 acc0 = zero, acc1 = zero;                   // two independent chains: row blocks i and i + 1
+#pragma unroll
+      for (int kk = 0; kk < KSS; ++kk) {
+        const bf16x8 af0 = *reinterpret_cast<const bf16x8*>(u + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+        const bf16x8 af1 = *reinterpret_cast<const bf16x8*>(u + ((i + 1) * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0, bcur[kk], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1, bcur[kk], acc1, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        o[i][r] += cw0 * acc0[r];
+        o[i + 1][r] += cw0 * acc1[r];
+      }
+    }
+    if (cl + 1 < gk) stash((cl + 1) & 1);
+    __syncthreads();
+  }
+  if (bias) cst0 += (float)bias[(size_t)k * D + d0];
+  bf16* ybase = y + (((size_t)b * G + k) * N + n0) * D;
+  const int lane_off = 4 * lhi * D + d0;
+  const int nlim = N - n0 - 4 * lhi;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
+      if (rr < nlim) ybase[(size_t)rr * D + lane_off] = (bf16)(o[i][r] + cst0);
+    }
+}
+
 }  // namespace dchag

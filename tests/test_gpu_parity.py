@@ -454,9 +454,23 @@ def test_forward_can_be_captured_in_a_graph_and_replayed():
                                             ("deep1000", 2), ("hyperspectral_linear", 6),
                                             ("hyperspectral_flat", 4)])
 def test_forward_full_size_on_sampled_patches(name, per_batch):
+    _forward_on_sampled_patches(get_config(name), name, per_batch)
+
+
+@pytest.mark.parametrize("narrow", [False, True])
+def test_forward_linear_first_level_patch_tiles(monkeypatch, narrow):
+    """The fused tokenizer + linear first level with 128 patches per workgroup (taken when that leaves a workgroup per
+    compute unit) and with 64: N = 500 patches (ragged last tile either way), 16 pixels per patch, groups 4 + 4 + ... + 1."""
+    if narrow:
+        monkeypatch.setenv("DCHAG_MIX_NARROW", "1")
+    cfg = cfg_of(dtype="bf16", B=4, C=33, H=80, W=100, p=4, D=512, heads=8, group_sizes=(4, 9),
+                 level_kinds=("linear", "attention"))
+    _forward_on_sampled_patches(cfg, f"linear first level, narrow={narrow}", 10)
+
+
+def _forward_on_sampled_patches(cfg, name, per_batch):
     """The configurations of the benchmark at full size, in the launch configuration the benchmark
     times; the oracle computes a seeded sample of patches (every weight takes part in every patch)."""
-    cfg = get_config(name)
     say(f"full-size {name}: generating inputs")
     pr = make_problem(cfg)
     say(f"full-size {name}: running the GPU path")
