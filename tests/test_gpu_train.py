@@ -301,7 +301,8 @@ def test_backward_is_deterministic():
 RAGGED_TILES = dict(dtype="bf16", B=4, C=250, H=40, W=100, p=4, D=256, heads=8, group_sizes=(32, 8))
 
 
-@pytest.mark.parametrize("name,per_batch", [("weather", 4), ("hyperspectral", 3), ("ragged_tiles", 12)])
+@pytest.mark.parametrize("name,per_batch", [("weather", 4), ("hyperspectral", 3), ("ragged_tiles", 12), ("deep", 2),
+                                            ("wide", 2), ("hyperspectral_linear", 3), ("hyperspectral_flat", 2)])
 def test_backward_full_size_with_upstream_gradient_on_sampled_patches(name, per_batch):
     """Full-size configurations in the launch configuration of the benchmark.  The upstream gradient is
     non-zero on a seeded sample of patches only; the path is independent per patch, so every other patch
