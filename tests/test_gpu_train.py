@@ -109,6 +109,28 @@ def test_forward_folded_matches_oracle(kw):
     assert err < TOL[d]
 
 
+@pytest.mark.parametrize("name,per_batch", [("weather", 4), ("hyperspectral", 4), ("hyperspectral_linear", 4),
+                                            ("hyperspectral_flat", 3), ("deep", 2)])
+def test_forward_folded_full_size_on_sampled_patches(name, per_batch):
+    """dchag_forward_folded at the benchmark's sizes and launch configuration, against the oracle on a seeded sample of
+    patches; every output row is finite."""
+    cfg = get_config(name)
+    say(f"forward_folded full-size {name}: generating inputs")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    out = dchag.dchag_forward_folded(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
+                                     [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    bs, ns = sample_patches(cfg.B, cfg.N, per_batch, seed=29)
+    say(f"forward_folded full-size {name}: oracle on {bs.size} patches")
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns))
+    got = host(out[torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()])
+    err = rel_err(got, want)
+    say(f"forward_folded full-size {name}: err={err:.3e}")
+    assert err < TOL[d]
+    assert torch.isfinite(out.float()).all()
+
+
 def test_forward_folded_without_biases_and_sharp_softmax():
     cfg = get_config("tiny")
     pr = make_problem(cfg, biases=False, query_scale=30.0)
