@@ -47,6 +47,13 @@ def stage_model(cfg, levels_in, stage, level, fused_tokens=False):
     if stage == "tokenize_mix":
         # tokenizer fused with a linear first level: pixels, tokenizer and mixing weights in, group tokens out
         return "hbm", (B * cfg.C * cfg.H * cfg.W + cfg.C * D * cfg.p * cfg.p + G * g * D + B * G * N * D) * es
+    if stage == "fold_value":
+        # weight-only: Wf[c] = Wv[k(c)] We[c] (and the two folded bias vectors)
+        return "mfma", 2.0 * cfg.C * D * D * (cfg.p * cfg.p + 2)
+    if stage == "tokenize_attend":
+        # tokenizer fused with an attention first level (value projection folded into the tokenizer weights):
+        # pixels, folded weights and softmax weights in, pre-projection outputs out
+        return "hbm", (B * cfg.C * cfg.H * cfg.W + cfg.C * D * cfg.p * cfg.p + B * G * N * D) * es + tok * h * 4
     if stage == "channel_mix":
         return "hbm", (tok * D + G * g * D + B * G * N * D) * es
     if stage == "vproj":

@@ -268,7 +268,9 @@ typedef enum {
   DCHAG_STAGE_BWD_TOKENS = 15,     /* gradient at the level's input tokens                      */
   DCHAG_STAGE_BWD_KEY_QUERY = 16,  /* key / query weight gradients (rank-one per head)          */
   DCHAG_STAGE_BWD_TOKENIZE = 17,   /* tokenizer backward (dWe, token bias, dx)                  */
-  DCHAG_STAGE_BWD_CHANNEL_MIX = 18 /* backward of a linear level                                */
+  DCHAG_STAGE_BWD_CHANNEL_MIX = 18,/* backward of a linear level                                */
+  DCHAG_STAGE_FOLD_VALUE = 19,     /* value projection folded into the tokenizer (weight-only)  */
+  DCHAG_STAGE_TOKENIZE_ATTEND = 20 /* tokenizer fused with an attention first level             */
 } dchag_stage;
 
 typedef struct {

@@ -47,7 +47,7 @@ class _CStageTime(ctypes.Structure):
 STAGE_NAMES = {0: "tokenize", 1: "query", 2: "fold", 3: "scores", 4: "vproj", 5: "softmax_agg", 6: "oproj",
                7: "fused_vagg", 8: "channel_mix", 9: "tokenize_mix", 10: "head_sums", 11: "head_vproj",
                12: "bwd_oproj", 13: "bwd_value", 14: "bwd_softmax", 15: "bwd_tokens", 16: "bwd_key_query",
-               17: "bwd_tokenize", 18: "bwd_channel_mix"}
+               17: "bwd_tokenize", 18: "bwd_channel_mix", 19: "fold_value", 20: "tokenize_attend"}
 
 LEVEL_ATTENTION, LEVEL_LINEAR = 0, 1
 

@@ -589,9 +589,56 @@ inline bool tokenize_mix_ok(dchag_dtype dt, const dchag_level* levels, int pp, i
   return dt == DCHAG_BF16 && levels[0].kind == DCHAG_LEVEL_LINEAR && (pp == 16 || pp == 64) && D % 256 == 0 &&
          !getenv("DCHAG_GENERIC_TOKENIZE");
 }
+// The ring-buffered kernel of the fused tokenizer + first level takes 8 x 8 patches whose rows, like every weight and
+// vector row it streams, are whole 16-byte pieces (DCHAG_FIRST_LEVEL_REGS, a debugging aid, keeps the older kernels).
+inline bool aligned16(const void* ptr) { return !(reinterpret_cast<uintptr_t>(ptr) & 15); }
+inline bool reduce_ring_ok(int p, int W, int D, const void* x, const void* Wt, const void* v0, const void* v1,
+                           const void* v2) {
+  return p == 8 && W % 8 == 0 && D % 256 == 0 && aligned16(x) && aligned16(Wt) && aligned16(v0) && aligned16(v1) &&
+         aligned16(v2) && !getenv("DCHAG_FIRST_LEVEL_REGS");
+}
+// part / part_bytes: optional fp32 scratch for partial sums; with it, and too few tiles to give every compute unit two
+// workgroups, a group's members are dealt to up to 16 workgroups per tile (DCHAG_FIRST_LEVEL_SPLIT overrides the count).
+template <bool ATT>
+int launch_reduce_ring(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
+                       const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias, bf16* y,
+                       hipStream_t st, float* part = nullptr, size_t part_bytes = 0) {
+  const int N = (H / 8) * (W / 8), G = groups_of(C, g);
+  TileWork tw{};
+  tw.n_tiles = D / kRedCols;
+  tw.m_tiles = (N + kRedPatches - 1) / kRedPatches;
+  tw.nb = B;
+  const long total = (long)G * B * tw.m_tiles * tw.n_tiles;
+  if (total > (1L << 26)) return DCHAG_ERR_SHAPE;
+  tw.total = (int)total;
+  const size_t per_split = (size_t)B * G * N * D;
+  const int gmin = std::min(g, C - (G - 1) * g);                  // members of the shortest group
+  int S = 1;
+  while (total * S < 2L * compute_units() && 2 * S <= std::min(16, gmin)) S *= 2;
+  if (const char* e = getenv("DCHAG_FIRST_LEVEL_SPLIT")) S = std::max(1, std::min(std::min(16, gmin), atoi(e)));
+  while (S > 1 && (!part || (size_t)S * per_split * 4 > part_bytes)) S >>= 1;
+  const int per = (int)((total * S + kXcds - 1) / kXcds);
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_reduce_ring<ATT>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kRedLdsBytes) != hipSuccess)
+    return DCHAG_ERR_LAUNCH;
+  k_tokenize_reduce_ring<ATT><<<dim3((unsigned)(per * kXcds)), 512, kRedLdsBytes, st>>>(
+      C, H, W, D, g, G, heads, round_up(g, 8), round_up(N, 32), tw, x, Wt, wmix, v1, v2, alpha, bias, y, S, part);
+  int rc = launch_status();
+  if (rc || S == 1) return rc;
+  const long quads = (long)per_split / 4;
+  k_vagg_merge<<<dim3((unsigned)((quads + 255) / 256)), 256, 0, st>>>(quads, S, G, N, D, (long)per_split, part, bias, y);
+  return launch_status();
+}
+
 int tokenize_mix_forward(int B, int C, int H, int W, int p, int D, const void* x, const void* We, const void* be,
                          const void* ce, const dchag_level* lv, bf16* y, hipStream_t st) {
   const int N = (H / p) * (W / p), pp = p * p, g = lv->group_size, G = groups_of(C, g);
+  if (reduce_ring_ok(p, W, D, x, We, lv->Wv, be, ce)) {
+    StageTimer tm(DCHAG_STAGE_TOKENIZE_MIX, st);
+    return launch_reduce_ring<false>(B, C, H, W, D, g, 1, static_cast<const bf16*>(x), static_cast<const bf16*>(We),
+                                     static_cast<const bf16*>(lv->Wv), static_cast<const bf16*>(be),
+                                     static_cast<const bf16*>(ce), nullptr, static_cast<const bf16*>(lv->bv), y, st);
+  }
   // 128 patches per workgroup (eight wavefronts) while that leaves a workgroup per compute unit, else 64 (four);
   // DCHAG_MIX_NARROW (debugging aid) keeps the 64-patch kernel
   const bool wide = N >= 128 && (long)((N + 127) / 128) * (D / 256) * G * B >= compute_units() && !getenv("DCHAG_MIX_NARROW");

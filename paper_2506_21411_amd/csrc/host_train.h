@@ -55,12 +55,16 @@ inline size_t pixel_scratch(size_t off, int C, int pp, int D, int heads, int G0,
   return off;
 }
 
+// Tokenizer weights with the first level's value projection folded in, Wf [C,D,64], and two folded bias vectors [C,D].
+inline size_t value_fold_bytes(int C, int D) { return align_up((size_t)C * D * 64 * 2) + 2 * align_up((size_t)C * D * 2); }
+
 inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int heads, int n_levels,
                           const int32_t* group_sizes) {
   FoldedWs w{};
   const size_t es = elem_size(dt);
   size_t off = 0;
-  w.tokens = off; off += align_up((size_t)B * C * N * D * es);
+  // the tokens, or (bf16, 64 pixels per patch) what replaces them when the first level's values come from the pixels
+  w.tokens = off; off += std::max(align_up((size_t)B * C * N * D * es), dt == DCHAG_BF16 && pp == 64 ? value_fold_bytes(C, D) : 0);
   int c_in = C;
   size_t lvl_max = 0, inter_max = 0;
   for (int l = 0; l < n_levels; ++l) {
@@ -363,6 +367,59 @@ PixelScores pixel_scores_of(const void* x, const void* We, const void* be, const
                      reinterpret_cast<bf16*>(ws + msb)};
 }
 
+template <typename TC>
+int gemm_per_channel(GemmDesc d, int C, int g, long a_grp, long b_ch, long c_ch, const bf16* A, const bf16* Bm, TC* Cm,
+                     hipStream_t st);
+
+// First attention level of the inference path with the value projection folded into the tokenizer (bf16, 8 x 8
+// patches): Wf[c] = Wv[k(c)] We[c] and the folded biases Wv be, Wv ce are weight-only products, then one kernel goes
+// from pixels and softmax weights to the pre-projection output o [B,G,N,D]; neither tokens nor per-head token
+// averages exist.  fold: value_fold_bytes(C, D) of scratch.
+inline bool attend_ring_ok(int B, int C, int N, int p, int W, int D, int heads, const void* x, const dchag_level* lv) {
+  const int dh = D / heads;
+  return lv->kind != DCHAG_LEVEL_LINEAR && reduce_ring_ok(p, W, D, x, lv->Wv, nullptr, nullptr, nullptr) &&
+         D % heads == 0 && dh % 64 == 0 && (kRedCols % dh == 0 || dh % kRedCols == 0) && !getenv("DCHAG_VALUE_UNFOLDED");
+}
+inline int attend_ring_forward(int B, int C, int H, int W, int D, int heads, const dchag_level* lv, const bf16* x,
+                               const bf16* We, const bf16* be, const bf16* ce, const float* alpha, unsigned char* fold,
+                               size_t fold_bytes, bf16* o, hipStream_t st) {
+  const int g = lv->group_size, G = groups_of(C, g);
+  const bf16* Wv = static_cast<const bf16*>(lv->Wv);
+  bf16* Wf = reinterpret_cast<bf16*>(fold);
+  bf16* fb[2] = {reinterpret_cast<bf16*>(fold + align_up((size_t)C * D * 64 * 2)),
+                 reinterpret_cast<bf16*>(fold + align_up((size_t)C * D * 64 * 2) + align_up((size_t)C * D * 2))};
+  const bf16* tb[2] = {be, ce};
+  int rc;
+  {
+    StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
+    GemmDesc d{};                                                 // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk)
+    d.M = D; d.N = 64; d.K = D; d.nb = 1;
+    d.A = {0, 0, 0, (long)D, 1};
+    d.Bm = {0, 0, 0, 64, 1};
+    d.C = {0, 0, 0, 64, 1};
+    d.scale = 1.f;
+    if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * 64, (long)D * 64, Wv, We, Wf, st))) return rc;
+    for (int i = 0; i < 2; ++i) {
+      if (!tb[i]) continue;
+      GemmDesc e{};                                               // (Wv v)[c](o) = sum_d v[c](d) Wv[k](o, d)
+      e.M = g; e.N = D; e.K = D; e.nb = 1; e.nk = G; e.na = 1;
+      e.ragged = 1; e.ragged_total = C; e.ragged_nominal = g;
+      e.A = {0, (long)g * D, 0, (long)D, 1};
+      e.Bm = {0, (long)D * D, 0, 1, (long)D};
+      e.C = {0, (long)g * D, 0, (long)D, 1};
+      e.scale = 1.f;
+      if ((rc = launch_gemm_bf16<bf16>(e, tb[i], Wv, nullptr, fb[i], st))) return rc;
+    }
+  }
+  StageTimer tm(DCHAG_STAGE_TOKENIZE_ATTEND, st);
+  // what is left of the scratch behind the folded weights takes partial sums (few groups: members dealt to several
+  // workgroups per tile)
+  const size_t used = value_fold_bytes(C, D);
+  return launch_reduce_ring<true>(B, C, H, W, D, g, heads, x, Wf, nullptr, be ? fb[0] : nullptr, ce ? fb[1] : nullptr,
+                                  alpha, static_cast<const bf16*>(lv->bv), o, st,
+                                  reinterpret_cast<float*>(fold + used), fold_bytes > used ? fold_bytes - used : 0);
+}
+
 template <typename T>
 int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
                         const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
@@ -382,9 +439,35 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
       first = 1;
     }
   }
-  if (!first && (rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st))) return rc;
   const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
+  if constexpr (std::is_same<T, bf16>::value) {
+    // an attention first level straight from the pixels: scores through the composed score weights, values through
+    // the folded tokenizer weights (which sit where the tokens would have been)
+    if (!first && use_px && attend_ring_ok(B, C, N, p, W, D, heads, x, &levels[0])) {
+      g_level = 1;
+      const KeptLevel kl = kept_level(dt, B, C, N, D, heads, gs[0], false, false);
+      const LevelBufs<bf16> lb = level_bufs<bf16>(ws + w.level, kl);
+      if ((rc = fast_scores(B, C, N, D, heads, &levels[0], nullptr, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, &px))) return rc;
+      if ((rc = attend_ring_forward(B, C, H, W, D, heads, &levels[0], static_cast<const bf16*>(x),
+                                    static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+                                    static_cast<const bf16*>(ce), lb.alpha_f, ws + w.tokens, w.ping - w.tokens, lb.o,
+                                    st)))
+        return rc;
+      bf16* zout = n_levels == 1 ? static_cast<bf16*>(out) : reinterpret_cast<bf16*>(ws + w.ping);
+      {
+        StageTimer tm(DCHAG_STAGE_OPROJ, st);
+        const int G0 = groups_of(C, gs[0]);
+        if ((rc = oproj(B, D, RowBlocks{G0, G0 * N, N}, lb.o, static_cast<const bf16*>(levels[0].Wo),
+                        static_cast<const bf16*>(levels[0].bo), zout, st)))
+          return rc;
+      }
+      zin = zout;
+      c_in = groups_of(C, gs[0]);
+      first = 1;
+    }
+  }
+  if (!first && (rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st))) return rc;
   for (int l = first; l < n_levels; ++l) {
     g_level = l + 1;
     T* zout = (l + 1 == n_levels) ? static_cast<T*>(out) : reinterpret_cast<T*>(ws + ((l & 1) ? w.pong : w.ping));

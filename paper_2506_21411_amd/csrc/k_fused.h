@@ -1598,4 +1598,258 @@ __global__ __launch_bounds__(512) void k_tokenize_mix_wide(int C, int H, int W, 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Tokenizer fused with the first aggregation level, operands streamed through a three-stage LDS ring
+// (8 x 8 patches only: a patch and a weight row are both one 128-byte LDS row).  Two forms:
+//   ATT = false (D-CHAG-L, paper Sections 3.2/3.3: linear partial aggregation)
+//     y[b,k,n,d] = sum_cl wmix[k][cl][d] * (Wt[c] u[b,c,n] + v1[c] + v2[c])[d] + bias[k][d]
+//   ATT = true (cross-attention level, paper Section 2.1, with the value projection folded into the tokenizer
+//     weights: Wt[c] = Wv[k] We[c], v1 = Wv be, v2 = Wv ce; exact because the softmax weights sum to one)
+//     y[b,k,n,d] = sum_cl alpha[b][k][cl][head(d)][n] * (Wt[c] u[b,c,n] + v1[c] + v2[c])[d] + bias[k][d]
+// c = k*g + cl; u = the 64 pixels of patch n; alpha laid out [B][G][gpad][heads][Np] (fp32).
+// Workgroup = 128 patches x 256 columns x all members of one group; wavefront (wm, wn) of 2 x 4 owns 64 patches x
+// 64 columns as 2 x 2 MFMA blocks.  One ring stage = one member: its 128 patches (16 KiB, gathered from the image
+// 16 bytes per lane), its 256 weight rows (32 KiB) and 4 KiB of per-member vectors (per-column scalars, softmax
+// weights of the slice's heads), all by direct-to-LDS loads issued two members ahead; one barrier per member.
+// Workgroups are dealt to the XCDs in contiguous ranges of the (k, b, patch tile, column slice) order, so the
+// workgroups that share a member's weights or a patch tile meet in one L2.
+// With S > 1 the members of a group are dealt to S workgroups per tile (few groups: not enough tiles to fill the
+// chip otherwise); each writes its fp32 partial sums to ypart [S][B][G][N][D] and k_vagg_merge adds them and the bias.
+// Requires D % 256 == 0, W % 8 == 0, 16-byte aligned x; ATT: (D / heads) % 64 == 0 and 256 % dh == 0 or dh % 256 == 0.
+// Dynamic LDS: kRedLdsBytes.
+// ---------------------------------------------------------------------------------------------
+constexpr int kRedPatches = 128, kRedCols = 256;
+constexpr int kRedABytes = kRedPatches * 128, kRedBBytes = kRedCols * 128, kRedXBytes = 4096;
+constexpr int kRedStageBytes = kRedABytes + kRedBBytes + kRedXBytes;           // 52 KiB
+constexpr int kRedLdsBytes = 3 * kRedStageBytes;                              // 156 KiB
+
+template <bool ATT>
+__global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int W, int D, int g, int G, int heads,
+                                                              int gpad, int Np, TileWork tw,
+                                                              const bf16* __restrict__ x, const bf16* __restrict__ Wt,
+                                                              const bf16* __restrict__ wmix,
+                                                              const bf16* __restrict__ v1, const bf16* __restrict__ v2,
+                                                              const float* __restrict__ alpha,
+                                                              const bf16* __restrict__ bias, bf16* __restrict__ y,
+                                                              int S, float* __restrict__ ypart) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  int k, b, pt, cs, split;
+  {
+    // position w of the (k, b, patch tile, column slice, split) order; each XCD takes a contiguous range of it
+    const int total = tw.total * S, per = (total + kXcds - 1) / kXcds;
+    const int w = (blockIdx.x % kXcds) * per + blockIdx.x / kXcds;
+    if ((int)(blockIdx.x / kXcds) >= per || w >= total) return;   // uniform: the whole workgroup leaves
+    split = w % S;
+    tw.decode_linear(w / S, k, b, pt, cs);
+  }
+  const int pw = W / 8, N = (H / 8) * pw;
+  const size_t HW = (size_t)H * W;
+  const int n0 = pt * kRedPatches, col_base = cs * kRedCols;
+  // this workgroup's members of the group: the S workgroups of a tile share them out evenly
+  const int gfull = min(g, C - k * g);
+  const int m_lo = split * gfull / S, gk = (split + 1) * gfull / S - m_lo;
+  const int c0 = k * g + m_lo;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lhi = lane >> 5;
+  const int dh = D / heads;
+
+  // ---- issue side: per-lane sources of this wavefront's loads of one member ----
+  const bf16* a_src[2];
+  const bf16* b_src[4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = wave * 16 + i * 8 + (lane >> 3);
+    const int n = min(n0 + row, N - 1);                  // rows past the image repeat its last patch; never stored
+    const int q = (lane & 7) ^ swz_chunk(row);           // logical chunk = pixel row of the patch
+    a_src[i] = x + ((size_t)b * C + c0) * HW + (size_t)((n / pw) * 8 + q) * W + (n % pw) * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = wave * 32 + i * 8 + (lane >> 3);
+    const int q = (lane & 7) ^ swz_chunk(row);
+    b_src[i] = Wt + ((size_t)c0 * D + col_base + row) * 64 + q * 8;
+  }
+  // wavefront w < 4 may also fill the stage's vector slot w (1 KiB = two 512-byte halves, one per half wavefront)
+  const unsigned char* e_src = reinterpret_cast<const unsigned char*>(Wt);   // absent vector: any valid 1 KiB
+  size_t e_step = 0;
+  bool extra = false;
+  {
+    const size_t col_off = ((size_t)c0 * D + col_base + 8 * l32) * 2;
+    const bf16* v = nullptr;
+    if (ATT) {
+      if (wave == 0) { extra = true; v = lhi ? v2 : v1; }
+    } else {
+      if (wave == 0) {
+        extra = true;
+        if (lhi) v = v1;
+        else { e_src = reinterpret_cast<const unsigned char*>(wmix) + (((size_t)k * g + m_lo) * D + col_base + 8 * l32) * 2; e_step = (size_t)D * 2; }
+      } else if (wave == 1) { extra = true; v = v2; }
+    }
+    if (v) { e_src = reinterpret_cast<const unsigned char*>(v) + col_off; e_step = (size_t)D * 2; }
+    if (ATT && (wave == 2 || wave == 3)) {
+      extra = true;
+      const int nhs = dh >= kRedCols ? 1 : kRedCols / dh;
+      const int head = col_base / dh + min(2 * (wave - 2) + lhi, nhs - 1);
+      e_src = reinterpret_cast<const unsigned char*>(alpha + ((((size_t)b * G + k) * gpad + m_lo) * heads + head) * Np +
+                                                     min(n0 + 4 * l32, Np - 4));
+      e_step = (size_t)heads * Np * 4;
+    }
+  }
+  extra = __builtin_amdgcn_readfirstlane(extra);
+  const size_t b_step = (size_t)D * 64;
+  auto issue = [&](int stage) {
+    unsigned char* st = smem + stage * kRedStageBytes;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      load16_to_lds(a_src[i], st + (wave * 2 + i) * 1024);
+      a_src[i] += HW;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      load16_to_lds(b_src[i], st + kRedABytes + (wave * 4 + i) * 1024);
+      b_src[i] += b_step;
+    }
+    if (extra) {
+      load16_to_lds(e_src, st + kRedABytes + kRedBBytes + wave * 1024);
+      e_src += e_step;
+    }
+  };
+
+  // ---- compute side ----
+  const int a_base = (wm * 64 + l32) * 128, b_base = kRedABytes + (wn * 64 + l32) * 128;
+  int ck[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) ck[kk] = ((kk * 2 + lhi) ^ swz_chunk(l32)) * 16;
+  const int xoff = kRedABytes + kRedBBytes;
+  const int colj = (wn * 64 + l32) * 2;                  // byte offset of this lane's first column in a 512-byte vector
+  const int hrel = ATT ? (col_base + wn * 64) / dh - col_base / dh : 0;
+
+  f32x16 o[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[i][j][r] = 0.f;
+  float cst[2] = {0.f, 0.f};                             // ATT = false: patch-independent part sum_c w * (v1 + v2)
+
+  if (gk > 0) issue(0);
+  if (gk > 1) issue(1);
+  int sc = 0, si = 2;
+  for (int m = 0; m < gk; ++m) {
+    // member m has landed (this wavefront's share: at most the loads of member m + 1 stay in flight) ...
+    if (m + 1 < gk) {
+      if (extra) wait_vmcnt<7>();
+      else wait_vmcnt<6>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    // ... and for everyone; all wavefronts are done with member m - 1, whose stage takes member m + 2
+    __builtin_amdgcn_s_barrier();
+    if (m + 2 < gk) issue(si);
+    si = si == 2 ? 0 : si + 1;
+    const unsigned char* st = smem + sc * kRedStageBytes;
+    sc = sc == 2 ? 0 : sc + 1;
+
+    float vb[2];                                         // per-column constant of this member: v1 + v2
+    float wj[2] = {1.f, 1.f};
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const unsigned char* xs = st + xoff + colj + j * 64;
+      float s = 0.f;
+      if (ATT) {
+        if (v1) s += (float)*reinterpret_cast<const bf16*>(xs);
+        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + 512);
+      } else {
+        wj[j] = (float)*reinterpret_cast<const bf16*>(xs);
+        if (v1) s += (float)*reinterpret_cast<const bf16*>(xs + 512);
+        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + 1024);
+      }
+      vb[j] = s;
+    }
+    f32x16 acc[2][2];
+    bf16x8 af[2][2], bf[2][2];                           // [buffer][block]
+#pragma unroll
+    for (int i = 0; i < 2; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(st + a_base + i * 4096 + ck[0]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bf[0][j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[0]);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < 4) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) af[nxt][i] = *reinterpret_cast<const bf16x8*>(st + a_base + i * 4096 + ck[kk + 1]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bf[nxt][j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[kk + 1]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          if (kk == 0) {
+            // the accumulation starts from the member's per-column constant (ATT) or from zero
+            const float c = ATT ? vb[j] : 0.f;
+            const f32x16 init = {c, c, c, c, c, c, c, c, c, c, c, c, c, c, c, c};
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bf[cur][j], init, 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bf[cur][j], acc[i][j], 0, 0, 0);
+          }
+        }
+    }
+    if (ATT) {
+      // rows of accumulator register r: 8 (r / 4) + 4 lhi + r % 4 of the block
+      const float* al = reinterpret_cast<const float*>(st + xoff + 2048 + hrel * 512) + wm * 64 + 4 * lhi;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 a4 = *reinterpret_cast<const f32x4*>(al + i * 32 + 8 * q);
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[i][j][4 * q + e] += a4[e] * acc[i][j][4 * q + e];
+        }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        cst[j] += wj[j] * vb[j];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[i][j][r] += wj[j] * acc[i][j][r];
+      }
+    }
+  }
+
+  const size_t yoff = (((size_t)b * G + k) * N + n0 + wm * 64) * D + col_base + wn * 64 + l32;
+  const int nlim = N - n0 - wm * 64 - 4 * lhi;           // rows of this lane's half that are inside the image
+  if (S > 1) {                                           // partial sum over this workgroup's members; k_vagg_merge adds them up
+    float* pbase = ypart + (size_t)split * tw.nb * G * N * D + yoff;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
+          if (rr < nlim) pbase[(size_t)(rr + 4 * lhi) * D + j * 32] = o[i][j][r] + cst[j];
+        }
+    return;
+  }
+  bf16* ybase = y + yoff;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = col_base + wn * 64 + j * 32 + l32;
+    const float add = cst[j] + (bias ? (float)bias[(size_t)k * D + col] : 0.f);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
+        if (rr < nlim) ybase[(size_t)(rr + 4 * lhi) * D + j * 32] = (bf16)(o[i][j][r] + add);
+      }
+  }
+}
+
 }  // namespace dchag

@@ -468,6 +468,20 @@ def test_forward_linear_first_level_patch_tiles(monkeypatch, narrow):
     _forward_on_sampled_patches(cfg, f"linear first level, narrow={narrow}", 10)
 
 
+@pytest.mark.parametrize("route", ["ring", "registers", "registers_narrow"])
+def test_forward_linear_first_level_of_8x8_patches(monkeypatch, route):
+    """The fused tokenizer + linear first level on 8 x 8 patches: the kernel that streams a member's patches and weights
+    through an LDS ring, and the two that pass them through registers; N = 204 patches (two tiles of 128 or four of 64,
+    the last ragged), two 256-column slices, groups 4 + 4 + 4 + 1."""
+    if route != "ring":
+        monkeypatch.setenv("DCHAG_FIRST_LEVEL_REGS", "1")
+    if route == "registers_narrow":
+        monkeypatch.setenv("DCHAG_MIX_NARROW", "1")
+    cfg = cfg_of(dtype="bf16", B=2, C=13, H=96, W=136, p=8, D=512, heads=8, group_sizes=(4, 4),
+                 level_kinds=("linear", "attention"))
+    _forward_on_sampled_patches(cfg, f"linear first level of 8 x 8 patches, {route}", 30)
+
+
 def _forward_on_sampled_patches(cfg, name, per_batch):
     """The configurations of the benchmark at full size, in the launch configuration the benchmark
     times; the oracle computes a seeded sample of patches (every weight takes part in every patch)."""

@@ -131,6 +131,73 @@ def test_forward_folded_full_size_on_sampled_patches(name, per_batch):
     assert torch.isfinite(out.float()).all()
 
 
+# Shapes whose first level takes its values from the pixels (8 x 8 patches, heads of 64 columns or a multiple).
+PIXEL_VALUES = [
+    # heads of 64: four heads per 256-column slice, two slices; N = 204 (two patch tiles, the second ragged); groups 4 + 4 + 3
+    dict(dtype="bf16", B=2, C=11, H=96, W=136, p=8, D=512, heads=8, group_sizes=(4, 3)),
+    # heads of 256: one head per slice; one flat layer over 3 channels
+    dict(dtype="bf16", B=1, C=3, H=64, W=64, p=8, D=1024, heads=4, group_sizes=(3,)),
+    # heads of 128: two per slice; groups 3 + 3
+    dict(dtype="bf16", B=1, C=6, H=32, W=48, p=8, D=512, heads=4, group_sizes=(3, 2)),
+]
+
+
+@pytest.mark.parametrize("kw", PIXEL_VALUES)
+@pytest.mark.parametrize("route", ["folded_into_tokenizer", "head_sums"])
+def test_forward_folded_first_level_values_from_pixels(monkeypatch, kw, route):
+    """The first attention level of dchag_forward_folded with the value projection folded into the tokenizer weights
+    (one kernel from pixels and softmax weights to the level's pre-projection output), and, on the same shapes, the
+    route through tokens and per-head token averages."""
+    if route == "head_sums":
+        monkeypatch.setenv("DCHAG_VALUE_UNFOLDED", "1")
+    cfg = cfg_of(**kw)
+    say(f"forward_folded pixel values {route} {kw}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    out = dchag.dchag_forward_folded(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
+                                     [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[d]
+
+
+@pytest.mark.parametrize("drop", ["be", "ce", "both"])
+def test_forward_folded_first_level_values_from_pixels_without_token_biases(drop):
+    cfg = cfg_of(**PIXEL_VALUES[0])
+    say(f"forward_folded pixel values without {drop}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    be = None if drop in ("be", "both") else pr.be
+    ce = None if drop in ("ce", "both") else pr.ce
+    out = dchag.dchag_forward_folded(dev(pr.x, d), dev(pr.We, d), dev(be, d), dev(ce, d),
+                                     [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    want = oracle.forward(pr.x, pr.We, be, ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[d]
+
+
+@pytest.mark.parametrize("split", ["1", "3"])
+def test_forward_folded_first_level_values_from_pixels_member_split(monkeypatch, split):
+    """The members of a group in one workgroup per tile, and dealt to three (partial sums merged by a second kernel);
+    by itself the library splits only when the tiles do not fill the chip."""
+    monkeypatch.setenv("DCHAG_FIRST_LEVEL_SPLIT", split)
+    cfg = cfg_of(**PIXEL_VALUES[0])
+    say(f"forward_folded pixel values, members dealt to {split}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    out = dchag.dchag_forward_folded(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
+                                     [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    err = rel_err(host(out), want)
+    say(f"  err={err:.3e}")
+    assert err < TOL[d]
+
+
 def test_forward_folded_without_biases_and_sharp_softmax():
     cfg = get_config("tiny")
     pr = make_problem(cfg, biases=False, query_scale=30.0)
