@@ -392,13 +392,31 @@ inline int attend_ring_forward(int B, int C, int H, int W, int D, int heads, con
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
-    GemmDesc d{};                                                 // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk)
-    d.M = D; d.N = 64; d.K = D; d.nb = 1;
-    d.A = {0, 0, 0, (long)D, 1};
-    d.Bm = {0, 0, 0, 64, 1};
-    d.C = {0, 0, 0, 64, 1};
-    d.scale = 1.f;
-    if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * 64, (long)D * 64, Wv, We, Wf, st))) return rc;
+    // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk): four channels per work item share a 256-row tile of Wv
+    // (DCHAG_FOLD_VALUE_GEMM, a debugging aid, takes the general product kernel, one channel per workgroup)
+    if (aligned16(Wv) && aligned16(We) && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
+      TileWork tw{};
+      tw.n_tiles = (std::min(g, C) + 3) / 4;
+      tw.m_tiles = D / kGemmBM;
+      tw.nb = 1;
+      const long total = (long)G * tw.m_tiles * tw.n_tiles;
+      if (total > (1L << 30)) return DCHAG_ERR_SHAPE;
+      tw.total = (int)total;
+      const int per = (tw.total + kXcds - 1) / kXcds;
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_fold_value_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kGemmRingBytes) != hipSuccess)
+        return DCHAG_ERR_LAUNCH;
+      k_fold_value_dl<<<dim3((unsigned)(per * kXcds)), 512, kGemmRingBytes, st>>>(C, D, g, tw, Wv, We, Wf);
+      if ((rc = launch_status())) return rc;
+    } else {
+      GemmDesc d{};
+      d.M = D; d.N = 64; d.K = D; d.nb = 1;
+      d.A = {0, 0, 0, (long)D, 1};
+      d.Bm = {0, 0, 0, 64, 1};
+      d.C = {0, 0, 0, 64, 1};
+      d.scale = 1.f;
+      if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * 64, (long)D * 64, Wv, We, Wf, st))) return rc;
+    }
     for (int i = 0; i < 2; ++i) {
       if (!tb[i]) continue;
       GemmDesc e{};                                               // (Wv v)[c](o) = sum_d v[c](d) Wv[k](o, d)

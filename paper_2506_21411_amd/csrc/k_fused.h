@@ -722,6 +722,94 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
 }
 
 // ---------------------------------------------------------------------------------------------
+// Value projection folded into the tokenizer weights (weight-only; 64 pixels per patch), on the same core:
+//   Wf[c][o][kk] = sum_d Wv[k][o][d] * We[c][d][kk],   k = c / g.
+// Work item: group k, 256 rows o, four channels of the group (one per wavefront column wn).  The A operand (rows of
+// Wv, contraction index contiguous) goes through the ring as in k_linear_dl; the B stage holds, per channel, the 64
+// rows d of the slice as they lie in memory (128 bytes of kk each), so a B fragment (8 consecutive d of one column
+// kk) is put together from eight 2-byte LDS reads -- the operand is small, the A tile is shared by the four channels,
+// which is what the product's L2 traffic hinges on.  Requires D % 256 == 0.  Dynamic LDS: the ring (128 KiB).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void k_fold_value_dl(int C, int D, int g, TileWork tw, const bf16* __restrict__ Wv,
+                                                       const bf16* __restrict__ We, bf16* __restrict__ Wf) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  int k, b, mt, nt;
+  if (!tw.decode(blockIdx.x, k, b, mt, nt)) return;
+  const int c0 = k * g, gk = min(g, C - c0), q0 = nt * 4;
+  if (q0 >= gk) return;                                  // uniform: a short last group has fewer quads
+  const int r0 = mt * kGemmBM;
+  const int KT = D / kGemmBK;
+  GemmLane L;
+  L.init();
+  const bf16* a_src[4];
+  const bf16* b_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = L.load_row(i);
+    a_src[i] = Wv + ((size_t)k * D + r0 + row) * D + L.load_chunk(row) * 8;
+    const int c = c0 + min(q0 + (row >> 6), gk - 1);     // a missing channel of the quad repeats the last one; not stored
+    b_src[i] = We + ((size_t)c * D + (row & 63)) * 64 + L.load_chunk(row) * 8;
+  }
+  int ki = 0, si = 0;
+  auto issue = [&]() {
+    unsigned char* st = smem + si * kGemmStageBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load16_to_lds(a_src[i] + ki * kGemmBK, st + (L.wave * 4 + i) * 1024);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      load16_to_lds(b_src[i] + (size_t)ki * 64 * 64, st + kGemmBM * 128 + (L.wave * 4 + i) * 1024);
+    si ^= 1;
+    ki = (ki + 1 < KT) ? ki + 1 : ki;                    // past the end: harmless re-load of the last slice
+  };
+  // byte offset, inside a stage's B half, of element (d = 8 lhi + i of a 16-deep k-step, column kk = 32 j + l32) of this
+  // wavefront's channel; the k-step adds 16 rows (2048 bytes, no change of the row's chunk swizzle)
+  int boff[2][8];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = L.wn * 64 + L.lhi * 8 + i, col = j * 32 + L.l32;
+      boff[j][i] = kGemmBM * 128 + row * 128 + (((col >> 3) ^ swz_chunk(row)) * 16) + (col & 7) * 2;
+    }
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  issue();
+  int sc = 0;
+  for (int kt = 0; kt < KT; ++kt) {
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    issue();
+    const unsigned char* st = smem + sc * kGemmStageBytes;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      Frags f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(st + L.a_base + i * 4096 + L.ck[kk]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f.b[j][i] = *reinterpret_cast<const bf16*>(st + boff[j][i] + kk * 2048);
+      mfma_step(acc, f);
+    }
+    sc ^= 1;
+  }
+  wait_vmcnt<0>();                                       // no load may still target LDS when the block retires
+  if (q0 + L.wn >= gk) return;
+  bf16* out = Wf + ((size_t)(c0 + q0 + L.wn) * D + r0 + L.wm * 128 + 4 * L.lhi) * 64 + L.l32;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) out[(size_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * 64 + j * 32] = (bf16)acc[i][j][r];
+}
+
+// ---------------------------------------------------------------------------------------------
 // Level-1 scores straight from the pixels.  The tokenizer is linear, so the score of token
 // t = We[c] u + be[c] + ce[c] against the folded key M[k][a] is
 //   t . M[k][a] = u . (We[c]^T M[k][a]) + (be[c] + ce[c]) . M[k][a]

@@ -143,13 +143,16 @@ PIXEL_VALUES = [
 
 
 @pytest.mark.parametrize("kw", PIXEL_VALUES)
-@pytest.mark.parametrize("route", ["folded_into_tokenizer", "head_sums"])
+@pytest.mark.parametrize("route", ["folded_into_tokenizer", "fold_by_general_product", "head_sums"])
 def test_forward_folded_first_level_values_from_pixels(monkeypatch, kw, route):
     """The first attention level of dchag_forward_folded with the value projection folded into the tokenizer weights
-    (one kernel from pixels and softmax weights to the level's pre-projection output), and, on the same shapes, the
-    route through tokens and per-head token averages."""
+    (one kernel from pixels and softmax weights to the level's pre-projection output; the weight-only fold by its own
+    four-channel kernel or by the general product kernel), and, on the same shapes, the route through tokens and
+    per-head token averages."""
     if route == "head_sums":
         monkeypatch.setenv("DCHAG_VALUE_UNFOLDED", "1")
+    if route == "fold_by_general_product":
+        monkeypatch.setenv("DCHAG_FOLD_VALUE_GEMM", "1")
     cfg = cfg_of(**kw)
     say(f"forward_folded pixel values {route} {kw}")
     pr = make_problem(cfg)
