@@ -55,16 +55,18 @@ inline size_t pixel_scratch(size_t off, int C, int pp, int D, int heads, int G0,
   return off;
 }
 
-// Tokenizer weights with the first level's value projection folded in, Wf [C,D,64], and two folded bias vectors [C,D].
-inline size_t value_fold_bytes(int C, int D) { return align_up((size_t)C * D * 64 * 2) + 2 * align_up((size_t)C * D * 2); }
+// Tokenizer weights with the first level's value projection folded in, Wf [C,D,pp], and two folded bias vectors [C,D].
+inline size_t value_fold_bytes(int C, int D, int pp) {
+  return align_up((size_t)C * D * pp * 2) + 2 * align_up((size_t)C * D * 2);
+}
 
 inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int heads, int n_levels,
                           const int32_t* group_sizes) {
   FoldedWs w{};
   const size_t es = elem_size(dt);
   size_t off = 0;
-  // the tokens, or (bf16, 64 pixels per patch) what replaces them when the first level's values come from the pixels
-  w.tokens = off; off += std::max(align_up((size_t)B * C * N * D * es), dt == DCHAG_BF16 && pp == 64 ? value_fold_bytes(C, D) : 0);
+  // the tokens, or (bf16, 16 or 64 pixels per patch) what replaces them when the first level's values come from the pixels
+  w.tokens = off; off += std::max(align_up((size_t)B * C * N * D * es), dt == DCHAG_BF16 && (pp == 16 || pp == 64) ? value_fold_bytes(C, D, pp) : 0);
   int c_in = C;
   size_t lvl_max = 0, inter_max = 0;
   for (int l = 0; l < n_levels; ++l) {
@@ -371,30 +373,36 @@ template <typename TC>
 int gemm_per_channel(GemmDesc d, int C, int g, long a_grp, long b_ch, long c_ch, const bf16* A, const bf16* Bm, TC* Cm,
                      hipStream_t st);
 
-// First attention level of the inference path with the value projection folded into the tokenizer (bf16, 8 x 8
-// patches): Wf[c] = Wv[k(c)] We[c] and the folded biases Wv be, Wv ce are weight-only products, then one kernel goes
-// from pixels and softmax weights to the pre-projection output o [B,G,N,D]; neither tokens nor per-head token
-// averages exist.  fold: value_fold_bytes(C, D) of scratch.
-inline bool attend_ring_ok(int B, int C, int N, int p, int W, int D, int heads, const void* x, const dchag_level* lv) {
-  const int dh = D / heads;
-  return lv->kind != DCHAG_LEVEL_LINEAR && reduce_ring_ok(p, W, D, x, lv->Wv, nullptr, nullptr, nullptr) &&
-         D % heads == 0 && dh % 64 == 0 && (kRedCols % dh == 0 || dh % kRedCols == 0) && !getenv("DCHAG_VALUE_UNFOLDED");
+// First attention level of the inference path with the value projection folded into the tokenizer (bf16, 4 x 4 or
+// 8 x 8 patches): Wf[c] = Wv[k(c)] We[c] and the folded biases Wv be, Wv ce are weight-only products, then one kernel
+// goes from pixels and softmax weights to the pre-projection output o [B,G,N,D]; neither tokens nor per-head token
+// averages exist.  fold: scratch of fold_bytes >= value_fold_bytes(C, D, p*p); what is left behind the folded weights
+// takes partial sums.  attend_ring_ok: the shape takes the ring kernel; attend_wide_ok: the kernel that passes the
+// operands through registers.
+inline bool attend_wide_ok(int p, int D, int heads, const dchag_level* lv) {
+  const int pp = p * p, dh = D / heads;
+  return lv->kind != DCHAG_LEVEL_LINEAR && (pp == 16 || pp == 64) && D % 256 == 0 && D % heads == 0 && dh % 32 == 0 &&
+         (256 % dh == 0 || dh % 256 == 0) && !getenv("DCHAG_VALUE_UNFOLDED");
 }
-inline int attend_ring_forward(int B, int C, int H, int W, int D, int heads, const dchag_level* lv, const bf16* x,
-                               const bf16* We, const bf16* be, const bf16* ce, const float* alpha, unsigned char* fold,
-                               size_t fold_bytes, bf16* o, hipStream_t st) {
-  const int g = lv->group_size, G = groups_of(C, g);
+inline bool attend_ring_ok(int p, int W, int D, int heads, const void* x, const dchag_level* lv) {
+  return attend_wide_ok(p, D, heads, lv) && reduce_ring_ok(p, W, D, x, nullptr, nullptr, nullptr, nullptr) &&
+         (D / heads) % 64 == 0;
+}
+inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int heads, const dchag_level* lv,
+                                 const bf16* x, const bf16* We, const bf16* be, const bf16* ce, const float* alpha,
+                                 unsigned char* fold, size_t fold_bytes, bf16* o, hipStream_t st) {
+  const int g = lv->group_size, G = groups_of(C, g), pp = p * p, N = (H / p) * (W / p);
   const bf16* Wv = static_cast<const bf16*>(lv->Wv);
+  const size_t wf_bytes = align_up((size_t)C * D * pp * 2), vec_bytes = align_up((size_t)C * D * 2);
   bf16* Wf = reinterpret_cast<bf16*>(fold);
-  bf16* fb[2] = {reinterpret_cast<bf16*>(fold + align_up((size_t)C * D * 64 * 2)),
-                 reinterpret_cast<bf16*>(fold + align_up((size_t)C * D * 64 * 2) + align_up((size_t)C * D * 2))};
+  bf16* fb[2] = {reinterpret_cast<bf16*>(fold + wf_bytes), reinterpret_cast<bf16*>(fold + wf_bytes + vec_bytes)};
   const bf16* tb[2] = {be, ce};
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
-    // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk): four channels per work item share a 256-row tile of Wv
-    // (DCHAG_FOLD_VALUE_GEMM, a debugging aid, takes the general product kernel, one channel per workgroup)
-    if (aligned16(Wv) && aligned16(We) && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
+    // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk).  64 pixels per patch: four channels per work item share a 256-row
+    // tile of Wv (DCHAG_FOLD_VALUE_GEMM, a debugging aid, takes the general product kernel, one channel per workgroup)
+    if (pp == 64 && aligned16(Wv) && aligned16(We) && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
       TileWork tw{};
       tw.n_tiles = (std::min(g, C) + 3) / 4;
       tw.m_tiles = D / kGemmBM;
@@ -410,12 +418,12 @@ inline int attend_ring_forward(int B, int C, int H, int W, int D, int heads, con
       if ((rc = launch_status())) return rc;
     } else {
       GemmDesc d{};
-      d.M = D; d.N = 64; d.K = D; d.nb = 1;
+      d.M = D; d.N = pp; d.K = D; d.nb = 1;
       d.A = {0, 0, 0, (long)D, 1};
-      d.Bm = {0, 0, 0, 64, 1};
-      d.C = {0, 0, 0, 64, 1};
+      d.Bm = {0, 0, 0, (long)pp, 1};
+      d.C = {0, 0, 0, (long)pp, 1};
       d.scale = 1.f;
-      if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * 64, (long)D * 64, Wv, We, Wf, st))) return rc;
+      if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * pp, (long)D * pp, Wv, We, Wf, st))) return rc;
     }
     for (int i = 0; i < 2; ++i) {
       if (!tb[i]) continue;
@@ -430,12 +438,24 @@ inline int attend_ring_forward(int B, int C, int H, int W, int D, int heads, con
     }
   }
   StageTimer tm(DCHAG_STAGE_TOKENIZE_ATTEND, st);
-  // what is left of the scratch behind the folded weights takes partial sums (few groups: members dealt to several
-  // workgroups per tile)
-  const size_t used = value_fold_bytes(C, D);
-  return launch_reduce_ring<true>(B, C, H, W, D, g, heads, x, Wf, nullptr, be ? fb[0] : nullptr, ce ? fb[1] : nullptr,
-                                  alpha, static_cast<const bf16*>(lv->bv), o, st,
-                                  reinterpret_cast<float*>(fold + used), fold_bytes > used ? fold_bytes - used : 0);
+  const bf16* v1 = be ? fb[0] : nullptr;
+  const bf16* v2 = ce ? fb[1] : nullptr;
+  const bf16* bv = static_cast<const bf16*>(lv->bv);
+  if (attend_ring_ok(p, W, D, heads, x, lv)) {
+    const size_t used = wf_bytes + 2 * vec_bytes;
+    return launch_reduce_ring<true>(B, C, H, W, D, g, heads, x, Wf, nullptr, v1, v2, alpha, bv, o, st,
+                                    reinterpret_cast<float*>(fold + used), fold_bytes > used ? fold_bytes - used : 0);
+  }
+  if (B > 65535 || G > 65535) return DCHAG_ERR_SHAPE;
+  const int dh = D / heads, nhs = dh >= 256 ? 1 : 256 / dh;
+  const size_t lds = (size_t)2 * 128 * (pp * 2 + 16) + (size_t)2 * nhs * 512;
+  auto kern = pp == 16 ? k_tokenize_attend_wide<1> : k_tokenize_attend_wide<4>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+      hipSuccess)
+    return DCHAG_ERR_LAUNCH;
+  kern<<<dim3((unsigned)(((N + 127) / 128) * (D / 256)), G, B), 512, lds, st>>>(
+      C, H, W, p, D, g, heads, round_up(g, 8), round_up(N, 32), x, Wf, v1, v2, alpha, bv, o);
+  return launch_status();
 }
 
 template <typename T>
@@ -462,12 +482,12 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   if constexpr (std::is_same<T, bf16>::value) {
     // an attention first level straight from the pixels: scores through the composed score weights, values through
     // the folded tokenizer weights (which sit where the tokens would have been)
-    if (!first && use_px && attend_ring_ok(B, C, N, p, W, D, heads, x, &levels[0])) {
+    if (!first && use_px && attend_wide_ok(p, D, heads, &levels[0])) {
       g_level = 1;
       const KeptLevel kl = kept_level(dt, B, C, N, D, heads, gs[0], false, false);
       const LevelBufs<bf16> lb = level_bufs<bf16>(ws + w.level, kl);
       if ((rc = fast_scores(B, C, N, D, heads, &levels[0], nullptr, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, &px))) return rc;
-      if ((rc = attend_ring_forward(B, C, H, W, D, heads, &levels[0], static_cast<const bf16*>(x),
+      if ((rc = attend_pixels_forward(B, C, H, W, p, D, heads, &levels[0], static_cast<const bf16*>(x),
                                     static_cast<const bf16*>(We), static_cast<const bf16*>(be),
                                     static_cast<const bf16*>(ce), lb.alpha_f, ws + w.tokens, w.ping - w.tokens, lb.o,
                                     st)))

@@ -1686,6 +1686,134 @@ __global__ __launch_bounds__(512) void k_tokenize_mix_wide(int C, int H, int W, 
     }
 }
 
+// The attention form of k_tokenize_mix_wide (cross-attention first level with the value projection folded into the
+// tokenizer weights: Wf[c] = Wv[k] We[c], v1 = Wv be, v2 = Wv ce), for the shapes the ring kernel below does not take
+// (16 pixels per patch, heads of 32 columns, unaligned images):
+//   y[b,k,n,d] = sum_{cl < gk} alpha[b][k][cl][head(d)][n] * (Wf[c] u[b,c,n] + v1[c] + v2[c])[d] + bias[k][d].
+// The member's constant enters as the MFMA's C operand; its softmax weights (NHS heads x 128 patches, fp32) travel with
+// the patches through registers into LDS.  Requires (D / heads) % 32 == 0 and 256 % dh == 0 or dh % 256 == 0.
+// Dynamic LDS: 2 * 128 * (p*p*2 + 16) + 2 * NHS * 512 bytes.
+template <int KSS>
+__global__ __launch_bounds__(512) void k_tokenize_attend_wide(int C, int H, int W, int p, int D, int g, int heads,
+                                                              int gpad, int Np, const bf16* __restrict__ x,
+                                                              const bf16* __restrict__ Wf, const bf16* __restrict__ v1,
+                                                              const bf16* __restrict__ v2,
+                                                              const float* __restrict__ alpha,
+                                                              const bf16* __restrict__ bias, bf16* __restrict__ y) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int pp = 16 * KSS, pieces = pp / 4;
+  constexpr int rbp = pp * 2 + 16;
+  constexpr int PB = 128;                                // patches per workgroup
+  constexpr int NG = (PB * pieces + 511) / 512;          // 8-byte pieces a thread gathers per member
+  const int pw = W / p, N = (H / p) * pw;
+  const int ns_n = D / 256;
+  const int n0 = (blockIdx.x / ns_n) * PB, col_base = (blockIdx.x % ns_n) * 256;
+  const int k = blockIdx.y, b = blockIdx.z, G = gridDim.y;
+  const int c0 = k * g, gk = min(g, C - c0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int d0 = col_base + wave * 32 + l32;             // this lane's column
+  const int dh = D / heads, nhs = dh >= 256 ? 1 : 256 / dh, h0 = col_base / dh;
+  const int hrel = (col_base + wave * 32) / dh - h0;     // the wavefront's 32 columns lie in one head
+  unsigned char* alds = smem + 2 * PB * rbp;             // [2][nhs][128] floats
+
+  bf16x4 gv[NG];
+  bf16x8 bfrag[KSS];
+  f32x4 av = {0.f, 0.f, 0.f, 0.f};
+  float a0;
+  int goff[NG];
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    const int idx = tid + 512 * i;
+    const int t = idx / pieces, q = idx % pieces;
+    const int r = (q * 4) / p, s0 = (q * 4) % p;
+    const int n = n0 + t;
+    goff[i] = (idx < PB * pieces && n < N) ? ((n / pw) * p + r) * W + (n % pw) * p + s0 : -1;
+  }
+  // thread t < 32 nhs fetches the weights of head h0 + t / 32 for patches n0 + 4 (t % 32) .. + 3
+  const float* asrc = alpha + ((((size_t)b * G + k) * gpad) * heads + h0 + min(tid >> 5, nhs - 1)) * Np +
+                      min(n0 + 4 * (tid & 31), Np - 4);
+  auto fetch = [&](int cl) {
+    const int c = c0 + cl;
+    const bf16* img = x + ((size_t)b * C + c) * H * W;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      gv[i] = bf16x4{};
+      if (goff[i] >= 0) gv[i] = *reinterpret_cast<const bf16x4*>(img + goff[i]);
+    }
+    const bf16* wrow = Wf + ((size_t)c * D + d0) * pp + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk) bfrag[kk] = *reinterpret_cast<const bf16x8*>(wrow + kk * 16);
+    a0 = 0.f;
+    if (v1) a0 += (float)v1[(size_t)c * D + d0];
+    if (v2) a0 += (float)v2[(size_t)c * D + d0];
+    if (tid < 32 * nhs) av = *reinterpret_cast<const f32x4*>(asrc + (size_t)cl * heads * Np);
+  };
+  auto stash = [&](int buf) {
+    unsigned char* u = smem + buf * PB * rbp;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      const int idx = tid + 512 * i;
+      if (idx < PB * pieces) *reinterpret_cast<bf16x4*>(u + (idx / pieces) * rbp + (idx % pieces) * 8) = gv[i];
+    }
+    if (tid < 32 * nhs) *reinterpret_cast<f32x4*>(alds + buf * nhs * 512 + tid * 16) = av;
+  };
+
+  f32x16 o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int cl = 0; cl < gk; ++cl) {
+    const unsigned char* u = smem + (cl & 1) * PB * rbp;
+    const float* al = reinterpret_cast<const float*>(alds + (cl & 1) * nhs * 512 + hrel * 512) + 4 * lhi;
+    bf16x8 bcur[KSS];
+#pragma unroll
+    for (int kk = 0; kk < KSS; ++kk) bcur[kk] = bfrag[kk];
+    const float cb = a0;
+    if (cl + 1 < gk) fetch(cl + 1);
+    const f32x16 init = {cb, cb, cb, cb, cb, cb, cb, cb, cb, cb, cb, cb, cb, cb, cb, cb};
+#pragma unroll
+    for (int i = 0; i < 4; i += 2) {
+      f32x16 acc0 = init, acc1 = init;                   // two independent chains: row blocks i and i + 1
+#pragma unroll
+      for (int kk = 0; kk < KSS; ++kk) {
+        const bf16x8 af0 = *reinterpret_cast<const bf16x8*>(u + (i * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+        const bf16x8 af1 = *reinterpret_cast<const bf16x8*>(u + ((i + 1) * 32 + l32) * rbp + (kk * 2 + lhi) * 16);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0, bcur[kk], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1, bcur[kk], acc1, 0, 0, 0);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 w0 = *reinterpret_cast<const f32x4*>(al + i * 32 + 8 * q);
+        const f32x4 w1 = *reinterpret_cast<const f32x4*>(al + (i + 1) * 32 + 8 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          o[i][4 * q + e] += w0[e] * acc0[4 * q + e];
+          o[i + 1][4 * q + e] += w1[e] * acc1[4 * q + e];
+        }
+      }
+    }
+    if (cl + 1 < gk) stash((cl + 1) & 1);
+    __syncthreads();
+  }
+  const float add = bias ? (float)bias[(size_t)k * D + d0] : 0.f;
+  bf16* ybase = y + (((size_t)b * G + k) * N + n0) * D;
+  const int lane_off = 4 * lhi * D + d0;
+  const int nlim = N - n0 - 4 * lhi;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
+      if (rr < nlim) ybase[(size_t)rr * D + lane_off] = (bf16)(o[i][r] + add);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Tokenizer fused with the first aggregation level, operands streamed through a three-stage LDS ring
 // (8 x 8 patches only: a patch and a weight row are both one 128-byte LDS row).  Two forms:
