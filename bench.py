@@ -346,6 +346,11 @@ def main() -> int:
         ms2, _, _ = timed(c2, t2, 3, 10, profile=False)
         other.append({"workload": "weather", "tokens": c2.tokens, "ms_per_step": round(ms2, 4),
                       "value": c2.tokens / (ms2 * 1e-3), "unit": "tokens/s"})
+        mode["name"] = "folded"
+        ms2f, _, _ = timed(c2, t2, 3, 10, profile=False)
+        other.append({"workload": "weather", "call": "dchag_forward_folded", "tokens": c2.tokens,
+                      "ms_per_step": round(ms2f, 4), "value": c2.tokens / (ms2f * 1e-3), "unit": "tokens/s"})
+        mode["name"] = "forward"
         del t2
         torch.cuda.empty_cache()
         # the same hyperspectral shape with a linear first level (D-CHAG-L), cross-attention at the top, and as

@@ -162,7 +162,17 @@ int dchag_forward_pos(dchag_dtype dt, int B, int C, int H, int W, int p, int D, 
  * per (group, patch, head) instead of once per member -- g*D*D multiply-adds per group and patch
  * become D*D + g*heads*D.  The paper states the layer as plain cross-attention (Section 2.1); this
  * is the same function evaluated in another order, kept as a call of its own so that the as-defined
- * path stays measurable.  workspace: dchag_workspace_bytes(..., which = 2).
+ * path stays measurable.
+ * At the first level the tokens are themselves linear in the pixels (Section 2.1: z[c] = We[c] u[c] + be[c] +
+ * ce[c] for the patch u[c]), so there the projection moves one step further, into the tokenizer:
+ *
+ *   o_a = sum_c alpha[c,a] ( (Wv We[c]) u[c] + Wv (be[c] + ce[c]) )_a + bv_a .
+ *
+ * For bf16 inputs with 4 x 4 or 8 x 8 patches, D a multiple of 256 and heads of 32 columns or a multiple (and the
+ * shapes whose scores come from the pixels: a multiple of 4 heads, at most 32) the call forms the weight-only
+ * products Wv We[c], Wv be, Wv ce first and then goes from pixels and softmax weights to o in one kernel; the
+ * per-channel tokens and the per-head averages u_a of that level never exist.  Other shapes, fp32 and the upper
+ * levels take the u_a route.  workspace: dchag_workspace_bytes(..., which = 2).
  */
 int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
                          const void *x, const void *We, const void *be, const void *ce,
@@ -213,8 +223,10 @@ int dchag_backward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int
  * level its inputs, folded keys, softmax weights, per-head token averages, pre-projection outputs), and
  * dchag_backward_kept is the reverse sweep alone.  dchag_backward_kept must be given the same arguments and the
  * workspace of the dchag_forward_keep call, untouched in between (the library cannot check that); any number of
- * dchag_backward_kept calls (different dout) may follow one dchag_forward_keep.  Results equal those of
- * dchag_forward_folded and dchag_backward bit for bit.  For callers that keep activations between the two passes,
+ * dchag_backward_kept calls (different dout) may follow one dchag_forward_keep.  The gradients equal those of
+ * dchag_backward bit for bit; the output equals dchag_forward_folded's bit for bit wherever that call takes the
+ * u_a route at the first level, and up to rounding where it folds the projection into the tokenizer (the kept
+ * forward always forms tokens and u_a: the reverse sweep reads them).  For callers that keep activations between the two passes,
  * as training loops do; the paper describes the two passes of its module (Section 3.3), not how they share state.
  */
 int dchag_forward_keep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,

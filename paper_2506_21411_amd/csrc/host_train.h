@@ -395,8 +395,7 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
   const bf16* Wv = static_cast<const bf16*>(lv->Wv);
   const size_t wf_bytes = align_up((size_t)C * D * pp * 2), vec_bytes = align_up((size_t)C * D * 2);
   bf16* Wf = reinterpret_cast<bf16*>(fold);
-  bf16* fb[2] = {reinterpret_cast<bf16*>(fold + wf_bytes), reinterpret_cast<bf16*>(fold + wf_bytes + vec_bytes)};
-  const bf16* tb[2] = {be, ce};
+  bf16* fb[1] = {reinterpret_cast<bf16*>(fold + wf_bytes)};
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
@@ -425,21 +424,25 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
       d.scale = 1.f;
       if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * pp, (long)D * pp, Wv, We, Wf, st))) return rc;
     }
-    for (int i = 0; i < 2; ++i) {
-      if (!tb[i]) continue;
-      GemmDesc e{};                                               // (Wv v)[c](o) = sum_d v[c](d) Wv[k](o, d)
-      e.M = g; e.N = D; e.K = D; e.nb = 1; e.nk = G; e.na = 1;
+    if (be || ce) {
+      // (Wv (be + ce))[c](o) = sum over the vectors v present, sum_d v[c](d) Wv[k](o, d): one product whose batch
+      // index walks from be to ce and is summed over
+      const bf16* first = be ? be : ce;
+      GemmDesc e{};
+      e.M = g; e.N = D; e.K = D; e.nk = G; e.na = 1;
+      e.nb = be && ce ? 2 : 1;
+      e.reduce_b = 1;
       e.ragged = 1; e.ragged_total = C; e.ragged_nominal = g;
-      e.A = {0, (long)g * D, 0, (long)D, 1};
+      e.A = {be && ce ? (long)(ce - be) : 0, (long)g * D, 0, (long)D, 1};
       e.Bm = {0, (long)D * D, 0, 1, (long)D};
       e.C = {0, (long)g * D, 0, (long)D, 1};
       e.scale = 1.f;
-      if ((rc = launch_gemm_bf16<bf16>(e, tb[i], Wv, nullptr, fb[i], st))) return rc;
+      if ((rc = launch_gemm_bf16<bf16>(e, first, Wv, nullptr, fb[0], st))) return rc;
     }
   }
   StageTimer tm(DCHAG_STAGE_TOKENIZE_ATTEND, st);
-  const bf16* v1 = be ? fb[0] : nullptr;
-  const bf16* v2 = ce ? fb[1] : nullptr;
+  const bf16* v1 = be || ce ? fb[0] : nullptr;
+  const bf16* v2 = nullptr;
   const bf16* bv = static_cast<const bf16*>(lv->bv);
   if (attend_ring_ok(p, W, D, heads, x, lv)) {
     const size_t used = wf_bytes + 2 * vec_bytes;
