@@ -426,14 +426,18 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
     }
     if (be || ce) {
       // (Wv (be + ce))[c](o) = sum over the vectors v present, sum_d v[c](d) Wv[k](o, d): one product whose batch
-      // index walks from be to ce and is summed over
+      // index walks from be to ce (their distance in elements, taken on the integer addresses: the two are separate
+      // allocations in one flat device address space) and is summed over
       const bf16* first = be ? be : ce;
+      const long be_to_ce = be && ce ? (long)((reinterpret_cast<intptr_t>(ce) - reinterpret_cast<intptr_t>(be)) /
+                                              (intptr_t)sizeof(bf16))
+                                     : 0;
       GemmDesc e{};
       e.M = g; e.N = D; e.K = D; e.nk = G; e.na = 1;
       e.nb = be && ce ? 2 : 1;
       e.reduce_b = 1;
       e.ragged = 1; e.ragged_total = C; e.ragged_nominal = g;
-      e.A = {be && ce ? (long)(ce - be) : 0, (long)g * D, 0, (long)D, 1};
+      e.A = {be_to_ce, (long)g * D, 0, (long)D, 1};
       e.Bm = {0, (long)D * D, 0, 1, (long)D};
       e.C = {0, (long)g * D, 0, (long)D, 1};
       e.scale = 1.f;
