@@ -1984,40 +1984,35 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
       }
       vb[j] = s;
     }
+    // Row block i = 0 first, then i = 1: while the matrix pipe works on the second block the vector ALUs scale the
+    // first into the running sum (the two instruction streams are interleaved below, one MFMA per four FMAs).
     f32x16 acc[2][2];
-    bf16x8 af[2][2], bf[2][2];                           // [buffer][block]
-#pragma unroll
-    for (int i = 0; i < 2; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(st + a_base + i * 4096 + ck[0]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) bf[0][j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[0]);
+    bf16x8 bfr[4][2], af[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk + 1 < 4) {
+      af[kk] = *reinterpret_cast<const bf16x8*>(st + a_base + ck[kk]);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) af[nxt][i] = *reinterpret_cast<const bf16x8*>(st + a_base + i * 4096 + ck[kk + 1]);
+      for (int j = 0; j < 2; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[kk]);
+    }
+    const float* al = reinterpret_cast<const float*>(st + xoff + 2048 + hrel * 512) + wm * 64 + 4 * lhi;
+    auto product = [&](int i) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) bf[nxt][j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[kk + 1]);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           if (kk == 0) {
             // the accumulation starts from the member's per-column constant (ATT) or from zero
             const float c = ATT ? vb[j] : 0.f;
             const f32x16 init = {c, c, c, c, c, c, c, c, c, c, c, c, c, c, c, c};
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bf[cur][j], init, 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk], bfr[kk][j], init, 0, 0, 0);
           } else {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bf[cur][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk], bfr[kk][j], acc[i][j], 0, 0, 0);
           }
         }
-    }
-    if (ATT) {
-      // rows of accumulator register r: 8 (r / 4) + 4 lhi + r % 4 of the block
-      const float* al = reinterpret_cast<const float*>(st + xoff + 2048 + hrel * 512) + wm * 64 + 4 * lhi;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
+    };
+    auto scale_in = [&](int i) {
+      if (ATT) {
+        // rows of accumulator register r: 8 (r / 4) + 4 lhi + r % 4 of the block
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const f32x4 a4 = *reinterpret_cast<const f32x4*>(al + i * 32 + 8 * q);
@@ -2026,15 +2021,29 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[i][j][4 * q + e] += a4[e] * acc[i][j][4 * q + e];
         }
-    } else {
+      } else {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        cst[j] += wj[j] * vb[j];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[i][j][r] += wj[j] * acc[i][j][r];
       }
+    };
+    product(0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) af[kk] = *reinterpret_cast<const bf16x8*>(st + a_base + 4096 + ck[kk]);
+    __builtin_amdgcn_sched_barrier(0);
+    product(1);
+    scale_in(0);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // four vector-ALU instructions
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    scale_in(1);
+    if (!ATT) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) cst[j] += wj[j] * vb[j];
     }
   }
 
