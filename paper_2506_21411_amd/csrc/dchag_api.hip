@@ -597,15 +597,14 @@ inline bool reduce_ring_ok(int p, int W, int D, const void* x, const void* Wt, c
   return p == 8 && W % 8 == 0 && D % 256 == 0 && aligned16(x) && aligned16(Wt) && aligned16(v0) && aligned16(v1) &&
          aligned16(v2) && !getenv("DCHAG_FIRST_LEVEL_REGS");
 }
-// part / part_bytes: optional fp32 scratch for partial sums; with it, and too few tiles to give every compute unit two
-// workgroups, a group's members are dealt to up to 16 workgroups per tile (DCHAG_FIRST_LEVEL_SPLIT overrides the count).
-template <bool ATT>
-int launch_reduce_ring(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
-                       const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias, bf16* y,
-                       hipStream_t st, float* part = nullptr, size_t part_bytes = 0) {
+template <bool ATT, int WN>
+int launch_reduce_ring_cols(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
+                            const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias,
+                            bf16* y, hipStream_t st, float* part, size_t part_bytes) {
+  typedef RedCfg<WN> Cfg;
   const int N = (H / 8) * (W / 8), G = groups_of(C, g);
   TileWork tw{};
-  tw.n_tiles = D / kRedCols;
+  tw.n_tiles = D / Cfg::kCols;
   tw.m_tiles = (N + kRedPatches - 1) / kRedPatches;
   tw.nb = B;
   const long total = (long)G * B * tw.m_tiles * tw.n_tiles;
@@ -613,21 +612,37 @@ int launch_reduce_ring(int B, int C, int H, int W, int D, int g, int heads, cons
   tw.total = (int)total;
   const size_t per_split = (size_t)B * G * N * D;
   const int gmin = std::min(g, C - (G - 1) * g);                  // members of the shortest group
+  const long fill = (WN == 4 ? 2L : 4L) * compute_units();        // workgroups that give every compute unit two rounds
   int S = 1;
-  while (total * S < 2L * compute_units() && 2 * S <= std::min(16, gmin)) S *= 2;
+  while (total * S < fill && 2 * S <= std::min(16, gmin)) S *= 2;
   if (const char* e = getenv("DCHAG_FIRST_LEVEL_SPLIT")) S = std::max(1, std::min(std::min(16, gmin), atoi(e)));
   while (S > 1 && (!part || (size_t)S * per_split * 4 > part_bytes)) S >>= 1;
   const int per = (int)((total * S + kXcds - 1) / kXcds);
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_reduce_ring<ATT>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kRedLdsBytes) != hipSuccess)
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_reduce_ring<ATT, WN>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes) != hipSuccess)
     return DCHAG_ERR_LAUNCH;
-  k_tokenize_reduce_ring<ATT><<<dim3((unsigned)(per * kXcds)), 512, kRedLdsBytes, st>>>(
+  k_tokenize_reduce_ring<ATT, WN><<<dim3((unsigned)(per * kXcds)), Cfg::kThreads, Cfg::kLdsBytes, st>>>(
       C, H, W, D, g, G, heads, round_up(g, 8), round_up(N, 32), tw, x, Wt, wmix, v1, v2, alpha, bias, y, S, part);
   int rc = launch_status();
   if (rc || S == 1) return rc;
   const long quads = (long)per_split / 4;
   k_vagg_merge<<<dim3((unsigned)((quads + 255) / 256)), 256, 0, st>>>(quads, S, G, N, D, (long)per_split, part, bias, y);
   return launch_status();
+}
+
+// part / part_bytes: optional fp32 scratch for partial sums; with it, and too few tiles to give every compute unit two
+// rounds of workgroups, a group's members are dealt to up to 16 workgroups per tile (DCHAG_FIRST_LEVEL_SPLIT overrides
+// the count).  Workgroups of 128 columns, two per compute unit (DCHAG_RING_COLS = 256: one of 256 columns).
+template <bool ATT>
+int launch_reduce_ring(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
+                       const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias, bf16* y,
+                       hipStream_t st, float* part = nullptr, size_t part_bytes = 0) {
+  const char* e = getenv("DCHAG_RING_COLS");
+  if (e && atoi(e) == 256)
+    return launch_reduce_ring_cols<ATT, 4>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
+                                           part_bytes);
+  return launch_reduce_ring_cols<ATT, 2>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
+                                         part_bytes);
 }
 
 int tokenize_mix_forward(int B, int C, int H, int W, int p, int D, const void* x, const void* We, const void* be,

@@ -1834,20 +1834,26 @@ __global__ __launch_bounds__(512) void k_tokenize_attend_wide(int C, int H, int 
 // Requires D % 256 == 0, W % 8 == 0, 16-byte aligned x; ATT: (D / heads) % 64 == 0 and 256 % dh == 0 or dh % 256 == 0.
 // Dynamic LDS: kRedLdsBytes.
 // ---------------------------------------------------------------------------------------------
-constexpr int kRedPatches = 128, kRedCols = 256;
-constexpr int kRedABytes = kRedPatches * 128, kRedBBytes = kRedCols * 128, kRedXBytes = 4096;
-constexpr int kRedStageBytes = kRedABytes + kRedBBytes + kRedXBytes;           // 52 KiB
-constexpr int kRedLdsBytes = 3 * kRedStageBytes;                              // 156 KiB
+constexpr int kRedPatches = 128;
+template <int WN>
+struct RedCfg {                                            // WN wavefront columns of 64: 256 or 128 columns per workgroup
+  static constexpr int kWaves = 2 * WN, kThreads = kWaves * 64, kCols = WN * 64;
+  static constexpr int kABytes = kRedPatches * 128, kBBytes = kCols * 128, kXBytes = 4096;
+  static constexpr int kStageBytes = kABytes + kBBytes + kXBytes;           // 52 or 36 KiB
+  static constexpr int kStages = WN == 4 ? 3 : 2;                           // one workgroup per compute unit, or two
+  static constexpr int kLdsBytes = kStages * kStageBytes;                   // 156 or 72 KiB
+};
 
-template <bool ATT>
-__global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int W, int D, int g, int G, int heads,
-                                                              int gpad, int Np, TileWork tw,
-                                                              const bf16* __restrict__ x, const bf16* __restrict__ Wt,
-                                                              const bf16* __restrict__ wmix,
-                                                              const bf16* __restrict__ v1, const bf16* __restrict__ v2,
-                                                              const float* __restrict__ alpha,
-                                                              const bf16* __restrict__ bias, bf16* __restrict__ y,
-                                                              int S, float* __restrict__ ypart) {
+template <bool ATT, int WN>
+__global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduce_ring(
+    int C, int H, int W, int D, int g, int G, int heads, int gpad, int Np, TileWork tw, const bf16* __restrict__ x,
+    const bf16* __restrict__ Wt, const bf16* __restrict__ wmix, const bf16* __restrict__ v1,
+    const bf16* __restrict__ v2, const float* __restrict__ alpha, const bf16* __restrict__ bias, bf16* __restrict__ y,
+    int S, float* __restrict__ ypart) {
+  typedef RedCfg<WN> Cfg;
+  constexpr int kRedCols = Cfg::kCols, kRedABytes = Cfg::kABytes, kRedBBytes = Cfg::kBBytes;
+  constexpr int kRedStageBytes = Cfg::kStageBytes, NS = Cfg::kStages;
+  constexpr int AL = 16 / Cfg::kWaves;                   // A loads per wavefront and member
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   int k, b, pt, cs, split;
   {
@@ -1867,15 +1873,15 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
   const int c0 = k * g + m_lo;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lhi = lane >> 5;
+  const int wm = wave / WN, wn = wave % WN, l32 = lane & 31, lhi = lane >> 5;
   const int dh = D / heads;
 
   // ---- issue side: per-lane sources of this wavefront's loads of one member ----
-  const bf16* a_src[2];
+  const bf16* a_src[AL];
   const bf16* b_src[4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int row = wave * 16 + i * 8 + (lane >> 3);
+  for (int i = 0; i < AL; ++i) {
+    const int row = wave * (AL * 8) + i * 8 + (lane >> 3);
     const int n = min(n0 + row, N - 1);                  // rows past the image repeat its last patch; never stored
     const int q = (lane & 7) ^ swz_chunk(row);           // logical chunk = pixel row of the patch
     a_src[i] = x + ((size_t)b * C + c0) * HW + (size_t)((n / pw) * 8 + q) * W + (n % pw) * 8;
@@ -1886,39 +1892,41 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
     const int q = (lane & 7) ^ swz_chunk(row);
     b_src[i] = Wt + ((size_t)c0 * D + col_base + row) * 64 + q * 8;
   }
-  // wavefront w < 4 may also fill the stage's vector slot w (1 KiB = two 512-byte halves, one per half wavefront)
-  const unsigned char* e_src = reinterpret_cast<const unsigned char*>(Wt);   // absent vector: any valid 1 KiB
+  // The stage's 4 KiB of vectors: four per-column vectors of kCols bf16 each (ATT: v1, v2, -, -; else wmix, v1, v2, -)
+  // in the first 2 KiB, filled by the first wavefront(s), 64 / (kCols / 8) vectors per load; behind them the softmax
+  // weights of the slice's heads (512 bytes each: 128 patches), two heads per load of the next wavefront(s).
+  constexpr int LPV = kRedCols / 8, VPI = 64 / LPV, NVW = 4 / VPI;
+  const unsigned char* e_src = reinterpret_cast<const unsigned char*>(Wt);   // absent vector: any valid 16 bytes
   size_t e_step = 0;
   bool extra = false;
-  {
-    const size_t col_off = ((size_t)c0 * D + col_base + 8 * l32) * 2;
-    const bf16* v = nullptr;
-    if (ATT) {
-      if (wave == 0) { extra = true; v = lhi ? v2 : v1; }
-    } else {
-      if (wave == 0) {
-        extra = true;
-        if (lhi) v = v1;
-        else { e_src = reinterpret_cast<const unsigned char*>(wmix) + (((size_t)k * g + m_lo) * D + col_base + 8 * l32) * 2; e_step = (size_t)D * 2; }
-      } else if (wave == 1) { extra = true; v = v2; }
+  int e_slot = 0;
+  if (wave < NVW && (!ATT || wave == 0)) {
+    extra = true;
+    e_slot = wave * 1024;
+    const int vi = wave * VPI + lane / LPV, lv = lane % LPV;
+    const bf16* v = ATT ? (vi == 0 ? v1 : (vi == 1 ? v2 : nullptr)) : (vi == 0 ? wmix : (vi == 1 ? v1 : (vi == 2 ? v2 : nullptr)));
+    if (v) {
+      const size_t row0 = (!ATT && vi == 0) ? (size_t)k * g + m_lo : (size_t)c0;
+      e_src = reinterpret_cast<const unsigned char*>(v + row0 * D + col_base + 8 * lv);
+      e_step = (size_t)D * 2;
     }
-    if (v) { e_src = reinterpret_cast<const unsigned char*>(v) + col_off; e_step = (size_t)D * 2; }
-    if (ATT && (wave == 2 || wave == 3)) {
-      extra = true;
-      const int nhs = dh >= kRedCols ? 1 : kRedCols / dh;
-      const int head = col_base / dh + min(2 * (wave - 2) + lhi, nhs - 1);
-      e_src = reinterpret_cast<const unsigned char*>(alpha + ((((size_t)b * G + k) * gpad + m_lo) * heads + head) * Np +
-                                                     min(n0 + 4 * l32, Np - 4));
-      e_step = (size_t)heads * Np * 4;
-    }
+  } else if (ATT && wave >= NVW && wave < NVW + WN / 2) {
+    extra = true;
+    e_slot = 2048 + (wave - NVW) * 1024;
+    const int nhs = dh >= kRedCols ? 1 : kRedCols / dh;
+    const int head = col_base / dh + min(2 * (wave - NVW) + lhi, nhs - 1);
+    e_src = reinterpret_cast<const unsigned char*>(alpha + ((((size_t)b * G + k) * gpad + m_lo) * heads + head) * Np +
+                                                   min(n0 + 4 * l32, Np - 4));
+    e_step = (size_t)heads * Np * 4;
   }
   extra = __builtin_amdgcn_readfirstlane(extra);
+  e_slot = __builtin_amdgcn_readfirstlane(e_slot);
   const size_t b_step = (size_t)D * 64;
   auto issue = [&](int stage) {
     unsigned char* st = smem + stage * kRedStageBytes;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      load16_to_lds(a_src[i], st + (wave * 2 + i) * 1024);
+    for (int i = 0; i < AL; ++i) {
+      load16_to_lds(a_src[i], st + (wave * AL + i) * 1024);
       a_src[i] += HW;
     }
 #pragma unroll
@@ -1927,7 +1935,7 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
       b_src[i] += b_step;
     }
     if (extra) {
-      load16_to_lds(e_src, st + kRedABytes + kRedBBytes + wave * 1024);
+      load16_to_lds(e_src, st + kRedABytes + kRedBBytes + e_slot);
       e_src += e_step;
     }
   };
@@ -1938,7 +1946,8 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) ck[kk] = ((kk * 2 + lhi) ^ swz_chunk(l32)) * 16;
   const int xoff = kRedABytes + kRedBBytes;
-  const int colj = (wn * 64 + l32) * 2;                  // byte offset of this lane's first column in a 512-byte vector
+  constexpr int VB = kRedCols * 2;                       // bytes of one per-column vector
+  const int colj = (wn * 64 + l32) * 2;                  // byte offset of this lane's first column in a vector
   const int hrel = ATT ? (col_base + wn * 64) / dh - col_base / dh : 0;
 
   f32x16 o[2][2];
@@ -1950,23 +1959,24 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
       for (int r = 0; r < 16; ++r) o[i][j][r] = 0.f;
   float cst[2] = {0.f, 0.f};                             // ATT = false: patch-independent part sum_c w * (v1 + v2)
 
-  if (gk > 0) issue(0);
-  if (gk > 1) issue(1);
-  int sc = 0, si = 2;
+#pragma unroll
+  for (int s0 = 0; s0 < NS - 1; ++s0)
+    if (gk > s0) issue(s0);
+  int sc = 0, si = NS - 1;
   for (int m = 0; m < gk; ++m) {
-    // member m has landed (this wavefront's share: at most the loads of member m + 1 stay in flight) ...
-    if (m + 1 < gk) {
-      if (extra) wait_vmcnt<7>();
-      else wait_vmcnt<6>();
+    // member m has landed (this wavefront's share: with three stages the loads of member m + 1 may stay in flight) ...
+    if (NS == 3 && m + 1 < gk) {
+      if (extra) wait_vmcnt<AL + 5>();
+      else wait_vmcnt<AL + 4>();
     } else {
       wait_vmcnt<0>();
     }
-    // ... and for everyone; all wavefronts are done with member m - 1, whose stage takes member m + 2
+    // ... and for everyone; all wavefronts are done with member m - 1, whose stage takes member m + NS - 1
     __builtin_amdgcn_s_barrier();
-    if (m + 2 < gk) issue(si);
-    si = si == 2 ? 0 : si + 1;
+    if (m + NS - 1 < gk) issue(si);
+    si = si == NS - 1 ? 0 : si + 1;
     const unsigned char* st = smem + sc * kRedStageBytes;
-    sc = sc == 2 ? 0 : sc + 1;
+    sc = sc == NS - 1 ? 0 : sc + 1;
 
     float vb[2];                                         // per-column constant of this member: v1 + v2
     float wj[2] = {1.f, 1.f};
@@ -1976,11 +1986,11 @@ __global__ __launch_bounds__(512) void k_tokenize_reduce_ring(int C, int H, int 
       float s = 0.f;
       if (ATT) {
         if (v1) s += (float)*reinterpret_cast<const bf16*>(xs);
-        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + 512);
+        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + VB);
       } else {
         wj[j] = (float)*reinterpret_cast<const bf16*>(xs);
-        if (v1) s += (float)*reinterpret_cast<const bf16*>(xs + 512);
-        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + 1024);
+        if (v1) s += (float)*reinterpret_cast<const bf16*>(xs + VB);
+        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + 2 * VB);
       }
       vb[j] = s;
     }
