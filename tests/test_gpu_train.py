@@ -330,10 +330,10 @@ def test_backward_linear_first_level_through_the_tokens_still_matches(monkeypatc
 
 
 @pytest.mark.parametrize("kw", [SMALL[0], SMALL[3], SMALL[4], SMALL[10], SMALL[13]])
-def test_forward_keep_and_backward_kept_equal_the_recomputing_calls(kw):
-    """A training step that keeps its activations: the output equals dchag_forward_folded's and every gradient
-    equals dchag_backward's bit for bit (same kernels on the same buffers), for two upstream gradients in a row
-    after one forward."""
+def test_forward_keep_and_backward_kept_equal_the_recomputing_calls(monkeypatch, kw):
+    """A training step that keeps its activations: the output equals dchag_forward_folded's (on its route through the
+    tokens at the first level, which the kept forward always takes) and every gradient equals dchag_backward's bit for
+    bit (same kernels on the same buffers), for two upstream gradients in a row after one forward."""
     cfg = cfg_of(**kw)
     say(f"keep / kept {kw}")
     pr = make_problem(cfg)
@@ -344,8 +344,10 @@ def test_forward_keep_and_backward_kept_equal_the_recomputing_calls(kw):
     wsb = dchag.dchag_workspace_bytes(dt, cfg.B, cfg.C, cfg.H, cfg.W, cfg.p, cfg.D, cfg.heads, list(cfg.group_sizes), 3)
     ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
     out = dchag.dchag_forward_keep(x, We, be, ce, lv_dev, cfg.p, cfg.heads, ws)
+    monkeypatch.setenv("DCHAG_VALUE_UNFOLDED", "1")
     ref = dchag.dchag_forward_folded(x, We, be, ce, lv_dev, cfg.p, cfg.heads)
     torch.cuda.synchronize()
+    monkeypatch.delenv("DCHAG_VALUE_UNFOLDED")
     assert torch.equal(out, ref)
     want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
     assert rel_err(host(out), want) < TOL[d]
