@@ -4,6 +4,8 @@
 // Both calls evaluate an attention level with the value projection behind the weighted sum:
 //   alpha = softmax over the group of (z . M),  u_a = sum_c alpha[c,a] z[c],  o_a = Wv_a u_a + bv_a,
 //   y = Wo o + bo.
+// The inference call takes its first level straight from the pixels where the shape allows (tokens are linear in
+// the pixels, so Wv moves into the tokenizer weights: attend_pixels_forward).
 // The backward call keeps alpha, u and o of every level in its workspace and then walks the levels
 // in reverse (paper Section 3.3: the backward pass is local, the plain reverse of the forward).
 

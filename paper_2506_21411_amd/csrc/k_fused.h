@@ -6,6 +6,11 @@
 //   k_vagg_mfma       value projection GEMM whose epilogue takes the softmax-weighted sum over
 //                     the channels of the group, so that the projected values never leave the CU
 //   k_linear_dl       plain per-group projection GEMM (output projection)
+//   k_fold_value_dl   weight-only product Wv We[c] (value projection folded into the tokenizer weights)
+//   k_scores_pixels*, k_compose_score_weights*   first-level scores straight from the pixels
+//   k_tokenize_ws, k_tokenize_mfma               the per-channel tokenizer (paper Section 2.1)
+//   k_tokenize_reduce_ring, k_tokenize_mix_*, k_tokenize_attend_wide   tokenizer fused with the first level
+//                     (linear level of D-CHAG-L, or attention level with folded value weights): no tokens in HBM
 //
 // The two GEMM kernels share one core: 256x256 block tile, 8 wavefronts (2 x 4), 32x32x16 bf16
 // MFMA, K staged in 64-element slices through two LDS stages that are filled by direct-to-LDS
