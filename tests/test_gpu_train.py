@@ -139,6 +139,9 @@ PIXEL_VALUES = [
     dict(dtype="bf16", B=1, C=3, H=64, W=64, p=8, D=1024, heads=4, group_sizes=(3,)),
     # heads of 128: two per slice; groups 3 + 3
     dict(dtype="bf16", B=1, C=6, H=32, W=48, p=8, D=512, heads=4, group_sizes=(3, 2)),
+    # a last group of one member, three batch elements, N = 45 (one ragged tile): 18 work items, not a multiple of the
+    # eight ranges they are dealt to
+    dict(dtype="bf16", B=3, C=9, H=40, W=72, p=8, D=256, heads=4, group_sizes=(4, 3)),
     # 4 x 4 patches (the kernel that passes the operands through registers): N = 156 (two tiles, the second ragged),
     # heads of 64, groups 4 + 4 + 1
     dict(dtype="bf16", B=2, C=9, H=48, W=52, p=4, D=512, heads=8, group_sizes=(4, 3)),
