@@ -597,31 +597,31 @@ inline bool reduce_ring_ok(int p, int W, int D, const void* x, const void* Wt, c
   return p == 8 && W % 8 == 0 && D % 256 == 0 && aligned16(x) && aligned16(Wt) && aligned16(v0) && aligned16(v1) &&
          aligned16(v2) && !getenv("DCHAG_FIRST_LEVEL_REGS");
 }
-template <bool ATT, int WN>
+template <bool ATT, int CFG>
 int launch_reduce_ring_cols(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
                             const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias,
                             bf16* y, hipStream_t st, float* part, size_t part_bytes) {
-  typedef RedCfg<WN> Cfg;
+  typedef RedCfg<CFG> Cfg;
   const int N = (H / 8) * (W / 8), G = groups_of(C, g);
   TileWork tw{};
   tw.n_tiles = D / Cfg::kCols;
-  tw.m_tiles = (N + kRedPatches - 1) / kRedPatches;
+  tw.m_tiles = (N + Cfg::kPatches - 1) / Cfg::kPatches;
   tw.nb = B;
   const long total = (long)G * B * tw.m_tiles * tw.n_tiles;
   if (total > (1L << 26)) return DCHAG_ERR_SHAPE;
   tw.total = (int)total;
   const size_t per_split = (size_t)B * G * N * D;
   const int gmin = std::min(g, C - (G - 1) * g);                  // members of the shortest group
-  const long fill = (WN == 4 ? 2L : 4L) * compute_units();        // workgroups that give every compute unit two rounds
+  const long fill = 2L * Cfg::kPerCu * compute_units();           // workgroups that give every compute unit two rounds
   int S = 1;
   while (total * S < fill && 2 * S <= std::min(16, gmin)) S *= 2;
   if (const char* e = getenv("DCHAG_FIRST_LEVEL_SPLIT")) S = std::max(1, std::min(std::min(16, gmin), atoi(e)));
   while (S > 1 && (!part || (size_t)S * per_split * 4 > part_bytes)) S >>= 1;
   const int per = (int)((total * S + kXcds - 1) / kXcds);
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_reduce_ring<ATT, WN>),
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_reduce_ring<ATT, CFG>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes) != hipSuccess)
     return DCHAG_ERR_LAUNCH;
-  k_tokenize_reduce_ring<ATT, WN><<<dim3((unsigned)(per * kXcds)), Cfg::kThreads, Cfg::kLdsBytes, st>>>(
+  k_tokenize_reduce_ring<ATT, CFG><<<dim3((unsigned)(per * kXcds)), Cfg::kThreads, Cfg::kLdsBytes, st>>>(
       C, H, W, D, g, G, heads, round_up(g, 8), round_up(N, 32), tw, x, Wt, wmix, v1, v2, alpha, bias, y, S, part);
   int rc = launch_status();
   if (rc || S == 1) return rc;
@@ -632,16 +632,16 @@ int launch_reduce_ring_cols(int B, int C, int H, int W, int D, int g, int heads,
 
 // part / part_bytes: optional fp32 scratch for partial sums; with it, and too few tiles to give every compute unit two
 // rounds of workgroups, a group's members are dealt to up to 16 workgroups per tile (DCHAG_FIRST_LEVEL_SPLIT overrides
-// the count).  Workgroups of 128 columns, two per compute unit (DCHAG_RING_COLS = 256: one of 256 columns).
+// the count).  Workgroups of 128 patches x 128 columns, two per compute unit (DCHAG_RING_SHAPE = 0: 128 x 256, one).
 template <bool ATT>
 int launch_reduce_ring(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
                        const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias, bf16* y,
                        hipStream_t st, float* part = nullptr, size_t part_bytes = 0) {
-  const char* e = getenv("DCHAG_RING_COLS");
-  if (e && atoi(e) == 256)
-    return launch_reduce_ring_cols<ATT, 4>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
+  const char* e = getenv("DCHAG_RING_SHAPE");
+  if (e && atoi(e) == 0)
+    return launch_reduce_ring_cols<ATT, 0>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
                                            part_bytes);
-  return launch_reduce_ring_cols<ATT, 2>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
+  return launch_reduce_ring_cols<ATT, 1>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
                                          part_bytes);
 }
 

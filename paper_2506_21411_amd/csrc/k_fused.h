@@ -1839,26 +1839,34 @@ __global__ __launch_bounds__(512) void k_tokenize_attend_wide(int C, int H, int 
 // Requires D % 256 == 0, W % 8 == 0, 16-byte aligned x; ATT: (D / heads) % 64 == 0 and 256 % dh == 0 or dh % 256 == 0.
 // Dynamic LDS: kRedLdsBytes.
 // ---------------------------------------------------------------------------------------------
-constexpr int kRedPatches = 128;
-template <int WN>
-struct RedCfg {                                            // WN wavefront columns of 64: 256 or 128 columns per workgroup
-  static constexpr int kWaves = 2 * WN, kThreads = kWaves * 64, kCols = WN * 64;
-  static constexpr int kABytes = kRedPatches * 128, kBBytes = kCols * 128, kXBytes = 4096;
+// Workgroup shapes of k_tokenize_reduce_ring.  CFG 0: 128 patches x 256 columns, 8 wavefronts (2 x 4) of 64 x 64, three
+// stages, one workgroup per compute unit.  CFG 1: 128 x 128, 4 wavefronts (2 x 2) of 64 x 64, two stages, two workgroups
+// per compute unit (the one taken: 0.107 against 0.114 ms at the headline shape; 64 x 128 with wavefronts of 64 x 32,
+// three workgroups per compute unit, was slower than both: 0.127 ms).
+template <int CFG>
+struct RedCfg {
+  static constexpr int kPatches = 128;
+  static constexpr int WM = kPatches / 64, WN = CFG == 1 ? 2 : 4, TN = 2;
+  static constexpr int kWaves = WM * WN, kThreads = kWaves * 64, kCols = WN * TN * 32;
+  static constexpr int kABytes = kPatches * 128, kBBytes = kCols * 128, kXBytes = 4096;
   static constexpr int kStageBytes = kABytes + kBBytes + kXBytes;           // 52 or 36 KiB
-  static constexpr int kStages = WN == 4 ? 3 : 2;                           // one workgroup per compute unit, or two
+  static constexpr int kStages = CFG == 0 ? 3 : 2;
+  static constexpr int kPerCu = CFG + 1;                                    // workgroups per compute unit
   static constexpr int kLdsBytes = kStages * kStageBytes;                   // 156 or 72 KiB
 };
 
-template <bool ATT, int WN>
-__global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduce_ring(
+template <bool ATT, int CFG>
+__global__ __launch_bounds__(RedCfg<CFG>::kThreads, RedCfg<CFG>::kPerCu) void k_tokenize_reduce_ring(
     int C, int H, int W, int D, int g, int G, int heads, int gpad, int Np, TileWork tw, const bf16* __restrict__ x,
     const bf16* __restrict__ Wt, const bf16* __restrict__ wmix, const bf16* __restrict__ v1,
     const bf16* __restrict__ v2, const float* __restrict__ alpha, const bf16* __restrict__ bias, bf16* __restrict__ y,
     int S, float* __restrict__ ypart) {
-  typedef RedCfg<WN> Cfg;
+  typedef RedCfg<CFG> Cfg;
+  constexpr int WN = Cfg::WN, TN = Cfg::TN, kRedPatches = Cfg::kPatches;
   constexpr int kRedCols = Cfg::kCols, kRedABytes = Cfg::kABytes, kRedBBytes = Cfg::kBBytes;
   constexpr int kRedStageBytes = Cfg::kStageBytes, NS = Cfg::kStages;
-  constexpr int AL = 16 / Cfg::kWaves;                   // A loads per wavefront and member
+  constexpr int AL = kRedPatches / 8 / Cfg::kWaves;      // A loads per wavefront and member
+  constexpr int BL = kRedCols / 8 / Cfg::kWaves;         // B loads per wavefront and member
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   int k, b, pt, cs, split;
   {
@@ -1879,11 +1887,12 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / WN, wn = wave % WN, l32 = lane & 31, lhi = lane >> 5;
+  const int wcol = wn * TN * 32;                         // first column of this wavefront inside the slice
   const int dh = D / heads;
 
   // ---- issue side: per-lane sources of this wavefront's loads of one member ----
   const bf16* a_src[AL];
-  const bf16* b_src[4];
+  const bf16* b_src[BL];
 #pragma unroll
   for (int i = 0; i < AL; ++i) {
     const int row = wave * (AL * 8) + i * 8 + (lane >> 3);
@@ -1892,15 +1901,17 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
     a_src[i] = x + ((size_t)b * C + c0) * HW + (size_t)((n / pw) * 8 + q) * W + (n % pw) * 8;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = wave * 32 + i * 8 + (lane >> 3);
+  for (int i = 0; i < BL; ++i) {
+    const int row = wave * (BL * 8) + i * 8 + (lane >> 3);
     const int q = (lane & 7) ^ swz_chunk(row);
     b_src[i] = Wt + ((size_t)c0 * D + col_base + row) * 64 + q * 8;
   }
-  // The stage's 4 KiB of vectors: four per-column vectors of kCols bf16 each (ATT: v1, v2, -, -; else wmix, v1, v2, -)
-  // in the first 2 KiB, filled by the first wavefront(s), 64 / (kCols / 8) vectors per load; behind them the softmax
-  // weights of the slice's heads (512 bytes each: 128 patches), two heads per load of the next wavefront(s).
+  // The stage's vectors: four per-column vectors of kCols bf16 each (ATT: v1, v2, -, -; else wmix, v1, v2, -) in the
+  // first half, filled by the first wavefront(s), 64 / (kCols / 8) vectors per load; in the second half the softmax
+  // weights of the slice's heads (kPatches floats each), 64 / (kPatches / 4) heads per load of the next wavefront(s).
   constexpr int LPV = kRedCols / 8, VPI = 64 / LPV, NVW = 4 / VPI;
+  constexpr int AOFF = Cfg::kXBytes / 2, LPH = kRedPatches / 4, HPI = 64 / LPH, HB = kRedPatches * 4;
+  constexpr int NAW = (kRedCols / 64 + HPI - 1) / HPI;   // heads are at least 64 columns wide
   const unsigned char* e_src = reinterpret_cast<const unsigned char*>(Wt);   // absent vector: any valid 16 bytes
   size_t e_step = 0;
   bool extra = false;
@@ -1915,13 +1926,13 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
       e_src = reinterpret_cast<const unsigned char*>(v + row0 * D + col_base + 8 * lv);
       e_step = (size_t)D * 2;
     }
-  } else if (ATT && wave >= NVW && wave < NVW + WN / 2) {
+  } else if (ATT && wave >= NVW && wave < NVW + NAW) {
     extra = true;
-    e_slot = 2048 + (wave - NVW) * 1024;
+    e_slot = AOFF + (wave - NVW) * 1024;
     const int nhs = dh >= kRedCols ? 1 : kRedCols / dh;
-    const int head = col_base / dh + min(2 * (wave - NVW) + lhi, nhs - 1);
+    const int head = col_base / dh + min(HPI * (wave - NVW) + lane / LPH, nhs - 1);
     e_src = reinterpret_cast<const unsigned char*>(alpha + ((((size_t)b * G + k) * gpad + m_lo) * heads + head) * Np +
-                                                   min(n0 + 4 * l32, Np - 4));
+                                                   min(n0 + 4 * (lane % LPH), Np - 4));
     e_step = (size_t)heads * Np * 4;
   }
   extra = __builtin_amdgcn_readfirstlane(extra);
@@ -1935,8 +1946,8 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
       a_src[i] += HW;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      load16_to_lds(b_src[i], st + kRedABytes + (wave * 4 + i) * 1024);
+    for (int i = 0; i < BL; ++i) {
+      load16_to_lds(b_src[i], st + kRedABytes + (wave * BL + i) * 1024);
       b_src[i] += b_step;
     }
     if (extra) {
@@ -1946,23 +1957,25 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
   };
 
   // ---- compute side ----
-  const int a_base = (wm * 64 + l32) * 128, b_base = kRedABytes + (wn * 64 + l32) * 128;
+  const int a_base = (wm * 64 + l32) * 128, b_base = kRedABytes + (wcol + l32) * 128;
   int ck[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) ck[kk] = ((kk * 2 + lhi) ^ swz_chunk(l32)) * 16;
   const int xoff = kRedABytes + kRedBBytes;
   constexpr int VB = kRedCols * 2;                       // bytes of one per-column vector
-  const int colj = (wn * 64 + l32) * 2;                  // byte offset of this lane's first column in a vector
-  const int hrel = ATT ? (col_base + wn * 64) / dh - col_base / dh : 0;
+  const int colj = (wcol + l32) * 2;                     // byte offset of this lane's first column in a vector
+  const int hrel = ATT ? (col_base + wcol) / dh - col_base / dh : 0;
 
-  f32x16 o[2][2];
+  f32x16 o[2][TN];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[i][j][r] = 0.f;
-  float cst[2] = {0.f, 0.f};                             // ATT = false: patch-independent part sum_c w * (v1 + v2)
+  float cst[TN];                                         // ATT = false: patch-independent part sum_c w * (v1 + v2)
+#pragma unroll
+  for (int j = 0; j < TN; ++j) cst[j] = 0.f;
 
 #pragma unroll
   for (int s0 = 0; s0 < NS - 1; ++s0)
@@ -1971,8 +1984,8 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
   for (int m = 0; m < gk; ++m) {
     // member m has landed (this wavefront's share: with three stages the loads of member m + 1 may stay in flight) ...
     if (NS == 3 && m + 1 < gk) {
-      if (extra) wait_vmcnt<AL + 5>();
-      else wait_vmcnt<AL + 4>();
+      if (extra) wait_vmcnt<AL + BL + 1>();
+      else wait_vmcnt<AL + BL>();
     } else {
       wait_vmcnt<0>();
     }
@@ -1983,12 +1996,13 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
     const unsigned char* st = smem + sc * kRedStageBytes;
     sc = sc == NS - 1 ? 0 : sc + 1;
 
-    float vb[2];                                         // per-column constant of this member: v1 + v2
-    float wj[2] = {1.f, 1.f};
+    float vb[TN];                                        // per-column constant of this member: v1 + v2
+    float wj[TN];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < TN; ++j) {
       const unsigned char* xs = st + xoff + colj + j * 64;
       float s = 0.f;
+      wj[j] = 1.f;
       if (ATT) {
         if (v1) s += (float)*reinterpret_cast<const bf16*>(xs);
         if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + VB);
@@ -2001,20 +2015,20 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
     }
     // Row block i = 0 first, then i = 1: while the matrix pipe works on the second block the vector ALUs scale the
     // first into the running sum (the two instruction streams are interleaved below, one MFMA per four FMAs).
-    f32x16 acc[2][2];
-    bf16x8 bfr[4][2], af[4];
+    f32x16 acc[2][TN];
+    bf16x8 bfr[4][TN], af[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       af[kk] = *reinterpret_cast<const bf16x8*>(st + a_base + ck[kk]);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[kk]);
+      for (int j = 0; j < TN; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[kk]);
     }
-    const float* al = reinterpret_cast<const float*>(st + xoff + 2048 + hrel * 512) + wm * 64 + 4 * lhi;
+    const float* al = reinterpret_cast<const float*>(st + xoff + AOFF + hrel * HB) + wm * 64 + 4 * lhi;
     auto product = [&](int i) {
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < TN; ++j) {
           if (kk == 0) {
             // the accumulation starts from the member's per-column constant (ATT) or from zero
             const float c = ATT ? vb[j] : 0.f;
@@ -2032,13 +2046,13 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
         for (int q = 0; q < 4; ++q) {
           const f32x4 a4 = *reinterpret_cast<const f32x4*>(al + i * 32 + 8 * q);
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[i][j][4 * q + e] += a4[e] * acc[i][j][4 * q + e];
         }
       } else {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[i][j][r] += wj[j] * acc[i][j][r];
       }
@@ -2050,7 +2064,7 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
     product(1);
     scale_in(0);
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int t = 0; t < 4 * TN; ++t) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
       __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // four vector-ALU instructions
     }
@@ -2058,16 +2072,16 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
     scale_in(1);
     if (!ATT) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) cst[j] += wj[j] * vb[j];
+      for (int j = 0; j < TN; ++j) cst[j] += wj[j] * vb[j];
     }
   }
 
-  const size_t yoff = (((size_t)b * G + k) * N + n0 + wm * 64) * D + col_base + wn * 64 + l32;
+  const size_t yoff = (((size_t)b * G + k) * N + n0 + wm * 64) * D + col_base + wcol + l32;
   const int nlim = N - n0 - wm * 64 - 4 * lhi;           // rows of this lane's half that are inside the image
   if (S > 1) {                                           // partial sum over this workgroup's members; k_vagg_merge adds them up
     float* pbase = ypart + (size_t)split * tw.nb * G * N * D + yoff;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -2079,8 +2093,8 @@ __global__ __launch_bounds__(2 * WN * 64, WN == 4 ? 1 : 2) void k_tokenize_reduc
   }
   bf16* ybase = y + yoff;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = col_base + wn * 64 + j * 32 + l32;
+  for (int j = 0; j < TN; ++j) {
+    const int col = col_base + wcol + j * 32 + l32;
     const float add = cst[j] + (bias ? (float)bias[(size_t)k * D + col] : 0.f);
 #pragma unroll
     for (int i = 0; i < 2; ++i)

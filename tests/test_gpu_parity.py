@@ -468,14 +468,14 @@ def test_forward_linear_first_level_patch_tiles(monkeypatch, narrow):
     _forward_on_sampled_patches(cfg, f"linear first level, narrow={narrow}", 10)
 
 
-@pytest.mark.parametrize("route", ["ring", "ring_256_columns", "registers", "registers_narrow"])
+@pytest.mark.parametrize("route", ["ring", "ring_shape_0", "registers", "registers_narrow"])
 def test_forward_linear_first_level_of_8x8_patches(monkeypatch, route):
     """The fused tokenizer + linear first level on 8 x 8 patches: the kernel that streams a member's patches and weights
-    through an LDS ring (workgroups of 128 columns, two per compute unit, or of 256 columns), and the two that pass them
-    through registers; N = 204 patches (two tiles of 128 or four of 64,
+    through an LDS ring (workgroups of 128 patches x 128 columns, two per compute unit, or 128 x 256, one), and the two
+    that pass them through registers; N = 204 patches (two tiles of 128 or four of 64,
     the last ragged), two 256-column slices, groups 4 + 4 + 4 + 1."""
-    if route == "ring_256_columns":
-        monkeypatch.setenv("DCHAG_RING_COLS", "256")
+    if route.startswith("ring_shape_"):
+        monkeypatch.setenv("DCHAG_RING_SHAPE", route[-1])
     elif route != "ring":
         monkeypatch.setenv("DCHAG_FIRST_LEVEL_REGS", "1")
     if route == "registers_narrow":

@@ -151,7 +151,7 @@ PIXEL_VALUES = [
 
 
 @pytest.mark.parametrize("kw", PIXEL_VALUES)
-@pytest.mark.parametrize("route", ["folded_into_tokenizer", "ring_256_columns", "fold_by_general_product", "head_sums"])
+@pytest.mark.parametrize("route", ["folded_into_tokenizer", "ring_shape_0", "fold_by_general_product", "head_sums"])
 def test_forward_folded_first_level_values_from_pixels(monkeypatch, kw, route):
     """The first attention level of dchag_forward_folded with the value projection folded into the tokenizer weights
     (one kernel from pixels and softmax weights to the level's pre-projection output; the weight-only fold by its own
@@ -161,8 +161,8 @@ def test_forward_folded_first_level_values_from_pixels(monkeypatch, kw, route):
         monkeypatch.setenv("DCHAG_VALUE_UNFOLDED", "1")
     if route == "fold_by_general_product":
         monkeypatch.setenv("DCHAG_FOLD_VALUE_GEMM", "1")
-    if route == "ring_256_columns":
-        monkeypatch.setenv("DCHAG_RING_COLS", "256")
+    if route.startswith("ring_shape_"):
+        monkeypatch.setenv("DCHAG_RING_SHAPE", route[-1])
     cfg = cfg_of(**kw)
     say(f"forward_folded pixel values {route} {kw}")
     pr = make_problem(cfg)
