@@ -391,6 +391,31 @@ def test_identity_projection_folded_into_the_tokenizer():
             np.testing.assert_allclose(V[n, c], want, rtol=0, atol=TOL)
 
 
+def test_identity_first_level_output_from_the_pixels():
+    """The two identities above together, as the inference path uses them at level 1: per head a,
+    o_a = sum_c alpha[c,a] ((W_v W_e[c]) u[c] + W_v (b_e[c] + e[c]))_a + b_v,a  (the weights sum to one over the group),
+    with a short last group (5 channels in groups of 3 + 2)."""
+    cfg = small_cfg(C=5, group_sizes=(3, 2), B=2)
+    pr = make_problem(cfg)
+    lv = pr.levels[0]
+    h, dh = cfg.heads, cfg.D // cfg.heads
+    t = oracle.tokenize(pr.x, pr.We, pr.be, pr.ce, cfg.p)                          # [B*N, C, D]
+    _, alpha, pre = oracle.aggregate_level(t, lv, h, want_alpha=True, want_pre=True)
+    p, pw, g = cfg.p, cfg.W // cfg.p, cfg.group_sizes[0]
+    for row in range(cfg.B * cfg.N):
+        b, n = divmod(row, cfg.N)
+        pi, pj = divmod(n, pw)
+        for k in range(n_groups(cfg.C, g)):
+            want = f64(lv.bv[k]).copy()
+            for c in range(k * g, min((k + 1) * g, cfg.C)):
+                u = f64(pr.x[b, c, pi * p:(pi + 1) * p, pj * p:(pj + 1) * p]).reshape(-1)
+                v = (f64(lv.Wv[k]) @ f64(pr.We[c])) @ u + f64(lv.Wv[k]) @ (f64(pr.be[c]) + f64(pr.ce[c]))
+                for a in range(h):
+                    sl = slice(a * dh, (a + 1) * dh)
+                    want[sl] += alpha[row, c, a] * v[sl]
+            np.testing.assert_allclose(pre[row, k], want, rtol=0, atol=TOL)
+
+
 # ---------------------------------------------------------------------------
 # hierarchy bookkeeping and argument checks
 # ---------------------------------------------------------------------------
