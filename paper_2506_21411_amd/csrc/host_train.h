@@ -57,9 +57,9 @@ inline size_t pixel_scratch(size_t off, int C, int pp, int D, int heads, int G0,
   return off;
 }
 
-// Tokenizer weights with the first level's value projection folded in, Wf [C,D,pp], and two folded bias vectors [C,D].
+// Tokenizer weights with the first level's value projection folded in, Wf [C,D,pp], and the folded token bias [C,D].
 inline size_t value_fold_bytes(int C, int D, int pp) {
-  return align_up((size_t)C * D * pp * 2) + 2 * align_up((size_t)C * D * 2);
+  return align_up((size_t)C * D * pp * 2) + align_up((size_t)C * D * 2);
 }
 
 inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int heads, int n_levels,
@@ -397,7 +397,7 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
   const bf16* Wv = static_cast<const bf16*>(lv->Wv);
   const size_t wf_bytes = align_up((size_t)C * D * pp * 2), vec_bytes = align_up((size_t)C * D * 2);
   bf16* Wf = reinterpret_cast<bf16*>(fold);
-  bf16* fb[1] = {reinterpret_cast<bf16*>(fold + wf_bytes)};
+  bf16* fb = reinterpret_cast<bf16*>(fold + wf_bytes);   // Wv (be + ce), [C,D]
   int rc;
   {
     StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
@@ -443,15 +443,15 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
       e.Bm = {0, (long)D * D, 0, 1, (long)D};
       e.C = {0, (long)g * D, 0, (long)D, 1};
       e.scale = 1.f;
-      if ((rc = launch_gemm_bf16<bf16>(e, first, Wv, nullptr, fb[0], st))) return rc;
+      if ((rc = launch_gemm_bf16<bf16>(e, first, Wv, nullptr, fb, st))) return rc;
     }
   }
   StageTimer tm(DCHAG_STAGE_TOKENIZE_ATTEND, st);
-  const bf16* v1 = be || ce ? fb[0] : nullptr;
+  const bf16* v1 = be || ce ? fb : nullptr;
   const bf16* v2 = nullptr;
   const bf16* bv = static_cast<const bf16*>(lv->bv);
   if (attend_ring_ok(p, W, D, heads, x, lv)) {
-    const size_t used = wf_bytes + 2 * vec_bytes;
+    const size_t used = wf_bytes + vec_bytes;
     return launch_reduce_ring<true>(B, C, H, W, D, g, heads, x, Wf, nullptr, v1, v2, alpha, bv, o, st,
                                     reinterpret_cast<float*>(fold + used), fold_bytes > used ? fold_bytes - used : 0);
   }
