@@ -110,7 +110,7 @@ def test_forward_folded_matches_oracle(kw):
 
 
 @pytest.mark.parametrize("name,per_batch", [("weather", 4), ("hyperspectral", 4), ("hyperspectral_linear", 4),
-                                            ("hyperspectral_flat", 3), ("deep", 2)])
+                                            ("hyperspectral_flat", 3), ("deep", 2), ("wide", 2), ("deep1000", 2)])
 def test_forward_folded_full_size_on_sampled_patches(name, per_batch):
     """dchag_forward_folded at the benchmark's sizes and launch configuration, against the oracle on a seeded sample of
     patches; every output row is finite."""
