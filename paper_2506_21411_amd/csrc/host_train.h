@@ -426,7 +426,10 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
       d.scale = 1.f;
       if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * pp, (long)D * pp, Wv, We, Wf, st))) return rc;
     }
-    if (be || ce) {
+    if ((be || ce) && aligned16(Wv) && aligned16(be) && aligned16(ce) && G <= 65535 && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
+      k_fold_token_bias<<<dim3(D / 32, G), 256, 0, st>>>(C, D, g, Wv, be, ce, fb);
+      if ((rc = launch_status())) return rc;
+    } else if (be || ce) {
       // (Wv (be + ce))[c](o) = sum over the vectors v present, sum_d v[c](d) Wv[k](o, d): one product whose batch
       // index walks from be to ce (their distance in elements, taken on the integer addresses: the two are separate
       // allocations in one flat device address space) and is summed over

@@ -814,6 +814,48 @@ __global__ __launch_bounds__(512) void k_fold_value_dl(int C, int D, int g, Tile
       for (int r = 0; r < 16; ++r) out[(size_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * 64 + j * 32] = (bf16)acc[i][j][r];
 }
 
+// The token biases under the same fold (weight-only):  fb[c][o] = sum_d (be[c][d] + ce[c][d]) * Wv[k][o][d],  k = c / g;
+// either vector may be absent.  grid (D / 32, G), block 256: 32 rows o of Wv against the group's members, 32 per pass
+// (one 32 x 32 MFMA block: rows o, columns members, operands straight from memory), the four wavefronts a quarter of d
+// each, their partial blocks merged in LDS in a fixed order.  Requires D % 64 == 0 and 16-byte aligned rows.
+__global__ __launch_bounds__(256) void k_fold_token_bias(int C, int D, int g, const bf16* __restrict__ Wv,
+                                                         const bf16* __restrict__ be, const bf16* __restrict__ ce,
+                                                         bf16* __restrict__ fb) {
+  __shared__ float part[4][32][33];
+  const int k = blockIdx.y, o0 = blockIdx.x * 32;
+  const int c0 = k * g, gk = min(g, C - c0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lhi = lane >> 5;
+  const int dq = D / 4;
+  const bf16* arow = Wv + ((size_t)k * D + o0 + l32) * D + wave * dq + lhi * 8;
+  for (int cb = 0; cb < gk; cb += 32) {
+    const size_t coff = (size_t)(c0 + min(cb + l32, gk - 1)) * D + wave * dq + lhi * 8;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int ks = 0; ks < dq; ks += 16) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(arow + ks);
+      if (be) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, *reinterpret_cast<const bf16x8*>(be + coff + ks), acc, 0, 0, 0);
+      if (ce) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, *reinterpret_cast<const bf16x8*>(ce + coff + ks), acc, 0, 0, 0);
+    }
+    // accumulator register r of lane (member l32, half lhi): row o = 8 (r / 4) + 4 lhi + r % 4
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave][8 * (r >> 2) + 4 * lhi + (r & 3)][l32] = acc[r];
+    __syncthreads();
+    {
+      const int mm = tid >> 3, r0 = 4 * (tid & 7);       // member of the pass, four adjacent rows o
+      if (cb + mm < gk) {
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+        bf16x4_t out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          out[e] = (bf16)(part[0][r0 + e][mm] + part[1][r0 + e][mm] + part[2][r0 + e][mm] + part[3][r0 + e][mm]);
+        *reinterpret_cast<bf16x4_t*>(fb + (size_t)(c0 + cb + mm) * D + o0 + r0) = out;
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Level-1 scores straight from the pixels.  The tokenizer is linear, so the score of token
 // t = We[c] u + be[c] + ce[c] against the folded key M[k][a] is
