@@ -422,12 +422,12 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     // a debugging aid, keeps them apart)
     const size_t slds = (size_t)std::min(g, Cin) * heads * 33 * 4;
     if (slds <= 150 * 1024 && B <= 65535 && G <= 65535 && !getenv("DCHAG_PIXEL_SCORES_TWO_KERNELS")) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_pixels_softmax),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds) != hipSuccess)
+      auto sk = pp == 64 ? k_scores_pixels_softmax<64> : (pp == 16 ? k_scores_pixels_softmax<16> : k_scores_pixels_softmax<0>);
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(sk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds) !=
+          hipSuccess)
         return DCHAG_ERR_LAUNCH;
-      k_scores_pixels_softmax<<<dim3((N + 31) / 32, G, B), 256, slds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G,
-                                                                            Np, px->x, px->Msb, px->cs,
-                                                                            alpha_tm ? nullptr : alpha, alpha_tm);
+      sk<<<dim3((N + 31) / 32, G, B), 256, slds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G, Np, px->x, px->Msb,
+                                                      px->cs, alpha_tm ? nullptr : alpha, alpha_tm);
       if ((rc = launch_status())) return rc;
       if (tm_done && alpha_tm) *tm_done = true;
     } else {

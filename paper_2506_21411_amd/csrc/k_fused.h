@@ -1134,6 +1134,9 @@ __global__ __launch_bounds__(256) void k_scores_pixels(int C, int H, int W, int 
 // then every (head, patch) is normalised over the members in the order and with the arithmetic of k_softmax_alpha,
 // and the weights are written in the layout of the forward kernels (alpha_f[b][k][cl][head][n], zeros for padding
 // members and the pitch) and / or token-major (alpha_tm[b,c,n,head]), whichever pointer is given.
+// PP: pixels per patch when known at compile time (16 or 64: a channel's operand loads are then issued together, and
+// those of the wavefront's next channel while the current one is multiplied), 0 for any other patch size.
+template <int PP>
 __global__ __launch_bounds__(256) void k_scores_pixels_softmax(int C, int H, int W, int p, int heads, int g, int gpad,
                                                                int G, int Np, const bf16* __restrict__ x,
                                                                const bf16* __restrict__ Msb,
@@ -1141,40 +1144,79 @@ __global__ __launch_bounds__(256) void k_scores_pixels_softmax(int C, int H, int
                                                                float* __restrict__ alpha_f,
                                                                float* __restrict__ alpha_tm) {
   extern __shared__ __attribute__((aligned(16))) float sc[];       // [gk][heads][33]
-  const int pp = p * p, pw = W / p, N = (H / p) * pw;
+  const int pp = PP ? PP : p * p, pw = W / p, N = (H / p) * pw;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
   const int k = blockIdx.y, b = blockIdx.z;
   const int c0 = k * g, gk = min(g, C - c0);
   const int n0 = blockIdx.x * 32;
   const int n = min(n0 + l32, N - 1);
   const int pi = n / pw, pj = n % pw;
-  for (int cl = wave; cl < gk; cl += 4) {
-    const int c = c0 + cl;
-    const bf16* img = x + ((size_t)b * C + c) * H * W + (size_t)(pi * p) * W + pj * p;
-    const bf16* mrow = Msb + ((size_t)c * heads + min(l32, heads - 1)) * pp;
-    f32x16 acc;
+  const size_t img_off = (size_t)(pi * p) * W + pj * p;
+  // one 8-pixel chunk of this lane's patch of channel c, and the matching chunk of the composed score weights
+  auto load_a = [&](int c, int kc) -> bf16x8 {
+    const bf16* img = x + ((size_t)b * C + c) * H * W + img_off;
+    bf16x8 a;
+    if (p == 4) {
+      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc) * W);
+      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc + 1) * W);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    for (int kc = lhi; kc < pp / 8; kc += 2) {          // 8-pixel chunk of the patch
-      bf16x8 a;
-      if (p == 4) {
-        const bf16x4 lo = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc) * W);
-        const bf16x4 hi = *reinterpret_cast<const bf16x4*>(img + (size_t)(2 * kc + 1) * W);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { a[e] = lo[e]; a[4 + e] = hi[e]; }
-      } else {
-        const int r = (kc * 8) / p, s0 = (kc * 8) % p;
-        a = *reinterpret_cast<const bf16x8*>(img + (size_t)r * W + s0);
-      }
-      bf16x8 m = *reinterpret_cast<const bf16x8*>(mrow + kc * 8);
-      if (l32 >= heads) m = bf16x8{};
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, m, acc, 0, 0, 0);
+      for (int e = 0; e < 4; ++e) { a[e] = lo[e]; a[4 + e] = hi[e]; }
+    } else {
+      const int r = (kc * 8) / p, s0 = (kc * 8) % p;
+      a = *reinterpret_cast<const bf16x8*>(img + (size_t)r * W + s0);
     }
-    if (l32 < heads) {                                   // lane: head l32, patches 8 (r / 4) + 4 lhi + r % 4
-      const float add = cs[(size_t)c * heads + l32];
+    return a;
+  };
+  auto load_m = [&](int c, int kc) -> bf16x8 {
+    bf16x8 m = *reinterpret_cast<const bf16x8*>(Msb + ((size_t)c * heads + min(l32, heads - 1)) * pp + kc * 8);
+    if (l32 >= heads) m = bf16x8{};
+    return m;
+  };
+  auto leave = [&](int cl, const f32x16& acc) {          // lane: head l32, patches 8 (r / 4) + 4 lhi + r % 4
+    if (l32 < heads) {
+      const float add = cs[(size_t)(c0 + cl) * heads + l32];
       float* dst = sc + ((size_t)cl * heads + l32) * 33 + 4 * lhi;
 #pragma unroll
       for (int r = 0; r < 16; ++r) dst[8 * (r >> 2) + (r & 3)] = acc[r] + add;
+    }
+  };
+  if constexpr (PP > 0) {
+    constexpr int NIT = PP / 16;                         // chunks per lane half
+    bf16x8 a0[NIT], m0[NIT], a1[NIT], m1[NIT];
+    auto fetch = [&](int cl, bf16x8 (&a)[NIT], bf16x8 (&m)[NIT]) {
+#pragma unroll
+      for (int t = 0; t < NIT; ++t) {
+        a[t] = load_a(c0 + cl, lhi + 2 * t);
+        m[t] = load_m(c0 + cl, lhi + 2 * t);
+      }
+    };
+    auto product = [&](int cl, const bf16x8 (&a)[NIT], const bf16x8 (&m)[NIT]) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+      for (int t = 0; t < NIT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], m[t], acc, 0, 0, 0);
+      leave(cl, acc);
+    };
+    int cl = wave;
+    if (cl < gk) fetch(cl, a0, m0);
+    while (cl < gk) {
+      if (cl + 4 < gk) fetch(cl + 4, a1, m1);
+      product(cl, a0, m0);
+      cl += 4;
+      if (cl >= gk) break;
+      if (cl + 4 < gk) fetch(cl + 4, a0, m0);
+      product(cl, a1, m1);
+      cl += 4;
+    }
+  } else {
+    for (int cl = wave; cl < gk; cl += 4) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      for (int kc = lhi; kc < pp / 8; kc += 2)           // 8-pixel chunk of the patch
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_a(c0 + cl, kc), load_m(c0 + cl, kc), acc, 0, 0, 0);
+      leave(cl, acc);
     }
   }
   __syncthreads();
@@ -1190,17 +1232,25 @@ __global__ __launch_bounds__(256) void k_scores_pixels_softmax(int C, int H, int
   }
   __syncthreads();
   if (alpha_f) {
-    for (int idx = threadIdx.x; idx < gpad * heads * 32; idx += 256) {      // patch fastest: 128-byte runs
-      const int patch = idx & 31, head = (idx >> 5) % heads, cl = (idx >> 5) / heads;
-      const float v = (cl < gk && n0 + patch < N) ? sc[((size_t)cl * heads + head) * 33 + patch] : 0.f;
-      alpha_f[((((size_t)b * G + k) * gpad + cl) * heads + head) * Np + n0 + patch] = v;
+    for (int idx = threadIdx.x; idx < gpad * heads * 8; idx += 256) {       // four patches per thread: 16-byte stores
+      const int quad = idx & 7, head = (idx >> 3) % heads, cl = (idx >> 3) / heads;
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        v[e] = (cl < gk && n0 + 4 * quad + e < N) ? sc[((size_t)cl * heads + head) * 33 + 4 * quad + e] : 0.f;
+      *reinterpret_cast<f32x4*>(alpha_f + ((((size_t)b * G + k) * gpad + cl) * heads + head) * Np + n0 + 4 * quad) = v;
     }
   }
   if (alpha_tm) {
-    for (int idx = threadIdx.x; idx < gk * heads * 32; idx += 256) {        // head fastest: runs of 4 heads bytes
-      const int head = idx % heads, patch = (idx / heads) & 31, cl = idx / (heads * 32);
-      if (n0 + patch < N)
-        alpha_tm[(((size_t)b * C + c0 + cl) * N + n0 + patch) * heads + head] = sc[((size_t)cl * heads + head) * 33 + patch];
+    const int hq = heads / 4;                            // heads % 4 == 0: four heads per thread, 16-byte stores
+    for (int idx = threadIdx.x; idx < gk * 32 * hq; idx += 256) {
+      const int h4 = idx % hq, patch = (idx / hq) & 31, cl = idx / (hq * 32);
+      if (n0 + patch < N) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = sc[((size_t)cl * heads + 4 * h4 + e) * 33 + patch];
+        *reinterpret_cast<f32x4*>(alpha_tm + (((size_t)b * C + c0 + cl) * N + n0 + patch) * heads + 4 * h4) = v;
+      }
     }
   }
 }
