@@ -168,8 +168,8 @@ int dchag_forward_pos(dchag_dtype dt, int B, int C, int H, int W, int p, int D, 
  *
  *   o_a = sum_c alpha[c,a] ( (Wv We[c]) u[c] + Wv (be[c] + ce[c]) )_a + bv_a .
  *
- * For bf16 inputs with 4 x 4 or 8 x 8 patches, D a multiple of 256 and heads of 32 columns or a multiple (and the
- * shapes whose scores come from the pixels: a multiple of 4 heads, at most 32) the call forms the weight-only
+ * For bf16 inputs with 4 x 4 or 8 x 8 patches, D a multiple of 256 and heads of 32, 64, 128, ... columns (32 times a
+ * power of two; and the shapes whose scores come from the pixels: a multiple of 4 heads, at most 32) the call forms the weight-only
  * products Wv We[c], Wv be, Wv ce first and then goes from pixels and softmax weights to o in one kernel; the
  * per-channel tokens and the per-head averages u_a of that level never exist.  Other shapes, fp32 and the upper
  * levels take the u_a route.  workspace: dchag_workspace_bytes(..., which = 2).
