@@ -111,6 +111,12 @@ def load_library():
     lib.dchag_forward_pos.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
     lib.dchag_forward_folded.restype = i
     lib.dchag_forward_folded.argtypes = lib.dchag_forward.argtypes
+    lib.dchag_value_fold_bytes.restype = sz
+    lib.dchag_value_fold_bytes.argtypes = [i] * 5 + [ctypes.POINTER(_CLevel)]
+    lib.dchag_fold_value.restype = i
+    lib.dchag_fold_value.argtypes = [i] * 5 + [vp] * 3 + [ctypes.POINTER(_CLevel), vp, sz, vp]
+    lib.dchag_forward_prefolded.restype = i
+    lib.dchag_forward_prefolded.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
     lib.dchag_backward.restype = i
     lib.dchag_backward.argtypes = ([i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, vp, vp,
                                                         ctypes.POINTER(_CLevelGrads), vp, sz, vp])
@@ -279,6 +285,50 @@ def dchag_forward_folded(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.T
                                                _ptr(ce, x), len(levels), arr, _ptr(out, x),
                                                ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
                                                _stream(stream)))
+    return out
+
+
+def dchag_fold_value(We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor], level0: LevelWeights,
+                     p: int, heads: int, stream=None) -> Optional[torch.Tensor]:
+    """The weight-only products of dchag_forward_folded's first level, for dchag_forward_prefolded; None when the
+    library does not take that shape's first level from the pixels (dchag_value_fold_bytes == 0)."""
+    C, D = We.shape[0], We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    dt = _dt(We)
+    lib = load_library()
+    lv = _clevel(level0, We)
+    need = lib.dchag_value_fold_bytes(dt, C, p, D, heads, ctypes.byref(lv))
+    if need == 0:
+        return None
+    folded = _workspace(need, We.device)
+    _check(lib.dchag_fold_value(dt, C, p, D, heads, _ptr(We), _ptr(be, We), _ptr(ce, We), ctypes.byref(lv),
+                                ctypes.c_void_p(folded.data_ptr()), folded.numel(), _stream(stream)))
+    return folded
+
+
+def dchag_forward_prefolded(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                            levels: List[LevelWeights], p: int, heads: int, folded: torch.Tensor,
+                            out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                            stream=None) -> torch.Tensor:
+    """dchag_forward_folded with the first level's weight-only products taken from `folded` (dchag_fold_value)."""
+    B, C, H, W = x.shape
+    D = We.shape[1]
+    if tuple(We.shape) != (C, D, p * p):
+        raise ValueError("We must be [C, D, p*p]")
+    N = (H // p) * (W // p) if p > 0 else 0
+    dt = _dt(x)
+    if workspace is None:
+        workspace = _workspace(dchag_workspace_bytes(dt, B, C, H, W, p, D, heads, [lv.group_size for lv in levels], 2),
+                               x.device)
+    if out is None:
+        out = torch.empty((B, N, D), dtype=x.dtype, device=x.device)
+    arr = (_CLevel * len(levels))(*[_clevel(lv, x) for lv in levels])
+    _check(load_library().dchag_forward_prefolded(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x),
+                                                  _ptr(ce, x), len(levels), arr,
+                                                  ctypes.c_void_p(folded.data_ptr()), _ptr(out, x),
+                                                  ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                                  _stream(stream)))
     return out
 
 

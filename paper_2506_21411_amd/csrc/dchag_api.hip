@@ -923,6 +923,49 @@ int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int 
   return forward_folded_impl<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out, ws, w, st);
 }
 
+size_t dchag_value_fold_bytes(dchag_dtype dt, int C, int p, int D, int heads, const dchag_level* level0) {
+  if (!level0 || C < 1 || p < 1 || D < 1 || heads < 1 || D % heads || level0->group_size < 1) return 0;
+  if (!values_from_pixels(dt, p, D, heads, level0)) return 0;
+  return value_fold_bytes(C, D, p * p);
+}
+
+int dchag_fold_value(dchag_dtype dt, int C, int p, int D, int heads, const void* We, const void* be, const void* ce,
+                     const dchag_level* level0, void* folded, size_t folded_bytes, void* stream) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
+  if (!We || !level0 || !folded) return DCHAG_ERR_NULL;
+  int rc = check_level(level0);
+  if (rc) return rc;
+  if (C < 1 || p < 1 || D < 1 || heads < 1 || D % heads || (long)C * D * p * p > (1L << 40)) return DCHAG_ERR_SHAPE;
+  const size_t need = dchag_value_fold_bytes(dt, C, p, D, heads, level0);
+  if (need == 0) return DCHAG_ERR_SHAPE;                 // a shape whose first level is not taken from the pixels
+  if (misaligned(We) || misaligned(be) || misaligned(ce)) return DCHAG_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(folded) & (kAlign - 1)) || folded_bytes < need) return DCHAG_ERR_WORKSPACE;
+  g_level = 1;
+  return fold_value_weights(C, p, D, level0, static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+                            static_cast<const bf16*>(ce), static_cast<unsigned char*>(folded),
+                            static_cast<hipStream_t>(stream));
+}
+
+int dchag_forward_prefolded(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
+                            const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
+                            const void* folded, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t gs[16], kinds[16];
+  int rc = check_chain(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, kinds);
+  if (rc) return rc;
+  if (!out || !folded) return DCHAG_ERR_NULL;
+  if (misaligned(out)) return DCHAG_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(folded) & (kAlign - 1)) return DCHAG_ERR_WORKSPACE;
+  if (!values_from_pixels(dt, p, D, heads, &levels[0])) return DCHAG_ERR_SHAPE;
+  const int N = (H / p) * (W / p);
+  const FoldedWs w = folded_ws(dt, B, C, N, p * p, D, heads, n_levels, gs);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || w.total == 0 ||
+      workspace_bytes < w.total)
+    return DCHAG_ERR_WORKSPACE;
+  return forward_folded_impl<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out,
+                                   static_cast<unsigned char*>(workspace), w, static_cast<hipStream_t>(stream),
+                                   static_cast<const unsigned char*>(folded));
+}
+
 // which: 1 = forward that keeps, 2 = reverse sweep, 3 = both (dchag_backward)
 static int train_call(int which, dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
                       const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels, void* out,

@@ -390,74 +390,87 @@ inline bool attend_ring_ok(int p, int W, int D, int heads, const void* x, const 
   return attend_wide_ok(p, D, heads, lv) && reduce_ring_ok(p, W, D, x, nullptr, nullptr, nullptr, nullptr) &&
          (D / heads) % 64 == 0;
 }
-inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int heads, const dchag_level* lv,
-                                 const bf16* x, const bf16* We, const bf16* be, const bf16* ce, const float* alpha,
-                                 unsigned char* fold, size_t fold_bytes, bf16* o, hipStream_t st) {
-  const int g = lv->group_size, G = groups_of(C, g), pp = p * p, N = (H / p) * (W / p);
+// Shapes whose first level dchag_forward_folded takes from the pixels (scores through composed score weights, values
+// through folded tokenizer weights).
+inline bool values_from_pixels(dchag_dtype dt, int p, int D, int heads, const dchag_level* lv) {
+  return dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads) && attend_wide_ok(p, D, heads, lv);
+}
+
+// The weight-only part: fold (value_fold_bytes(C, D, p*p) bytes) receives Wf [C,D,p*p] and Wv (be + ce) [C,D].
+inline int fold_value_weights(int C, int p, int D, const dchag_level* lv, const bf16* We, const bf16* be, const bf16* ce,
+                              unsigned char* fold, hipStream_t st) {
+  const int g = lv->group_size, G = groups_of(C, g), pp = p * p;
   const bf16* Wv = static_cast<const bf16*>(lv->Wv);
-  const size_t wf_bytes = align_up((size_t)C * D * pp * 2), vec_bytes = align_up((size_t)C * D * 2);
+  const size_t wf_bytes = align_up((size_t)C * D * pp * 2);
   bf16* Wf = reinterpret_cast<bf16*>(fold);
   bf16* fb = reinterpret_cast<bf16*>(fold + wf_bytes);   // Wv (be + ce), [C,D]
   int rc;
-  {
-    StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
-    // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk).  64 pixels per patch: four channels per work item share a 256-row
-    // tile of Wv (DCHAG_FOLD_VALUE_GEMM, a debugging aid, takes the general product kernel, one channel per workgroup)
-    if (pp == 64 && aligned16(Wv) && aligned16(We) && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
-      TileWork tw{};
-      tw.n_tiles = (std::min(g, C) + 3) / 4;
-      tw.m_tiles = D / kGemmBM;
-      tw.nb = 1;
-      const long total = (long)G * tw.m_tiles * tw.n_tiles;
-      if (total > (1L << 30)) return DCHAG_ERR_SHAPE;
-      tw.total = (int)total;
-      const int per = (tw.total + kXcds - 1) / kXcds;
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_fold_value_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kGemmRingBytes) != hipSuccess)
-        return DCHAG_ERR_LAUNCH;
-      k_fold_value_dl<<<dim3((unsigned)(per * kXcds)), 512, kGemmRingBytes, st>>>(C, D, g, tw, Wv, We, Wf);
-      if ((rc = launch_status())) return rc;
-    } else {
-      GemmDesc d{};
-      d.M = D; d.N = pp; d.K = D; d.nb = 1;
-      d.A = {0, 0, 0, (long)D, 1};
-      d.Bm = {0, 0, 0, (long)pp, 1};
-      d.C = {0, 0, 0, (long)pp, 1};
-      d.scale = 1.f;
-      if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * pp, (long)D * pp, Wv, We, Wf, st))) return rc;
-    }
-    if ((be || ce) && aligned16(Wv) && aligned16(be) && aligned16(ce) && G <= 65535 && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
-      k_fold_token_bias<<<dim3(D / 32, G), 256, 0, st>>>(C, D, g, Wv, be, ce, fb);
-      if ((rc = launch_status())) return rc;
-    } else if (be || ce) {
-      // (Wv (be + ce))[c](o) = sum over the vectors v present, sum_d v[c](d) Wv[k](o, d): one product whose batch
-      // index walks from be to ce (their distance in elements, taken on the integer addresses: the two are separate
-      // allocations in one flat device address space) and is summed over
-      const bf16* first = be ? be : ce;
-      const long be_to_ce = be && ce ? (long)((reinterpret_cast<intptr_t>(ce) - reinterpret_cast<intptr_t>(be)) /
-                                              (intptr_t)sizeof(bf16))
-                                     : 0;
-      GemmDesc e{};
-      e.M = g; e.N = D; e.K = D; e.nk = G; e.na = 1;
-      e.nb = be && ce ? 2 : 1;
-      e.reduce_b = 1;
-      e.ragged = 1; e.ragged_total = C; e.ragged_nominal = g;
-      e.A = {be_to_ce, (long)g * D, 0, (long)D, 1};
-      e.Bm = {0, (long)D * D, 0, 1, (long)D};
-      e.C = {0, (long)g * D, 0, (long)D, 1};
-      e.scale = 1.f;
-      if ((rc = launch_gemm_bf16<bf16>(e, first, Wv, nullptr, fb, st))) return rc;
-    }
+  StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
+  // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk).  64 pixels per patch: four channels per work item share a 256-row
+  // tile of Wv (DCHAG_FOLD_VALUE_GEMM, a debugging aid, takes the general product kernel, one channel per workgroup)
+  if (pp == 64 && aligned16(Wv) && aligned16(We) && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
+    TileWork tw{};
+    tw.n_tiles = (std::min(g, C) + 3) / 4;
+    tw.m_tiles = D / kGemmBM;
+    tw.nb = 1;
+    const long total = (long)G * tw.m_tiles * tw.n_tiles;
+    if (total > (1L << 30)) return DCHAG_ERR_SHAPE;
+    tw.total = (int)total;
+    const int per = (tw.total + kXcds - 1) / kXcds;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_fold_value_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kGemmRingBytes) != hipSuccess)
+      return DCHAG_ERR_LAUNCH;
+    k_fold_value_dl<<<dim3((unsigned)(per * kXcds)), 512, kGemmRingBytes, st>>>(C, D, g, tw, Wv, We, Wf);
+    if ((rc = launch_status())) return rc;
+  } else {
+    GemmDesc d{};
+    d.M = D; d.N = pp; d.K = D; d.nb = 1;
+    d.A = {0, 0, 0, (long)D, 1};
+    d.Bm = {0, 0, 0, (long)pp, 1};
+    d.C = {0, 0, 0, (long)pp, 1};
+    d.scale = 1.f;
+    if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * pp, (long)D * pp, Wv, We, Wf, st))) return rc;
   }
+  if ((be || ce) && aligned16(Wv) && aligned16(be) && aligned16(ce) && G <= 65535 && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
+    k_fold_token_bias<<<dim3(D / 32, G), 256, 0, st>>>(C, D, g, Wv, be, ce, fb);
+    if ((rc = launch_status())) return rc;
+  } else if (be || ce) {
+    // (Wv (be + ce))[c](o) = sum over the vectors v present, sum_d v[c](d) Wv[k](o, d): one product whose batch
+    // index walks from be to ce (their distance in elements, taken on the integer addresses: the two are separate
+    // allocations in one flat device address space) and is summed over
+    const bf16* first = be ? be : ce;
+    const long be_to_ce = be && ce ? (long)((reinterpret_cast<intptr_t>(ce) - reinterpret_cast<intptr_t>(be)) /
+                                            (intptr_t)sizeof(bf16))
+                                   : 0;
+    GemmDesc e{};
+    e.M = g; e.N = D; e.K = D; e.nk = G; e.na = 1;
+    e.nb = be && ce ? 2 : 1;
+    e.reduce_b = 1;
+    e.ragged = 1; e.ragged_total = C; e.ragged_nominal = g;
+    e.A = {be_to_ce, (long)g * D, 0, (long)D, 1};
+    e.Bm = {0, (long)D * D, 0, 1, (long)D};
+    e.C = {0, (long)g * D, 0, (long)D, 1};
+    e.scale = 1.f;
+    if ((rc = launch_gemm_bf16<bf16>(e, first, Wv, nullptr, fb, st))) return rc;
+  }
+  return DCHAG_OK;
+}
+
+// From pixels, softmax weights and the folded weights (fold, as fold_value_weights leaves it) to the pre-projection
+// output o [B,G,N,D].  part / part_bytes: scratch for partial sums (few groups: members dealt to several workgroups).
+inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int heads, const dchag_level* lv,
+                                 const bf16* x, bool token_bias, const float* alpha, const unsigned char* fold,
+                                 unsigned char* part, size_t part_bytes, bf16* o, hipStream_t st) {
+  const int g = lv->group_size, G = groups_of(C, g), pp = p * p, N = (H / p) * (W / p);
+  const bf16* Wf = reinterpret_cast<const bf16*>(fold);
+  const bf16* fb = reinterpret_cast<const bf16*>(fold + align_up((size_t)C * D * pp * 2));
   StageTimer tm(DCHAG_STAGE_TOKENIZE_ATTEND, st);
-  const bf16* v1 = be || ce ? fb : nullptr;
+  const bf16* v1 = token_bias ? fb : nullptr;
   const bf16* v2 = nullptr;
   const bf16* bv = static_cast<const bf16*>(lv->bv);
-  if (attend_ring_ok(p, W, D, heads, x, lv)) {
-    const size_t used = wf_bytes + vec_bytes;
+  if (attend_ring_ok(p, W, D, heads, x, lv))
     return launch_reduce_ring<true>(B, C, H, W, D, g, heads, x, Wf, nullptr, v1, v2, alpha, bv, o, st,
-                                    reinterpret_cast<float*>(fold + used), fold_bytes > used ? fold_bytes - used : 0);
-  }
+                                    reinterpret_cast<float*>(part), part_bytes);
   if (B > 65535 || G > 65535) return DCHAG_ERR_SHAPE;
   const int dh = D / heads, nhs = dh >= 256 ? 1 : 256 / dh;
   const size_t lds = (size_t)2 * 128 * (pp * 2 + 16) + (size_t)2 * nhs * 512;
@@ -473,7 +486,8 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
 template <typename T>
 int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
                         const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
-                        const int32_t* gs, void* out, unsigned char* ws, const FoldedWs& w, hipStream_t st) {
+                        const int32_t* gs, void* out, unsigned char* ws, const FoldedWs& w, hipStream_t st,
+                        const unsigned char* prefolded = nullptr) {
   const int N = (H / p) * (W / p);
   g_level = 0;
   int rc;
@@ -494,15 +508,25 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   if constexpr (std::is_same<T, bf16>::value) {
     // an attention first level straight from the pixels: scores through the composed score weights, values through
     // the folded tokenizer weights (which sit where the tokens would have been)
-    if (!first && use_px && attend_wide_ok(p, D, heads, &levels[0])) {
+    if (!first && values_from_pixels(dt, p, D, heads, &levels[0])) {
       g_level = 1;
       const KeptLevel kl = kept_level(dt, B, C, N, D, heads, gs[0], false, false);
       const LevelBufs<bf16> lb = level_bufs<bf16>(ws + w.level, kl);
       if ((rc = fast_scores(B, C, N, D, heads, &levels[0], nullptr, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, &px))) return rc;
-      if ((rc = attend_pixels_forward(B, C, H, W, p, D, heads, &levels[0], static_cast<const bf16*>(x),
-                                    static_cast<const bf16*>(We), static_cast<const bf16*>(be),
-                                    static_cast<const bf16*>(ce), lb.alpha_f, ws + w.tokens, w.ping - w.tokens, lb.o,
-                                    st)))
+      // the folded weights: the caller's (prepared once for fixed weights), else formed here, where the tokens would
+      // have been; what is left of that region takes partial sums
+      unsigned char* region = ws + w.tokens;
+      size_t used = 0;
+      const unsigned char* fold = prefolded;
+      if (!fold) {
+        if ((rc = fold_value_weights(C, p, D, &levels[0], static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+                                     static_cast<const bf16*>(ce), region, st)))
+          return rc;
+        fold = region;
+        used = value_fold_bytes(C, D, p * p);
+      }
+      if ((rc = attend_pixels_forward(B, C, H, W, p, D, heads, &levels[0], static_cast<const bf16*>(x), be || ce,
+                                      lb.alpha_f, fold, region + used, (w.ping - w.tokens) - used, lb.o, st)))
         return rc;
       bf16* zout = n_levels == 1 ? static_cast<bf16*>(out) : reinterpret_cast<bf16*>(ws + w.ping);
       {

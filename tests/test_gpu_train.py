@@ -211,6 +211,44 @@ def test_forward_folded_first_level_values_from_pixels_member_split(monkeypatch,
     assert err < TOL[d]
 
 
+@pytest.mark.parametrize("kw", PIXEL_VALUES)
+def test_forward_prefolded_equals_forward_folded(kw):
+    """The first level's weight-only products prepared once (dchag_fold_value) and two forward calls with them, the
+    second on another input: bit for bit the results of dchag_forward_folded, which forms them in every call."""
+    cfg = cfg_of(**kw)
+    say(f"forward_prefolded {kw}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    x, We, be, ce = dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d)
+    lv = [dev_level(l, d) for l in pr.levels]
+    folded = dchag.dchag_fold_value(We, be, ce, lv[0], cfg.p, cfg.heads)
+    assert folded is not None
+    for scale in (1.0, -0.5):
+        xs = (x.float() * scale).to(x.dtype)
+        got = dchag.dchag_forward_prefolded(xs, We, be, ce, lv, cfg.p, cfg.heads, folded)
+        want = dchag.dchag_forward_folded(xs, We, be, ce, lv, cfg.p, cfg.heads)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want)
+    ref = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads).reshape(cfg.B, cfg.N, cfg.D)
+    got = dchag.dchag_forward_prefolded(x, We, be, ce, lv, cfg.p, cfg.heads, folded)
+    assert rel_err(host(got), ref) < TOL[d]
+
+
+def test_forward_prefolded_rejects_shapes_without_a_fold():
+    """fp32, and patches of 2 x 2, have no first level taken from the pixels: nothing to prepare, and the prepared
+    call says so."""
+    for kw in (SMALL[0], SMALL[6]):
+        cfg = cfg_of(**kw)
+        pr = make_problem(cfg)
+        d = cfg.dtype
+        x, We, be, ce = dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d)
+        lv = [dev_level(l, d) for l in pr.levels]
+        assert dchag.dchag_fold_value(We, be, ce, lv[0], cfg.p, cfg.heads) is None
+        dummy = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+        with pytest.raises(dchag.DchagError):
+            dchag.dchag_forward_prefolded(x, We, be, ce, lv, cfg.p, cfg.heads, dummy)
+
+
 def test_forward_folded_without_biases_and_sharp_softmax():
     cfg = get_config("tiny")
     pr = make_problem(cfg, biases=False, query_scale=30.0)
