@@ -180,26 +180,30 @@ int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int 
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * dchag_forward_folded for callers whose weights stay fixed between calls (inference): the weight-only products of
- * its first level (paper Section 2.1's tokenizer and first cross-attention layer composed, see above),
+ * dchag_forward_folded for callers whose weights stay fixed between calls (inference).  Everything in that call
+ * that depends on the weights alone is formed once by dchag_fold_value into a caller-owned device buffer `folded`:
+ * the first level's folded tokenizer weights and token bias (paper Section 2.1's tokenizer and first cross-attention
+ * layer composed, see above),
  *
  *   Wf[c] = Wv[k(c)] We[c]   [C, D, p*p]      and      Wv[k(c)] (be[c] + ce[c])   [C, D],
  *
- * are formed once by dchag_fold_value into a caller-owned device buffer `folded` and then passed to every
- * dchag_forward_prefolded call, which is dchag_forward_folded without that part of the work (same arguments otherwise,
- * same result bit for bit; workspace which = 2).
+ * and, for every attention level, the projected query Q = Wq q + bq, the query folded into the key weights, and (first
+ * level) their composition with the tokenizer weights that scores the pixels directly.  dchag_forward_prefolded is
+ * dchag_forward_folded without that work (same arguments otherwise, same result bit for bit; workspace which = 2).
  *   dchag_value_fold_bytes: size of `folded` for a shape, 0 if dchag_forward_folded does not take that shape's first
- *     level from the pixels (then there is nothing to prepare: use dchag_forward_folded).  level0: the first level
- *     (host struct; only its kind and group size are read).
- *   dchag_fold_value: We, be, ce as in dchag_tokenize (be, ce may be NULL), level0 = levels[0]; folded 256-byte
- *     aligned, folded_bytes at least dchag_value_fold_bytes(...).  Asynchronous on `stream`.
- *   The caller redoes dchag_fold_value whenever We, be, ce or levels[0].Wv change; the library cannot check that.
+ *     level from the pixels (then there is nothing to prepare: use dchag_forward_folded).  levels: host array as in
+ *     dchag_forward (only kinds and group sizes are read).
+ *   dchag_fold_value: We, be, ce as in dchag_tokenize (be, ce may be NULL), levels as in dchag_forward; folded
+ *     256-byte aligned, folded_bytes at least dchag_value_fold_bytes(...).  Asynchronous on `stream`.
+ *   The caller redoes dchag_fold_value whenever a weight changes; the library cannot check that.
  * Errors: as dchag_forward; DCHAG_ERR_SHAPE for a shape with dchag_value_fold_bytes(...) == 0; DCHAG_ERR_WORKSPACE for
  * a NULL, misaligned or short `folded`.
  */
-size_t dchag_value_fold_bytes(dchag_dtype dt, int C, int p, int D, int heads, const dchag_level *level0);
+size_t dchag_value_fold_bytes(dchag_dtype dt, int C, int p, int D, int heads,
+                              int n_levels, const dchag_level *levels);
 int dchag_fold_value(dchag_dtype dt, int C, int p, int D, int heads,
-                     const void *We, const void *be, const void *ce, const dchag_level *level0,
+                     const void *We, const void *be, const void *ce,
+                     int n_levels, const dchag_level *levels,
                      void *folded, size_t folded_bytes, void *stream);
 int dchag_forward_prefolded(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads,
                             const void *x, const void *We, const void *be, const void *ce,

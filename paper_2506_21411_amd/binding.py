@@ -112,9 +112,9 @@ def load_library():
     lib.dchag_forward_folded.restype = i
     lib.dchag_forward_folded.argtypes = lib.dchag_forward.argtypes
     lib.dchag_value_fold_bytes.restype = sz
-    lib.dchag_value_fold_bytes.argtypes = [i] * 5 + [ctypes.POINTER(_CLevel)]
+    lib.dchag_value_fold_bytes.argtypes = [i] * 6 + [ctypes.POINTER(_CLevel)]
     lib.dchag_fold_value.restype = i
-    lib.dchag_fold_value.argtypes = [i] * 5 + [vp] * 3 + [ctypes.POINTER(_CLevel), vp, sz, vp]
+    lib.dchag_fold_value.argtypes = [i] * 5 + [vp] * 3 + [i, ctypes.POINTER(_CLevel), vp, sz, vp]
     lib.dchag_forward_prefolded.restype = i
     lib.dchag_forward_prefolded.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
     lib.dchag_backward.restype = i
@@ -288,21 +288,21 @@ def dchag_forward_folded(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.T
     return out
 
 
-def dchag_fold_value(We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor], level0: LevelWeights,
-                     p: int, heads: int, stream=None) -> Optional[torch.Tensor]:
-    """The weight-only products of dchag_forward_folded's first level, for dchag_forward_prefolded; None when the
-    library does not take that shape's first level from the pixels (dchag_value_fold_bytes == 0)."""
+def dchag_fold_value(We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],
+                     levels: List[LevelWeights], p: int, heads: int, stream=None) -> Optional[torch.Tensor]:
+    """Everything of dchag_forward_folded that depends on the weights alone, for dchag_forward_prefolded; None when
+    the library does not take that shape's first level from the pixels (dchag_value_fold_bytes == 0)."""
     C, D = We.shape[0], We.shape[1]
     if tuple(We.shape) != (C, D, p * p):
         raise ValueError("We must be [C, D, p*p]")
     dt = _dt(We)
     lib = load_library()
-    lv = _clevel(level0, We)
-    need = lib.dchag_value_fold_bytes(dt, C, p, D, heads, ctypes.byref(lv))
+    arr = (_CLevel * len(levels))(*[_clevel(lv, We) for lv in levels])
+    need = lib.dchag_value_fold_bytes(dt, C, p, D, heads, len(levels), arr)
     if need == 0:
         return None
     folded = _workspace(need, We.device)
-    _check(lib.dchag_fold_value(dt, C, p, D, heads, _ptr(We), _ptr(be, We), _ptr(ce, We), ctypes.byref(lv),
+    _check(lib.dchag_fold_value(dt, C, p, D, heads, _ptr(We), _ptr(be, We), _ptr(ce, We), len(levels), arr,
                                 ctypes.c_void_p(folded.data_ptr()), folded.numel(), _stream(stream)))
     return folded
 

@@ -368,26 +368,29 @@ bool pixel_scores_ok(int p, int heads) {
 // Qp, the folded keys in Mf / Mb and the softmax weights in alpha, laid out [B][G][gpad][heads][Np].
 // alpha_tm (optional): where the softmax weights are also wanted token-major [B,Cin,N,heads]; *tm_done tells whether
 // they were written (only the one-kernel pixel route does it; otherwise the caller re-lays alpha).
+// phase: 0 = everything; 1 = the weight-only prep alone (Qp, Mf, Mb and, with px, its composed score weights; B, N, zin
+// and alpha are not used); 2 = scores and softmax alone, from a prep that is already in those buffers.
 int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, float* Qp, float* Mf,
                 bf16* Mb, float* alpha, hipStream_t st, const PixelScores* px, float* alpha_tm = nullptr,
-                bool* tm_done = nullptr) {
+                bool* tm_done = nullptr, int phase = 0) {
   if (tm_done) *tm_done = false;
   const int g = lv->group_size;
   const int G = groups_of(Cin, g);
   const int gpad = round_up(g, 8), Np = round_up(N, 32);
   int rc;
-  {
+  if (phase != 2) {
     StageTimer tm(DCHAG_STAGE_QUERY, st);
     k_project_query<bf16><<<dim3((D + 3) / 4, G), 256, 0, st>>>(
         D, static_cast<const bf16*>(lv->query), static_cast<const bf16*>(lv->Wq), static_cast<const bf16*>(lv->bq), Qp);
     if ((rc = launch_status())) return rc;
   }
-  {
+  if (phase != 2) {
     StageTimer tm(DCHAG_STAGE_FOLD, st);
     k_fold_query_into_key<bf16><<<dim3((D + 63) / 64, heads, G), 256, 0, st>>>(
         D, heads, static_cast<const bf16*>(lv->Wk), Qp, Mf, Mb, px ? px->MfT : nullptr);
     if ((rc = launch_status())) return rc;
   }
+  if (phase == 1 && !px) return DCHAG_OK;
   if (px) {
     StageTimer tm(DCHAG_STAGE_SCORES, st);
     const int pp = px->p * px->p;
@@ -395,7 +398,7 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     // the vector-ALU kernel): pp = 16 .. 128 in blocks of 8 pixels, groups that are multiples of the block's channels
     const int cpb = (pp == 16 || pp == 32 || pp == 64 || pp == 128) ? 16 / (pp / 8) : 0;
     const bool compose_mfma = cpb > 0 && g % cpb == 0 && D % 128 == 0 && heads <= 32 && !getenv("DCHAG_COMPOSE_VALU");
-    if (compose_mfma) {
+    if (compose_mfma && phase != 2) {
       const dim3 cgrid((unsigned)((Cin + cpb - 1) / cpb));
       if (heads <= 16)
         k_compose_score_weights_mfma<1><<<cgrid, 256, 0, st>>>(Cin, D, heads, pp, g, Mf, px->We, px->be, px->ce, px->Ms,
@@ -414,10 +417,11 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(compose), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)clds) != hipSuccess)
       return DCHAG_ERR_LAUNCH;
-    if (!compose_mfma) {
+    if (!compose_mfma && phase != 2) {
       compose<<<dim3(Cin), 256, clds, st>>>(D, heads, pp, g, DQ, px->MfT, px->We, px->be, px->ce, px->Ms, px->Msb, px->cs);
       if ((rc = launch_status())) return rc;
     }
+    if (phase == 1) return DCHAG_OK;
     // scores and softmax in one kernel while a group's scores of 32 patches fit LDS (DCHAG_PIXEL_SCORES_TWO_KERNELS,
     // a debugging aid, keeps them apart)
     const size_t slds = (size_t)std::min(g, Cin) * heads * 33 * 4;
@@ -923,27 +927,42 @@ int dchag_forward_folded(dchag_dtype dt, int B, int C, int H, int W, int p, int 
   return forward_folded_impl<bf16>(dt, B, C, H, W, p, D, heads, x, We, be, ce, n_levels, levels, gs, out, ws, w, st);
 }
 
-size_t dchag_value_fold_bytes(dchag_dtype dt, int C, int p, int D, int heads, const dchag_level* level0) {
-  if (!level0 || C < 1 || p < 1 || D < 1 || heads < 1 || D % heads || level0->group_size < 1) return 0;
-  if (!values_from_pixels(dt, p, D, heads, level0)) return 0;
-  return value_fold_bytes(C, D, p * p);
+// Shared checks of the two calls that size and fill a prepared buffer: the chain of levels and its first level's route.
+static int check_prepare(dchag_dtype dt, int C, int p, int D, int heads, int n_levels, const dchag_level* levels) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
+  if (!levels) return DCHAG_ERR_NULL;
+  if (n_levels < 1 || n_levels > 16 || C < 1 || p < 1 || p > 64 || D < 1 || heads < 1 || D % heads ||
+      (long)C * D * p * p > (1L << 40))
+    return DCHAG_ERR_SHAPE;
+  int c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    if (levels[l].group_size < 1 || (levels[l].kind != DCHAG_LEVEL_ATTENTION && levels[l].kind != DCHAG_LEVEL_LINEAR))
+      return DCHAG_ERR_SHAPE;
+    c_in = groups_of(c_in, levels[l].group_size);
+  }
+  if (c_in != 1 || levels[n_levels - 1].kind != DCHAG_LEVEL_ATTENTION) return DCHAG_ERR_SHAPE;
+  return values_from_pixels(dt, p, D, heads, &levels[0]) ? DCHAG_OK : DCHAG_ERR_SHAPE;
+}
+
+size_t dchag_value_fold_bytes(dchag_dtype dt, int C, int p, int D, int heads, int n_levels, const dchag_level* levels) {
+  if (check_prepare(dt, C, p, D, heads, n_levels, levels)) return 0;
+  return prepared_layout(C, p * p, D, heads, n_levels, levels).total;
 }
 
 int dchag_fold_value(dchag_dtype dt, int C, int p, int D, int heads, const void* We, const void* be, const void* ce,
-                     const dchag_level* level0, void* folded, size_t folded_bytes, void* stream) {
-  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
-  if (!We || !level0 || !folded) return DCHAG_ERR_NULL;
-  int rc = check_level(level0);
-  if (rc) return rc;
-  if (C < 1 || p < 1 || D < 1 || heads < 1 || D % heads || (long)C * D * p * p > (1L << 40)) return DCHAG_ERR_SHAPE;
-  const size_t need = dchag_value_fold_bytes(dt, C, p, D, heads, level0);
-  if (need == 0) return DCHAG_ERR_SHAPE;                 // a shape whose first level is not taken from the pixels
+                     int n_levels, const dchag_level* levels, void* folded, size_t folded_bytes, void* stream) {
+  int rc = check_prepare(dt, C, p, D, heads, n_levels, levels);
+  if (rc) return rc;                                     // DCHAG_ERR_SHAPE: nothing to prepare for this shape
+  if (!We || !folded) return DCHAG_ERR_NULL;
+  for (int l = 0; l < n_levels; ++l)
+    if ((rc = check_level(&levels[l]))) return rc;
   if (misaligned(We) || misaligned(be) || misaligned(ce)) return DCHAG_ERR_ALIGN;
-  if ((reinterpret_cast<uintptr_t>(folded) & (kAlign - 1)) || folded_bytes < need) return DCHAG_ERR_WORKSPACE;
-  g_level = 1;
-  return fold_value_weights(C, p, D, level0, static_cast<const bf16*>(We), static_cast<const bf16*>(be),
-                            static_cast<const bf16*>(ce), static_cast<unsigned char*>(folded),
-                            static_cast<hipStream_t>(stream));
+  if ((reinterpret_cast<uintptr_t>(folded) & (kAlign - 1)) ||
+      folded_bytes < prepared_layout(C, p * p, D, heads, n_levels, levels).total)
+    return DCHAG_ERR_WORKSPACE;
+  // the patch size stands in for the image size: the prep reads weights only
+  return prepare_folded(C, p, p, p, D, heads, We, be, ce, n_levels, levels, static_cast<unsigned char*>(folded),
+                        static_cast<hipStream_t>(stream));
 }
 
 int dchag_forward_prefolded(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,

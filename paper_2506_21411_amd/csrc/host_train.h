@@ -286,10 +286,10 @@ int generic_alpha(int B, int Cin, int N, int D, int heads, const dchag_level* lv
 
 // alpha of one level through the score kernels of the bf16 forward path, then re-laid token-major.
 inline int fast_alpha(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin,
-                      const LevelBufs<bf16>& lb, hipStream_t st, const PixelScores* px) {
+                      const LevelBufs<bf16>& lb, hipStream_t st, const PixelScores* px, int phase = 0) {
   const int g = lv->group_size, G = groups_of(Cin, g);
   bool tm_done = false;
-  int rc = fast_scores(B, Cin, N, D, heads, lv, zin, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, px, lb.alpha, &tm_done);
+  int rc = fast_scores(B, Cin, N, D, heads, lv, zin, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, px, lb.alpha, &tm_done, phase);
   if (rc || tm_done) return rc;
   StageTimer tm(DCHAG_STAGE_SCORES, st);
   const long total = (long)B * Cin * N * heads;
@@ -326,15 +326,16 @@ inline int oproj(int B, int D, RowBlocks rb, const bf16* o, const bf16* Wo, cons
 }
 
 // One attention level evaluated as  alpha -> u -> o -> y  (y skipped when zout is NULL).  px: the first
-// level of the bf16 path may take its scores from the pixels.
+// level of the bf16 path may take its scores from the pixels.  phase = 2: the level's weight-only prep (projected
+// query, folded keys) is already in lb (bf16 score-kernel path only).
 template <typename T>
 int folded_level_forward(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dchag_level* lv, const T* zin,
-                         T* zout, const LevelBufs<T>& lb, hipStream_t st, const PixelScores* px) {
+                         T* zout, const LevelBufs<T>& lb, hipStream_t st, const PixelScores* px, int phase = 0) {
   const int g = lv->group_size, G = groups_of(Cin, g), dh = D / heads;
   const T* Wv = static_cast<const T*>(lv->Wv);
   int rc;
   if constexpr (std::is_same<T, bf16>::value) {
-    if (train_fast(dt, D, heads)) rc = fast_alpha(B, Cin, N, D, heads, lv, zin, lb, st, px);
+    if (train_fast(dt, D, heads)) rc = fast_alpha(B, Cin, N, D, heads, lv, zin, lb, st, px, phase);
     else rc = generic_alpha<T>(B, Cin, N, D, heads, lv, zin, lb, st);
   } else {
     rc = generic_alpha<T>(B, Cin, N, D, heads, lv, zin, lb, st);
@@ -483,6 +484,61 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
   return launch_status();
 }
 
+// What dchag_fold_value leaves in the caller's buffer: the folded tokenizer weights and token bias of the first level,
+// then every attention level's weight-only prep (projected query, folded keys fp32 + bf16) and the first level's composed
+// score weights.
+struct PreparedLayout {
+  size_t fold, qp[16], mf[16], mb[16], ms, msb, cs, mft, total;
+};
+inline PreparedLayout prepared_layout(int C, int pp, int D, int heads, int n_levels, const dchag_level* levels) {
+  PreparedLayout L{};
+  size_t off = 0;
+  L.fold = off; off += value_fold_bytes(C, D, pp);
+  int c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    const int G = groups_of(c_in, levels[l].group_size);
+    if (levels[l].kind != DCHAG_LEVEL_LINEAR) {
+      L.qp[l] = off; off += align_up((size_t)G * D * 4);
+      L.mf[l] = off; off += align_up((size_t)G * heads * D * 4);
+      L.mb[l] = off; off += align_up((size_t)G * heads * D * 2);
+    }
+    c_in = G;
+  }
+  off = pixel_scratch(off, C, pp, D, heads, groups_of(C, levels[0].group_size), &L.ms, &L.msb, &L.cs, &L.mft);
+  L.total = off;
+  return L;
+}
+// The pieces of level l inside a prepared buffer, in the form the level code takes them.
+inline void use_prepared(const unsigned char* pf, const PreparedLayout& L, int l, LevelBufs<bf16>& lb) {
+  unsigned char* q = const_cast<unsigned char*>(pf);     // read only from here on (phase 2 of the score code)
+  lb.Qp = reinterpret_cast<float*>(q + L.qp[l]);
+  lb.Mf = reinterpret_cast<float*>(q + L.mf[l]);
+  lb.Mb = reinterpret_cast<bf16*>(q + L.mb[l]);
+}
+inline int prepare_folded(int C, int H, int W, int p, int D, int heads, const void* We, const void* be, const void* ce,
+                          int n_levels, const dchag_level* levels, unsigned char* pf, hipStream_t st) {
+  const PreparedLayout L = prepared_layout(C, p * p, D, heads, n_levels, levels);
+  int rc;
+  g_level = 1;
+  if ((rc = fold_value_weights(C, p, D, &levels[0], static_cast<const bf16*>(We), static_cast<const bf16*>(be),
+                               static_cast<const bf16*>(ce), pf + L.fold, st)))
+    return rc;
+  const PixelScores px = pixel_scores_of<bf16>(nullptr, We, be, ce, H, W, p, pf, L.ms, L.msb, L.cs, L.mft);
+  int c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    g_level = l + 1;
+    if (levels[l].kind != DCHAG_LEVEL_LINEAR) {
+      LevelBufs<bf16> lb{};
+      use_prepared(pf, L, l, lb);
+      if ((rc = fast_scores(1, c_in, 1, D, heads, &levels[l], nullptr, lb.Qp, lb.Mf, lb.Mb, nullptr, st,
+                            l == 0 ? &px : nullptr, nullptr, nullptr, 1)))
+        return rc;
+    }
+    c_in = groups_of(c_in, levels[l].group_size);
+  }
+  return DCHAG_OK;
+}
+
 template <typename T>
 int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int heads, const void* x,
                         const void* We, const void* be, const void* ce, int n_levels, const dchag_level* levels,
@@ -505,19 +561,29 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   }
   const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
+  PreparedLayout PL{};
+  if (prefolded) PL = prepared_layout(C, p * p, D, heads, n_levels, levels);
   if constexpr (std::is_same<T, bf16>::value) {
     // an attention first level straight from the pixels: scores through the composed score weights, values through
     // the folded tokenizer weights (which sit where the tokens would have been)
     if (!first && values_from_pixels(dt, p, D, heads, &levels[0])) {
       g_level = 1;
       const KeptLevel kl = kept_level(dt, B, C, N, D, heads, gs[0], false, false);
-      const LevelBufs<bf16> lb = level_bufs<bf16>(ws + w.level, kl);
-      if ((rc = fast_scores(B, C, N, D, heads, &levels[0], nullptr, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, &px))) return rc;
+      LevelBufs<bf16> lb = level_bufs<bf16>(ws + w.level, kl);
+      PixelScores px0 = px;
+      if (prefolded) {                                   // the level's weight-only prep comes with the folded weights
+        use_prepared(prefolded, PL, 0, lb);
+        px0 = pixel_scores_of<bf16>(x, We, be, ce, H, W, p, const_cast<unsigned char*>(prefolded), PL.ms, PL.msb, PL.cs,
+                                    PL.mft);
+      }
+      if ((rc = fast_scores(B, C, N, D, heads, &levels[0], nullptr, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, &px0, nullptr,
+                            nullptr, prefolded ? 2 : 0)))
+        return rc;
       // the folded weights: the caller's (prepared once for fixed weights), else formed here, where the tokens would
       // have been; what is left of that region takes partial sums
       unsigned char* region = ws + w.tokens;
       size_t used = 0;
-      const unsigned char* fold = prefolded;
+      const unsigned char* fold = prefolded ? prefolded + PL.fold : nullptr;
       if (!fold) {
         if ((rc = fold_value_weights(C, p, D, &levels[0], static_cast<const bf16*>(We), static_cast<const bf16*>(be),
                                      static_cast<const bf16*>(ce), region, st)))
@@ -549,8 +615,16 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
       rc = run_level_linear<T>(B, c_in, N, D, &levels[l], zin, zout, st);
     else {
       const KeptLevel kl = kept_level(dt, B, c_in, N, D, heads, gs[l], false, false);
-      rc = folded_level_forward<T>(dt, B, c_in, N, D, heads, &levels[l], zin, zout, level_bufs<T>(ws + w.level, kl), st,
-                                   (l == 0 && use_px) ? &px : nullptr);
+      LevelBufs<T> lb = level_bufs<T>(ws + w.level, kl);
+      int phase = 0;
+      if constexpr (std::is_same<T, bf16>::value) {
+        if (prefolded && l > 0 && train_fast(dt, D, heads)) {
+          use_prepared(prefolded, PL, l, lb);
+          phase = 2;
+        }
+      }
+      rc = folded_level_forward<T>(dt, B, c_in, N, D, heads, &levels[l], zin, zout, lb, st,
+                                   (l == 0 && use_px) ? &px : nullptr, phase);
     }
     if (rc) return rc;
     zin = zout;

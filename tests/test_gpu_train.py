@@ -213,15 +213,15 @@ def test_forward_folded_first_level_values_from_pixels_member_split(monkeypatch,
 
 @pytest.mark.parametrize("kw", PIXEL_VALUES)
 def test_forward_prefolded_equals_forward_folded(kw):
-    """The first level's weight-only products prepared once (dchag_fold_value) and two forward calls with them, the
-    second on another input: bit for bit the results of dchag_forward_folded, which forms them in every call."""
+    """Everything that depends on the weights alone prepared once (dchag_fold_value) and two forward calls with it, the
+    second on another input: bit for bit the results of dchag_forward_folded, which forms it in every call."""
     cfg = cfg_of(**kw)
     say(f"forward_prefolded {kw}")
     pr = make_problem(cfg)
     d = cfg.dtype
     x, We, be, ce = dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d)
     lv = [dev_level(l, d) for l in pr.levels]
-    folded = dchag.dchag_fold_value(We, be, ce, lv[0], cfg.p, cfg.heads)
+    folded = dchag.dchag_fold_value(We, be, ce, lv, cfg.p, cfg.heads)
     assert folded is not None
     for scale in (1.0, -0.5):
         xs = (x.float() * scale).to(x.dtype)
@@ -243,7 +243,7 @@ def test_forward_prefolded_rejects_shapes_without_a_fold():
         d = cfg.dtype
         x, We, be, ce = dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d)
         lv = [dev_level(l, d) for l in pr.levels]
-        assert dchag.dchag_fold_value(We, be, ce, lv[0], cfg.p, cfg.heads) is None
+        assert dchag.dchag_fold_value(We, be, ce, lv, cfg.p, cfg.heads) is None
         dummy = torch.zeros(4096, dtype=torch.uint8, device="cuda")
         with pytest.raises(dchag.DchagError):
             dchag.dchag_forward_prefolded(x, We, be, ce, lv, cfg.p, cfg.heads, dummy)
