@@ -234,6 +234,25 @@ def test_forward_prefolded_equals_forward_folded(kw):
     assert rel_err(host(got), ref) < TOL[d]
 
 
+@pytest.mark.parametrize("name", ["hyperspectral", "weather", "hyperspectral_flat", "deep1000"])
+def test_forward_prefolded_full_size_equals_forward_folded(name):
+    """The same equality at the benchmark's sizes and launch configurations (the folded call itself is checked against
+    the oracle on sampled patches above)."""
+    cfg = get_config(name)
+    say(f"forward_prefolded full-size {name}")
+    pr = make_problem(cfg)
+    d = cfg.dtype
+    x, We, be, ce = dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d)
+    lv = [dev_level(l, d) for l in pr.levels]
+    folded = dchag.dchag_fold_value(We, be, ce, lv, cfg.p, cfg.heads)
+    assert folded is not None
+    got = dchag.dchag_forward_prefolded(x, We, be, ce, lv, cfg.p, cfg.heads, folded)
+    want = dchag.dchag_forward_folded(x, We, be, ce, lv, cfg.p, cfg.heads)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    assert torch.isfinite(got.float()).all()
+
+
 def test_forward_prefolded_rejects_shapes_without_a_fold():
     """fp32, and patches of 2 x 2, have no first level taken from the pixels: nothing to prepare, and the prepared
     call says so."""
