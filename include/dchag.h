@@ -17,7 +17,13 @@
  *     accumulation is always fp32.  The `dchag_level` structs themselves live
  *     in HOST memory and hold device pointers.
  *   - The caller owns every buffer (inputs, weights, outputs, workspace).  The
- *     library allocates no device memory and keeps no state between calls.
+ *     library allocates no device memory and keeps no state between calls that
+ *     changes a result.  Process-wide state, all of it listed here: the table of
+ *     debugging switches read from the environment at load time (dchag_debug_reload),
+ *     per-device caches of the compute-unit count and of the dynamic-LDS limits
+ *     already raised (both mutex- or atomic-guarded), and the stage-timing records of
+ *     dchag_profile_begin/end.  Calls on different host threads are safe as
+ *     long as they do not share a workspace and no profile is being taken.
  *     Inputs and weights are only read; outputs are fully overwritten; the
  *     workspace contents are undefined afterwards.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -288,9 +294,8 @@ size_t dchag_workspace_bytes(dchag_dtype dt, int B, int C, int H, int W, int p, 
  * dchag_profile_begin and dchag_profile_end every kernel the library launches is bracketed
  * by a pair of HIP events recorded on the call's own stream; dchag_profile_end waits for the
  * recorded events, writes up to `cap` records in launch order and returns how many there
- * were in total (or a negative status).  This is the only process-wide state of the
- * library; it is not thread-safe and it creates HIP events, so it must not be used under
- * stream capture.  `records` is HOST memory.
+ * were in total (or a negative status).  It is not thread-safe and it creates HIP events,
+ * so it must not be used under stream capture.  `records` is HOST memory.
  */
 typedef enum {
   DCHAG_STAGE_TOKENIZE = 0,        /* per-channel patch embedding                              */
@@ -300,7 +305,8 @@ typedef enum {
   DCHAG_STAGE_VPROJ = 4,           /* value projection                                         */
   DCHAG_STAGE_SOFTMAX_AGG = 5,     /* softmax over the group and weighted sum of the values    */
   DCHAG_STAGE_OPROJ = 6,           /* output projection                                        */
-  DCHAG_STAGE_FUSED_VAGG = 7,      /* value projection + scores + online softmax + sum, fused  */
+  DCHAG_STAGE_FUSED_VAGG = 7,      /* value projection with the softmax-weighted sum over the
+                                      group in its epilogue (weights computed beforehand)      */
   DCHAG_STAGE_CHANNEL_MIX = 8,     /* linear (D-CHAG-L) level: weighted sum over the group      */
   DCHAG_STAGE_TOKENIZE_MIX = 9,    /* tokenizer fused with a linear first level                 */
   DCHAG_STAGE_HEAD_SUMS = 10,      /* per-head softmax-weighted token averages u_a              */
@@ -324,6 +330,14 @@ typedef struct {
 
 int dchag_profile_begin(void);
 int dchag_profile_end(dchag_stage_time *records, int cap);
+
+/*
+ * Debugging switches.  The library reads a set of DCHAG_* environment variables (kernel-route overrides used by its
+ * tests) ONCE, when it is loaded; calls never read the environment.  dchag_debug_reload reads them again.  It is a
+ * test aid, not thread-safe, and must not run while another thread is inside a call; change a switch that alters how
+ * work is split (and with it workspace sizes) only between a dchag_workspace_bytes / call pair, never inside one.
+ */
+void dchag_debug_reload(void);
 
 /* Static, never-NULL description of a status code. */
 const char *dchag_strerror(int status);

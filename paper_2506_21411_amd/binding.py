@@ -105,6 +105,8 @@ def load_library():
     lib.dchag_tokenize.argtypes = [i] * 7 + [vp] * 6
     lib.dchag_aggregate_level.restype = i
     lib.dchag_aggregate_level.argtypes = [i] * 6 + [ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
+    lib.dchag_debug_reload.restype = None
+    lib.dchag_debug_reload.argtypes = []
     lib.dchag_forward.restype = i
     lib.dchag_forward.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, sz, vp]
     lib.dchag_forward_pos.restype = i
@@ -215,6 +217,11 @@ def dchag_aggregate_level(tokens_in: torch.Tensor, level: LevelWeights, heads: i
                                                 _ptr(out, tokens_in), ctypes.c_void_p(workspace.data_ptr()),
                                                 workspace.numel(), _stream(stream)))
     return out
+
+
+def dchag_debug_reload() -> None:
+    """Re-read the DCHAG_* debugging switches from the environment (the library reads them once, at load)."""
+    load_library().dchag_debug_reload()
 
 
 def dchag_forward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor], ce: Optional[torch.Tensor],

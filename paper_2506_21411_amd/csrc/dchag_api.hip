@@ -8,7 +8,10 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 #include <type_traits>
+#include <unordered_map>
 #include <vector>
 
 #include "dchag_dev.h"
@@ -20,6 +23,83 @@
 using namespace dchag;
 
 namespace {
+
+// Debugging switches (environment variables DCHAG_*): read ONCE, when the library is loaded, into this table; the
+// calls only look the table up, so the environment of a running process cannot change how a call and the
+// dchag_workspace_bytes that sized its workspace split the work.  dchag_debug_reload() reads them again (tests).
+enum Switch {
+  SW_COLSUM,
+  SW_COMPOSE_VALU,
+  SW_DZ_PT,
+  SW_DZ_VALU,
+  SW_FIRST_LEVEL_REGS,
+  SW_FIRST_LEVEL_SPLIT,
+  SW_FOLD_VALUE_GEMM,
+  SW_GEMM,
+  SW_GEMM_GENERIC,
+  SW_GEMM_SCALAR_STORES,
+  SW_GENERIC_LEVEL,
+  SW_GENERIC_TOKENIZE,
+  SW_LINEAR_TOKENS,
+  SW_MFMA_TILE,
+  SW_MIX_NARROW,
+  SW_PIXEL_SCORES_TWO_KERNELS,
+  SW_RING_SHAPE,
+  SW_RPART_VALU,
+  SW_SCORES_ONE_KERNEL,
+  SW_SCORES_PER_QUAD,
+  SW_TOKENIZE_PER_TILE,
+  SW_TOKENS_UNFUSED,
+  SW_TOKEN_SCORES,
+  SW_VAGG_SPLIT,
+  SW_VALUE_UNFOLDED,
+  SW_COUNT
+};
+struct SwitchTable {
+  bool set[SW_COUNT];
+  char value[SW_COUNT][16];
+  void read() {
+    static const char* const names[SW_COUNT] = {
+    "DCHAG_COLSUM",
+    "DCHAG_COMPOSE_VALU",
+    "DCHAG_DZ_PT",
+    "DCHAG_DZ_VALU",
+    "DCHAG_FIRST_LEVEL_REGS",
+    "DCHAG_FIRST_LEVEL_SPLIT",
+    "DCHAG_FOLD_VALUE_GEMM",
+    "DCHAG_GEMM",
+    "DCHAG_GEMM_GENERIC",
+    "DCHAG_GEMM_SCALAR_STORES",
+    "DCHAG_GENERIC_LEVEL",
+    "DCHAG_GENERIC_TOKENIZE",
+    "DCHAG_LINEAR_TOKENS",
+    "DCHAG_MFMA_TILE",
+    "DCHAG_MIX_NARROW",
+    "DCHAG_PIXEL_SCORES_TWO_KERNELS",
+    "DCHAG_RING_SHAPE",
+    "DCHAG_RPART_VALU",
+    "DCHAG_SCORES_ONE_KERNEL",
+    "DCHAG_SCORES_PER_QUAD",
+    "DCHAG_TOKENIZE_PER_TILE",
+    "DCHAG_TOKENS_UNFUSED",
+    "DCHAG_TOKEN_SCORES",
+    "DCHAG_VAGG_SPLIT",
+    "DCHAG_VALUE_UNFOLDED"};
+    for (int i = 0; i < SW_COUNT; ++i) {
+      const char* e = getenv(names[i]);
+      set[i] = e != nullptr;
+      value[i][0] = 0;
+      if (e) {
+        strncpy(value[i], e, sizeof(value[i]) - 1);
+        value[i][sizeof(value[i]) - 1] = 0;
+      }
+    }
+  }
+  SwitchTable() { read(); }
+};
+SwitchTable g_switches;
+// The value of a switch, or nullptr when it is not set.
+inline const char* dbg(Switch s) { return g_switches.set[s] ? g_switches.value[s] : nullptr; }
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -54,7 +134,7 @@ int vagg_splits(int B, int Cin, int N, int D, int g) {
   const int nch_min = (std::min(g, last) + 7) / 8;
   const long items = (long)(D / 256) * ((N + 31) / 32) * B * G;
   int S = 1;
-  if (const char* e = getenv("DCHAG_VAGG_SPLIT")) S = std::max(1, atoi(e));
+  if (const char* e = dbg(SW_VAGG_SPLIT)) S = std::max(1, atoi(e));
   else while (items * S < 2L * compute_units() && S < 8) S *= 2;
   while (S > nch_min) S >>= 1;
   return std::max(S, 1);
@@ -63,7 +143,7 @@ int vagg_splits(int B, int Cin, int N, int D, int g) {
 LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g) {
   const int G = groups_of(Cin, g);
   const size_t es = elem_size(dt);
-  const bool fast = fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL");
+  const bool fast = fast_level(dt, D, heads) && !dbg(SW_GENERIC_LEVEL);
   LevelWs w{};
   size_t off = 0;
   w.qp = off; off += align_up((size_t)G * D * 4);
@@ -131,6 +211,10 @@ struct StageRecord {
 bool g_profiling = false;
 int g_level = 0;
 std::vector<StageRecord> g_records;
+// The level a stage record is filed under; written only while a profile is being taken.
+inline void set_level(int level) {
+  if (g_profiling) g_level = level;
+}
 
 struct StageTimer {
   hipStream_t st;
@@ -153,22 +237,37 @@ struct StageTimer {
   }
 };
 
+// Compute units of the CURRENT device (looked up once per device; 256 without a device).
+constexpr int kMaxDevices = 64;
 int compute_units() {
-  static int cus = 0;
-  if (!cus) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n >= kXcds)
-      cus = n;
-    else
-      cus = 256;
-  }
-  return cus;
+  static std::atomic<int> cus[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  int n = cus[dev].load(std::memory_order_relaxed);
+  if (n) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds) n = 256;
+  cus[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
+// Raises a kernel's dynamic-LDS limit to at least `bytes`, once per (device, kernel): later launches only look the
+// table up.  Returns 0 or DCHAG_ERR_LAUNCH.
+int ensure_dynamic_lds(const void* kernel, int bytes) {
+  static std::mutex mu;
+  static std::unordered_map<const void*, int> done[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DCHAG_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = done[dev].find(kernel);
+  if (it != done[dev].end() && it->second >= bytes) return DCHAG_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return DCHAG_ERR_LAUNCH;
+  done[dev][kernel] = bytes;
+  return DCHAG_OK;
 }
 
 bool force_generic() {
   // DCHAG_GEMM=generic routes the bf16 projections through the fp32-FMA tile kernel (debug aid).
-  const char* e = getenv("DCHAG_GEMM");
+  const char* e = dbg(SW_GEMM);
   return e && strcmp(e, "generic") == 0;
 }
 
@@ -191,7 +290,7 @@ int launch_tokenize_mfma(int B, int C, int H, int W, int p, int D, const bf16* x
                          const bf16* ce, bf16* tokens, hipStream_t st) {
   const int N = (H / p) * (W / p);
   const int ks = p * p / 16;
-  if ((ks == 1 || ks == 2 || ks == 4) && p * p == 16 * ks && D % 256 == 0 && !getenv("DCHAG_TOKENIZE_PER_TILE")) {
+  if ((ks == 1 || ks == 2 || ks == 4) && p * p == 16 * ks && D % 256 == 0 && !dbg(SW_TOKENIZE_PER_TILE)) {
     // weight-stationary form: enough blocks for about eight per compute unit, each walking `per` tiles
     const int T = B * ((N + 127) / 128);
     const long base = (long)(D / 256) * C;
@@ -201,18 +300,14 @@ int launch_tokenize_mfma(int B, int C, int H, int W, int p, int D, const bf16* x
     ts = (T + per - 1) / per;
     const size_t wlds = (size_t)2 * 128 * (p * p * 2 + 16);
     auto wk = ks == 1 ? k_tokenize_ws<1> : ks == 2 ? k_tokenize_ws<2> : k_tokenize_ws<4>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(wk), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)wlds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(wk), (int)wlds)) return DCHAG_ERR_LAUNCH;
     StageTimer tm(DCHAG_STAGE_TOKENIZE, st);
     wk<<<dim3(D / 256, C, ts), 256, wlds, st>>>(B, C, H, W, p, D, per, x, We, be, ce, tokens);
     return launch_status();
   }
   const size_t lds = (size_t)128 * (p * p * 2 + 16);
   auto kern = ks == 1 ? k_tokenize_mfma<1> : ks == 2 ? k_tokenize_mfma<2> : ks == 4 ? k_tokenize_mfma<4> : k_tokenize_mfma<0>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          (int)lds) != hipSuccess)
-    return DCHAG_ERR_LAUNCH;
+  if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds)) return DCHAG_ERR_LAUNCH;
   StageTimer tm(DCHAG_STAGE_TOKENIZE, st);
   kern<<<dim3((N + 127) / 128, C, B), 256, lds, st>>>(C, H, W, p, D, x, We, be, ce, tokens);
   return launch_status();
@@ -237,20 +332,14 @@ int launch_linear_mfma_cfg(int B, int D, RowBlocks rb, const bf16* A, const bf16
   const int per = (tw.total + kXcds - 1) / kXcds;
   const size_t lds = (size_t)2 * (BM + BN) * 128;
   auto kern = k_linear_mfma<BM, BN, WM, WN, SH>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
-    attr_set = true;
-  }
+  if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds)) return DCHAG_ERR_LAUNCH;
   kern<<<dim3(per * kXcds), dim3(WM * WN * 64), lds, st>>>(D, rb, tw, A, Wt, bias, Y, rowadd);
   return launch_status();
 }
 
 int mfma_variant() {
   // DCHAG_MFMA_TILE selects the block tiling of the bf16 projection kernel (tuning aid).
-  const char* e = getenv("DCHAG_MFMA_TILE");
+  const char* e = dbg(SW_MFMA_TILE);
   return e ? atoi(e) : 0;
 }
 
@@ -340,9 +429,7 @@ int launch_linear_dl(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, 
   if (tw.total * 2 < compute_units())                    // too few 256x256 tiles to fill the chip: 128x128 tiles
     return launch_linear_mfma_cfg<128, 128, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st, rowadd);
   const int per = (tw.total + kXcds - 1) / kXcds;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_linear_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          kGemmRingBytes) != hipSuccess)
-    return DCHAG_ERR_LAUNCH;
+  if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_linear_dl), kGemmRingBytes)) return DCHAG_ERR_LAUNCH;
   k_linear_dl<<<dim3(per * kXcds), dim3(512), kGemmRingBytes, st>>>(D, rb, tw, A, Wt, bias, Y, rowadd);
   return launch_status();
 }
@@ -361,7 +448,7 @@ struct PixelScores {
 bool pixel_scores_ok(int p, int heads) {
   const int pp = p * p;
   return heads % 4 == 0 && heads <= 32 && pp % 16 == 0 && (p == 4 || p % 8 == 0) && (heads / 4) * (pp / 4) <= 256 &&
-         pp <= 256 && !getenv("DCHAG_TOKEN_SCORES");
+         pp <= 256 && !dbg(SW_TOKEN_SCORES);
 }
 
 // Weight-only prep, scores and softmax of one level on the bf16 MFMA path: leaves the projected query in
@@ -397,7 +484,7 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     // MFMA form of the weight composition where the shape allows it (DCHAG_COMPOSE_VALU, a debugging aid, keeps
     // the vector-ALU kernel): pp = 16 .. 128 in blocks of 8 pixels, groups that are multiples of the block's channels
     const int cpb = (pp == 16 || pp == 32 || pp == 64 || pp == 128) ? 16 / (pp / 8) : 0;
-    const bool compose_mfma = cpb > 0 && g % cpb == 0 && D % 128 == 0 && heads <= 32 && !getenv("DCHAG_COMPOSE_VALU");
+    const bool compose_mfma = cpb > 0 && g % cpb == 0 && D % 128 == 0 && heads <= 32 && !dbg(SW_COMPOSE_VALU);
     if (compose_mfma && phase != 2) {
       const dim3 cgrid((unsigned)((Cin + cpb - 1) / cpb));
       if (heads <= 16)
@@ -414,9 +501,7 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     while (D % DQ) DQ >>= 1;
     const size_t clds = (size_t)DQ * (pp * 2 + heads * 4 + 4) + (size_t)3 * TPL * 64 * 20 * 4;
     auto compose = TPL == 1 ? k_compose_score_weights<1> : (TPL == 2 ? k_compose_score_weights<2> : k_compose_score_weights<4>);
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(compose), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)clds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(compose), (int)clds)) return DCHAG_ERR_LAUNCH;
     if (!compose_mfma && phase != 2) {
       compose<<<dim3(Cin), 256, clds, st>>>(D, heads, pp, g, DQ, px->MfT, px->We, px->be, px->ce, px->Ms, px->Msb, px->cs);
       if ((rc = launch_status())) return rc;
@@ -425,11 +510,9 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     // scores and softmax in one kernel while a group's scores of 32 patches fit LDS (DCHAG_PIXEL_SCORES_TWO_KERNELS,
     // a debugging aid, keeps them apart)
     const size_t slds = (size_t)std::min(g, Cin) * heads * 33 * 4;
-    if (slds <= 150 * 1024 && B <= 65535 && G <= 65535 && !getenv("DCHAG_PIXEL_SCORES_TWO_KERNELS")) {
+    if (slds <= 150 * 1024 && B <= 65535 && G <= 65535 && !dbg(SW_PIXEL_SCORES_TWO_KERNELS)) {
       auto sk = pp == 64 ? k_scores_pixels_softmax<64> : (pp == 16 ? k_scores_pixels_softmax<16> : k_scores_pixels_softmax<0>);
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(sk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds) !=
-          hipSuccess)
-        return DCHAG_ERR_LAUNCH;
+      if (ensure_dynamic_lds(reinterpret_cast<const void*>(sk), (int)slds)) return DCHAG_ERR_LAUNCH;
       sk<<<dim3((N + 31) / 32, G, B), 256, slds, st>>>(Cin, px->H, px->W, px->p, heads, g, gpad, G, Np, px->x, px->Msb,
                                                       px->cs, alpha_tm ? nullptr : alpha, alpha_tm);
       if ((rc = launch_status())) return rc;
@@ -455,17 +538,15 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
     const dim3 ggrid((N + 15) / 16, G * qsplit, B);
 #define DCHAG_SCORES_GROUP(NB_, KI_)                                                                         \
   k_scores_group<NB_, KI_><<<ggrid, 256, 0, st>>>(Cin, N, heads, g, gpad, Np, qsplit, qper, zin, Mb, alpha)
-    const bool resident = D % 128 == 0 && !getenv("DCHAG_SCORES_PER_QUAD");
+    const bool resident = D % 128 == 0 && !dbg(SW_SCORES_PER_QUAD);
     // scores + softmax in one kernel: folded keys of the whole row in registers, raw scores in LDS
     const size_t slds = (size_t)16 * (2 * D + 16) + (size_t)gpad * 2048;
     // DCHAG_SCORES_ONE_KERNEL = 0 / 1 overrides the size heuristic (never the shape limits)
-    const char* force = getenv("DCHAG_SCORES_ONE_KERNEL");
+    const char* force = dbg(SW_SCORES_ONE_KERNEL);
     const bool fits = NB <= 1 && D % 256 == 0 && slds <= 150 * 1024;
     const bool one_kernel = fits && (force ? force[0] == '1' : (long)(Np / 32) * G * B >= compute_units());
     if (one_kernel) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_scores_softmax),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds) != hipSuccess)
-        return DCHAG_ERR_LAUNCH;
+      if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_scores_softmax), (int)slds)) return DCHAG_ERR_LAUNCH;
       k_scores_softmax<<<dim3(Np / 32, G, B), 512, slds, st>>>(Cin, N, D, heads, g, gpad, Np, zin, Mb, alpha);
       if ((rc = launch_status())) return rc;
     } else {
@@ -519,9 +600,7 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
     const int dh = D / heads;
     const int NHS = dh >= kGemmBN ? 1 : kGemmBN / dh;
     const int lds = kGemmRingBytes + 3 * 8 * NHS * 32 * 4;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_vagg_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            lds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_vagg_mfma), lds)) return DCHAG_ERR_LAUNCH;
     // persistent workgroups: one per compute unit (the LDS ring allows no more), `slots` per XCD
     const int slots = per < compute_units() / kXcds ? per : compute_units() / kXcds;
     k_vagg_mfma<<<dim3(slots * kXcds), dim3(512), lds, st>>>(Cin, N, D, heads, g, gpad, G, Np, tw, slots, zin,
@@ -591,7 +670,7 @@ int check_level_shape(int B, int Cin, int N, int D, int heads, int g) {
 // reach HBM.  y [B,G,N,D].
 inline bool tokenize_mix_ok(dchag_dtype dt, const dchag_level* levels, int pp, int D) {
   return dt == DCHAG_BF16 && levels[0].kind == DCHAG_LEVEL_LINEAR && (pp == 16 || pp == 64) && D % 256 == 0 &&
-         !getenv("DCHAG_GENERIC_TOKENIZE");
+         !dbg(SW_GENERIC_TOKENIZE);
 }
 // The ring-buffered kernel of the fused tokenizer + first level takes 8 x 8 patches whose rows, like every weight and
 // vector row it streams, are whole 16-byte pieces (DCHAG_FIRST_LEVEL_REGS, a debugging aid, keeps the older kernels).
@@ -599,7 +678,7 @@ inline bool aligned16(const void* ptr) { return !(reinterpret_cast<uintptr_t>(pt
 inline bool reduce_ring_ok(int p, int W, int D, const void* x, const void* Wt, const void* v0, const void* v1,
                            const void* v2) {
   return p == 8 && W % 8 == 0 && D % 256 == 0 && aligned16(x) && aligned16(Wt) && aligned16(v0) && aligned16(v1) &&
-         aligned16(v2) && !getenv("DCHAG_FIRST_LEVEL_REGS");
+         aligned16(v2) && !dbg(SW_FIRST_LEVEL_REGS);
 }
 template <bool ATT, int CFG>
 int launch_reduce_ring_cols(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
@@ -619,12 +698,10 @@ int launch_reduce_ring_cols(int B, int C, int H, int W, int D, int g, int heads,
   const long fill = 2L * Cfg::kPerCu * compute_units();           // workgroups that give every compute unit two rounds
   int S = 1;
   while (total * S < fill && 2 * S <= std::min(16, gmin)) S *= 2;
-  if (const char* e = getenv("DCHAG_FIRST_LEVEL_SPLIT")) S = std::max(1, std::min(std::min(16, gmin), atoi(e)));
+  if (const char* e = dbg(SW_FIRST_LEVEL_SPLIT)) S = std::max(1, std::min(std::min(16, gmin), atoi(e)));
   while (S > 1 && (!part || (size_t)S * per_split * 4 > part_bytes)) S >>= 1;
   const int per = (int)((total * S + kXcds - 1) / kXcds);
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tokenize_reduce_ring<ATT, CFG>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes) != hipSuccess)
-    return DCHAG_ERR_LAUNCH;
+  if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_tokenize_reduce_ring<ATT, CFG>), Cfg::kLdsBytes)) return DCHAG_ERR_LAUNCH;
   k_tokenize_reduce_ring<ATT, CFG><<<dim3((unsigned)(per * kXcds)), Cfg::kThreads, Cfg::kLdsBytes, st>>>(
       C, H, W, D, g, G, heads, round_up(g, 8), round_up(N, 32), tw, x, Wt, wmix, v1, v2, alpha, bias, y, S, part);
   int rc = launch_status();
@@ -641,7 +718,7 @@ template <bool ATT>
 int launch_reduce_ring(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
                        const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias, bf16* y,
                        hipStream_t st, float* part = nullptr, size_t part_bytes = 0) {
-  const char* e = getenv("DCHAG_RING_SHAPE");
+  const char* e = dbg(SW_RING_SHAPE);
   if (e && atoi(e) == 0)
     return launch_reduce_ring_cols<ATT, 0>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
                                            part_bytes);
@@ -660,14 +737,12 @@ int tokenize_mix_forward(int B, int C, int H, int W, int p, int D, const void* x
   }
   // 128 patches per workgroup (eight wavefronts) while that leaves a workgroup per compute unit, else 64 (four);
   // DCHAG_MIX_NARROW (debugging aid) keeps the 64-patch kernel
-  const bool wide = N >= 128 && (long)((N + 127) / 128) * (D / 256) * G * B >= compute_units() && !getenv("DCHAG_MIX_NARROW");
+  const bool wide = N >= 128 && (long)((N + 127) / 128) * (D / 256) * G * B >= compute_units() && !dbg(SW_MIX_NARROW);
   const int PB = wide ? 128 : 64;
   const size_t lds = (size_t)2 * PB * (pp * 2 + 16);
   auto mixk = wide ? (pp == 16 ? k_tokenize_mix_wide<1> : k_tokenize_mix_wide<4>)
                    : (pp == 16 ? k_tokenize_mix_mfma<1> : k_tokenize_mix_mfma<4>);
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(mixk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
-      hipSuccess)
-    return DCHAG_ERR_LAUNCH;
+  if (ensure_dynamic_lds(reinterpret_cast<const void*>(mixk), (int)lds)) return DCHAG_ERR_LAUNCH;
   StageTimer tm(DCHAG_STAGE_TOKENIZE_MIX, st);
   mixk<<<dim3((unsigned)(((N + PB - 1) / PB) * (D / 256)), G, B), wide ? 512 : 256, lds, st>>>(
       C, H, W, p, D, g, static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
@@ -681,7 +756,9 @@ int tokenize_mix_forward(int B, int C, int H, int W, int p, int D, const void* x
 
 extern "C" {
 
-const char* dchag_version(void) { return "0.2"; }
+const char* dchag_version(void) { return "0.3"; }
+
+void dchag_debug_reload(void) { g_switches.read(); }
 
 int dchag_profile_begin(void) {
   for (StageRecord& r : g_records) {
@@ -752,7 +829,7 @@ int dchag_tokenize(dchag_dtype dt, int B, int C, int H, int W, int p, int D, con
     return launch_tokenize<float>(B, C, H, W, p, D, static_cast<const float*>(x), static_cast<const float*>(We),
                                   static_cast<const float*>(be), static_cast<const float*>(ce),
                                   static_cast<float*>(tokens), st);
-  if ((p * p) % 16 == 0 && p * p <= 256 && D % 64 == 0 && !getenv("DCHAG_GENERIC_TOKENIZE"))
+  if ((p * p) % 16 == 0 && p * p <= 256 && D % 64 == 0 && !dbg(SW_GENERIC_TOKENIZE))
     return launch_tokenize_mfma(B, C, H, W, p, D, static_cast<const bf16*>(x), static_cast<const bf16*>(We),
                                 static_cast<const bf16*>(be), static_cast<const bf16*>(ce),
                                 static_cast<bf16*>(tokens), st);
@@ -771,7 +848,7 @@ int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int head
   if ((rc = check_level_shape(B, Cin, N, D, heads, lvl->group_size))) return rc;
   if (misaligned(tokens_in) || misaligned(tokens_out)) return DCHAG_ERR_ALIGN;
   if (lvl->kind == DCHAG_LEVEL_LINEAR) {  // needs no workspace
-    g_level = 1;
+    set_level(1);
     if (dt == DCHAG_F32)
       return run_level_linear<float>(B, Cin, N, D, lvl, static_cast<const float*>(tokens_in),
                                      static_cast<float*>(tokens_out), static_cast<hipStream_t>(stream));
@@ -783,11 +860,11 @@ int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int head
     return DCHAG_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
-  g_level = 1;
+  set_level(1);
   if (dt == DCHAG_F32)
     return run_level<float>(dt, B, Cin, N, D, heads, lvl, static_cast<const float*>(tokens_in),
                             static_cast<float*>(tokens_out), ws, st);
-  if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL"))
+  if (fast_level(dt, D, heads) && !dbg(SW_GENERIC_LEVEL))
     return run_level_fast(B, Cin, N, D, heads, lvl, static_cast<const bf16*>(tokens_in),
                           static_cast<bf16*>(tokens_out), ws, st);
   return run_level<bf16>(dt, B, Cin, N, D, heads, lvl, static_cast<const bf16*>(tokens_in),
@@ -823,13 +900,13 @@ static int forward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   hipStream_t st = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
 
-  g_level = 0;
+  set_level(0);
   const void* zin = ws + w.tokens;
   c_in = C;
   int first = 0;
   const int pp0 = p * p;
   if (tokenize_mix_ok(dt, levels, pp0, D)) {
-    g_level = 1;
+    set_level(1);
     bf16* y = reinterpret_cast<bf16*>(ws + w.ping);
     if ((rc = tokenize_mix_forward(B, C, H, W, p, D, x, We, be, ce, &levels[0], y, st))) return rc;
     zin = y;
@@ -838,7 +915,7 @@ static int forward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   } else if ((rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, stream)))
     return rc;
   for (int l = first; l < n_levels; ++l) {
-    g_level = l + 1;
+    set_level(l + 1);
     void* zout = (l + 1 == n_levels) ? out : static_cast<void*>(ws + ((l & 1) ? w.pong : w.ping));
     const void* rowadd = (l + 1 == n_levels) ? pos : nullptr;
     if (levels[l].kind == DCHAG_LEVEL_LINEAR)
@@ -849,7 +926,7 @@ static int forward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
     else if (dt == DCHAG_F32)
       rc = run_level<float>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const float*>(zin),
                             static_cast<float*>(zout), ws + w.level, st, static_cast<const float*>(rowadd));
-    else if (fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL")) {
+    else if (fast_level(dt, D, heads) && !dbg(SW_GENERIC_LEVEL)) {
       PixelScores px{static_cast<const bf16*>(x), static_cast<const bf16*>(We), static_cast<const bf16*>(be),
                      static_cast<const bf16*>(ce), H, W, p, reinterpret_cast<float*>(ws + w.ms),
                      reinterpret_cast<float*>(ws + w.cs), reinterpret_cast<float*>(ws + w.mft),

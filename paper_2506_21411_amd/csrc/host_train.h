@@ -16,7 +16,7 @@ struct KeptLevel {
 
 // Shapes whose scores go through the score kernels of the bf16 forward path.
 inline bool train_fast(dchag_dtype dt, int D, int heads) {
-  return fast_level(dt, D, heads) && !getenv("DCHAG_GENERIC_LEVEL");
+  return fast_level(dt, D, heads) && !dbg(SW_GENERIC_LEVEL);
 }
 
 inline KeptLevel kept_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g, bool linear,
@@ -95,7 +95,7 @@ inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, in
 // LDS), fewer while that leaves compute units without a block.
 inline int dz_patches(int B, int G, int N, int D, int g) {
   int pt = 16;
-  if (const char* e = getenv("DCHAG_DZ_PT")) pt = atoi(e) > 0 ? atoi(e) : pt;
+  if (const char* e = dbg(SW_DZ_PT)) pt = atoi(e) > 0 ? atoi(e) : pt;
   while (pt > 1 && (size_t)2 * pt * g * 16 * 4 > 64 * 1024) pt >>= 1;
   while (pt > 1 && (long)B * G * ((N + pt - 1) / pt) * ((D + 1023) / 1024) < 2L * compute_units()) pt >>= 1;
   return pt;
@@ -161,7 +161,7 @@ int launch_gemm(const GemmDesc& d, const TA* A, const TB* Bm, const TB* bias, TC
 // one unit stride, every other stride and offset a multiple of 8 elements (16-byte rows).
 inline bool mult8(long v) { return (v & 7) == 0; }
 inline bool gemm_mfma_ok(const GemmDesc& d) {
-  if (d.K % 64 || d.ragged == 2 || getenv("DCHAG_GEMM_GENERIC")) return false;
+  if (d.K % 64 || d.ragged == 2 || dbg(SW_GEMM_GENERIC)) return false;
   const bool at = d.A.s1 != 1, bt = d.Bm.s0 != 1;
   if (at && (d.A.s0 != 1 || d.M % 8 || d.M < 8 || d.ragged)) return false;
   if (bt && (d.Bm.s1 != 1 || d.N % 8 || d.N < 8)) return false;
@@ -179,9 +179,7 @@ int launch_gemm_mfma_tile(const GemmDesc& d, const bf16* A, const bf16* Bm, cons
   auto kern = at ? (bt ? k_gemm_mfma<BM, BN, WM, WN, true, true, TC> : k_gemm_mfma<BM, BN, WM, WN, true, false, TC>)
                  : (bt ? k_gemm_mfma<BM, BN, WM, WN, false, true, TC> : k_gemm_mfma<BM, BN, WM, WN, false, false, TC>);
   constexpr int lds = 2 * (BM + BN) * 128;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
-      hipSuccess)
-    return DCHAG_ERR_LAUNCH;
+  if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds)) return DCHAG_ERR_LAUNCH;
   kern<<<dim3((d.N + BN - 1) / BN, (unsigned)mt, (unsigned)batch), 256, lds, st>>>(d, A, Bm, bias, C, rowsum);
   return launch_status();
 }
@@ -195,7 +193,7 @@ int launch_gemm_bf16(const GemmDesc& d0, const bf16* A, const bf16* Bm, const bf
   if (!gemm_mfma_ok(d0)) return launch_gemm<bf16, bf16, TC>(d0, A, Bm, bias, C, st);
   GemmDesc d = d0;
   d.c_vec = sizeof(TC) == 2 && d.C.s1 == 1 && d.N % 8 == 0 && mult8(d.C.sb) && mult8(d.C.sk) && mult8(d.C.sa) &&
-            mult8(d.C.s0) && !(reinterpret_cast<uintptr_t>(C) & 15) && !getenv("DCHAG_GEMM_SCALAR_STORES");
+            mult8(d.C.s0) && !(reinterpret_cast<uintptr_t>(C) & 15) && !dbg(SW_GEMM_SCALAR_STORES);
   if (d.N <= 64) return launch_gemm_mfma_tile<128, 64, 4, 1, TC>(d, A, Bm, bias, C, rowsum, st);
   if (d.M <= 64) return launch_gemm_mfma_tile<64, 128, 1, 4, TC>(d, A, Bm, bias, C, rowsum, st);
   // a product of few 128 x 128 tiles (the one-group top level) takes 64 x 64 tiles: four times the blocks
@@ -205,7 +203,7 @@ int launch_gemm_bf16(const GemmDesc& d0, const bf16* A, const bf16* Bm, const bf
   return launch_gemm_mfma_tile<128, 128, 2, 2, TC>(d, A, Bm, bias, C, rowsum, st);
 }
 // True when launch_gemm_bf16 will deliver the row sums of A along with the product.
-inline bool gemm_rowsum_ok(const GemmDesc& d) { return gemm_mfma_ok(d) && d.A.s1 != 1 && !getenv("DCHAG_COLSUM"); }
+inline bool gemm_rowsum_ok(const GemmDesc& d) { return gemm_mfma_ok(d) && d.A.s1 != 1 && !dbg(SW_COLSUM); }
 
 // Same-type products of the level kernels: MFMA for bf16 where it tiles, the fp32-FMA kernel otherwise.
 inline int gemm_tt(const GemmDesc& d, const float* A, const float* Bm, const float* bias, float* C, hipStream_t st) {
@@ -306,10 +304,8 @@ inline int head_sums(int B, int Cin, int N, int D, int heads, int g, const float
 inline int head_sums(int B, int Cin, int N, int D, int heads, int g, const float* alpha, const bf16* z, bf16* u,
                      hipStream_t st) {
   const size_t lds = (size_t)std::min(g, Cin) * 16 * 4;
-  if (D % 4 == 0 && lds <= 160 * 1024 - 4096 && !getenv("DCHAG_GENERIC_LEVEL")) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_sums_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
+  if (D % 4 == 0 && lds <= 160 * 1024 - 4096 && !dbg(SW_GENERIC_LEVEL)) {
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_head_sums_bf16), (int)lds)) return DCHAG_ERR_LAUNCH;
     k_head_sums_bf16<<<dim3(N, groups_of(Cin, g), B), 256, lds, st>>>(Cin, N, D, heads, g, alpha, z, u);
   } else {
     k_head_sums<bf16, 16><<<dim3(N, groups_of(Cin, g), B), 256, 0, st>>>(Cin, N, D, heads, g, alpha, z, u);
@@ -385,7 +381,7 @@ int gemm_per_channel(GemmDesc d, int C, int g, long a_grp, long b_ch, long c_ch,
 inline bool attend_wide_ok(int p, int D, int heads, const dchag_level* lv) {
   const int pp = p * p, dh = D / heads;
   return lv->kind != DCHAG_LEVEL_LINEAR && (pp == 16 || pp == 64) && D % 256 == 0 && D % heads == 0 && dh % 32 == 0 &&
-         (256 % dh == 0 || dh % 256 == 0) && !getenv("DCHAG_VALUE_UNFOLDED");
+         (256 % dh == 0 || dh % 256 == 0) && !dbg(SW_VALUE_UNFOLDED);
 }
 inline bool attend_ring_ok(int p, int W, int D, int heads, const void* x, const dchag_level* lv) {
   return attend_wide_ok(p, D, heads, lv) && reduce_ring_ok(p, W, D, x, nullptr, nullptr, nullptr, nullptr) &&
@@ -409,7 +405,7 @@ inline int fold_value_weights(int C, int p, int D, const dchag_level* lv, const 
   StageTimer tm(DCHAG_STAGE_FOLD_VALUE, st);
   // Wf[c](o, kk) = sum_d Wv[k](o, d) We[c](d, kk).  64 pixels per patch: four channels per work item share a 256-row
   // tile of Wv (DCHAG_FOLD_VALUE_GEMM, a debugging aid, takes the general product kernel, one channel per workgroup)
-  if (pp == 64 && aligned16(Wv) && aligned16(We) && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
+  if (pp == 64 && aligned16(Wv) && aligned16(We) && !dbg(SW_FOLD_VALUE_GEMM)) {
     TileWork tw{};
     tw.n_tiles = (std::min(g, C) + 3) / 4;
     tw.m_tiles = D / kGemmBM;
@@ -418,9 +414,7 @@ inline int fold_value_weights(int C, int p, int D, const dchag_level* lv, const 
     if (total > (1L << 30)) return DCHAG_ERR_SHAPE;
     tw.total = (int)total;
     const int per = (tw.total + kXcds - 1) / kXcds;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_fold_value_dl), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kGemmRingBytes) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_fold_value_dl), kGemmRingBytes)) return DCHAG_ERR_LAUNCH;
     k_fold_value_dl<<<dim3((unsigned)(per * kXcds)), 512, kGemmRingBytes, st>>>(C, D, g, tw, Wv, We, Wf);
     if ((rc = launch_status())) return rc;
   } else {
@@ -432,7 +426,7 @@ inline int fold_value_weights(int C, int p, int D, const dchag_level* lv, const 
     d.scale = 1.f;
     if ((rc = gemm_per_channel<bf16>(d, C, g, (long)D * D, (long)D * pp, (long)D * pp, Wv, We, Wf, st))) return rc;
   }
-  if ((be || ce) && aligned16(Wv) && aligned16(be) && aligned16(ce) && G <= 65535 && !getenv("DCHAG_FOLD_VALUE_GEMM")) {
+  if ((be || ce) && aligned16(Wv) && aligned16(be) && aligned16(ce) && G <= 65535 && !dbg(SW_FOLD_VALUE_GEMM)) {
     k_fold_token_bias<<<dim3(D / 32, G), 256, 0, st>>>(C, D, g, Wv, be, ce, fb);
     if ((rc = launch_status())) return rc;
   } else if (be || ce) {
@@ -476,9 +470,7 @@ inline int attend_pixels_forward(int B, int C, int H, int W, int p, int D, int h
   const int dh = D / heads, nhs = dh >= 256 ? 1 : 256 / dh;
   const size_t lds = (size_t)2 * 128 * (pp * 2 + 16) + (size_t)2 * nhs * 512;
   auto kern = pp == 16 ? k_tokenize_attend_wide<1> : k_tokenize_attend_wide<4>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
-      hipSuccess)
-    return DCHAG_ERR_LAUNCH;
+  if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds)) return DCHAG_ERR_LAUNCH;
   kern<<<dim3((unsigned)(((N + 127) / 128) * (D / 256)), G, B), 512, lds, st>>>(
       C, H, W, p, D, g, heads, round_up(g, 8), round_up(N, 32), x, Wf, v1, v2, alpha, bv, o);
   return launch_status();
@@ -519,14 +511,14 @@ inline int prepare_folded(int C, int H, int W, int p, int D, int heads, const vo
                           int n_levels, const dchag_level* levels, unsigned char* pf, hipStream_t st) {
   const PreparedLayout L = prepared_layout(C, p * p, D, heads, n_levels, levels);
   int rc;
-  g_level = 1;
+  set_level(1);
   if ((rc = fold_value_weights(C, p, D, &levels[0], static_cast<const bf16*>(We), static_cast<const bf16*>(be),
                                static_cast<const bf16*>(ce), pf + L.fold, st)))
     return rc;
   const PixelScores px = pixel_scores_of<bf16>(nullptr, We, be, ce, H, W, p, pf, L.ms, L.msb, L.cs, L.mft);
   int c_in = C;
   for (int l = 0; l < n_levels; ++l) {
-    g_level = l + 1;
+    set_level(l + 1);
     if (levels[l].kind != DCHAG_LEVEL_LINEAR) {
       LevelBufs<bf16> lb{};
       use_prepared(pf, L, l, lb);
@@ -545,13 +537,13 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
                         const int32_t* gs, void* out, unsigned char* ws, const FoldedWs& w, hipStream_t st,
                         const unsigned char* prefolded = nullptr) {
   const int N = (H / p) * (W / p);
-  g_level = 0;
+  set_level(0);
   int rc;
   const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
   int c_in = C, first = 0;
   if constexpr (std::is_same<T, bf16>::value) {
     if (n_levels > 1 && tokenize_mix_ok(dt, levels, p * p, D)) {      // tokenizer and linear first level in one kernel
-      g_level = 1;
+      set_level(1);
       bf16* y = reinterpret_cast<bf16*>(ws + w.ping);
       if ((rc = tokenize_mix_forward(B, C, H, W, p, D, x, We, be, ce, &levels[0], y, st))) return rc;
       zin = y;
@@ -567,7 +559,7 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
     // an attention first level straight from the pixels: scores through the composed score weights, values through
     // the folded tokenizer weights (which sit where the tokens would have been)
     if (!first && values_from_pixels(dt, p, D, heads, &levels[0])) {
-      g_level = 1;
+      set_level(1);
       const KeptLevel kl = kept_level(dt, B, C, N, D, heads, gs[0], false, false);
       LevelBufs<bf16> lb = level_bufs<bf16>(ws + w.level, kl);
       PixelScores px0 = px;
@@ -609,7 +601,7 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   }
   if (!first && (rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st))) return rc;
   for (int l = first; l < n_levels; ++l) {
-    g_level = l + 1;
+    set_level(l + 1);
     T* zout = (l + 1 == n_levels) ? static_cast<T*>(out) : reinterpret_cast<T*>(ws + ((l & 1) ? w.pong : w.ping));
     if (levels[l].kind == DCHAG_LEVEL_LINEAR)
       rc = run_level_linear<T>(B, c_in, N, D, &levels[l], zin, zout, st);
@@ -655,7 +647,7 @@ inline int softmax_backward(int B, int Cin, int N, int D, int heads, int g, cons
                             const float* alpha, float* ds, hipStream_t st) {
   const int G = groups_of(Cin, g);
   const int mt = (std::min(g, Cin) + 15) / 16;
-  if (D % 32 == 0 && mt <= 4 && !getenv("DCHAG_GENERIC_LEVEL")) {
+  if (D % 32 == 0 && mt <= 4 && !dbg(SW_GENERIC_LEVEL)) {
     const long items = (long)B * G * N;
     const dim3 grid((unsigned)((items + 3) / 4));
     if (mt == 1) k_dalpha_softmax_mfma<1><<<grid, 256, 0, st>>>(items, Cin, N, D, heads, g, G, z, w, alpha, ds);
@@ -665,10 +657,8 @@ inline int softmax_backward(int B, int Cin, int N, int D, int heads, int g, cons
   }
   const size_t big_lds = ((size_t)16 * ((std::min(g, Cin) + 15) / 16) + 17) * 16 * 4;
   const long items = (long)B * G * N;
-  if (D % 32 == 0 && big_lds <= 128 * 1024 && items <= 0x7fffffffL && !getenv("DCHAG_GENERIC_LEVEL")) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dalpha_softmax_group),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)big_lds) != hipSuccess)
-      return DCHAG_ERR_LAUNCH;
+  if (D % 32 == 0 && big_lds <= 128 * 1024 && items <= 0x7fffffffL && !dbg(SW_GENERIC_LEVEL)) {
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_dalpha_softmax_group), (int)big_lds)) return DCHAG_ERR_LAUNCH;
     k_dalpha_softmax_group<<<dim3((unsigned)items), 256, big_lds, st>>>(Cin, N, D, heads, g, G, z, w, alpha, ds);
     return launch_status();
   }
@@ -688,8 +678,8 @@ inline bool tokens_fused(int B, int Cin, int N, int D, int heads, int g) {
   const int G = groups_of(Cin, g);
   const size_t lds = (size_t)2 * dz_patches(B, G, N, D, g) * g * 16 * 4;
   return D % 256 == 0 && D <= 2048 && heads <= 16 && std::min(g, Cin) <= 32 && lds <= 128 * 1024 &&
-         !getenv("DCHAG_DZ_VALU") && !getenv("DCHAG_GENERIC_LEVEL") && !getenv("DCHAG_TOKENS_UNFUSED") &&
-         !getenv("DCHAG_RPART_VALU");
+         !dbg(SW_DZ_VALU) && !dbg(SW_GENERIC_LEVEL) && !dbg(SW_TOKENS_UNFUSED) &&
+         !dbg(SW_RPART_VALU);
 }
 inline int sum_key_path_partials(int B, int G, int n_tiles, int heads, int D, const float* rpart, float* r,
                                  hipStream_t st) {
@@ -754,8 +744,8 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
   const int G = groups_of(Cin, g);
   const int pt = dz_patches(B, G, N, D, g);
   const size_t lds = (size_t)2 * pt * g * 16 * 4;
-  const bool mfma = D % 256 == 0 && heads <= 32 && !getenv("DCHAG_DZ_VALU");
-  if ((!mfma && heads > 16) || D % 4 || lds > 128 * 1024 || getenv("DCHAG_GENERIC_LEVEL"))
+  const bool mfma = D % 256 == 0 && heads <= 32 && !dbg(SW_DZ_VALU);
+  if ((!mfma && heads > 16) || D % 4 || lds > 128 * 1024 || dbg(SW_GENERIC_LEVEL))
     return tokens_backward_generic<bf16>(B, Cin, N, D, heads, g, zin, w, alpha, ds, Mf, dz, r, want_r, st);
   const int n_tiles = (N + pt - 1) / pt;
   int rc;
@@ -767,21 +757,17 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
       else k_dz_mfma<2><<<grid, 256, 0, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, w, Mb, dz);
       if ((rc = launch_status())) return rc;
       if (want_r) {                                               // DCHAG_RPART_VALU (debugging aid): vector-ALU sums
-        const bool valu = getenv("DCHAG_RPART_VALU") != nullptr;
+        const bool valu = dbg(SW_RPART_VALU) != nullptr;
         const size_t rl = (size_t)pt * g * (heads <= 16 ? 16 : 32) * 4;
         auto rk = valu ? (heads <= 16 ? k_rpart_bf16<1> : k_rpart_bf16<2>)
                        : (heads <= 16 ? k_rpart_mfma<1> : k_rpart_mfma<2>);
         const size_t rlds = valu ? lds / 2 : rl;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(rk), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)rlds) != hipSuccess)
-          return DCHAG_ERR_LAUNCH;
+        if (ensure_dynamic_lds(reinterpret_cast<const void*>(rk), (int)rlds)) return DCHAG_ERR_LAUNCH;
         rk<<<grid, 256, rlds, st>>>(Cin, N, D, heads, g, n_tiles, pt, ds, zin, rpart);
         if ((rc = launch_status())) return rc;
       }
     } else {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dz_rpart_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds) != hipSuccess)
-        return DCHAG_ERR_LAUNCH;
+      if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_dz_rpart_bf16), (int)lds)) return DCHAG_ERR_LAUNCH;
       k_dz_rpart_bf16<<<grid, 256, lds, st>>>(Cin, N, D, heads, g, n_tiles, pt, alpha, ds, zin, w, Mb, dz, rpart);
       if ((rc = launch_status())) return rc;
     }
@@ -796,7 +782,7 @@ inline int tokens_backward(int B, int Cin, int N, int D, int heads, int g, const
 template <typename TV, typename T>
 int outer_rows(int D, int G, int rows_per_vec, float scale, const float* rowv, const TV* colv, T* out, hipStream_t st) {
   const bool vec = D % 8 == 0 && !((reinterpret_cast<uintptr_t>(colv) | reinterpret_cast<uintptr_t>(out)) & 15) &&
-                   !getenv("DCHAG_GEMM_SCALAR_STORES");
+                   !dbg(SW_GEMM_SCALAR_STORES);
   if (vec) {
     const long chunks = (long)D * (D / 8);
     k_outer_rows_vec<TV, T><<<dim3((unsigned)((chunks + 2047) / 2048), G), 256, 0, st>>>(D, rows_per_vec, scale, rowv,
@@ -907,7 +893,7 @@ int linear_level_backward(int B, int Cin, int N, int D, const dchag_level* lv, c
   int rc;
   StageTimer tm(DCHAG_STAGE_BWD_CHANNEL_MIX, st);
   const long total = (long)B * Cin * N * D;
-  const bool vec = D % 8 == 0 && Cin <= 65535 && B <= 65535 && !getenv("DCHAG_GEMM_SCALAR_STORES") &&
+  const bool vec = D % 8 == 0 && Cin <= 65535 && B <= 65535 && !dbg(SW_GEMM_SCALAR_STORES) &&
                    !((reinterpret_cast<uintptr_t>(lv->Wv) | reinterpret_cast<uintptr_t>(dy) |
                       reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(zin) |
                       reinterpret_cast<uintptr_t>(gr->dWv)) & 15);
@@ -981,7 +967,7 @@ int tokenizer_backward(int B, int C, int H, int W, int p, int D, const T* x, con
 // tokens would have been.  DCHAG_LINEAR_TOKENS (debugging aid) keeps the route through the tokens.
 inline bool linear_first_without_tokens(dchag_dtype dt, int B, int C, int N, int pp, int D, int n_levels,
                                         const dchag_level* levels) {
-  if (dt != DCHAG_BF16 || n_levels < 2 || levels[0].kind != DCHAG_LEVEL_LINEAR || getenv("DCHAG_LINEAR_TOKENS"))
+  if (dt != DCHAG_BF16 || n_levels < 2 || levels[0].kind != DCHAG_LEVEL_LINEAR || dbg(SW_LINEAR_TOKENS))
     return false;
   const int cpr = pp / 8;
   if (pp % 8 || (cpr & (cpr - 1)) || cpr > 64 || D % 8) return false;
@@ -1075,14 +1061,14 @@ int keep_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int h
                  const void* be, const void* ce, int n_levels, const dchag_level* levels, const int32_t* gs, void* out,
                  unsigned char* ws, const BackwardWs& w, hipStream_t st) {
   const int N = (H / p) * (W / p);
-  g_level = 0;
+  set_level(0);
   int rc;
   const T* zin = reinterpret_cast<const T*>(ws + w.tokens);
   int c_in = C, first = 0;
   if constexpr (std::is_same<T, bf16>::value) {
     // a linear first level whose reverse needs no tokens: tokenizer and level in one kernel, nothing else kept
     if (linear_first_without_tokens(dt, B, C, N, p * p, D, n_levels, levels) && tokenize_mix_ok(dt, levels, p * p, D)) {
-      g_level = 1;
+      set_level(1);
       const KeptLevel kl = kept_level(dt, B, C, N, D, heads, gs[0], true, true);
       bf16* y = reinterpret_cast<bf16*>(ws + w.kept[0] + kl.y);
       if ((rc = tokenize_mix_forward(B, C, H, W, p, D, x, We, be, ce, &levels[0], y, st))) return rc;
@@ -1095,7 +1081,7 @@ int keep_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int h
   const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
   for (int l = first; l < n_levels; ++l) {
-    g_level = l + 1;
+    set_level(l + 1);
     const bool linear = levels[l].kind == DCHAG_LEVEL_LINEAR, last = l + 1 == n_levels;
     const KeptLevel kl = kept_level(dt, B, c_in, N, D, heads, gs[l], linear, !last);
     unsigned char* lw = ws + w.kept[l];
@@ -1135,7 +1121,7 @@ int reverse_sweep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
   bool no_tokens = false;
   if constexpr (std::is_same<T, bf16>::value) no_tokens = linear_first_without_tokens(dt, B, C, N, p * p, D, n_levels, levels);
   for (int l = n_levels - 1; l >= 0; --l) {
-    g_level = l + 1;
+    set_level(l + 1);
     unsigned char* lw = ws + w.kept[l];
     T* dz = reinterpret_cast<T*>(ws + w.dz[l & 1]);
     if constexpr (std::is_same<T, bf16>::value) {
@@ -1145,7 +1131,7 @@ int reverse_sweep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
                                    static_cast<const bf16*>(ce), dy, static_cast<bf16*>(dx), static_cast<bf16*>(dWe),
                                    static_cast<bf16*>(dtok_bias), reinterpret_cast<bf16*>(ws + w.patches),
                                    ws + w.tokens, st);
-        g_level = 0;
+        set_level(0);
         return rc;
       }
     }
@@ -1160,7 +1146,7 @@ int reverse_sweep(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int 
     if (rc) return rc;
     dy = dz;
   }
-  g_level = 0;
+  set_level(0);
   if (!dx && !dWe && !dtok_bias) return DCHAG_OK;
   return tokenizer_backward<T>(B, C, H, W, p, D, static_cast<const T*>(x), static_cast<const T*>(We), dy,
                                static_cast<T*>(dx), static_cast<T*>(dWe), static_cast<T*>(dtok_bias),

@@ -1309,7 +1309,10 @@ __global__ __launch_bounds__(256, 2) void k_tokenize_mfma(int C, int H, int W, i
   constexpr int NF = KSS ? KSS : 1;
   bf16x8 bfrag[NF][2];                                   // weight fragments of the slice about to be multiplied
   if (KSS) {
-    const bf16* wrow = Wc + (size_t)(wave * 64 + 2 * l32) * pp + lhi * 8;
+    // a wavefront whose first slice lies past D (D < 256) never enters the loop below: it preloads slice 0 instead,
+    // so that no read leaves We
+    const int colp = wave * 64 < D ? wave * 64 : 0;
+    const bf16* wrow = Wc + (size_t)(colp + 2 * l32) * pp + lhi * 8;
 #pragma unroll
     for (int kk = 0; kk < NF; ++kk)
 #pragma unroll

@@ -25,3 +25,36 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+class _SwitchEnv:
+    """pytest's monkeypatch with one addition: after every change of the environment the library re-reads its
+    DCHAG_* debugging switches (it reads them once, when it is loaded, and never during a call)."""
+
+    def __init__(self, mp):
+        self._mp = mp
+
+    @staticmethod
+    def _reload():
+        import paper_2506_21411_amd as dchag
+        if os.path.exists(dchag.library_path()):
+            dchag.dchag_debug_reload()
+
+    def setenv(self, *a, **k):
+        self._mp.setenv(*a, **k)
+        self._reload()
+
+    def delenv(self, *a, **k):
+        self._mp.delenv(*a, **k)
+        self._reload()
+
+    def __getattr__(self, name):
+        return getattr(self._mp, name)
+
+
+@pytest.fixture
+def monkeypatch(monkeypatch):
+    proxy = _SwitchEnv(monkeypatch)
+    yield proxy
+    monkeypatch.undo()
+    proxy._reload()

@@ -87,9 +87,17 @@ def get_config(name: str) -> ShapeCfg:
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bf16 (ties to even); result stays float32."""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    out = np.empty_like(a)
+    src, dst = a.reshape(-1).view(np.uint32), out.reshape(-1).view(np.uint32)
+    step = 1 << 24                                     # blocks that stay in cache-friendly temporaries
+    for i in range(0, src.size, step):
+        u = src[i:i + step]
+        r = (u >> np.uint32(16)) & np.uint32(1)
+        r += np.uint32(0x7FFF)
+        r += u                                         # finite inputs only: no carry out of 32 bits
+        r &= np.uint32(0xFFFF0000)
+        dst[i:i + step] = r
+    return out
 
 
 @dataclass
