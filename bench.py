@@ -7,7 +7,12 @@ channel-patch tokens per second, B*C*N / time.  Prints ONE JSON line.  --mode fo
 times dchag_forward_folded / dchag_backward the same way (the default run reports them as side lines).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload hyperspectral|weather|...]
-                    [--mode forward|folded|backward]
+                    [--mode forward|folded|backward] [--peaks] [--flat-sweep]
+
+Before the W warm-up steps the device is kept busy with the same step for --spin-ms milliseconds: after an idle
+phase (here: the host-side generation of the inputs) the first tens of launches of a heavy kernel run up to 35 %
+slower while the power state settles, which has nothing to do with the kernels.  The K timed steps follow the
+W warm-up steps directly.
 """
 from __future__ import annotations
 
@@ -23,10 +28,42 @@ if ROOT not in sys.path:
 
 PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_tflops": 157.3}
 
-# HBM-side bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs summarised in
-# profiles/hbm_traffic_hyperspectral.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the scales a plain
-# 1 GiB copy kernel gives for the same counters).  Valid for that workload and kernel only.
-MEASURED_TRAFFIC = {("hyperspectral", "fused_vagg", 1): 1678.0e6}
+# Stage names of the library's timing records -> kernel name prefixes in the rocprofv3 summaries under profiles/.
+STAGE_KERNEL = {"fused_vagg": "k_vagg_mfma", "tokenize": "k_tokenize_ws", "tokenize_mix": "k_tokenize_reduce_ring",
+                "tokenize_attend": "k_tokenize_reduce_ring", "oproj": "k_linear_dl"}
+
+
+def measured_traffic(workload, stage, level):
+    """HBM-side bytes per launch of a kernel, read from profiles/hbm_traffic_<workload>.txt (two rocprofv3 --pmc runs,
+    FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy; the file states the
+    scales).  None where no such profile has been committed for the workload and kernel."""
+    kern = STAGE_KERNEL.get(stage)
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if kern is None or not os.path.exists(path):
+        return None
+    rows = [ln.split() for ln in open(path) if ln.startswith(kern)]
+    rows = [r for r in rows if len(r) >= 2 and r[-1] == "MB"]
+    if not rows:
+        return None
+    # several launches of one kernel per step are listed as (i/m), level 1 first
+    pick = rows[min(level, len(rows)) - 1] if level >= 1 else rows[0]
+    try:
+        return float(pick[-2]) * 1e6
+    except ValueError:
+        return None
+
+
+def error_report(got, want):
+    """The three error figures reported beside every oracle comparison (y = GPU, r = oracle, d = y - r):
+    max_norm = max|d| / max|r| (the gated one), elementwise = max_i |d_i| / max(|r_i|, rms r), rms = rms d / rms r."""
+    import numpy as np
+    d = np.abs(np.asarray(got, dtype=np.float64) - want)
+    rms_r = float(np.sqrt(np.mean(np.square(want))))
+    return {"max_norm": float(d.max() / np.abs(want).max()),
+            "elementwise": float((d / np.maximum(np.abs(want), rms_r)).max()),
+            "rms": float(np.sqrt(np.mean(np.square(d))) / rms_r),
+            "definition": "max_norm = max|y-r|/max|r| (gate: 2e-2 bf16, 1e-4 fp32); elementwise = max_i |y_i-r_i| / "
+                          "max(|r_i|, rms r); rms = rms(y-r)/rms(r)"}
 
 
 def stage_model(cfg, levels_in, stage, level, fused_tokens=False):
@@ -40,6 +77,12 @@ def stage_model(cfg, levels_in, stage, level, fused_tokens=False):
     if stage == "bwd_tokenize":
         # token gradients read for dWe and again for dx; pixels in, pixel gradients out, weights in and out
         return "hbm", (2 * B * cfg.C * N * D + 2 * B * cfg.C * cfg.H * cfg.W + 2 * cfg.C * D * cfg.p * cfg.p) * es
+    if stage == "key_prep":
+        # Wq and Wk of every group read once: of one level, or (level 0) of all attention levels of the call
+        kinds = list(cfg.level_kinds or ["attention"] * len(cfg.group_sizes))
+        lvls = range(len(levels_in)) if level == 0 else [level - 1]
+        return "hbm", sum(2 * ((levels_in[i] + cfg.group_sizes[i] - 1) // cfg.group_sizes[i]) * D * D * es
+                          for i in lvls if kinds[i] == "attention")
     cin = levels_in[level - 1]
     g = cfg.group_sizes[level - 1]
     G = (cin + g - 1) // g
@@ -108,7 +151,11 @@ def main() -> int:
     ap.add_argument("--mode", default="forward", choices=["forward", "folded", "backward"],
                     help="what one step is: dchag_forward (the headline), dchag_forward_folded, or dchag_backward")
     ap.add_argument("--cpu-patches", type=int, default=384, help="patches the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--no-other", action="store_true", help="skip the short weather-like side measurement")
+    ap.add_argument("--spin-ms", type=float, default=300.0,
+                    help="milliseconds of untimed steps before the warm-up steps (settles the power state)")
+    ap.add_argument("--no-other", action="store_true", help="skip every side measurement (other calls, other workloads)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="only measure the achievable rates (MFMA-only loop, stream copy) and print them")
     ap.add_argument("--flat-sweep", action="store_true",
                     help="also time the hyperspectral shape at C = 128 .. 1024 channels as one flat layer and as the "
                          "two-level hierarchy (groups of 32), forward")
@@ -125,13 +172,51 @@ def main() -> int:
     import torch
 
     import paper_2506_21411_amd as dchag
-    from workloads import get_config, level_inputs, make_problem, sample_patches
+    from workloads import get_config, level_inputs, make_problem, sample_patches, sample_patches_covering
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
     dchag.load_library()
+
+    def events():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def measure_peaks():
+        """Achievable rates on this device: a loop of nothing but bf16 MFMAs, and a 1 GiB stream copy."""
+        sink = torch.empty(1024 * 512, dtype=torch.float32, device="cuda")
+        best = 0.0
+        for _ in range(3):
+            dchag.dchag_yardstick_mfma(2000, sink)
+        for _ in range(5):
+            e0, e1 = events()
+            e0.record()
+            flops = dchag.dchag_yardstick_mfma(20000, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        copy = 0.0
+        for _ in range(3):
+            dchag.dchag_yardstick_copy(dst, src)
+        for _ in range(5):
+            e0, e1 = events()
+            e0.record()
+            nbytes = dchag.dchag_yardstick_copy(dst, src)
+            e1.record()
+            torch.cuda.synchronize()
+            copy = max(copy, 2.0 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        del src, dst, sink
+        torch.cuda.empty_cache()
+        return {"mfma_bf16_tflops": round(best, 1), "copy_gbs": round(copy, 1),
+                "how": "dchag_yardstick_mfma (16 wavefronts per compute unit, 8 independent 32x32x16 bf16 MFMAs per "
+                       "round, registers only) and dchag_yardstick_copy (1 GiB read + 1 GiB written), best of 5"}
+
+    if args.peaks:
+        print(json.dumps({"achievable": measure_peaks(), "nominal": PEAK}))
+        return 0
 
     def prepare(cfg):
         tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
@@ -170,46 +255,94 @@ def main() -> int:
         return {"grads": grads, "dout": dout, "dx": torch.empty_like(x), "dWe": torch.empty_like(We),
                 "dtb": torch.empty_like(ce), "ws": torch.empty(wsb, dtype=torch.uint8, device="cuda")}
 
-    mode = {"name": args.mode, "bwd": None}
-
-    def step(cfg, t):
+    def make_step(cfg, t, call, bw=None, folded=None):
         x, We, be, ce, levels, ws, out = t
-        if mode["name"] == "forward":
-            dchag.dchag_forward(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
-        elif mode["name"] == "folded":
-            dchag.dchag_forward_folded(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
-        else:
-            bw = mode["bwd"]
-            dchag.dchag_backward(x, We, be, ce, levels, cfg.p, cfg.heads, bw["dout"], bw["grads"], dx=bw["dx"],
-                                 dWe=bw["dWe"], dtok_bias=bw["dtb"], workspace=bw["ws"])
+        if call == "dchag_forward":
+            return lambda: dchag.dchag_forward(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
+        if call == "dchag_forward_folded":
+            return lambda: dchag.dchag_forward_folded(x, We, be, ce, levels, cfg.p, cfg.heads, out=out, workspace=ws)
+        if call == "dchag_forward_prefolded":
+            return lambda: dchag.dchag_forward_prefolded(x, We, be, ce, levels, cfg.p, cfg.heads, folded, out=out,
+                                                         workspace=ws)
+        if call == "dchag_backward":
+            return lambda: dchag.dchag_backward(x, We, be, ce, levels, cfg.p, cfg.heads, bw["dout"], bw["grads"],
+                                                dx=bw["dx"], dWe=bw["dWe"], dtok_bias=bw["dtb"], workspace=bw["ws"])
+        raise ValueError(call)
 
-    def timed(cfg, t, warmup, steps, profile):
+    def spin_up(step, ms):
+        if ms <= 0:
+            return
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for _ in range(10):
+                step()
+            torch.cuda.synchronize()
+
+    def timed(step, warmup, steps, profile=False):
         for _ in range(warmup):
-            step(cfg, t)
+            step()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0, e1 = events()
         if profile:
             dchag.dchag_profile_begin()
         t0 = time.perf_counter()
         e0.record()
         for _ in range(steps):
-            step(cfg, t)
+            step()
         e1.record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
         recs = dchag.dchag_profile_end() if profile else []
         return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps, recs
 
+    def stage_table(cfg, recs, steps):
+        """Per-stage averages over a profiled region, each against the roofline that bounds it."""
+        lv_in = level_inputs(cfg.C, cfg.group_sizes)
+        agg = {}
+        for name, level, dur in recs:
+            a = agg.setdefault((name, level), [0.0, 0])
+            a[0] += dur
+            a[1] += 1
+        stages = []
+        for (name, level), (tot, cnt) in agg.items():
+            fused = name == "bwd_tokens" and ("bwd_softmax", level) not in agg
+            bound, amount = stage_model(cfg, lv_in, name, level, fused)
+            avg = tot / steps                            # per step: a stage may take several launches
+            if bound == "mfma":
+                ach, peak, unit = amount / (avg * 1e-3) / 1e12, PEAK["mfma_bf16_tflops"] if cfg.dtype == "bf16" else PEAK["fp32_tflops"], "TFLOP/s"
+            else:
+                ach, peak, unit = amount / (avg * 1e-3) / 1e9, PEAK["hbm_gbs"], "GB/s"
+            stages.append({"stage": name, "level": level, "avg_ms": round(avg, 5), "launches": cnt // steps, "bound": bound,
+                           "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
+        stages.sort(key=lambda s: -s["avg_ms"])
+        return stages
+
+    def dominant(stages):
+        d = stages[0]
+        return {"kernel": f"{d['stage']}@level{d['level']}", "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"],
+                "unit": d["unit"], "frac": d["frac"], "avg_ms": d["avg_ms"]}
+
+    def oracle_check(cfg, pr, out, bs, ns):
+        """The CPU oracle on the sampled patches against the GPU's output there; returns (seconds, error report)."""
+        import oracle
+        t0 = time.perf_counter()
+        want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns))
+        dt_cpu = time.perf_counter() - t0
+        got = out[torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()].to(torch.float64).cpu().numpy()
+        return dt_cpu, error_report(got, want)
+
     cfg = get_config(args.workload)
     pr, t = prepare(cfg)
-    if args.mode == "backward":
-        mode["bwd"] = prepare_backward(cfg, t)
-    # untimed-stage pass first (value), then the same steps again with per-launch events (roofline)
-    ms_plain, wall_plain, _ = timed(cfg, t, args.warmup, args.steps, profile=False)
-    ms_prof, _, recs = timed(cfg, t, 1, args.steps, profile=True)
-    ms = ms_plain
+    call = {"forward": "dchag_forward", "folded": "dchag_forward_folded", "backward": "dchag_backward"}[args.mode]
+    bwd = prepare_backward(cfg, t) if args.mode == "backward" else None
+    step = make_step(cfg, t, call, bw=bwd)
+    spin_up(step, args.spin_ms)
+    # the timed pass (value), then the same steps again with per-launch events (roofline)
+    ms, wall_plain, _ = timed(step, args.warmup, args.steps)
+    ms_prof, _, recs = timed(step, 1, args.steps, profile=True)
     tokens = cfg.tokens
     value = tokens / (ms * 1e-3)
+    stages = stage_table(cfg, recs, args.steps)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -218,32 +351,53 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # per-stage averages over the profiled region
-    lv_in = level_inputs(cfg.C, cfg.group_sizes)
-    agg = {}
-    for name, level, dur in recs:
-        a = agg.setdefault((name, level), [0.0, 0])
-        a[0] += dur
-        a[1] += 1
-    stages = []
-    for (name, level), (tot, cnt) in agg.items():
-        fused = name == "bwd_tokens" and ("bwd_softmax", level) not in agg
-        bound, amount = stage_model(cfg, lv_in, name, level, fused)
-        avg = tot / args.steps                       # per step: a stage may take several launches
-        if bound == "mfma":
-            ach, peak, unit = amount / (avg * 1e-3) / 1e12, PEAK["mfma_bf16_tflops"] if cfg.dtype == "bf16" else PEAK["fp32_tflops"], "TFLOP/s"
-        else:
-            ach, peak, unit = amount / (avg * 1e-3) / 1e9, PEAK["hbm_gbs"], "GB/s"
-        stages.append({"stage": name, "level": level, "avg_ms": round(avg, 5), "launches": cnt // args.steps, "bound": bound,
-                       "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
-    stages.sort(key=lambda s: -s["avg_ms"])
-    dom = stages[0] if stages else None
+    achievable = measure_peaks()
     roofline = None
-    if dom:
-        roofline = {"kernel": f"{dom['stage']}@level{dom['level']}", "bound": dom["bound"], "achieved": dom["achieved"],
-                    "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
-                    "traffic": MEASURED_TRAFFIC.get((cfg.name, dom["stage"], dom["level"])),
-                    "avg_ms": dom["avg_ms"]}
+    if stages:
+        roofline = dominant(stages)
+        d0 = stages[0]
+        roofline["traffic"] = measured_traffic(cfg.name, d0["stage"], d0["level"])
+        ach_peak = achievable["mfma_bf16_tflops"] if roofline["bound"] == "mfma" else achievable["copy_gbs"]
+        roofline["achievable_peak"] = ach_peak
+        roofline["frac_of_achievable"] = round(roofline["achieved"] / ach_peak, 4)
+
+    # the staged entry points on the same workload: dchag_tokenize, then dchag_aggregate_level on level 1 with its
+    # tokens coming from HBM (its score kernel is the HBM-bound aggregation stage the target names)
+    staged = None
+    if pr.levels[0].kind == "attention" and args.mode == "forward" and cfg.dtype == "bf16":
+        x, We, be, ce, levels, ws, out = t
+        tok = dchag.dchag_tokenize(x, We, be, ce, cfg.p)
+        lvl_out = dchag.dchag_aggregate_level(tok, levels[0], cfg.heads)
+        agg_step = lambda: dchag.dchag_aggregate_level(tok, levels[0], cfg.heads, out=lvl_out)
+        spin_up(agg_step, args.spin_ms / 3)
+        _, _, srecs = timed(agg_step, 5, 20, profile=True)
+        acc = {}
+        for name, level, dur in srecs:
+            acc.setdefault(name, []).append(dur)
+        es = 4 if cfg.dtype == "f32" else 2
+        sc_ms = sum(acc["scores"]) / len(acc["scores"])
+        # algorithmic bytes: every token read once, one fp32 softmax weight per (token, head) written once
+        sc_bytes = cfg.tokens * cfg.D * es + cfg.tokens * cfg.heads * 4
+        sc_gbs = sc_bytes / (sc_ms * 1e-3) / 1e9
+        staged = {"call": "dchag_aggregate_level(level 1), tokens read from HBM; 20 calls after 5 warm-up calls",
+                  "stage_ms": {k: round(sum(v) / len(v), 5) for k, v in acc.items()},
+                  "scores_stage": {"bound": "hbm", "achieved": round(sc_gbs, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
+                                   "frac": round(sc_gbs / PEAK["hbm_gbs"], 4),
+                                   "frac_of_achievable": round(sc_gbs / achievable["copy_gbs"], 4),
+                                   "note": "scores + softmax over the group: every token read once (2*D bytes), "
+                                           "softmax weights written once (4*heads bytes per token)"}}
+        del tok, lvl_out
+
+    # the two stages the target names, side by side: the value-projection GEMM (MFMA) and the aggregation stage (HBM)
+    targets = None
+    if args.mode == "forward" and cfg.dtype == "bf16":
+        gemm = next((s_ for s_ in stages if s_["stage"] == "fused_vagg" and s_["level"] == 1), None)
+        targets = {"gemm_stage": None if gemm is None else
+                   {"kernel": "k_vagg_mfma (level-1 value projection, inside dchag_forward)", "bound": "mfma",
+                    "achieved": gemm["achieved"], "peak": gemm["peak"], "unit": gemm["unit"], "frac": gemm["frac"],
+                    "frac_of_achievable": round(gemm["achieved"] / achievable["mfma_bf16_tflops"], 4), "goal": 0.5},
+                   "aggregation_stage": None if staged is None else
+                   dict(staged["scores_stage"], kernel="k_scores_softmax (dchag_aggregate_level, tokens from HBM)", goal=0.6)}
 
     # the CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
     cpu = None
@@ -251,141 +405,74 @@ def main() -> int:
         import oracle
         per_b = max(1, args.cpu_patches // cfg.B)
         bs, ns = sample_patches(cfg.B, cfg.N, per_b, seed=23)
-        t0 = time.perf_counter()
-        want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns))
-        dt_cpu = time.perf_counter() - t0
-        got = t[6][torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()].to(torch.float64).cpu().numpy()
-        err = float(np.abs(got - want).max() / np.abs(want).max())
+        dt_cpu, err = oracle_check(cfg, pr, t[6], bs, ns)
         cpu = {"value": bs.size * cfg.C / dt_cpu, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{bs.size} of {cfg.B * cfg.N} patches ({bs.size * cfg.C} channel-patch tokens), fp64, "
-                         f"{dt_cpu:.1f} s; GPU-vs-oracle max|err|/max|ref| on them = {err:.2e}"}
+                         f"{dt_cpu:.1f} s; GPU-vs-oracle max|err|/max|ref| on them = {err['max_norm']:.2e}",
+               "error": err}
 
-    # the staged entry points on the same workload: dchag_tokenize, then dchag_aggregate_level on level 1
-    # with its tokens coming from HBM (its score kernel is the HBM-bound aggregation stage)
-    staged = None
-    if not args.no_other and pr.levels[0].kind == "attention" and args.mode == "forward":
-        x, We, be, ce, levels, ws, out = t
-        tok = dchag.dchag_tokenize(x, We, be, ce, cfg.p)
-        lvl_out = dchag.dchag_aggregate_level(tok, levels[0], cfg.heads)
-        torch.cuda.synchronize()
-        dchag.dchag_profile_begin()
-        for _ in range(5):
-            dchag.dchag_aggregate_level(tok, levels[0], cfg.heads, out=lvl_out)
-        torch.cuda.synchronize()
-        acc = {}
-        for name, level, dur in dchag.dchag_profile_end():
-            acc.setdefault(name, []).append(dur)
-        es = 4 if cfg.dtype == "f32" else 2
-        sc_ms = sum(acc["scores"]) / len(acc["scores"])
-        # algorithmic bytes: every token read once, one fp32 softmax weight per (token, head) written once
-        sc_bytes = cfg.tokens * cfg.D * es + cfg.tokens * cfg.heads * 4
-        staged = {"call": "dchag_aggregate_level(level 1), tokens read from HBM",
-                  "stage_ms": {k: round(sum(v) / len(v), 5) for k, v in acc.items()},
-                  "scores_stage": {"bound": "hbm", "achieved": round(sc_bytes / (sc_ms * 1e-3) / 1e9, 1),
-                                   "peak": PEAK["hbm_gbs"], "unit": "GB/s",
-                                   "frac": round(sc_bytes / (sc_ms * 1e-3) / 1e9 / PEAK["hbm_gbs"], 4),
-                                   "note": "scores + softmax over the group: every token read once (2*D bytes), "
-                                           "softmax weights written once (4*heads bytes per token)"}}
-        del tok, lvl_out
+    def side(cfg2, t2, call2, warm=5, steps=10, bw=None, folded=None, label=None):
+        """One side line: time of a call on a workload, and its dominant stage against that stage's roofline."""
+        st2 = make_step(cfg2, t2, call2, bw=bw, folded=folded)
+        spin_up(st2, 60.0)
+        ms2, _, _ = timed(st2, warm, steps)
+        _, _, r2 = timed(st2, 1, steps, profile=True)
+        row = {"workload": cfg2.name, "call": label or call2, "tokens": cfg2.tokens, "ms_per_step": round(ms2, 4),
+               "value": cfg2.tokens / (ms2 * 1e-3), "unit": "tokens/s"}
+        tab = stage_table(cfg2, r2, steps)
+        if tab:
+            row["dominant"] = dominant(tab)
+        return row
 
     other = []
     if not args.no_other and args.workload == "hyperspectral" and args.mode == "forward":
-        # the same workload through the other two calls (their own stage tables come with --mode)
-        mode["name"] = "folded"
-        msf, _, _ = timed(cfg, t, 3, 10, profile=False)
-        other.append({"workload": "hyperspectral", "call": "dchag_forward_folded", "tokens": cfg.tokens,
-                      "ms_per_step": round(msf, 4), "value": cfg.tokens / (msf * 1e-3), "unit": "tokens/s"})
-        # the same with everything that depends on the weights alone prepared once, outside the timed calls
+        # the same workload through the other calls (their own stage tables come with --mode)
+        other.append(side(cfg, t, "dchag_forward_folded"))
         xf, Wef, bef, cef, lvf, wsf, outf = t
         folded = dchag.dchag_fold_value(Wef, bef, cef, lvf, cfg.p, cfg.heads)
         if folded is not None:
-            for _ in range(3):
-                dchag.dchag_forward_prefolded(xf, Wef, bef, cef, lvf, cfg.p, cfg.heads, folded, out=outf, workspace=wsf)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(10):
-                dchag.dchag_forward_prefolded(xf, Wef, bef, cef, lvf, cfg.p, cfg.heads, folded, out=outf, workspace=wsf)
-            e1.record()
-            torch.cuda.synchronize()
-            mspf = e0.elapsed_time(e1) / 10
-            other.append({"workload": "hyperspectral", "call": "dchag_forward_prefolded (weights folded once, outside)",
-                          "tokens": cfg.tokens, "ms_per_step": round(mspf, 4), "value": cfg.tokens / (mspf * 1e-3),
-                          "unit": "tokens/s"})
-        del xf, Wef, bef, cef, lvf, wsf, outf, folded
-        mode["name"], mode["bwd"] = "backward", prepare_backward(cfg, t)
-        msb, _, _ = timed(cfg, t, 2, 5, profile=False)
-        other.append({"workload": "hyperspectral", "call": "dchag_backward (recomputes the forward)",
-                      "tokens": cfg.tokens, "ms_per_step": round(msb, 4), "value": cfg.tokens / (msb * 1e-3),
-                      "unit": "tokens/s"})
+            other.append(side(cfg, t, "dchag_forward_prefolded", folded=folded,
+                              label="dchag_forward_prefolded (weights folded once, outside)"))
+        del folded
+        bw = prepare_backward(cfg, t)
+        other.append(side(cfg, t, "dchag_backward", warm=2, steps=5, bw=bw, label="dchag_backward (recomputes the forward)"))
         # a training step that keeps its activations: dchag_forward_keep + dchag_backward_kept on one workspace
-        bw = mode["bwd"]
-        xk, Wk_, bk_, ck_, lvk, _, outk = t
 
         def train_step():
-            dchag.dchag_forward_keep(xk, Wk_, bk_, ck_, lvk, cfg.p, cfg.heads, bw["ws"], out=outk)
-            dchag.dchag_backward(xk, Wk_, bk_, ck_, lvk, cfg.p, cfg.heads, bw["dout"], bw["grads"], dx=bw["dx"],
+            dchag.dchag_forward_keep(xf, Wef, bef, cef, lvf, cfg.p, cfg.heads, bw["ws"], out=outf)
+            dchag.dchag_backward(xf, Wef, bef, cef, lvf, cfg.p, cfg.heads, bw["dout"], bw["grads"], dx=bw["dx"],
                                  dWe=bw["dWe"], dtok_bias=bw["dtb"], workspace=bw["ws"], kept=True)
-        for _ in range(2):
-            train_step()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(5):
-            train_step()
-        e1.record()
-        torch.cuda.synchronize()
-        mst = e0.elapsed_time(e1) / 5
+        mst, _, _ = timed(train_step, 2, 5)
         other.append({"workload": "hyperspectral", "call": "dchag_forward_keep + dchag_backward_kept (one training step)",
                       "tokens": cfg.tokens, "ms_per_step": round(mst, 4), "value": cfg.tokens / (mst * 1e-3),
                       "unit": "tokens/s"})
-        del xk, Wk_, bk_, ck_, lvk, outk, bw
-        mode["name"], mode["bwd"] = "forward", None
+        del bw
         # the forward with the positional embedding added in the last projection's epilogue
-        xx, Wee, bee, cee, lvls, wss, outt = t
-        pos = torch.randn((cfg.N, cfg.D), device="cuda", dtype=torch.float32).to(outt.dtype)
-        for _ in range(3):
-            dchag.dchag_forward_pos(xx, Wee, bee, cee, lvls, cfg.p, cfg.heads, pos, out=outt, workspace=wss)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(10):
-            dchag.dchag_forward_pos(xx, Wee, bee, cee, lvls, cfg.p, cfg.heads, pos, out=outt, workspace=wss)
-        e1.record()
-        torch.cuda.synchronize()
-        msp = e0.elapsed_time(e1) / 10
+        pos = torch.randn((cfg.N, cfg.D), device="cuda", dtype=torch.float32).to(outf.dtype)
+        msp, _, _ = timed(lambda: dchag.dchag_forward_pos(xf, Wef, bef, cef, lvf, cfg.p, cfg.heads, pos, out=outf,
+                                                          workspace=wsf), 3, 10)
         other.append({"workload": "hyperspectral", "call": "dchag_forward_pos", "tokens": cfg.tokens,
                       "ms_per_step": round(msp, 4), "value": cfg.tokens / (msp * 1e-3), "unit": "tokens/s"})
-        del xx, Wee, bee, cee, lvls, wss, outt, pos
-        del t
+        del xf, Wef, bef, cef, lvf, wsf, outf, pos
+        del t, step
         torch.cuda.empty_cache()
-        c2 = get_config("weather")
-        _, t2 = prepare(c2)
-        ms2, _, _ = timed(c2, t2, 3, 10, profile=False)
-        other.append({"workload": "weather", "tokens": c2.tokens, "ms_per_step": round(ms2, 4),
-                      "value": c2.tokens / (ms2 * 1e-3), "unit": "tokens/s"})
-        mode["name"] = "folded"
-        ms2f, _, _ = timed(c2, t2, 3, 10, profile=False)
-        other.append({"workload": "weather", "call": "dchag_forward_folded", "tokens": c2.tokens,
-                      "ms_per_step": round(ms2f, 4), "value": c2.tokens / (ms2f * 1e-3), "unit": "tokens/s"})
-        mode["name"] = "forward"
-        del t2
-        torch.cuda.empty_cache()
-        # the same hyperspectral shape with a linear first level (D-CHAG-L), cross-attention at the top, and as
-        # one flat cross-attention layer over all 512 channels (the baseline the hierarchy is compared with)
-        for wl in ("hyperspectral_linear", "hyperspectral_flat"):
-            c3 = get_config(wl)
-            _, t3 = prepare(c3)
-            ms3, _, _ = timed(c3, t3, 3, 10, profile=False)
-            other.append({"workload": wl, "tokens": c3.tokens, "ms_per_step": round(ms3, 4),
-                          "value": c3.tokens / (ms3 * 1e-3), "unit": "tokens/s"})
+        # the other configurations (forward, with the oracle's error on a sample spread over the kernels' tiles), the
+        # D-CHAG-L variant of the headline shape and the flat single-layer baseline
+        for wl in ("weather", "tiny", "wide", "deep", "deep1000", "hyperspectral_linear", "hyperspectral_flat"):
+            c2 = get_config(wl)
+            p2, t2 = prepare(c2)
+            row = side(c2, t2, "dchag_forward")
+            if wl in ("weather", "tiny", "wide", "deep", "deep1000"):
+                bs2, ns2 = sample_patches_covering(c2.B, c2.N, max(1, 16 // c2.B), seed=29)
+                dt2, err2 = oracle_check(c2, p2, t2[6], bs2, ns2)
+                row["oracle"] = {"patches": int(bs2.size), "seconds": round(dt2, 1), "error": err2}
+            other.append(row)
+            if wl in ("weather", "hyperspectral_linear"):
+                other.append(side(c2, t2, "dchag_forward_folded"))
             if wl == "hyperspectral_linear":        # and its backward (forward recomputation included)
-                mode["name"], mode["bwd"] = "backward", prepare_backward(c3, t3)
-                ms3b, _, _ = timed(c3, t3, 2, 5, profile=False)
-                other.append({"workload": wl, "call": "dchag_backward (recomputes the forward)", "tokens": c3.tokens,
-                              "ms_per_step": round(ms3b, 4), "value": c3.tokens / (ms3b * 1e-3), "unit": "tokens/s"})
-                mode["name"], mode["bwd"] = "forward", None
-            del t3
+                other.append(side(c2, t2, "dchag_backward", warm=2, steps=5, bw=prepare_backward(c2, t2),
+                                  label="dchag_backward (recomputes the forward)"))
+            del p2, t2
             torch.cuda.empty_cache()
 
     # hierarchy against the flat single layer over the channel count (forward, hyperspectral shape otherwise)
@@ -400,7 +487,7 @@ def main() -> int:
                 c4 = ShapeCfg(f"sweep_{kind}_{C}", "bf16", base.B, C, base.H, base.W, base.p, base.D, base.heads, gsz,
                               "ar1", 2)
                 _, t4 = prepare(c4)
-                ms4, _, _ = timed(c4, t4, 3, 10, profile=False)
+                ms4, _, _ = timed(make_step(c4, t4, "dchag_forward"), 3, 10)
                 row[kind + "_ms"] = round(ms4, 4)
                 row[kind + "_tokens_per_s"] = c4.tokens / (ms4 * 1e-3)
                 del t4
@@ -414,13 +501,14 @@ def main() -> int:
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "call": {"forward": "dchag_forward", "folded": "dchag_forward_folded",
-                                                  "backward": "dchag_backward"}[args.mode], "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "patch": cfg.p, "N": cfg.N,
-                   "D": cfg.D, "heads": cfg.heads, "group_sizes": list(cfg.group_sizes),
+        "config": {"workload": cfg.name, "call": call, "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "patch": cfg.p,
+                   "N": cfg.N, "D": cfg.D, "heads": cfg.heads, "group_sizes": list(cfg.group_sizes),
                    "level_kinds": list(cfg.level_kinds or ["attention"] * len(cfg.group_sizes)),
-                   "tokens_per_step": tokens},
+                   "tokens_per_step": tokens, "spin_up_ms_before_warmup": args.spin_ms},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "targets": targets,
+        "achievable_peaks": achievable,
         "stages": stages,
         "ms_per_step_with_stage_events": ms_prof,
         "wall_ms_per_step": wall_plain,

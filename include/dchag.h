@@ -319,7 +319,10 @@ typedef enum {
   DCHAG_STAGE_BWD_TOKENIZE = 17,   /* tokenizer backward (dWe, token bias, dx)                  */
   DCHAG_STAGE_BWD_CHANNEL_MIX = 18,/* backward of a linear level                                */
   DCHAG_STAGE_FOLD_VALUE = 19,     /* value projection folded into the tokenizer (weight-only)  */
-  DCHAG_STAGE_TOKENIZE_ATTEND = 20 /* tokenizer fused with an attention first level             */
+  DCHAG_STAGE_TOKENIZE_ATTEND = 20,/* tokenizer fused with an attention first level             */
+  DCHAG_STAGE_KEY_PREP = 21        /* projected queries and query-folded keys of one level (level
+                                      >= 1) or of all levels of the call at once (level 0); the
+                                      bf16 path's form of stages 1 and 2 (weight-only)            */
 } dchag_stage;
 
 typedef struct {
@@ -330,6 +333,19 @@ typedef struct {
 
 int dchag_profile_begin(void);
 int dchag_profile_end(dchag_stage_time *records, int cap);
+
+/*
+ * Yardsticks for benchmarks (not part of the paper's method): what this GPU reaches on a loop of nothing but bf16
+ * MFMAs and on a plain stream copy, so that a kernel's rate can be quoted against the achievable rate as well as
+ * against the nominal peak.  Both are asynchronous on `stream`; the caller times them (HIP events).
+ *   dchag_yardstick_mfma: every wavefront of 4 x (compute units) workgroups of 256 threads runs `iters` rounds of
+ *     eight independent 32x32x16 bf16 MFMAs on registers; *flops (HOST) receives the number of flops launched.
+ *     sink: device scratch of sink_floats >= 1024 x (compute units) floats (one value per thread is written).
+ *   dchag_yardstick_copy: dst[0 .. bytes) = src[0 .. bytes) in 16-byte pieces (bytes % 16 == 0): reads `bytes`,
+ *     writes `bytes`.
+ */
+int dchag_yardstick_mfma(int iters, float *sink, size_t sink_floats, double *flops, void *stream);
+int dchag_yardstick_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /*
  * Debugging switches.  The library reads a set of DCHAG_* environment variables (kernel-route overrides used by its

@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     DCHAG_BF16, DCHAG_F32, DchagError, LevelGrads, LevelWeights, dchag_aggregate_level,
     dchag_backward, dchag_debug_reload, dchag_fold_value, dchag_forward,
     dchag_forward_folded, dchag_forward_keep, dchag_forward_pos, dchag_forward_prefolded, dchag_profile_begin,
-    dchag_profile_end, dchag_tokenize, dchag_workspace_bytes, library_path, load_library,
+    dchag_profile_end, dchag_tokenize, dchag_workspace_bytes, dchag_yardstick_copy, dchag_yardstick_mfma, library_path,
+    load_library,
 )

@@ -47,7 +47,7 @@ class _CStageTime(ctypes.Structure):
 STAGE_NAMES = {0: "tokenize", 1: "query", 2: "fold", 3: "scores", 4: "vproj", 5: "softmax_agg", 6: "oproj",
                7: "fused_vagg", 8: "channel_mix", 9: "tokenize_mix", 10: "head_sums", 11: "head_vproj",
                12: "bwd_oproj", 13: "bwd_value", 14: "bwd_softmax", 15: "bwd_tokens", 16: "bwd_key_query",
-               17: "bwd_tokenize", 18: "bwd_channel_mix", 19: "fold_value", 20: "tokenize_attend"}
+               17: "bwd_tokenize", 18: "bwd_channel_mix", 19: "fold_value", 20: "tokenize_attend", 21: "key_prep"}
 
 LEVEL_ATTENTION, LEVEL_LINEAR = 0, 1
 
@@ -105,6 +105,10 @@ def load_library():
     lib.dchag_tokenize.argtypes = [i] * 7 + [vp] * 6
     lib.dchag_aggregate_level.restype = i
     lib.dchag_aggregate_level.argtypes = [i] * 6 + [ctypes.POINTER(_CLevel), vp, vp, vp, sz, vp]
+    lib.dchag_yardstick_mfma.restype = i
+    lib.dchag_yardstick_mfma.argtypes = [i, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
+    lib.dchag_yardstick_copy.restype = i
+    lib.dchag_yardstick_copy.argtypes = [vp, vp, sz, vp]
     lib.dchag_debug_reload.restype = None
     lib.dchag_debug_reload.argtypes = []
     lib.dchag_forward.restype = i
@@ -386,6 +390,22 @@ def dchag_backward(x: torch.Tensor, We: torch.Tensor, be: Optional[torch.Tensor]
     _check(fn(dt, B, C, H, W, p, D, heads, _ptr(x), _ptr(We, x), _ptr(be, x), _ptr(ce, x),
               len(levels), arr, _ptr(dout, x), _ptr(dx, x), _ptr(dWe, x), _ptr(dtok_bias, x), garr,
               ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+
+
+def dchag_yardstick_mfma(iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Launches the MFMA-only yardstick loop; returns the flops it performs.  sink: float32 device scratch."""
+    flops = ctypes.c_double(0.0)
+    _check(load_library().dchag_yardstick_mfma(int(iters), ctypes.c_void_p(sink.data_ptr()), sink.numel(),
+                                               ctypes.byref(flops), _stream(stream)))
+    return float(flops.value)
+
+
+def dchag_yardstick_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> int:
+    """Launches the stream-copy yardstick dst <- src; returns the bytes read (= the bytes written)."""
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().dchag_yardstick_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
+                                               nbytes, _stream(stream)))
+    return nbytes
 
 
 def dchag_profile_begin() -> None:

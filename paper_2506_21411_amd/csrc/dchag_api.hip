@@ -19,6 +19,7 @@
 #include "k_mfma.h"
 #include "k_fused.h"
 #include "k_train.h"
+#include "k_yardstick.h"
 
 using namespace dchag;
 
@@ -166,8 +167,25 @@ LevelWs level_ws(dchag_dtype dt, int B, int Cin, int N, int D, int heads, int g)
 }
 
 struct ForwardWs {
-  size_t tokens, ping, pong, level, ms, msb, cs, mft, total;
+  size_t tokens, ping, pong, level, ms, msb, cs, mft, prep[16], total;
 };
+
+// Projected query, folded keys (fp32 and bf16) of one level, prepared for all levels by one launch at the start of a
+// forward call: qp, mf, mb in this order inside the level's prep block.
+inline size_t prep_bytes(int G, int D, int heads) {
+  return align_up((size_t)G * D * 4) + align_up((size_t)G * heads * D * 4) + align_up((size_t)G * heads * D * 2);
+}
+struct PrepBufs {
+  float *Qp, *Mf;
+  bf16* Mb;
+};
+inline PrepBufs prep_bufs(unsigned char* base, int G, int D, int heads) {
+  PrepBufs p;
+  p.Qp = reinterpret_cast<float*>(base);
+  p.Mf = reinterpret_cast<float*>(base + align_up((size_t)G * D * 4));
+  p.Mb = reinterpret_cast<bf16*>(base + align_up((size_t)G * D * 4) + align_up((size_t)G * heads * D * 4));
+  return p;
+}
 
 // group_sizes has n_levels entries; returns total = 0 when the chain does not end in one group.
 ForwardWs forward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int heads, int n_levels,
@@ -197,6 +215,12 @@ ForwardWs forward_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, int hea
   w.msb = off; off += align_up((size_t)C * heads * pp * 2);
   w.cs = off; off += align_up((size_t)C * heads * 4);
   w.mft = off; off += align_up((size_t)groups_of(C, group_sizes[0]) * D * heads * 4);
+  c_in = C;
+  for (int l = 0; l < n_levels; ++l) {
+    const int G = groups_of(c_in, group_sizes[l]);
+    w.prep[l] = off; off += prep_bytes(G, D, heads);
+    c_in = G;
+  }
   w.total = off;
   return w;
 }
@@ -451,12 +475,40 @@ bool pixel_scores_ok(int p, int heads) {
          pp <= 256 && !dbg(SW_TOKEN_SCORES);
 }
 
+// Projected queries and query-folded keys of n attention levels (bf16, D % 8 == 0) in one launch.
+struct KeyPrepJob {
+  const dchag_level* lv;
+  int G;
+  PrepBufs out;
+  float* MfT;                      // optional transposed copy of the folded keys
+};
+int launch_query_keys(int D, int heads, const KeyPrepJob* jobs, int n, hipStream_t st) {
+  KeyPrepArgs args{};
+  int total = 0;
+  args.n_levels = n;
+  for (int i = 0; i < n; ++i) {
+    const dchag_level* lv = jobs[i].lv;
+    args.lv[i] = KeyPrepLevel{static_cast<const bf16*>(lv->query), static_cast<const bf16*>(lv->Wq),
+                              static_cast<const bf16*>(lv->bq),    static_cast<const bf16*>(lv->Wk),
+                              jobs[i].out.Qp, jobs[i].out.Mf, jobs[i].MfT, jobs[i].out.Mb, total};
+    total += jobs[i].G;
+  }
+  if (total > 65535 || heads > 65535) return DCHAG_ERR_SHAPE;
+  StageTimer tm(DCHAG_STAGE_KEY_PREP, st);
+  // shares of the columns per (head, group): enough blocks for two per compute unit, whole 512-column passes each
+  int shares = 1;
+  while ((long)heads * total * shares < 2L * compute_units() && D % (1024 * shares) == 0 && shares < 8) shares *= 2;
+  k_query_keys<<<dim3(heads, total, shares), 256, (size_t)(D / heads + 1536) * 4, st>>>(D, heads, args);
+  return launch_status();
+}
+
 // Weight-only prep, scores and softmax of one level on the bf16 MFMA path: leaves the projected query in
 // Qp, the folded keys in Mf / Mb and the softmax weights in alpha, laid out [B][G][gpad][heads][Np].
 // alpha_tm (optional): where the softmax weights are also wanted token-major [B,Cin,N,heads]; *tm_done tells whether
 // they were written (only the one-kernel pixel route does it; otherwise the caller re-lays alpha).
 // phase: 0 = everything; 1 = the weight-only prep alone (Qp, Mf, Mb and, with px, its composed score weights; B, N, zin
-// and alpha are not used); 2 = scores and softmax alone, from a prep that is already in those buffers.
+// and alpha are not used); 2 = scores and softmax alone, from a prep that is already in those buffers; 3 = everything
+// but the projected query and the folded keys, which are already in Qp, Mf, Mb (and px->MfT).
 int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, float* Qp, float* Mf,
                 bf16* Mb, float* alpha, hipStream_t st, const PixelScores* px, float* alpha_tm = nullptr,
                 bool* tm_done = nullptr, int phase = 0) {
@@ -465,17 +517,9 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
   const int G = groups_of(Cin, g);
   const int gpad = round_up(g, 8), Np = round_up(N, 32);
   int rc;
-  if (phase != 2) {
-    StageTimer tm(DCHAG_STAGE_QUERY, st);
-    k_project_query<bf16><<<dim3((D + 3) / 4, G), 256, 0, st>>>(
-        D, static_cast<const bf16*>(lv->query), static_cast<const bf16*>(lv->Wq), static_cast<const bf16*>(lv->bq), Qp);
-    if ((rc = launch_status())) return rc;
-  }
-  if (phase != 2) {
-    StageTimer tm(DCHAG_STAGE_FOLD, st);
-    k_fold_query_into_key<bf16><<<dim3((D + 63) / 64, heads, G), 256, 0, st>>>(
-        D, heads, static_cast<const bf16*>(lv->Wk), Qp, Mf, Mb, px ? px->MfT : nullptr);
-    if ((rc = launch_status())) return rc;
+  if (phase != 2 && phase != 3) {
+    const KeyPrepJob job{lv, G, PrepBufs{Qp, Mf, Mb}, px ? px->MfT : nullptr};
+    if ((rc = launch_query_keys(D, heads, &job, 1, st))) return rc;
   }
   if (phase == 1 && !px) return DCHAG_OK;
   if (px) {
@@ -575,8 +619,10 @@ int fast_scores(int B, int Cin, int N, int D, int heads, const dchag_level* lv, 
 // One aggregation level on the bf16 MFMA path: weight-only prep, scores (MFMA on the tokens, or
 // from the pixels at the first level of a forward call), softmax over the group, value projection
 // fused with the weighted sum over the group, output projection.
+// ready: the level's projected query and folded keys, when a launch at the start of the call has prepared them.
 int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* lv, const bf16* zin, bf16* zout,
-                   unsigned char* ws, hipStream_t st, const PixelScores* px = nullptr, const bf16* rowadd = nullptr) {
+                   unsigned char* ws, hipStream_t st, const PixelScores* px = nullptr, const bf16* rowadd = nullptr,
+                   const PrepBufs* ready = nullptr) {
   const int g = lv->group_size;
   const int G = groups_of(Cin, g);
   const int gpad = round_up(g, 8), Np = round_up(N, 32);
@@ -584,8 +630,11 @@ int run_level_fast(int B, int Cin, int N, int D, int heads, const dchag_level* l
   float* alpha = reinterpret_cast<float*>(ws + w.alpha);
   bf16* O = reinterpret_cast<bf16*>(ws + w.o);
   int rc;
-  if ((rc = fast_scores(B, Cin, N, D, heads, lv, zin, reinterpret_cast<float*>(ws + w.qp),
-                        reinterpret_cast<float*>(ws + w.mf), reinterpret_cast<bf16*>(ws + w.mb), alpha, st, px)))
+  const PrepBufs own{reinterpret_cast<float*>(ws + w.qp), reinterpret_cast<float*>(ws + w.mf),
+                     reinterpret_cast<bf16*>(ws + w.mb)};
+  const PrepBufs& pb = ready ? *ready : own;
+  if ((rc = fast_scores(B, Cin, N, D, heads, lv, zin, pb.Qp, pb.Mf, pb.Mb, alpha, st, px, nullptr, nullptr,
+                        ready ? 3 : 0)))
     return rc;
   {
     StageTimer tm(DCHAG_STAGE_FUSED_VAGG, st);
@@ -790,6 +839,27 @@ int dchag_profile_end(dchag_stage_time* records, int cap) {
   return rc ? rc : n;
 }
 
+int dchag_yardstick_mfma(int iters, float* sink, size_t sink_floats, double* flops, void* stream) {
+  if (!sink || !flops) return DCHAG_ERR_NULL;
+  if (iters < 1) return DCHAG_ERR_SHAPE;
+  if (misaligned(sink)) return DCHAG_ERR_ALIGN;
+  const int blocks = 4 * compute_units();                 // 16 wavefronts per compute unit, four per SIMD
+  if (sink_floats < (size_t)blocks * 256) return DCHAG_ERR_WORKSPACE;
+  k_yardstick_mfma<<<dim3(blocks), 256, 0, static_cast<hipStream_t>(stream)>>>(iters, sink);
+  *flops = (double)blocks * 4.0 * (double)iters * 8.0 * 32768.0;
+  return launch_status();
+}
+
+int dchag_yardstick_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src) return DCHAG_ERR_NULL;
+  if (bytes == 0 || bytes % 16) return DCHAG_ERR_SHAPE;
+  if (misaligned(dst) || misaligned(src)) return DCHAG_ERR_ALIGN;
+  const int blocks = 32 * compute_units();
+  k_yardstick_copy<<<dim3(blocks), 256, 0, static_cast<hipStream_t>(stream)>>>(bytes / 16, static_cast<const f32x4*>(src),
+                                                                             static_cast<f32x4*>(dst));
+  return launch_status();
+}
+
 const char* dchag_strerror(int status) {
   switch (status) {
     case DCHAG_OK: return "ok";
@@ -914,6 +984,24 @@ static int forward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
     first = 1;
   } else if ((rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, stream)))
     return rc;
+  // every attention level's weight-only prep (projected query, query folded into the key weights) in ONE launch
+  const bool fast = dt == DCHAG_BF16 && fast_level(dt, D, heads) && !dbg(SW_GENERIC_LEVEL);
+  PrepBufs ready[16];
+  if (fast) {
+    KeyPrepJob jobs[16];
+    int nj = 0, cl = c_in;
+    for (int l = first; l < n_levels; ++l) {
+      const int G = groups_of(cl, gs[l]);
+      if (levels[l].kind == DCHAG_LEVEL_ATTENTION) {
+        ready[l] = prep_bufs(ws + w.prep[l], G, D, heads);
+        const bool px0 = l == 0 && pixel_scores_ok(p, heads);
+        jobs[nj++] = KeyPrepJob{&levels[l], G, ready[l], px0 ? reinterpret_cast<float*>(ws + w.mft) : nullptr};
+      }
+      cl = G;
+    }
+    set_level(0);
+    if (nj && (rc = launch_query_keys(D, heads, jobs, nj, st))) return rc;
+  }
   for (int l = first; l < n_levels; ++l) {
     set_level(l + 1);
     void* zout = (l + 1 == n_levels) ? out : static_cast<void*>(ws + ((l & 1) ? w.pong : w.ping));
@@ -934,7 +1022,7 @@ static int forward_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
       const bool use_px = (l == 0) && pixel_scores_ok(p, heads);
       rc = run_level_fast(B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),
                           static_cast<bf16*>(zout), ws + w.level, st, use_px ? &px : nullptr,
-                          static_cast<const bf16*>(rowadd));
+                          static_cast<const bf16*>(rowadd), &ready[l]);
     }
     else
       rc = run_level<bf16>(dt, B, c_in, N, D, heads, &levels[l], static_cast<const bf16*>(zin),

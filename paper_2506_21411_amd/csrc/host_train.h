@@ -43,7 +43,7 @@ inline KeptLevel kept_level(dchag_dtype dt, int B, int Cin, int N, int D, int he
 }
 
 struct FoldedWs {
-  size_t tokens, ping, pong, level, ms, msb, cs, mft, total;
+  size_t tokens, ping, pong, level, ms, msb, cs, mft, prep[16], total;
 };
 
 // Scratch of the first level's pixel-score shortcut (composed score weights, fp32 and bf16; constants;
@@ -87,6 +87,12 @@ inline FoldedWs folded_ws(dchag_dtype dt, int B, int C, int N, int pp, int D, in
   w.pong = off; off += inter_max;
   w.level = off; off += lvl_max;
   off = pixel_scratch(off, C, pp, D, heads, groups_of(C, group_sizes[0]), &w.ms, &w.msb, &w.cs, &w.mft);
+  c_in = C;
+  for (int l = 0; l < n_levels; ++l) {                   // every level's projected query and folded keys (one launch)
+    const int G = groups_of(c_in, group_sizes[l]);
+    w.prep[l] = off; off += prep_bytes(G, D, heads);
+    c_in = G;
+  }
   w.total = off;
   return w;
 }
@@ -555,6 +561,26 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
   PreparedLayout PL{};
   if (prefolded) PL = prepared_layout(C, p * p, D, heads, n_levels, levels);
+  // every attention level's weight-only prep (projected query, query folded into the key weights) in ONE launch
+  PrepBufs ready[16];
+  bool hoisted = false;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (!prefolded && train_fast(dt, D, heads)) {
+      KeyPrepJob jobs[16];
+      int nj = 0, cl = c_in;
+      for (int l = first; l < n_levels; ++l) {
+        const int G = groups_of(cl, gs[l]);
+        if (levels[l].kind != DCHAG_LEVEL_LINEAR) {
+          ready[l] = prep_bufs(ws + w.prep[l], G, D, heads);
+          jobs[nj++] = KeyPrepJob{&levels[l], G, ready[l], l == 0 ? px.MfT : nullptr};
+        }
+        cl = G;
+      }
+      set_level(0);
+      if (nj && (rc = launch_query_keys(D, heads, jobs, nj, st))) return rc;
+      hoisted = nj > 0;
+    }
+  }
   if constexpr (std::is_same<T, bf16>::value) {
     // an attention first level straight from the pixels: scores through the composed score weights, values through
     // the folded tokenizer weights (which sit where the tokens would have been)
@@ -567,9 +593,13 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
         use_prepared(prefolded, PL, 0, lb);
         px0 = pixel_scores_of<bf16>(x, We, be, ce, H, W, p, const_cast<unsigned char*>(prefolded), PL.ms, PL.msb, PL.cs,
                                     PL.mft);
+      } else if (hoisted) {
+        lb.Qp = ready[0].Qp;
+        lb.Mf = ready[0].Mf;
+        lb.Mb = ready[0].Mb;
       }
       if ((rc = fast_scores(B, C, N, D, heads, &levels[0], nullptr, lb.Qp, lb.Mf, lb.Mb, lb.alpha_f, st, &px0, nullptr,
-                            nullptr, prefolded ? 2 : 0)))
+                            nullptr, prefolded ? 2 : (hoisted ? 3 : 0))))
         return rc;
       // the folded weights: the caller's (prepared once for fixed weights), else formed here, where the tokens would
       // have been; what is left of that region takes partial sums
@@ -613,6 +643,11 @@ int forward_folded_impl(dchag_dtype dt, int B, int C, int H, int W, int p, int D
         if (prefolded && l > 0 && train_fast(dt, D, heads)) {
           use_prepared(prefolded, PL, l, lb);
           phase = 2;
+        } else if (hoisted) {
+          lb.Qp = ready[l].Qp;
+          lb.Mf = ready[l].Mf;
+          lb.Mb = ready[l].Mb;
+          phase = 3;
         }
       }
       rc = folded_level_forward<T>(dt, B, c_in, N, D, heads, &levels[l], zin, zout, lb, st,
@@ -1080,6 +1115,27 @@ int keep_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int h
   if (!first && (rc = dchag_tokenize(dt, B, C, H, W, p, D, x, We, be, ce, ws + w.tokens, st))) return rc;
   const PixelScores px = pixel_scores_of<T>(x, We, be, ce, H, W, p, ws, w.ms, w.msb, w.cs, w.mft);
   const bool use_px = dt == DCHAG_BF16 && train_fast(dt, D, heads) && pixel_scores_ok(p, heads);
+  // every attention level's weight-only prep in ONE launch, straight into the level's kept buffers
+  int phase = 0;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (train_fast(dt, D, heads)) {
+      KeyPrepJob jobs[16];
+      int nj = 0, cl = c_in;
+      for (int l = first; l < n_levels; ++l) {
+        const bool linear = levels[l].kind == DCHAG_LEVEL_LINEAR;
+        const int G = groups_of(cl, gs[l]);
+        if (!linear) {
+          const LevelBufs<bf16> lb = level_bufs<bf16>(ws + w.kept[l], kept_level(dt, B, cl, N, D, heads, gs[l], false,
+                                                                                 l + 1 < n_levels));
+          jobs[nj++] = KeyPrepJob{&levels[l], G, PrepBufs{lb.Qp, lb.Mf, lb.Mb}, (l == 0 && use_px) ? px.MfT : nullptr};
+        }
+        cl = G;
+      }
+      set_level(0);
+      if (nj && (rc = launch_query_keys(D, heads, jobs, nj, st))) return rc;
+      if (nj) phase = 3;
+    }
+  }
   for (int l = first; l < n_levels; ++l) {
     set_level(l + 1);
     const bool linear = levels[l].kind == DCHAG_LEVEL_LINEAR, last = l + 1 == n_levels;
@@ -1090,7 +1146,7 @@ int keep_forward(dchag_dtype dt, int B, int C, int H, int W, int p, int D, int h
       rc = run_level_linear<T>(B, c_in, N, D, &levels[l], zin, y, st);
     else
       rc = folded_level_forward<T>(dt, B, c_in, N, D, heads, &levels[l], zin, y, level_bufs<T>(lw, kl), st,
-                                   (l == 0 && use_px) ? &px : nullptr);
+                                   (l == 0 && use_px) ? &px : nullptr, phase);
     if (rc) return rc;
     c_in = groups_of(c_in, gs[l]);
     zin = y;

@@ -36,9 +36,15 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// Each lane's 16 bytes of a wave-wide direct-to-LDS load land at lds_base + 16 * lane.
+// Each lane's 16 bytes of a wave-wide direct-to-LDS load land at lds_base + 16 * lane (lds_base is wave-uniform).
+// Written as an asm statement on purpose: the compiler files the builtin under "flat access that may touch LDS and
+// global memory", and while one is pending it turns every counted wait of the wavefront into a wait for zero, which
+// serialises the LDS fragment reads of the GEMM loops.  The kernels order these loads themselves (wait_vmcnt + barrier
+// before the stage is read; nothing outstanding when the block retires), so the compiler need not know them; the
+// memory clobber keeps it from moving LDS or global accesses across the statement.
 __device__ __forceinline__ void load16_to_lds(const void* src, void* lds_base) {
-  __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)lds_base, 16, 0, 0);
+  const unsigned lds_off = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_off), "v"(src) : "memory", "m0");
 }
 
 // LDS stages hold rows of 64 bf16 (128 bytes = 8 chunks of 16 bytes).  Chunk c of row r sits at chunk
@@ -49,6 +55,114 @@ __device__ __forceinline__ int swz_chunk(int row) { return (row >> 1) & 7; }
 constexpr int kGemmBM = 256, kGemmBN = 256, kGemmBK = 64, kGemmWM = 2, kGemmWN = 4, kGemmStages = 2;
 constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * kGemmBK * 2;             // 64 KiB
 constexpr int kGemmRingBytes = kGemmStages * kGemmStageBytes;                  // 128 KiB
+
+// ---------------------------------------------------------------------------------------------
+// Weight-only prep of attention levels (paper Section 2.1's cross-attention layer; the learned query is fixed, so its
+// projection and its product with the key weights depend on the weights alone), one launch for any number of levels:
+//   Q[k][i]    = sum_j Wq[k][i][j] query[k][j] + bq[k][i]
+//   M[k][a][d] = (1 / sqrt(dh)) sum_{i in head a} Wk[k][i][d] Q[k][i]      (the key bias shifts every score of a softmax
+//                                                                          equally and is dropped)
+// so that the score of token z for head a is z . M[k][a][:].  grid (heads, all groups of all levels, column shares),
+// block 256: a block of (head a, group k) first forms the dh entries of Q of its head (a wavefront per row of Wq, the
+// rows dealt round-robin), leaves them in LDS (and, the first share, in Qp), then sums the dh rows of Wk of that head
+// into its share of M's columns (fixed summation order).  Writes M as fp32 (Mf), bf16 (Mb) and, where asked,
+// transposed fp32 MfT[G][D][heads].  Requires dh % 4 == 0 and (D / shares) % 8 == 0.  Dynamic LDS: dh + 1536 floats.
+// ---------------------------------------------------------------------------------------------
+struct KeyPrepLevel {
+  const bf16 *query, *Wq, *bq, *Wk;
+  float *Qp, *Mf, *MfT;
+  bf16* Mb;
+  int g_first;                     // index of this level's first group in the launch's group axis
+};
+constexpr int kKeyPrepMaxLevels = 16;
+struct KeyPrepArgs {
+  int n_levels;
+  KeyPrepLevel lv[kKeyPrepMaxLevels];
+};
+
+__global__ __launch_bounds__(256) void k_query_keys(int D, int heads, KeyPrepArgs args) {
+  extern __shared__ float qs[];                          // [dh] projected query of the head, then [3][512] partial sums
+  const int a = blockIdx.x;
+  int l = 0;
+  while (l + 1 < args.n_levels && (int)blockIdx.y >= args.lv[l + 1].g_first) ++l;     // uniform over the block
+  const KeyPrepLevel& P = args.lv[l];
+  const int k = blockIdx.y - P.g_first;
+  const int dh = D / heads;
+  float* part = qs + dh;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bf16* q = P.query + (size_t)k * D;
+  const size_t row0 = (size_t)k * D + (size_t)a * dh;
+  // Q of this head: wavefront w takes rows w, w + 4, ..., eight of them at a time so that their loads are in flight
+  // together (every block of a head computes all of Q_a: the second block's reads come out of L2)
+  for (int r0 = wave; r0 < dh; r0 += 32) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = lane * 8; j < D; j += kWave * 8) {
+      const bf16x8 qv = *reinterpret_cast<const bf16x8*>(q + j);
+      bf16x8 wv[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        wv[t] = *reinterpret_cast<const bf16x8*>(P.Wq + (row0 + min(r0 + 4 * t, dh - 1)) * D + j);
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[t] += (float)wv[t][e] * (float)qv[e];
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float v = wave_sum(acc[t]);
+      const int r = r0 + 4 * t;
+      if (lane == 0 && r < dh) {
+        const float qv = v + (P.bq ? (float)P.bq[row0 + r] : 0.f);
+        if (blockIdx.z == 0) P.Qp[row0 + r] = qv;
+        qs[r] = qv;
+      }
+    }
+  }
+  __syncthreads();
+  // M of this head, this block's share of the columns: a lane takes eight adjacent columns (16-byte loads, eight rows
+  // in flight), wavefront w the w-th quarter of the head's rows; the four partial sums meet in LDS in that order
+  const float scale = rsqrtf((float)dh);
+  const int qrows = dh / 4;
+  const int cper = D / gridDim.z, cbeg = blockIdx.z * cper, cend = cbeg + cper;
+  for (int c0 = cbeg; c0 < cend; c0 += 512) {
+    const int d0 = c0 + lane * 8;
+    const bool live = d0 < cend;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (live) {
+      const bf16* w = P.Wk + (row0 + (size_t)wave * qrows) * D + d0;
+      const float* qh = qs + wave * qrows;
+#pragma unroll 8
+      for (int r = 0; r < qrows; ++r) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(w + (size_t)r * D);
+        const float qr = qh[r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += (float)v[e] * qr;
+      }
+    }
+    if (wave > 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part[(wave - 1) * 512 + lane * 8 + e] = acc[e];
+    }
+    __syncthreads();
+    if (wave == 0 && live) {
+      const size_t o = ((size_t)k * heads + a) * D + d0;
+      bf16x8 b8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        acc[e] = (((acc[e] + part[lane * 8 + e]) + part[512 + lane * 8 + e]) + part[1024 + lane * 8 + e]) * scale;
+        b8[e] = (bf16)acc[e];
+      }
+      *reinterpret_cast<f32x4*>(P.Mf + o) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+      *reinterpret_cast<f32x4*>(P.Mf + o + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+      *reinterpret_cast<bf16x8*>(P.Mb + o) = b8;
+      if (P.MfT) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) P.MfT[((size_t)k * D + d0 + e) * heads + a] = acc[e];
+      }
+    }
+    __syncthreads();
+  }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Scores.  S[b][k][cl][head][n] = z[b, c, n, :] . Mb[k][head][:]   (c = k*g + cl)
@@ -414,6 +528,21 @@ __device__ __forceinline__ void mfma_step_first(f32x16 (&acc)[4][2], const Frags
     for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], zero, 0, 0, 0);
 }
 
+// Scheduling of one k-step of the GEMM loops: the six fragment reads of step kk + 1 and the eight products of step kk
+// that were written since the last scheduling barrier are issued as product, read, product, read, ... (a read behind
+// each of the first six products), and nothing moves across the end of the step.  Left alone, the compiler sinks the
+// reads next to their use to save registers and then waits for each of them in turn; in this order every wait is a
+// counted one for fragments that were requested a whole step earlier.
+__device__ __forceinline__ void pin_step_schedule() {
+#pragma unroll
+  for (int t = 0; t < 6; ++t) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // One 64-deep slice: four k-steps with the fragments of step kk+1 read while step kk multiplies.
 __device__ __forceinline__ void mfma_slice(f32x16 (&acc)[4][2], const unsigned char* stage, const GemmLane& L) {
   Frags f0, f1;
@@ -571,25 +700,31 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
     for (int chunk = 0; chunk < ic.nch; ++chunk, ++gcc) {
       f32x16 acc[4][2];
       for (int kt = 0; kt < KT; ++kt) {
-        // k-steps 0..2 of the current slice; the fragments of step 0 were read across the last barrier
+        // k-steps 0..2 of the current slice; the fragments of step 0 were read across the last barrier.  Each step's
+        // products are issued with the reads of the step after it between them (pin_step_schedule).
         const unsigned char* st = smem + sc * kGemmStageBytes;
+        __builtin_amdgcn_sched_barrier(0);
         read_frags(f1, st, L, 1);
         if (kt == 0) mfma_step_first(acc, f0);           // a chunk starts from C = 0
         else mfma_step(acc, f0);
-        // The two wavefronts of a SIMD (wm = 0 and 1) issue their loads at different points of the slice, so
-        // that one's address arithmetic and load issue overlaps the other's MFMAs.
+        pin_step_schedule();
         if (L.wm == 1) issue();                          // slice after next -> the stage released at the last barrier
+        __builtin_amdgcn_sched_barrier(0);
         read_frags(f0, st, L, 2);
         mfma_step(acc, f1);
+        pin_step_schedule();
         read_frags(f1, st, L, 3);
         mfma_step(acc, f0);
+        pin_step_schedule();
         // every read of this stage is in registers and the next slice has landed: swap stages
         __builtin_amdgcn_s_waitcnt(0);                   // vmcnt(0) and lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         if (L.wm == 0) issue();                          // slice after next -> the stage just released
         sc ^= 1;
+        __builtin_amdgcn_sched_barrier(0);
         read_frags(f0, smem + sc * kGemmStageBytes, L, 0);
         mfma_step(acc, f1);
+        pin_step_schedule();
       }
       // o += alpha * acc over the 8 channels of the chunk (channel 2i in rows q = 0,1; 2i+1 in rows q = 2,3)
       const float* al = reinterpret_cast<const float*>(alds + (gcc % 3) * atile);
@@ -694,21 +829,40 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
     si ^= 1;
     ki = (ki + 1 < KT) ? ki + 1 : ki;                    // past the end: harmless re-load of the last slice
   };
+  // The pipeline of k_vagg_mfma: the fragments of a slice's first k-step are read across the barrier that hands the
+  // slice over, the products of its last k-step are issued behind that barrier, and the two wavefronts of a SIMD
+  // (wm = 0 and 1) issue their loads at different points of the slice.
   f32x16 acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  issue();
+  Frags f0, f1;
+  issue();                                               // slice 0 -> stage 0
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  if (L.wm == 0) issue();                                // slice 1 -> stage 1 (wm = 1 issues inside the loop)
+  read_frags(f0, smem, L, 0);
   int sc = 0;
   for (int kt = 0; kt < KT; ++kt) {
-    wait_vmcnt<0>();
+    const unsigned char* st = smem + sc * kGemmStageBytes;
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f1, st, L, 1);
+    if (kt == 0) mfma_step_first(acc, f0);
+    else mfma_step(acc, f0);
+    pin_step_schedule();
+    if (L.wm == 1) issue();                              // slice kt + 1 -> the stage released at the last barrier
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f0, st, L, 2);
+    mfma_step(acc, f1);
+    pin_step_schedule();
+    read_frags(f1, st, L, 3);
+    mfma_step(acc, f0);
+    pin_step_schedule();
+    __builtin_amdgcn_s_waitcnt(0);                       // vmcnt(0) and lgkmcnt(0): slice kt + 1 has landed
     __builtin_amdgcn_s_barrier();
-    issue();
-    mfma_slice(acc, smem + sc * kGemmStageBytes, L);
+    if (L.wm == 0) issue();                              // slice kt + 2 -> the stage just released
     sc ^= 1;
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f0, smem + sc * kGemmStageBytes, L, 0);   // past the last slice: a re-load of it, read and not used
+    mfma_step(acc, f1);
+    pin_step_schedule();
   }
   wait_vmcnt<0>();                                       // no load may still target LDS when the block retires
 #pragma unroll

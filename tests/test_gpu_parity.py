@@ -3,7 +3,9 @@ seeded inputs.
 
 Error measure (the target gives only a number): for an output tensor y and the oracle's y^,
     err = max_i |y_i - y^_i| / max_i |y^_i|
-must stay below 2e-2 for bf16 (bf16 storage, fp32 accumulation) and 1e-4 for fp32.
+must stay below 2e-2 for bf16 (bf16 storage, fp32 accumulation) and 1e-4 for fp32.  The full-size tests also print,
+beside that gated figure, the element-wise error max_i |y_i - y^_i| / max(|y^_i|, rms y^) and the rms error
+rms(y - y^) / rms(y^) (an element-wise relative error is unbounded where y^ is near zero, hence the rms floor).
 """
 import sys
 
@@ -14,6 +16,7 @@ import torch
 import oracle
 import paper_2506_21411_amd as dchag
 from workloads import ShapeCfg, get_config, make_problem, make_tokens, n_groups, sample_patches
+from workloads import sample_patches_covering
 from workloads import make_level, make_linear_level
 
 pytestmark = pytest.mark.gpu
@@ -43,6 +46,16 @@ def rel_err(got, want):
     assert got.shape == want.shape
     assert np.isfinite(got).all()
     return float(np.abs(got - want).max() / np.abs(want).max())
+
+
+def err_figures(got, want):
+    """(max-normalised error: the gated one, element-wise error with an rms floor, rms error), see the module docstring."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    d = np.abs(got - want)
+    rms = float(np.sqrt(np.mean(np.square(want))))
+    return (float(d.max() / np.abs(want).max()), float((d / np.maximum(np.abs(want), rms)).max()),
+            float(np.sqrt(np.mean(np.square(d))) / rms))
 
 
 def host(t):
@@ -450,11 +463,38 @@ def test_forward_can_be_captured_in_a_graph_and_replayed():
         assert torch.equal(out, eager)
 
 
-@pytest.mark.parametrize("name,per_batch", [("weather", 8), ("hyperspectral", 6), ("wide", 3), ("deep", 2),
-                                            ("deep1000", 2), ("hyperspectral_linear", 6),
-                                            ("hyperspectral_flat", 4)])
+FLAT1024 = ShapeCfg("flat1024", "bf16", 4, 1024, 128, 128, 8, 1024, 16, (1024,), "ar1", 2)
+
+
+@pytest.mark.parametrize("name,per_batch", [("weather", 22), ("hyperspectral", 14), ("wide", 40), ("deep", 22),
+                                            ("deep1000", 22), ("hyperspectral_linear", 14),
+                                            ("hyperspectral_flat", 14), ("flat1024", 6)])
 def test_forward_full_size_on_sampled_patches(name, per_batch):
-    _forward_on_sampled_patches(get_config(name), name, per_batch)
+    """Every configuration of the benchmark at full size (and the flat layer at the sweep's largest channel count,
+    whose value GEMM is dealt to eight items per group).  The sample holds, per batch item, the first and last patch
+    and the seams of the 32- and 128-patch tiles, and over the batch every position inside a 32-patch tile and every
+    tile of the patch axis (where B * per_batch allows), so the ends of every XCD's item range are in it."""
+    cfg = FLAT1024 if name == "flat1024" else get_config(name)
+    _forward_on_sampled_patches(cfg, name, per_batch, covering=True)
+
+
+@pytest.mark.parametrize("name", ["hyperspectral", "deep1000"])
+def test_forward_full_size_fast_and_generic_routes_agree_everywhere(monkeypatch, name):
+    """The whole output, every (b, n), of the MFMA path against the shape-generic level kernels (another tiling, the
+    projected values materialised and rounded once more): two independent GPU routes, compared at full size within the
+    bf16 tolerance.  The oracle samples patches; this covers every tile and item boundary."""
+    cfg = get_config(name)
+    say(f"full-size {name}: generating inputs")
+    pr = make_problem(cfg)
+    fast = run_forward(pr).float()
+    monkeypatch.setenv("DCHAG_GENERIC_LEVEL", "1")
+    say(f"full-size {name}: generic route")
+    slow = run_forward(pr).float()
+    scale = float(slow.abs().max())
+    worst = float((fast - slow).abs().amax(dim=-1).max()) / scale
+    per_row = (fast - slow).abs().amax(dim=-1) / scale                      # [B, N]
+    say(f"full-size {name}: fast vs generic, max|d|/max|ref| over all {per_row.numel()} patches = {worst:.3e}")
+    assert torch.isfinite(fast).all() and worst < TOL["bf16"]
 
 
 @pytest.mark.parametrize("narrow", [False, True])
@@ -485,19 +525,22 @@ def test_forward_linear_first_level_of_8x8_patches(monkeypatch, route):
     _forward_on_sampled_patches(cfg, f"linear first level of 8 x 8 patches, {route}", 30)
 
 
-def _forward_on_sampled_patches(cfg, name, per_batch):
+def _forward_on_sampled_patches(cfg, name, per_batch, covering=False):
     """The configurations of the benchmark at full size, in the launch configuration the benchmark
     times; the oracle computes a seeded sample of patches (every weight takes part in every patch)."""
     say(f"full-size {name}: generating inputs")
     pr = make_problem(cfg)
     say(f"full-size {name}: running the GPU path")
     out = run_forward(pr)
-    bs, ns = sample_patches(cfg.B, cfg.N, per_batch, seed=17)
+    sampler = sample_patches_covering if covering else sample_patches
+    bs, ns = sampler(cfg.B, cfg.N, per_batch, seed=17)
     say(f"full-size {name}: oracle on {bs.size} patches")
     want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns))
     got = host(out[torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()])
     err = rel_err(got, want)
-    say(f"full-size {name}: err={err:.3e}")
+    mx, el, rms = err_figures(got, want)
+    say(f"full-size {name}: max|d|/max|ref| = {mx:.3e} (gated), element-wise |d|/max(|ref|, rms ref) = {el:.3e}, "
+        f"rms(d)/rms(ref) = {rms:.3e}")
     assert err < TOL[cfg.dtype]
     # property that holds at any size: every output row is finite and no row was left untouched
     assert torch.isfinite(out.float()).all()

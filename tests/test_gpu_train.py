@@ -12,7 +12,7 @@ import torch
 
 import oracle
 import paper_2506_21411_amd as dchag
-from workloads import ShapeCfg, get_config, make_problem, n_groups, sample_patches
+from workloads import ShapeCfg, get_config, make_problem, n_groups, sample_patches, sample_patches_covering
 
 pytestmark = pytest.mark.gpu
 
@@ -109,8 +109,8 @@ def test_forward_folded_matches_oracle(kw):
     assert err < TOL[d]
 
 
-@pytest.mark.parametrize("name,per_batch", [("weather", 4), ("hyperspectral", 4), ("hyperspectral_linear", 4),
-                                            ("hyperspectral_flat", 3), ("deep", 2), ("wide", 2), ("deep1000", 2)])
+@pytest.mark.parametrize("name,per_batch", [("weather", 11), ("hyperspectral", 8), ("hyperspectral_linear", 8),
+                                            ("hyperspectral_flat", 6), ("deep", 11), ("wide", 20), ("deep1000", 11)])
 def test_forward_folded_full_size_on_sampled_patches(name, per_batch):
     """dchag_forward_folded at the benchmark's sizes and launch configuration, against the oracle on a seeded sample of
     patches; every output row is finite."""
@@ -121,7 +121,7 @@ def test_forward_folded_full_size_on_sampled_patches(name, per_batch):
     out = dchag.dchag_forward_folded(dev(pr.x, d), dev(pr.We, d), dev(pr.be, d), dev(pr.ce, d),
                                      [dev_level(lv, d) for lv in pr.levels], cfg.p, cfg.heads)
     torch.cuda.synchronize()
-    bs, ns = sample_patches(cfg.B, cfg.N, per_batch, seed=29)
+    bs, ns = sample_patches_covering(cfg.B, cfg.N, per_batch, seed=29)      # tile seams and both ends of the patch axis
     say(f"forward_folded full-size {name}: oracle on {bs.size} patches")
     want = oracle.forward(pr.x, pr.We, pr.be, pr.ce, pr.levels, cfg.p, cfg.heads, sample=(bs, ns))
     got = host(out[torch.from_numpy(bs).long().cuda(), torch.from_numpy(ns).long().cuda()])
@@ -462,8 +462,8 @@ def test_backward_is_deterministic():
 RAGGED_TILES = dict(dtype="bf16", B=4, C=250, H=40, W=100, p=4, D=256, heads=8, group_sizes=(32, 8))
 
 
-@pytest.mark.parametrize("name,per_batch", [("weather", 4), ("hyperspectral", 3), ("ragged_tiles", 12), ("deep", 2),
-                                            ("wide", 2), ("hyperspectral_linear", 3), ("hyperspectral_flat", 2)])
+@pytest.mark.parametrize("name,per_batch", [("weather", 6), ("hyperspectral", 4), ("ragged_tiles", 12), ("deep", 4),
+                                            ("wide", 6), ("hyperspectral_linear", 4), ("hyperspectral_flat", 3)])
 def test_backward_full_size_with_upstream_gradient_on_sampled_patches(name, per_batch):
     """Full-size configurations in the launch configuration of the benchmark.  The upstream gradient is
     non-zero on a seeded sample of patches only; the path is independent per patch, so every other patch
@@ -471,7 +471,7 @@ def test_backward_full_size_with_upstream_gradient_on_sampled_patches(name, per_
     cfg = cfg_of(**RAGGED_TILES) if name == "ragged_tiles" else get_config(name)
     say(f"backward full-size {name}: generating inputs")
     pr = make_problem(cfg)
-    bs, ns = sample_patches(cfg.B, cfg.N, per_batch, seed=19)
+    bs, ns = sample_patches_covering(cfg.B, cfg.N, per_batch, seed=19)      # tile seams and both ends of the patch axis
     rng = np.random.Generator(np.random.PCG64(43))
     from workloads import round_to_bf16
     ds = round_to_bf16(rng.standard_normal((bs.size, cfg.D)).astype(np.float32))

@@ -16,6 +16,8 @@ the same numbers.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence
 
@@ -23,7 +25,7 @@ import numpy as np
 
 __all__ = [
     "ShapeCfg", "Level", "Problem", "CONFIGS", "get_config", "n_groups", "make_level", "make_linear_level",
-    "level_inputs", "round_to_bf16", "make_problem", "make_tokens", "sample_patches",
+    "level_inputs", "round_to_bf16", "make_problem", "make_tokens", "sample_patches", "sample_patches_covering",
 ]
 
 
@@ -84,19 +86,37 @@ def get_config(name: str) -> ShapeCfg:
     return CONFIGS[name]
 
 
+_BLOCK = 1 << 22                       # elements per block of the block-parallel paths below
+_THREADS = max(1, min(16, os.cpu_count() or 1))
+
+
+def _for_blocks(n: int, fn) -> None:
+    """fn(lo, hi) over the blocks of range(n), on a few threads for large n (numpy releases the GIL in these loops);
+    the result does not depend on the number of threads."""
+    spans = [(i, min(n, i + _BLOCK)) for i in range(0, n, _BLOCK)]
+    if len(spans) <= 1 or _THREADS == 1:
+        for lo, hi in spans:
+            fn(lo, hi)
+        return
+    with ThreadPoolExecutor(_THREADS) as ex:
+        list(ex.map(lambda sp: fn(*sp), spans))
+
+
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bf16 (ties to even); result stays float32."""
     a = np.ascontiguousarray(a, dtype=np.float32)
     out = np.empty_like(a)
     src, dst = a.reshape(-1).view(np.uint32), out.reshape(-1).view(np.uint32)
-    step = 1 << 24                                     # blocks that stay in cache-friendly temporaries
-    for i in range(0, src.size, step):
-        u = src[i:i + step]
+
+    def block(lo, hi):
+        u = src[lo:hi]
         r = (u >> np.uint32(16)) & np.uint32(1)
         r += np.uint32(0x7FFF)
         r += u                                         # finite inputs only: no carry out of 32 bits
         r &= np.uint32(0xFFFF0000)
-        dst[i:i + step] = r
+        dst[lo:hi] = r
+
+    _for_blocks(src.size, block)
     return out
 
 
@@ -130,10 +150,26 @@ class Problem:
 
 
 def _normal(rng: np.random.Generator, shape, std: float = 1.0) -> np.ndarray:
-    a = rng.standard_normal(shape, dtype=np.float32)
-    if std != 1.0:
-        a *= np.float32(std)
-    return a
+    """N(0, std^2) float32 values.  Tensors of up to one block come straight from `rng`; a larger one takes ONE
+    63-bit draw from `rng` as its key and fills block i from PCG64([key, i]), so its blocks can be drawn on several
+    threads (the values depend on the seed alone, never on the number of threads)."""
+    n = int(np.prod(shape))
+    if n <= _BLOCK:
+        a = rng.standard_normal(shape, dtype=np.float32)
+        if std != 1.0:
+            a *= np.float32(std)
+        return a
+    key = int(rng.integers(0, 2 ** 63 - 1))
+    flat = np.empty(n, dtype=np.float32)
+
+    def block(lo, hi):
+        g = np.random.Generator(np.random.PCG64([key, lo // _BLOCK]))
+        g.standard_normal(out=flat[lo:hi], dtype=np.float32)
+        if std != 1.0:
+            flat[lo:hi] *= np.float32(std)
+
+    _for_blocks(n, block)
+    return flat.reshape(shape)
 
 
 def _box5(f: np.ndarray) -> np.ndarray:
@@ -264,6 +300,34 @@ def sample_patches(B: int, N: int, per_batch: int, seed: int):
         while len(pick) < k:
             pick.add(int(rng.integers(0, N)))
         for n in sorted(pick):
+            bs.append(b)
+            ns.append(n)
+    return np.asarray(bs, dtype=np.int32), np.asarray(ns, dtype=np.int32)
+
+
+def sample_patches_covering(B: int, N: int, per_batch: int, seed: int, tile: int = 32):
+    """A seeded sample of per_batch patches per batch item that is spread over the kernels' tiling: every batch item
+    gets its first and last patch and the seams of the 32- and 128-patch tiles (31, 32, 127, 128); the rest walks
+    through the residues modulo `tile` in a seeded order while cycling over the tiles, so that with
+    B * per_batch >= tile + 6 * B every position inside a tile and every tile of the patch axis is hit somewhere in the
+    sample.  Returns two int32 arrays (b, n), sorted by (b, n)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ntile = (N + tile - 1) // tile
+    want = min(per_batch, N)
+    forced = [n for n in (0, N - 1, tile - 1, tile, 4 * tile - 1, 4 * tile) if 0 <= n < N]
+    picks = [set(forced[:want]) for _ in range(B)]
+    order = [int(r) for r in rng.permutation(tile)]
+    i = 0
+    while any(len(p) < want for p in picks):
+        n = ((i * 3 + i // tile) % ntile) * tile + order[i % tile]
+        i += 1
+        if n >= N:
+            continue
+        b = min(range(B), key=lambda q: (len(picks[q]), q))
+        picks[b].add(n)
+    bs, ns = [], []
+    for b in range(B):
+        for n in sorted(picks[b]):
             bs.append(b)
             ns.append(n)
     return np.asarray(bs, dtype=np.int32), np.asarray(ns, dtype=np.int32)
