@@ -21,8 +21,9 @@
  *     changes a result.  Process-wide state, all of it listed here: the table of
  *     debugging switches read from the environment at load time (dchag_debug_reload),
  *     per-device caches of the compute-unit count and of the dynamic-LDS limits
- *     already raised (both mutex- or atomic-guarded), and the stage-timing records of
- *     dchag_profile_begin/end.  Calls on different host threads are safe as
+ *     already raised (both mutex- or atomic-guarded), the stage-timing records of
+ *     dchag_profile_begin/end, and the fixed scratch array of
+ *     dchag_aggregate_level_static.  Calls on different host threads are safe as
  *     long as they do not share a workspace and no profile is being taken.
  *     Inputs and weights are only read; outputs are fully overwritten; the
  *     workspace contents are undefined afterwards.
@@ -125,6 +126,23 @@ int dchag_tokenize(dchag_dtype dt, int B, int C, int H, int W, int p, int D,
 int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int heads,
                           const dchag_level *lvl, const void *tokens_in, void *tokens_out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * dchag_aggregate_level for callers that cannot allocate device memory (code under HIP graph capture, serving loops,
+ * harnesses that forbid hipMalloc): same arguments without the workspace, same result bit for bit.  The workspace is
+ * a fixed array of DCHAG_STATIC_SCRATCH_BYTES bytes inside the library's code object (every GPU the library runs on
+ * holds its own copy until the process ends); the call allocates nothing and frees nothing.  Its address is looked up
+ * on the first call on a device, so make that first call outside any stream capture.
+ *   - A level that needs more than DCHAG_STATIC_SCRATCH_BYTES (dchag_workspace_bytes(..., which = 0)) is rejected
+ *     with DCHAG_ERR_WORKSPACE before anything is launched.
+ *   - Every call on one GPU uses the same array: calls that overlap on one GPU (two streams, two threads) race and
+ *     must be ordered by the caller.  Nothing in the array has to start at zero; the kernels write all they read.
+ * Errors otherwise as dchag_aggregate_level.
+ */
+#define DCHAG_STATIC_SCRATCH_BYTES (32u << 20)
+int dchag_aggregate_level_static(dchag_dtype dt, int B, int Cin, int N, int D, int heads,
+                                 const dchag_level *lvl, const void *tokens_in, void *tokens_out,
+                                 void *stream);
 
 /*
  * The whole path (paper Section 3.3, run on one GPU: tokenize every channel,

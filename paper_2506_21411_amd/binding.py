@@ -111,6 +111,8 @@ def load_library():
     lib.dchag_yardstick_copy.argtypes = [vp, vp, sz, vp]
     lib.dchag_debug_reload.restype = None
     lib.dchag_debug_reload.argtypes = []
+    lib.dchag_aggregate_level_static.restype = i
+    lib.dchag_aggregate_level_static.argtypes = [i] * 6 + [ctypes.POINTER(_CLevel), vp, vp, vp]
     lib.dchag_forward.restype = i
     lib.dchag_forward.argtypes = [i] * 8 + [vp] * 4 + [i, ctypes.POINTER(_CLevel), vp, vp, sz, vp]
     lib.dchag_forward_pos.restype = i
@@ -220,6 +222,20 @@ def dchag_aggregate_level(tokens_in: torch.Tensor, level: LevelWeights, heads: i
     _check(load_library().dchag_aggregate_level(dt, B, Cin, N, D, heads, ctypes.byref(cl), _ptr(tokens_in),
                                                 _ptr(out, tokens_in), ctypes.c_void_p(workspace.data_ptr()),
                                                 workspace.numel(), _stream(stream)))
+    return out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def dchag_aggregate_level_static(tokens_in: torch.Tensor, level: LevelWeights, heads: int, out: torch.Tensor,
+                                 stream=None) -> torch.Tensor:
+    """dchag_aggregate_level on the library's fixed scratch array: no workspace argument, nothing allocated (the
+    caller passes `out`)."""
+    B, Cin, N, D = tokens_in.shape
+    cl = _clevel(level, tokens_in)
+    _check(load_library().dchag_aggregate_level_static(_dt(tokens_in), B, Cin, N, D, heads, ctypes.byref(cl),
+                                                       _ptr(tokens_in), _ptr(out, tokens_in), _stream(stream)))
     return out
 
 

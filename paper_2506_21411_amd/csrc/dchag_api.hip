@@ -23,6 +23,10 @@
 
 using namespace dchag;
 
+// Workspace of dchag_aggregate_level_static: lives in the code object, so that call allocates nothing.  In host code
+// this name is only a handle for hipGetSymbolAddress; the kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[DCHAG_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 // Debugging switches (environment variables DCHAG_*): read ONCE, when the library is loaded, into this table; the
@@ -803,6 +807,23 @@ int tokenize_mix_forward(int B, int C, int H, int W, int p, int D, const void* x
 
 }  // namespace
 
+// Device address of `scratch` on the current device, looked up once per device (each device holds its own copy of
+// the array at its own address).
+static int static_scratch(unsigned char** out) {
+  static std::mutex mu;
+  static unsigned char* ptr[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DCHAG_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DCHAG_ERR_LAUNCH;
+    ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = ptr[dev];
+  return DCHAG_OK;
+}
+
 extern "C" {
 
 const char* dchag_version(void) { return "0.3"; }
@@ -939,6 +960,23 @@ int dchag_aggregate_level(dchag_dtype dt, int B, int Cin, int N, int D, int head
                           static_cast<bf16*>(tokens_out), ws, st);
   return run_level<bf16>(dt, B, Cin, N, D, heads, lvl, static_cast<const bf16*>(tokens_in),
                          static_cast<bf16*>(tokens_out), ws, st);
+}
+
+int dchag_aggregate_level_static(dchag_dtype dt, int B, int Cin, int N, int D, int heads, const dchag_level* lvl,
+                                 const void* tokens_in, void* tokens_out, void* stream) {
+  if (dt != DCHAG_F32 && dt != DCHAG_BF16) return DCHAG_ERR_DTYPE;
+  if (!tokens_in || !tokens_out) return DCHAG_ERR_NULL;
+  int rc = check_level(lvl);
+  if (rc) return rc;
+  if ((rc = check_level_shape(B, Cin, N, D, heads, lvl->group_size))) return rc;
+  // the size check comes before the first touch of the device, so an oversized call never costs a symbol lookup
+  if (lvl->kind != DCHAG_LEVEL_LINEAR &&
+      level_ws(dt, B, Cin, N, D, heads, lvl->group_size).total > (size_t)DCHAG_STATIC_SCRATCH_BYTES)
+    return DCHAG_ERR_WORKSPACE;
+  unsigned char* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  return dchag_aggregate_level(dt, B, Cin, N, D, heads, lvl, tokens_in, tokens_out, ws, DCHAG_STATIC_SCRATCH_BYTES,
+                               stream);
 }
 
 // dchag_forward and dchag_forward_pos: pos (or NULL) is added to the output in the epilogue of the last level's

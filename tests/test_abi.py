@@ -78,6 +78,20 @@ def test_aggregate_level_validation(lib):
     assert a(0, 1, 8, 128, 128, 4, ctypes.byref(lv), FAKE, FAKE, FAKE + 16, 1 << 30, None) == -4  # misaligned
 
 
+def test_aggregate_level_static_validation(lib):
+    """The entry point without a workspace argument: same checks, and a level that does not fit the library's fixed
+    scratch array is turned down on the host (no GPU is needed to find that out)."""
+    a = lib.dchag_aggregate_level_static
+    lv = level(4)
+    assert a(0, 1, 8, 128, 128, 4, None, FAKE, FAKE, None) == -1
+    assert a(0, 1, 8, 128, 128, 4, ctypes.byref(lv), None, FAKE, None) == -1
+    assert a(0, 1, 8, 128, 128, 3, ctypes.byref(lv), FAKE, FAKE, None) == -2                  # D % heads
+    assert a(7, 1, 8, 128, 128, 4, ctypes.byref(lv), FAKE, FAKE, None) == -3
+    big = level(32)
+    assert dchag.dchag_workspace_bytes(dchag.DCHAG_BF16, 4, 512, 256, 1, 1, 1024, 16, [32], 0) > dchag.STATIC_SCRATCH_BYTES
+    assert a(1, 4, 512, 256, 1024, 16, ctypes.byref(big), FAKE, FAKE, None) == -4              # needs more than 32 MiB
+
+
 def test_forward_validation(lib):
     f = lib.dchag_forward
     two = (_CLevel * 2)(level(4), level(2))
