@@ -361,9 +361,12 @@ int dchag_profile_end(dchag_stage_time *records, int cap);
  *     sink: device scratch of sink_floats >= 1024 x (compute units) floats (one value per thread is written).
  *   dchag_yardstick_copy: dst[0 .. bytes) = src[0 .. bytes) in 16-byte pieces (bytes % 16 == 0): reads `bytes`,
  *     writes `bytes`.
+ *   dchag_yardstick_read: reads src[0 .. bytes) in 16-byte pieces and stores nothing (sink: device scratch of at
+ *     least 256 floats, never written in practice): the streaming-read rate.
  */
 int dchag_yardstick_mfma(int iters, float *sink, size_t sink_floats, double *flops, void *stream);
 int dchag_yardstick_copy(void *dst, const void *src, size_t bytes, void *stream);
+int dchag_yardstick_read(const void *src, size_t bytes, float *sink, void *stream);
 
 /*
  * Debugging switches.  The library reads a set of DCHAG_* environment variables (kernel-route overrides used by its

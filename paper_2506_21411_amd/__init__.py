@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     dchag_aggregate_level_static,
     dchag_backward, dchag_debug_reload, dchag_fold_value, dchag_forward,
     dchag_forward_folded, dchag_forward_keep, dchag_forward_pos, dchag_forward_prefolded, dchag_profile_begin,
-    dchag_profile_end, dchag_tokenize, dchag_workspace_bytes, dchag_yardstick_copy, dchag_yardstick_mfma, library_path,
-    load_library,
+    dchag_profile_end, dchag_tokenize, dchag_workspace_bytes, dchag_yardstick_copy, dchag_yardstick_mfma, dchag_yardstick_read, library_path,
+    load_library, use_library,
 )

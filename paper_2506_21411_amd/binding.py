@@ -90,6 +90,14 @@ def library_path() -> str:
     return _LIB_PATH
 
 
+def use_library(path: str) -> None:
+    """Point the binding at another build of the library (the benchmark's timing-probe builds); before the first call."""
+    global _LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _LIB_PATH = os.path.abspath(path)
+
+
 def load_library():
     """Loads libdchag.so (built by `python -m paper_2506_21411_amd.build`); raises if it is not there."""
     global _lib
@@ -109,6 +117,8 @@ def load_library():
     lib.dchag_yardstick_mfma.argtypes = [i, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
     lib.dchag_yardstick_copy.restype = i
     lib.dchag_yardstick_copy.argtypes = [vp, vp, sz, vp]
+    lib.dchag_yardstick_read.restype = i
+    lib.dchag_yardstick_read.argtypes = [vp, sz, vp, vp]
     lib.dchag_debug_reload.restype = None
     lib.dchag_debug_reload.argtypes = []
     lib.dchag_aggregate_level_static.restype = i
@@ -421,6 +431,14 @@ def dchag_yardstick_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> i
     nbytes = src.numel() * src.element_size()
     _check(load_library().dchag_yardstick_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
                                                nbytes, _stream(stream)))
+    return nbytes
+
+
+def dchag_yardstick_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> int:
+    """Launches the streaming-read yardstick over src; returns the bytes read.  sink: float32 device scratch (>= 256)."""
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().dchag_yardstick_read(ctypes.c_void_p(src.data_ptr()), nbytes,
+                                               ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
     return nbytes
 
 

@@ -17,9 +17,13 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, out: str = LIB, defines=()) -> str:
+    """Compiles the library to `out` (default: the in-tree libdchag.so); `defines` are extra -D macros (the timing
+    probes of the GEMM core, which must never be built into the in-tree library)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + SOURCES
+    if defines and os.path.abspath(out) == os.path.abspath(LIB):
+        raise ValueError("a build with extra defines needs its own --out file")
+    cmd = [hipcc] + HIPCC_FLAGS + ["-D" + d for d in defines] + ["-o", out] + SOURCES
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -28,9 +32,14 @@ def build(verbose: bool = True) -> str:
         print(out, flush=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    build()
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default=LIB)
+    ap.add_argument("--define", action="append", default=[], help="extra macro, e.g. DCHAG_GEMM_PROBE=8 (needs --out)")
+    a = ap.parse_args()
+    build(out=a.out, defines=a.define)
     sys.exit(0)

@@ -875,9 +875,21 @@ int dchag_yardstick_copy(void* dst, const void* src, size_t bytes, void* stream)
   if (!dst || !src) return DCHAG_ERR_NULL;
   if (bytes == 0 || bytes % 16) return DCHAG_ERR_SHAPE;
   if (misaligned(dst) || misaligned(src)) return DCHAG_ERR_ALIGN;
-  const int blocks = 32 * compute_units();
-  k_yardstick_copy<<<dim3(blocks), 256, 0, static_cast<hipStream_t>(stream)>>>(bytes / 16, static_cast<const f32x4*>(src),
-                                                                             static_cast<f32x4*>(dst));
+  const size_t pieces = bytes / 16, blocks = (pieces + 1023) / 1024;
+  if (blocks > 0x7fffffffu) return DCHAG_ERR_SHAPE;
+  k_yardstick_copy<<<dim3((unsigned)blocks), 256, 0, static_cast<hipStream_t>(stream)>>>(
+      pieces, static_cast<const f32x4*>(src), static_cast<f32x4*>(dst));
+  return launch_status();
+}
+
+int dchag_yardstick_read(const void* src, size_t bytes, float* sink, void* stream) {
+  if (!src || !sink) return DCHAG_ERR_NULL;
+  if (bytes == 0 || bytes % 16) return DCHAG_ERR_SHAPE;
+  if (misaligned(src) || misaligned(sink)) return DCHAG_ERR_ALIGN;
+  const size_t pieces = bytes / 16, blocks = (pieces + 1023) / 1024;
+  if (blocks > 0x7fffffffu) return DCHAG_ERR_SHAPE;
+  k_yardstick_read<<<dim3((unsigned)blocks), 256, 0, static_cast<hipStream_t>(stream)>>>(
+      pieces, static_cast<const f32x4*>(src), sink);
   return launch_status();
 }
 

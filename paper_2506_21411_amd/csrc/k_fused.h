@@ -505,7 +505,22 @@ struct Frags {
   bf16x8 a[4], b[2];
 };
 
+// Timing probes of the GEMM core (compile-time; 0 in the product build).  `python -m paper_2506_21411_amd.build
+// --define DCHAG_GEMM_PROBE=n --out <file>` builds a library whose RESULTS ARE MEANINGLESS and whose timing tells what
+// each part of k_vagg_mfma costs: bit 1 = no MFMAs (the fragments are still read), 2 = no fragment reads, 4 = no
+// barrier per slice, 8 = no global -> LDS loads.  Every access stays in bounds and every loop keeps its trip count.
+#ifndef DCHAG_GEMM_PROBE
+#define DCHAG_GEMM_PROBE 0
+#endif
+
 __device__ __forceinline__ void read_frags(Frags& f, const unsigned char* stage, const GemmLane& L, int kk) {
+  if (DCHAG_GEMM_PROBE & 2) {                            // keep the registers opaque, read nothing
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(f.a[i]));
+#pragma unroll
+    for (int j = 0; j < 2; ++j) asm volatile("" : "+v"(f.b[j]));
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(stage + L.a_base + i * 4096 + L.ck[kk]);
 #pragma unroll
@@ -513,6 +528,13 @@ __device__ __forceinline__ void read_frags(Frags& f, const unsigned char* stage,
 }
 
 __device__ __forceinline__ void mfma_step(f32x16 (&acc)[4][2], const Frags& f) {
+  if (DCHAG_GEMM_PROBE & 1) {                            // the fragments count as used, nothing is multiplied
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("" : : "v"(f.a[i]));
+#pragma unroll
+    for (int j = 0; j < 2; ++j) asm volatile("" : : "v"(f.b[j]));
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -521,6 +543,16 @@ __device__ __forceinline__ void mfma_step(f32x16 (&acc)[4][2], const Frags& f) {
 
 // First k-step of an accumulation: C = 0 is an inline operand of the MFMA, the accumulators need no clearing.
 __device__ __forceinline__ void mfma_step_first(f32x16 (&acc)[4][2], const Frags& f) {
+  if (DCHAG_GEMM_PROBE & 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    mfma_step(acc, f);
+    return;
+  }
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -660,12 +692,12 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
       unsigned char* st = smem + si * kGemmStageBytes + L.wave * 4096;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        load16_to_lds(a_cur[i], st + i * 1024);
+        if (!(DCHAG_GEMM_PROBE & 8)) load16_to_lds(a_cur[i], st + i * 1024);
         a_cur[i] += kGemmBK;
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        load16_to_lds(b_cur[i], st + kGemmBM * 128 + i * 1024);
+        if (!(DCHAG_GEMM_PROBE & 8)) load16_to_lds(b_cur[i], st + kGemmBM * 128 + i * 1024);
         b_cur[i] += kGemmBK;
       }
       if (++ki == KT) {
@@ -718,7 +750,7 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
         pin_step_schedule();
         // every read of this stage is in registers and the next slice has landed: swap stages
         __builtin_amdgcn_s_waitcnt(0);                   // vmcnt(0) and lgkmcnt(0)
-        __builtin_amdgcn_s_barrier();
+        if (!(DCHAG_GEMM_PROBE & 4)) __builtin_amdgcn_s_barrier();
         if (L.wm == 0) issue();                          // slice after next -> the stage just released
         sc ^= 1;
         __builtin_amdgcn_sched_barrier(0);

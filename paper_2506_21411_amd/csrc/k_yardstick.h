@@ -32,10 +32,29 @@ __global__ __launch_bounds__(256) void k_yardstick_mfma(int iters, float* __rest
   sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-// dst[i] = src[i] for n 16-byte pieces, grid-stride: reads 16 n bytes, writes 16 n bytes.
+// dst[i] = src[i] for n 16-byte pieces: reads 16 n bytes, writes 16 n bytes.  A block of 256 threads copies 1024
+// consecutive pieces, a thread four of them 256 pieces apart (four independent 16-byte loads in flight per lane).
 __global__ __launch_bounds__(256) void k_yardstick_copy(size_t n, const f32x4* __restrict__ src, f32x4* __restrict__ dst) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+  const size_t base = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  f32x4 v[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    if (base + 256 * t < n) v[t] = src[base + 256 * t];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    if (base + 256 * t < n) dst[base + 256 * t] = v[t];
+}
+
+// Reads n 16-byte pieces and writes (next to) nothing: the streaming-read rate.  The sum keeps the loads alive; a
+// thread stores it only if it equals a value it cannot take.
+__global__ __launch_bounds__(256) void k_yardstick_read(size_t n, const f32x4* __restrict__ src, float* __restrict__ sink) {
+  const size_t base = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  f32x4 v[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) v[t] = base + 256 * t < n ? src[base + 256 * t] : f32x4{0.f, 0.f, 0.f, 0.f};
+  const f32x4 s4 = (v[0] + v[1]) + (v[2] + v[3]);
+  const float s = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+  if (s == -1.2345e38f) sink[threadIdx.x] = s;
 }
 
 }  // namespace dchag
