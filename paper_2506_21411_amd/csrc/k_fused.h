@@ -508,7 +508,8 @@ struct Frags {
 // Timing probes of the GEMM core (compile-time; 0 in the product build).  `python -m paper_2506_21411_amd.build
 // --define DCHAG_GEMM_PROBE=n --out <file>` builds a library whose RESULTS ARE MEANINGLESS and whose timing tells what
 // each part of k_vagg_mfma costs: bit 1 = no MFMAs (the fragments are still read), 2 = no fragment reads, 4 = no
-// barrier per slice, 8 = no global -> LDS loads.  Every access stays in bounds and every loop keeps its trip count.
+// barrier per slice, 8 = no global -> LDS loads, 16 = k_linear_dl stores (next to) nothing.  Every access stays in bounds
+// and every loop keeps its trip count.
 #ifndef DCHAG_GEMM_PROBE
 #define DCHAG_GEMM_PROBE 0
 #endif
@@ -906,7 +907,7 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = r0 + L.wm * 128 + i * 32 + 8 * (r >> 2) + 4 * L.lhi + (r & 3);
-        if (row < rows)
+        if (row < rows && !((DCHAG_GEMM_PROBE & 16) && acc[i][j][r] != 12345.f))
           Yb[(size_t)row * D + col] = (bf16)(acc[i][j][r] + bvv + (rowadd ? (float)rowadd[(size_t)row * D + col] : 0.f));
       }
   }
