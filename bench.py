@@ -418,6 +418,11 @@ def main() -> int:
                    "aggregation_stage": None if staged is None else
                    dict(staged["scores_stage"], kernel="k_scores_softmax (dchag_aggregate_level, tokens from HBM)", goal=0.6)}
 
+    # the second named stage also sits inside the roofline block, next to the dominant kernel (the first)
+    if roofline and targets and targets.get("aggregation_stage"):
+        a = targets["aggregation_stage"]
+        roofline["aggregation_stage"] = {k_: a[k_] for k_ in ("kernel", "bound", "achieved", "peak", "unit", "frac")}
+
     # the CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
     cpu = None
     if args.cpu_patches > 0 and args.mode != "backward":
