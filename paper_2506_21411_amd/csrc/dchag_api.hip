@@ -45,6 +45,7 @@ enum Switch {
   SW_GEMM_SCALAR_STORES,
   SW_GENERIC_LEVEL,
   SW_GENERIC_TOKENIZE,
+  SW_LINEAR_SMALL_REGS,
   SW_LINEAR_TOKENS,
   SW_MFMA_TILE,
   SW_MIX_NARROW,
@@ -77,6 +78,7 @@ struct SwitchTable {
     "DCHAG_GEMM_SCALAR_STORES",
     "DCHAG_GENERIC_LEVEL",
     "DCHAG_GENERIC_TOKENIZE",
+    "DCHAG_LINEAR_SMALL_REGS",
     "DCHAG_LINEAR_TOKENS",
     "DCHAG_MFMA_TILE",
     "DCHAG_MIX_NARROW",
@@ -454,8 +456,19 @@ int launch_linear_dl(int B, int D, RowBlocks rb, const bf16* A, const bf16* Wt, 
   tw.m_tiles = (rb.rows_per_group + kGemmBM - 1) / kGemmBM;
   tw.nb = B;
   tw.total = tw.n_tiles * tw.m_tiles * B * rb.G;
-  if (tw.total * 2 < compute_units())                    // too few 256x256 tiles to fill the chip: 128x128 tiles
-    return launch_linear_mfma_cfg<128, 128, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st, rowadd);
+  if (tw.total * 2 < compute_units()) {                  // too few 256x256 tiles to fill the chip: 128x128 tiles, and
+    if (dbg(SW_LINEAR_SMALL_REGS))                         // loads three slices ahead (the debugging switch keeps the
+      return launch_linear_mfma_cfg<128, 128, 2, 2, 1>(B, D, rb, A, Wt, bias, Y, st, rowadd);   // register-staged kernel)
+    TileWork ts;
+    ts.n_tiles = D / 128;
+    ts.m_tiles = (rb.rows_per_group + 127) / 128;
+    ts.nb = B;
+    ts.total = ts.n_tiles * ts.m_tiles * B * rb.G;
+    const int pers = (ts.total + kXcds - 1) / kXcds;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_linear_ring), kSmallRingBytes)) return DCHAG_ERR_LAUNCH;
+    k_linear_ring<<<dim3(pers * kXcds), dim3(256), kSmallRingBytes, st>>>(D, rb, ts, A, Wt, bias, Y, rowadd);
+    return launch_status();
+  }
   const int per = (tw.total + kXcds - 1) / kXcds;
   if (ensure_dynamic_lds(reinterpret_cast<const void*>(k_linear_dl), kGemmRingBytes)) return DCHAG_ERR_LAUNCH;
   k_linear_dl<<<dim3(per * kXcds), dim3(512), kGemmRingBytes, st>>>(D, rb, tw, A, Wt, bias, Y, rowadd);
@@ -766,16 +779,17 @@ int launch_reduce_ring_cols(int B, int C, int H, int W, int D, int g, int heads,
 
 // part / part_bytes: optional fp32 scratch for partial sums; with it, and too few tiles to give every compute unit two
 // rounds of workgroups, a group's members are dealt to up to 16 workgroups per tile (DCHAG_FIRST_LEVEL_SPLIT overrides
-// the count).  Workgroups of 128 patches x 128 columns, two per compute unit (DCHAG_RING_SHAPE = 0: 128 x 256, one).
+// the count).  Workgroups of 128 patches x 256 columns, one per compute unit, three stages (DCHAG_RING_SHAPE = 1:
+// 128 x 128, two per compute unit, two stages).
 template <bool ATT>
 int launch_reduce_ring(int B, int C, int H, int W, int D, int g, int heads, const bf16* x, const bf16* Wt,
                        const bf16* wmix, const bf16* v1, const bf16* v2, const float* alpha, const bf16* bias, bf16* y,
                        hipStream_t st, float* part = nullptr, size_t part_bytes = 0) {
   const char* e = dbg(SW_RING_SHAPE);
-  if (e && atoi(e) == 0)
-    return launch_reduce_ring_cols<ATT, 0>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
+  if (e && atoi(e) == 1)
+    return launch_reduce_ring_cols<ATT, 1>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
                                            part_bytes);
-  return launch_reduce_ring_cols<ATT, 1>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
+  return launch_reduce_ring_cols<ATT, 0>(B, C, H, W, D, g, heads, x, Wt, wmix, v1, v2, alpha, bias, y, st, part,
                                          part_bytes);
 }
 

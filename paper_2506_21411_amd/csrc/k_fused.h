@@ -914,6 +914,107 @@ __global__ __launch_bounds__(512) void k_linear_dl(int D, RowBlocks rb, TileWork
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same projection for a problem of FEW tiles (the output projection of an upper level: 64 tiles of 128 x 128 at the
+// headline shape).  With less than one 256 x 256 tile per compute unit the run time is the depth of the contraction times
+// the round trip of one slice's loads, so this form trades tile size for depth of prefetch: 128 x 128 tiles, four
+// wavefronts (2 x 2) of 64 x 64, FOUR 32-KiB stages filled by direct-to-LDS loads issued three slices ahead; a slice
+// then costs its transfer and its 16 MFMAs per wavefront, not a round trip.  One barrier per slice; the fragments of a
+// slice are read behind it.  Requires D % 128 == 0.  Dynamic LDS: 128 KiB.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSmallStageBytes = 256 * 128, kSmallStages = 4, kSmallRingBytes = kSmallStages * kSmallStageBytes;
+
+__global__ __launch_bounds__(256) void k_linear_ring(int D, RowBlocks rb, TileWork tw, const bf16* __restrict__ A,
+                                                     const bf16* __restrict__ Wt, const bf16* __restrict__ bias,
+                                                     bf16* __restrict__ Y, const bf16* __restrict__ rowadd) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  int k, b, mt, nt;
+  if (!tw.decode(blockIdx.x, k, b, mt, nt)) return;
+  const int rows = rb.rows_of(k);
+  const int r0 = mt * 128, o0 = nt * 128;
+  if (r0 >= rows) return;
+  const int KT = D / kGemmBK;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, lhi = lane >> 5;
+  const bf16* Ab = A + (size_t)rb.first_row(b, k) * D;
+  bf16* Yb = Y + (size_t)rb.first_row(b, k) * D;
+  const bf16* Wb = Wt + (size_t)k * D * D;
+  // a stage: A rows 0..127, then B rows 0..127, 128 bytes each, chunks swizzled as in the large core; wavefront w loads
+  // rows 32 w .. 32 w + 31 of both (four loads each per slice)
+  const bf16* a_src[4];
+  const bf16* b_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = wave * 32 + i * 8 + (lane >> 3);
+    const int ch = ((lane & 7) ^ swz_chunk(row)) * 8;
+    a_src[i] = Ab + (size_t)min(r0 + row, rows - 1) * D + ch;
+    b_src[i] = Wb + (size_t)(o0 + row) * D + ch;
+  }
+  int issued = 0;
+  auto issue = [&]() {                                   // slice `issued` -> stage issued % 4
+    unsigned char* st = smem + (issued & 3) * kSmallStageBytes + wave * 4096;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load16_to_lds(a_src[i] + issued * kGemmBK, st + i * 1024);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load16_to_lds(b_src[i] + issued * kGemmBK, st + 128 * 128 + i * 1024);
+    ++issued;
+  };
+  const int a_base = (wm * 64 + l32) * 128, b_base = 128 * 128 + (wn * 64 + l32) * 128;
+  int ck[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) ck[kk] = ((kk * 2 + lhi) ^ swz_chunk(l32)) * 16;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int s0 = 0; s0 < 3 && s0 < KT; ++s0) issue();
+  for (int kt = 0; kt < KT; ++kt) {
+    // slice kt has landed (this wavefront's share; the slices behind it may stay in flight: 8 loads each) ...
+    const int behind = issued - 1 - kt;                  // uniform
+    if (behind >= 2) wait_vmcnt<16>();
+    else if (behind == 1) wait_vmcnt<8>();
+    else wait_vmcnt<0>();
+    // ... and for everyone; all wavefronts are done with slice kt - 1, whose stage takes slice kt + 3
+    __builtin_amdgcn_s_barrier();
+    if (issued < KT) issue();
+    const unsigned char* st = smem + (kt & 3) * kSmallStageBytes;
+    bf16x8 af[4][2], bfr[4][2];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[kk][i] = *reinterpret_cast<const bf16x8*>(st + a_base + i * 4096 + ck[kk]);
+        bfr[kk][i] = *reinterpret_cast<const bf16x8*>(st + b_base + i * 4096 + ck[kk]);
+      }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[i][j], 0, 0, 0);
+  }
+  wait_vmcnt<0>();                                       // nothing may still target LDS when the block retires
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = o0 + wn * 64 + j * 32 + l32;
+    const float bvv = bias ? (float)bias[(size_t)k * D + col] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = r0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+        if (row < rows)
+          Yb[(size_t)row * D + col] = (bf16)(acc[i][j][r] + bvv + (rowadd ? (float)rowadd[(size_t)row * D + col] : 0.f));
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Value projection folded into the tokenizer weights (weight-only; 64 pixels per patch), on the same core:
 //   Wf[c][o][kk] = sum_d Wv[k][o][d] * We[c][d][kk],   k = c / g.
 // Work item: group k, 256 rows o, four channels of the group (one per wavefront column wn).  The A operand (rows of
@@ -2248,6 +2349,7 @@ __global__ __launch_bounds__(RedCfg<CFG>::kThreads, RedCfg<CFG>::kPerCu) void k_
   const int colj = (wcol + l32) * 2;                     // byte offset of this lane's first column in a vector
   const int hrel = ATT ? (col_base + wcol) / dh - col_base / dh : 0;
 
+  const unsigned short mask1 = v1 ? 0xFFFF : 0, mask2 = v2 ? 0xFFFF : 0;
   f32x16 o[2][TN];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -2259,6 +2361,147 @@ __global__ __launch_bounds__(RedCfg<CFG>::kThreads, RedCfg<CFG>::kPerCu) void k_
 #pragma unroll
   for (int j = 0; j < TN; ++j) cst[j] = 0.f;
 
+  if constexpr (NS == 3) {
+    // Three stages: the pipeline of k_vagg_mfma with a member in the place of a slice.  The barrier sits behind the
+    // member's third k-step: by then every fragment of the member is in registers (its last k-step's, its softmax
+    // weights / mixing weights too), so the barrier hands its stage to member m + 3 and the next member over to
+    // everyone; the fragments of the next member's first k-step are read right behind the barrier and the member's last
+    // four products and its scaling into the running sum cover their latency.  Loads run two members ahead.
+    struct F2 {
+      bf16x8 a[2], b[TN];
+    };
+    auto read2 = [&](F2& f, const unsigned char* st, int kk) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(st + a_base + i * 4096 + ck[kk]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(st + b_base + j * 4096 + ck[kk]);
+    };
+    f32x16 acc[2][TN];
+    auto mfma2 = [&](const F2& f) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+    };
+    auto mfma2_from = [&](const F2& f, const float (&c)[TN]) {       // a member starts from its per-column constant
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const f32x16 init = {c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j], c[j]};
+#pragma unroll
+        for (int i = 0; i < 2; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], init, 0, 0, 0);
+      }
+    };
+    auto pin = [&]() {                                     // a fragment read behind each of the step's four products
+#pragma unroll
+      for (int t = 0; t < 2 + TN; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto vectors_of = [&](const unsigned char* st, float (&vb)[TN], float (&wj)[TN]) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const unsigned char* xs = st + xoff + colj + j * 64;
+        auto column_value = [&](int slot, unsigned short mask) {
+          const unsigned short raw = *reinterpret_cast<const unsigned short*>(xs + slot * VB) & mask;
+          return (float)__builtin_bit_cast(bf16, raw);
+        };
+        if (ATT) {
+          wj[j] = 1.f;
+          vb[j] = column_value(0, mask1) + column_value(1, mask2);
+        } else {
+          wj[j] = column_value(0, 0xFFFF);
+          vb[j] = column_value(1, mask1) + column_value(2, mask2);
+        }
+      }
+    };
+    if (gk == 0) return;                                   // uniform (the host never deals more shares than members)
+    issue(0);
+    if (gk > 1) issue(1);
+    if (gk > 1) {
+      if (extra) wait_vmcnt<AL + BL + 1>();
+      else wait_vmcnt<AL + BL>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    if (gk > 2) issue(2);
+    F2 f0, f1;
+    float vb[TN], wj[TN], vbn[TN], wjn[TN];
+    f32x4 areg[2][4];                                      // softmax weights of the member's rows (ATT)
+    read2(f0, smem, 0);
+    vectors_of(smem, vb, wj);
+    int sc = 0;
+    for (int m = 0; m < gk; ++m) {
+      const unsigned char* st = smem + sc * kRedStageBytes;
+      __builtin_amdgcn_sched_barrier(0);
+      read2(f1, st, 1);
+      if (ATT) mfma2_from(f0, vb);
+      else {
+        const float zero[TN] = {};
+        mfma2_from(f0, zero);
+      }
+      pin();
+      read2(f0, st, 2);
+      mfma2(f1);
+      pin();
+      read2(f1, st, 3);
+      mfma2(f0);
+      pin();
+      if (ATT) {
+        const float* al = reinterpret_cast<const float*>(st + xoff + AOFF + hrel * HB) + wm * 64 + 4 * lhi;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) areg[i][q] = *reinterpret_cast<const f32x4*>(al + i * 32 + 8 * q);
+      }
+      // member m + 1 has landed (this wavefront's share; member m + 2's loads may stay in flight) and every read of
+      // member m's stage is in registers
+      if (m + 2 < gk) {
+        if (extra) wait_vmcnt<AL + BL + 1>();
+        else wait_vmcnt<AL + BL>();
+        __builtin_amdgcn_s_waitcnt((7 << 4) | (63 & 15) | ((63 >> 4) << 14));   // lgkmcnt(0), vmcnt untouched
+      } else {
+        __builtin_amdgcn_s_waitcnt(0);
+      }
+      __builtin_amdgcn_s_barrier();
+      if (m + 3 < gk) issue(sc);                           // member m + 3 -> the stage just released
+      sc = sc == 2 ? 0 : sc + 1;
+      const unsigned char* sn = smem + sc * kRedStageBytes;
+      __builtin_amdgcn_sched_barrier(0);
+      read2(f0, sn, 0);                                    // past the last member: a stale stage, read and not used
+      vectors_of(sn, vbn, wjn);
+      mfma2(f1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ATT) {
+        // rows of accumulator register r: 8 (r / 4) + 4 lhi + r % 4 of the block
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) o[i][j][4 * q + e] += areg[i][q][e] * acc[i][j][4 * q + e];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[i][j][r] += wj[j] * acc[i][j][r];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) cst[j] += wj[j] * vb[j];
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        vb[j] = vbn[j];
+        wj[j] = wjn[j];
+      }
+    }
+    wait_vmcnt<0>();
+  } else {
 #pragma unroll
   for (int s0 = 0; s0 < NS - 1; ++s0)
     if (gk > s0) issue(s0);
@@ -2278,22 +2521,24 @@ __global__ __launch_bounds__(RedCfg<CFG>::kThreads, RedCfg<CFG>::kPerCu) void k_
     const unsigned char* st = smem + sc * kRedStageBytes;
     sc = sc == NS - 1 ? 0 : sc + 1;
 
+    // per-column vectors of this member, read without a branch: an absent vector's slot holds arbitrary bytes, which the
+    // mask turns into +0 (a branch per vector would put one LDS round trip after the other in front of the products)
     float vb[TN];                                        // per-column constant of this member: v1 + v2
     float wj[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const unsigned char* xs = st + xoff + colj + j * 64;
-      float s = 0.f;
-      wj[j] = 1.f;
+      auto column_value = [&](int slot, unsigned short mask) {
+        const unsigned short raw = *reinterpret_cast<const unsigned short*>(xs + slot * VB) & mask;
+        return (float)__builtin_bit_cast(bf16, raw);
+      };
       if (ATT) {
-        if (v1) s += (float)*reinterpret_cast<const bf16*>(xs);
-        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + VB);
+        wj[j] = 1.f;
+        vb[j] = column_value(0, mask1) + column_value(1, mask2);
       } else {
-        wj[j] = (float)*reinterpret_cast<const bf16*>(xs);
-        if (v1) s += (float)*reinterpret_cast<const bf16*>(xs + VB);
-        if (v2) s += (float)*reinterpret_cast<const bf16*>(xs + 2 * VB);
+        wj[j] = column_value(0, 0xFFFF);
+        vb[j] = column_value(1, mask1) + column_value(2, mask2);
       }
-      vb[j] = s;
     }
     // Row block i = 0 first, then i = 1: while the matrix pipe works on the second block the vector ALUs scale the
     // first into the running sum (the two instruction streams are interleaved below, one MFMA per four FMAs).
@@ -2356,6 +2601,7 @@ __global__ __launch_bounds__(RedCfg<CFG>::kThreads, RedCfg<CFG>::kPerCu) void k_
 #pragma unroll
       for (int j = 0; j < TN; ++j) cst[j] += wj[j] * vb[j];
     }
+  }
   }
 
   const size_t yoff = (((size_t)b * G + k) * N + n0 + wm * 64) * D + col_base + wcol + l32;

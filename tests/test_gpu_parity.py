@@ -147,19 +147,22 @@ def test_aggregate_level_matches_oracle(dtype, B, Cin, N, D, heads, g, biases):
     assert err < TOL[dtype]
 
 
-@pytest.mark.parametrize("one_kernel", ["0", "1"])
+@pytest.mark.parametrize("route", ["two_kernels", "one_kernel"])
 @pytest.mark.parametrize("B,Cin,N,D,heads,g", [
-    (2, 12, 40, 256, 4, 8),        # N = 40: second 32-patch tile holds 8 patches; short last group of 4
+    (2, 12, 40, 256, 4, 8),        # N = 40: second 32-patch tile holds 8 patches (pitch 64); short last group of 4
     (1, 33, 19, 512, 8, 16),       # last group of one member; fewer members than wavefronts in it
     (1, 70, 9, 256, 2, 70),        # one group of 70: wavefronts take 9 or 8 members each
     (1, 10, 50, 512, 16, 5),       # 16 heads: every key row of the 16-row fragment is a real head
     (1, 5, 20, 1024, 2, 5),        # D = 1024: 32 steps per token row
+    (1, 9, 17, 1024, 32, 9),       # 32 heads: two head blocks; N = 17 (one full 16-patch tile and one patch)
+    (2, 16, 48, 512, 8, 16),       # N = 48: the last 16-patch tile is full and the pitch (64) reaches beyond it
 ])
-def test_aggregate_level_score_kernels(monkeypatch, one_kernel, B, Cin, N, D, heads, g):
-    """Both score routes of the bf16 MFMA path on the same small shapes: scores and softmax in one kernel
-    (the library takes it by itself only on large inputs) and the two-kernel route."""
-    monkeypatch.setenv("DCHAG_SCORES_ONE_KERNEL", one_kernel)
-    say(f"score route one_kernel={one_kernel} B={B} Cin={Cin} N={N} D={D} h={heads} g={g}")
+def test_aggregate_level_score_kernels(monkeypatch, route, B, Cin, N, D, heads, g):
+    """The score routes of the bf16 MFMA path on the same small shapes: raw scores then a softmax kernel, and scores and
+    softmax in one kernel over 32 patches and all members (taken by itself only on large inputs).  A route that does not
+    tile a shape falls back to the two-kernel route."""
+    monkeypatch.setenv("DCHAG_SCORES_ONE_KERNEL", "1" if route == "one_kernel" else "0")
+    say(f"score route {route} B={B} Cin={Cin} N={N} D={D} h={heads} g={g}")
     rng = np.random.Generator(np.random.PCG64(400 + Cin))
     lv = make_level(rng, n_groups(Cin, g), g, D, "bf16", True)
     z = make_tokens(B, Cin, N, D, "bf16", seed=11)
@@ -508,10 +511,11 @@ def test_forward_linear_first_level_patch_tiles(monkeypatch, narrow):
     _forward_on_sampled_patches(cfg, f"linear first level, narrow={narrow}", 10)
 
 
-@pytest.mark.parametrize("route", ["ring", "ring_shape_0", "registers", "registers_narrow"])
+@pytest.mark.parametrize("route", ["ring", "ring_shape_1", "registers", "registers_narrow"])
 def test_forward_linear_first_level_of_8x8_patches(monkeypatch, route):
     """The fused tokenizer + linear first level on 8 x 8 patches: the kernel that streams a member's patches and weights
-    through an LDS ring (workgroups of 128 patches x 128 columns, two per compute unit, or 128 x 256, one), and the two
+    through an LDS ring (workgroups of 128 patches x 256 columns with three stages, one per compute unit, or 128 x 128 with
+    two stages, two per compute unit), and the two
     that pass them through registers; N = 204 patches (two tiles of 128 or four of 64,
     the last ragged), two 256-column slices, groups 4 + 4 + 4 + 1."""
     if route.startswith("ring_shape_"):

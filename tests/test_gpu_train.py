@@ -151,7 +151,7 @@ PIXEL_VALUES = [
 
 
 @pytest.mark.parametrize("kw", PIXEL_VALUES)
-@pytest.mark.parametrize("route", ["folded_into_tokenizer", "ring_shape_0", "fold_by_general_product", "head_sums"])
+@pytest.mark.parametrize("route", ["folded_into_tokenizer", "ring_shape_1", "fold_by_general_product", "head_sums"])
 def test_forward_folded_first_level_values_from_pixels(monkeypatch, kw, route):
     """The first attention level of dchag_forward_folded with the value projection folded into the tokenizer weights
     (one kernel from pixels and softmax weights to the level's pre-projection output; the weight-only fold by its own
