@@ -174,6 +174,25 @@ def test_aggregate_level_score_kernels(monkeypatch, route, B, Cin, N, D, heads, 
     assert err < TOL["bf16"]
 
 
+@pytest.mark.parametrize("regs", [False, True])
+def test_aggregate_level_output_projection_of_few_tiles(monkeypatch, regs):
+    """The output projection of a level with few tiles: the four-stage kernel that loads three slices ahead (taken by
+    itself) and the register-staged one behind DCHAG_LINEAR_SMALL_REGS; 3 groups of 100 rows per batch item (a ragged 128-row
+    tile each), D = 512 (eight slices, so the four stages wrap around twice), and a level of a single 16-row group."""
+    if regs:
+        monkeypatch.setenv("DCHAG_LINEAR_SMALL_REGS", "1")
+    for (B, Cin, N, D, heads, g) in ((2, 9, 100, 512, 8, 3), (1, 4, 16, 256, 4, 4)):
+        rng = np.random.Generator(np.random.PCG64(500 + Cin))
+        lv = make_level(rng, n_groups(Cin, g), g, D, "bf16", True)
+        z = make_tokens(B, Cin, N, D, "bf16", seed=21)
+        y = dchag.dchag_aggregate_level(dev(z, "bf16"), dev_level(lv, "bf16"), heads)
+        torch.cuda.synchronize()
+        want = oracle.aggregate_level(z.transpose(0, 2, 1, 3).reshape(B * N, Cin, D), lv, heads)
+        err = rel_err(host(y), want.reshape(B, N, -1, D).transpose(0, 2, 1, 3))
+        say(f"few-tile output projection regs={regs} B={B} Cin={Cin} N={N} D={D}: err={err:.3e}")
+        assert err < TOL["bf16"]
+
+
 def test_aggregate_level_large_enough_for_the_one_kernel_score_route():
     """A level big enough that the library picks the one-kernel score route by itself (at least one
     32-patch block per compute unit), ragged in N, checked on sampled patches."""
