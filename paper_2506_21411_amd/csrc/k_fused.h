@@ -461,6 +461,26 @@ __global__ __launch_bounds__(256) void k_softmax_alpha(int Cin, int N, int heads
     for (int cl = 0; cl < gpad; ++cl) p[cl * stride] = 0.f;
     return;
   }
+  if (gk <= 32) {
+    // the whole group in registers: all loads of the thread are in flight together, one pass over memory each way
+    // (same arithmetic and order as the loop below)
+    float v[32];
+#pragma unroll
+    for (int cl = 0; cl < 32; ++cl) v[cl] = cl < gk ? p[cl * stride] : -INFINITY;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int cl = 0; cl < 32; ++cl) mx = fmaxf(mx, v[cl]);
+    float den = 0.f;
+#pragma unroll
+    for (int cl = 0; cl < 32; ++cl)
+      if (cl < gk) den += __expf(v[cl] - mx);
+    const float inv = 1.f / den;
+#pragma unroll
+    for (int cl = 0; cl < 32; ++cl)
+      if (cl < gk) p[cl * stride] = __expf(v[cl] - mx) * inv;
+    for (int cl = gk; cl < gpad; ++cl) p[cl * stride] = 0.f;
+    return;
+  }
   float mx = -INFINITY;
   for (int cl = 0; cl < gk; ++cl) mx = fmaxf(mx, p[cl * stride]);
   float den = 0.f;
