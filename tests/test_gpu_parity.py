@@ -193,16 +193,17 @@ def test_aggregate_level_output_projection_of_few_tiles(monkeypatch, regs):
         assert err < TOL["bf16"]
 
 
-def test_aggregate_level_large_enough_for_the_one_kernel_score_route():
+@pytest.mark.parametrize("Cin", [24, 48])
+def test_aggregate_level_large_enough_for_the_one_kernel_score_route(Cin):
     """A level big enough that the library picks the one-kernel score route by itself (at least one
-    32-patch block per compute unit), ragged in N, checked on sampled patches."""
-    B, Cin, N, D, heads, g = 2, 24, 1500, 256, 4, 8
+    32-patch block per compute unit), ragged in N, checked on sampled patches (tile seams among them); three and six groups."""
+    B, N, D, heads, g = 2, 1500, 256, 4, 8
     rng = np.random.Generator(np.random.PCG64(77))
     lv = make_level(rng, n_groups(Cin, g), g, D, "bf16", True)
     z = make_tokens(B, Cin, N, D, "bf16", seed=12)
     y = dchag.dchag_aggregate_level(dev(z, "bf16"), dev_level(lv, "bf16"), heads)
     torch.cuda.synchronize()
-    ns = np.array([0, 1, 31, 32, 700, 1471, 1472, 1498, 1499])
+    ns = np.array([0, 1, 31, 32, 33, 63, 64, 700, 1439, 1440, 1471, 1472, 1498, 1499])
     zo = z[:, :, ns, :].transpose(0, 2, 1, 3).reshape(B * ns.size, Cin, D)
     want = oracle.aggregate_level(zo, lv, heads).reshape(B, ns.size, -1, D).transpose(0, 2, 1, 3)
     err = rel_err(host(y)[:, :, ns, :], want)
