@@ -92,6 +92,25 @@ def test_aggregate_level_static_validation(lib):
     assert a(1, 4, 512, 256, 1024, 16, ctypes.byref(big), FAKE, FAKE, None) == -4              # needs more than 32 MiB
 
 
+def test_yardstick_validation(lib):
+    """The benchmark's yardstick calls check their arguments on the host like every other entry point."""
+    flops = ctypes.c_double(0.0)
+    ym = lib.dchag_yardstick_mfma
+    ym.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    assert ym(10, None, 1 << 30, ctypes.byref(flops), None) == -1
+    assert ym(0, FAKE, 1 << 30, ctypes.byref(flops), None) == -2
+    assert ym(10, FAKE, 16, ctypes.byref(flops), None) == -4                     # scratch too small
+    yc = lib.dchag_yardstick_copy
+    yc.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert yc(None, FAKE, 1024, None) == -1
+    assert yc(FAKE, FAKE, 1000, None) == -2                                      # not a multiple of 16 bytes
+    assert yc(FAKE + 4, FAKE, 1024, None) == -6
+    yr = lib.dchag_yardstick_read
+    yr.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    assert yr(FAKE, 1024, None, None) == -1
+    assert yr(FAKE, 0, FAKE, None) == -2
+
+
 def test_forward_validation(lib):
     f = lib.dchag_forward
     two = (_CLevel * 2)(level(4), level(2))
