@@ -2246,6 +2246,13 @@ __global__ __launch_bounds__(512) void k_tokenize_attend_wide(int C, int H, int 
 // stages, one workgroup per compute unit.  CFG 1: 128 x 128, 4 wavefronts (2 x 2) of 64 x 64, two stages, two workgroups
 // per compute unit (the one taken: 0.107 against 0.114 ms at the headline shape; 64 x 128 with wavefronts of 64 x 32,
 // three workgroups per compute unit, was slower than both: 0.127 ms).
+// Timing probes of k_tokenize_reduce_ring's three-stage form (compile-time; 0 in the product build; results
+// meaningless, every access in bounds, every loop keeps its trip count): bit 1 = a member costs only its waits, its
+// barrier and its loads (no fragment reads, products or scaling), 2 = no global -> LDS loads.
+#ifndef DCHAG_RING_PROBE
+#define DCHAG_RING_PROBE 0
+#endif
+
 template <int CFG>
 struct RedCfg {
   static constexpr int kPatches = 128;
@@ -2343,6 +2350,7 @@ __global__ __launch_bounds__(RedCfg<CFG>::kThreads, RedCfg<CFG>::kPerCu) void k_
   const size_t b_step = (size_t)D * 64;
   auto issue = [&](int stage) {
     unsigned char* st = smem + stage * kRedStageBytes;
+    if (DCHAG_RING_PROBE & 2) return;
 #pragma unroll
     for (int i = 0; i < AL; ++i) {
       load16_to_lds(a_src[i], st + (wave * AL + i) * 1024);
@@ -2455,6 +2463,18 @@ __global__ __launch_bounds__(RedCfg<CFG>::kThreads, RedCfg<CFG>::kPerCu) void k_
     int sc = 0;
     for (int m = 0; m < gk; ++m) {
       const unsigned char* st = smem + sc * kRedStageBytes;
+      if (DCHAG_RING_PROBE & 1) {                          // waits, barrier and loads of a member, nothing else
+        if (m + 2 < gk) {
+          if (extra) wait_vmcnt<AL + BL + 1>();
+          else wait_vmcnt<AL + BL>();
+        } else {
+          __builtin_amdgcn_s_waitcnt(0);
+        }
+        __builtin_amdgcn_s_barrier();
+        if (m + 3 < gk) issue(sc);
+        sc = sc == 2 ? 0 : sc + 1;
+        continue;
+      }
       __builtin_amdgcn_sched_barrier(0);
       read2(f1, st, 1);
       if (ATT) mfma2_from(f0, vb);
