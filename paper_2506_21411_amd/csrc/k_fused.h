@@ -528,7 +528,8 @@ struct Frags {
 // Timing probes of the GEMM core (compile-time; 0 in the product build).  `python -m paper_2506_21411_amd.build
 // --define DCHAG_GEMM_PROBE=n --out <file>` builds a library whose RESULTS ARE MEANINGLESS and whose timing tells what
 // each part of k_vagg_mfma costs: bit 1 = no MFMAs (the fragments are still read), 2 = no fragment reads, 4 = no
-// barrier per slice, 8 = no global -> LDS loads, 16 = k_linear_dl stores (next to) nothing.  Every access stays in bounds
+// barrier per slice, 8 = no global -> LDS loads (32 = none of the A operand, 64 = none of the B operand, k_vagg_mfma only),
+// 16 = k_linear_dl stores (next to) nothing.  Every access stays in bounds
 // and every loop keeps its trip count.
 #ifndef DCHAG_GEMM_PROBE
 #define DCHAG_GEMM_PROBE 0
@@ -713,12 +714,12 @@ __global__ __launch_bounds__(512) void k_vagg_mfma(int Cin, int N, int D, int he
       unsigned char* st = smem + si * kGemmStageBytes + L.wave * 4096;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        if (!(DCHAG_GEMM_PROBE & 8)) load16_to_lds(a_cur[i], st + i * 1024);
+        if (!(DCHAG_GEMM_PROBE & (8 | 32))) load16_to_lds(a_cur[i], st + i * 1024);
         a_cur[i] += kGemmBK;
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        if (!(DCHAG_GEMM_PROBE & 8)) load16_to_lds(b_cur[i], st + kGemmBM * 128 + i * 1024);
+        if (!(DCHAG_GEMM_PROBE & (8 | 64))) load16_to_lds(b_cur[i], st + kGemmBM * 128 + i * 1024);
         b_cur[i] += kGemmBK;
       }
       if (++ki == KT) {
